@@ -1,0 +1,426 @@
+"""Pins for the CPU oracle: each check ties an oracle function to something other
+than itself -- exact fractions on tiny inputs, library routines, closed forms,
+invariants, and the worked example of Sec. 4.7 (tests/golden/).  No GPU needed.
+"""
+import itertools
+import json
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+from oracle import moei_oracle as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# =============================================================== O1 router / top-k
+def test_topk_matches_stable_argsort_library():
+    rng = np.random.default_rng(1)
+    for E, k in [(8, 2), (64, 6), (160, 6), (5, 5), (7, 1)]:
+        z = rng.standard_normal((9, E))
+        idx, w = O.route_topk(z, k, renorm=False)
+        ref = np.argsort(-z, axis=1, kind="stable")[:, :k]
+        assert (idx == ref).all()
+        p = scipy.special.softmax(z, axis=1)
+        np.testing.assert_allclose(w, np.take_along_axis(p, ref, 1), rtol=1e-13)
+
+
+def test_topk_ties_go_to_lowest_index():
+    z = np.array([[1.0, 3.0, 3.0, 0.5, 3.0, 1.0]])
+    idx, _ = O.route_topk(z, 4, renorm=False)
+    assert idx.tolist() == [[1, 2, 4, 0]]
+    idx, _ = O.route_topk(np.zeros((1, 6)), 3, renorm=True)
+    assert idx.tolist() == [[0, 1, 2]]
+
+
+def test_topk_special_cases():
+    rng = np.random.default_rng(2)
+    z = rng.standard_normal((4, 11))
+    idx, w = O.route_topk(z, 11, renorm=False)      # k = E: a permutation, weights = softmax
+    for b in range(4):
+        assert sorted(idx[b].tolist()) == list(range(11))
+        assert abs(w[b].sum() - 1.0) < 1e-14
+        assert (np.diff(z[b, idx[b]]) <= 0).all()
+    idx1, w1 = O.route_topk(z, 1, renorm=True)      # k = 1: argmax, renormalised weight is 1
+    assert (idx1[:, 0] == z.argmax(axis=1)).all()
+    assert (w1 == 1.0).all()
+    _, wr = O.route_topk(z, 3, renorm=True)
+    np.testing.assert_allclose(wr.sum(axis=1), 1.0, rtol=1e-14)
+    with pytest.raises(ValueError):
+        O.route_topk(z, 12, False)
+
+
+def test_topk_brute_force_subsets():
+    # the chosen set maximises the sum of logits over all k-subsets
+    rng = np.random.default_rng(3)
+    z = rng.standard_normal(7)
+    idx, _ = O.route_topk(z, 3, False)
+    best = max(itertools.combinations(range(7), 3), key=lambda c: sum(z[list(c)]))
+    assert sorted(idx[0].tolist()) == sorted(best)
+
+
+def test_softmax_closed_form_and_shift_invariance():
+    p = O.softmax([0.0, math.log(3.0)])
+    np.testing.assert_allclose(p, [0.25, 0.75], rtol=1e-15)
+    z = np.array([1000.0, 1001.0, 999.0])      # would overflow without max subtraction
+    np.testing.assert_allclose(O.softmax(z), O.softmax(z - 1000.0), rtol=1e-15)
+
+
+def test_router_logits_is_a_matvec_and_bf16_decode_is_exact():
+    rng = np.random.default_rng(4)
+    W = rng.standard_normal((6, 16)).astype(np.float32)
+    x = rng.standard_normal(16).astype(np.float32)
+    b = rng.standard_normal(6).astype(np.float32)
+    ref = torch.from_numpy(W).double() @ torch.from_numpy(x).double() + torch.from_numpy(b).double()
+    np.testing.assert_allclose(O.router_logits(W, x, b), ref.numpy(), rtol=1e-14)
+    # bf16 bit patterns decode exactly: compare with torch's own bfloat16
+    tb = torch.from_numpy(W).to(torch.bfloat16)
+    bits = tb.view(torch.int16).numpy().view(np.uint16)
+    assert (O.to_f64(bits) == tb.double().numpy()).all()
+    # asymmetric W: a transposed operand would fail the shape or the value
+    assert O.router_logits(W, x).shape == (6,)
+
+
+# ==================================================================== O2 EAM update
+def test_eam_update_row_sums_and_partial_rows():
+    L, E, k, n_tok = 5, 9, 3, 7
+    rng = np.random.default_rng(5)
+    eam = np.zeros((L, E), dtype=np.int64)
+    for t in range(n_tok):
+        for l in range(L):
+            idx = rng.choice(E, size=k, replace=False)
+            before = eam.copy()
+            O.eam_update(eam, l, idx)
+            assert eam[l].sum() == before[l].sum() + k          # each token adds k to row l
+            assert (np.delete(eam, l, 0) == np.delete(before, l, 0)).all()
+            assert (eam[l, idx] == before[l, idx] + 1).all()
+    assert (eam.sum(axis=1) == n_tok * k).all()                  # Sec. 4.3 row-sum property
+    assert eam.sum() == k * L * n_tok
+    assert eam.max() <= n_tok                                    # M[i][j] in {0..n}
+
+
+def test_eam_update_iteration_level_rows_above_current_layer_stay_zero():
+    L, E = 4, 6
+    eam = np.zeros((L, E), dtype=np.int64)
+    for l in range(L):
+        O.eam_update(eam, l, [l % E, (l + 1) % E])
+        assert (eam[l + 1:] == 0).all() and (eam[:l + 1].sum(axis=1) == 2).all()
+    with pytest.raises(ValueError):
+        O.eam_update(eam, L, [0])
+    with pytest.raises(ValueError):
+        O.eam_update(eam, 0, [E])
+
+
+# ==================================================================== O3 EAMC match
+def _brute_cosine(a, b):
+    a = [int(v) for v in np.asarray(a).reshape(-1)]
+    b = [int(v) for v in np.asarray(b).reshape(-1)]
+    d = sum(x * y for x, y in zip(a, b))
+    na = sum(x * x for x in a)
+    nb = sum(y * y for y in b)
+    if na == 0 or nb == 0:
+        return Fraction(0), 0.0
+    return Fraction(d * d, na * nb), d / math.sqrt(na * nb)
+
+
+def test_match_brute_force_tiny_exact():
+    rng = np.random.default_rng(6)
+    for trial in range(200):
+        N, L, E = rng.integers(1, 9), rng.integers(1, 4), rng.integers(1, 4)
+        T = rng.integers(0, 4, size=(N, L, E))
+        q = rng.integers(0, 4, size=(L, E))
+        best, sim, sims = O.eamc_match(T, q)
+        keys = [_brute_cosine(q, T[t]) for t in range(N)]
+        want = max(range(N), key=lambda t: (keys[t][0], -t))   # ties -> lowest index
+        assert best == want
+        for t in range(N):
+            assert abs(sims[t] - keys[t][1]) <= 1e-15
+        assert sim == sims[best]
+
+
+def test_match_known_values():
+    T = np.array([[[1, 1]], [[0, 5]], [[2, 0]], [[0, 0]]])
+    best, sim, sims = O.eamc_match(T, np.array([[3, 0]]))
+    np.testing.assert_allclose(sims, [1 / math.sqrt(2), 0.0, 1.0, 0.0], rtol=1e-15)
+    assert best == 2 and sim == 1.0
+
+
+def test_match_self_similarity_scale_invariance_and_ties():
+    rng = np.random.default_rng(7)
+    T = rng.integers(0, 50, size=(12, 3, 5))
+    q = T[7].copy()
+    best, sim, _ = O.eamc_match(T, q)
+    assert best == 7 and abs(sim - 1.0) < 1e-15
+    T2 = T.copy()
+    T2[3] = 4 * T[7]                        # a scaled copy ties exactly; lowest index wins
+    best, sim, sims = O.eamc_match(T2, q)
+    assert best == 3 and abs(sims[3] - sims[7]) < 1e-15
+    T3 = T.copy()
+    T3[5] *= 9                              # scaling any trace leaves every similarity unchanged
+    _, _, s_a = O.eamc_match(T, T[1] + 1)
+    _, _, s_b = O.eamc_match(T3, T[1] + 1)
+    np.testing.assert_allclose(s_a, s_b, rtol=1e-15)
+    # scaling the query changes nothing either
+    assert O.eamc_match(T, 3 * q)[0] == 7
+
+
+def test_match_degenerate_inputs():
+    assert O.eamc_match(np.zeros((0, 2, 3), dtype=np.int32), np.ones((2, 3)))[:2] == (-1, 0.0)
+    T = np.ones((3, 2, 2), dtype=np.int32)
+    best, sim, sims = O.eamc_match(T, np.zeros((2, 2), dtype=np.int32))    # empty query
+    assert best == 0 and sim == 0.0 and (sims == 0).all() and not np.isnan(sims).any()
+    T[0] = 0                                                               # empty trace
+    best, sim, sims = O.eamc_match(T, np.ones((2, 2), dtype=np.int32))
+    assert best == 1 and sims[0] == 0.0
+
+
+def test_match_equals_dense_matvec_of_normalised_rows():
+    # App. B.1 describes the search as a matrix multiplication: check against torch in fp64
+    rng = np.random.default_rng(8)
+    T = rng.integers(0, 300, size=(50, 6, 16))
+    q = rng.integers(0, 40, size=(6, 16))
+    _, _, sims = O.eamc_match(T, q)
+    Tn = torch.nn.functional.normalize(torch.from_numpy(T.reshape(50, -1)).double(), dim=1)
+    qn = torch.nn.functional.normalize(torch.from_numpy(q.reshape(-1)).double(), dim=0)
+    np.testing.assert_allclose(sims, (Tn @ qn).numpy(), rtol=1e-13)
+
+
+def test_match_exact_rank_agrees_with_fp64_and_finds_planted_group():
+    from moei_inputs import get_config, eamc_traces, make_request
+    cfg = get_config("C2").scaled(N=200)
+    T, cl, _ = eamc_traces(cfg, threads=4)
+    req = make_request(cfg, rid=3, decode=1)
+    best, sim, sims = O.eamc_match(T, req.prefill_eam)
+    top = sims.max()
+    assert sims[best] == top and best == int(np.nonzero(sims == top)[0][0])
+    assert cl[best] == req.source          # soft structure check: same activation group
+    assert sim > 0.9
+
+
+# ==================================================================== O4 priorities
+def test_priority_worked_example_from_the_paper():
+    g = json.load(open(os.path.join(GOLD, "alg1_worked_example.json")))
+    eam = np.array(g["eam"])
+    L, E = g["L"], g["E"]
+    eps = 2.0 ** g["eps_log2"]
+    res = np.ones((L, E), dtype=bool)
+    P, V, pf, ev = O.expert_priority(eam, 0, res, eps)
+    assert ev == g["evict_order_all_resident"]
+    for key, (an, ad, bn, bd) in ((k, v) for k, v in g["evict_scores_fraction_of_eps"].items() if k != "comment"):
+        i, j = map(int, key.split(","))
+        want = Fraction(an, ad) + Fraction(bn, bd) * Fraction(1, 2 ** 20)
+        assert abs(V[i, j] - float(want)) <= 1e-16 + 2e-16 * float(want)
+    # the narrative: E[2,2] is kept, E[2,1]/E[3,1] go first
+    keep = g["paper_retained_0based"][0] * E + g["paper_retained_0based"][1]
+    cands = sorted(i * E + j for i, j in g["paper_evict_candidates_0based"])
+    assert sorted(ev[:2]) == cands and ev.index(keep) >= 4
+    # prefetch at l = 0 with nothing resident
+    P, V, pf, ev = O.expert_priority(eam, 0, np.zeros((L, E), dtype=bool), eps)
+    want = [[0.0, 0.0], [0.0, 2 / 3], [0.0, 1 / 3]]
+    np.testing.assert_allclose(P, want, rtol=1e-15)
+    assert pf == g["prefetch_order_l0_none_resident"] and ev == []
+
+
+def _exact_orders(T, l, res, eps_frac, excl):
+    L, E = T.shape
+    Pk, Vk = {}, {}
+    for i in range(L):
+        R = int(T[i].sum())
+        for j in range(E):
+            f = i * E + j
+            Vk[f] = (int(T[i, j]) + eps_frac) * Fraction(L - i, L) / (R if R else 1)
+            Pk[f] = Fraction(int(T[i, j]), R) * (1 - Fraction(i - l, L)) if (i > l and R) else Fraction(0)
+    pf = sorted((f for f in Pk if f // E > l and Pk[f] > 0 and not res.reshape(-1)[f]), key=lambda f: (-Pk[f], f))
+    ev = sorted((f for f in Vk if res.reshape(-1)[f] and f not in excl), key=lambda f: (Vk[f], f))
+    return Pk, Vk, pf, ev
+
+
+def test_priority_orders_equal_exact_rational_orders():
+    rng = np.random.default_rng(9)
+    eps = 2.0 ** -20
+    for trial in range(150):
+        L, E = int(rng.integers(1, 7)), int(rng.integers(1, 7))
+        T = rng.integers(0, 5, size=(L, E)) * rng.integers(0, 2, size=(L, 1))   # some empty rows
+        l = int(rng.integers(-1, L))
+        res = rng.integers(0, 2, size=(L, E)).astype(bool)
+        excl = set(int(v) for v in rng.choice(L * E, size=min(2, L * E), replace=False))
+        P, V, pf, ev = O.expert_priority(T, l, res, eps, excl)
+        Pk, Vk, pf_x, ev_x = _exact_orders(T, l, res, Fraction(1, 2 ** 20), excl)
+        assert pf == pf_x and ev == ev_x
+        for f in range(L * E):
+            assert abs(P[f // E, f % E] - float(Pk[f])) <= 2e-16 * float(Pk[f])
+            assert abs(V[f // E, f % E] - float(Vk[f])) <= 2e-16 * float(Vk[f])
+
+
+def test_priority_monotone_in_layer_distance_and_scale_free():
+    L, E = 8, 4
+    T = np.tile(np.array([5, 3, 0, 2]), (L, 1))          # identical rows: only the layer term varies
+    eps = 2.0 ** -20
+    P, V, pf, ev = O.expert_priority(T, 2, np.zeros((L, E), bool), eps)
+    assert (P[:3] == 0).all()                             # nothing to prefetch at or below l
+    for j in (0, 1, 3):
+        assert (np.diff(P[3:, j]) < 0).all()              # strictly decreasing in i - l
+        assert (np.diff(V[:, j]) < 0).all()               # layer decay starts at the first layer
+    assert (P[:, 2] == 0).all() and all(f % E != 2 for f in pf)   # zero = predicted inactive
+    np.testing.assert_allclose(P[3, 0], (5 / 10) * (1 - 1 / 8), rtol=1e-15)
+    np.testing.assert_allclose(V[7, 1], (3 + eps) * (1 - 7 / 8) / 10, rtol=1e-15)
+    P2, V2, pf2, _ = O.expert_priority(7 * T, 2, np.zeros((L, E), bool), eps)
+    np.testing.assert_array_equal(P2, P)                  # row normalisation removes the scale
+    assert pf2 == pf
+    np.testing.assert_allclose(V2, V, rtol=0, atol=eps)   # up to the eps term
+    # residents are not prefetch candidates, non-residents are not eviction candidates
+    res = np.zeros((L, E), bool); res[4, 0] = True
+    _, _, pf3, ev3 = O.expert_priority(T, 2, res, eps)
+    assert 4 * E not in pf3 and ev3 == [4 * E]
+    assert O.expert_priority(T, 2, res, eps, exclude=[4 * E])[3] == []
+
+
+def test_aggregate_matches_sums_cells():
+    T = np.arange(24).reshape(4, 2, 3)
+    assert (O.aggregate_matches(T, [1]) == T[1]).all()
+    assert (O.aggregate_matches(T, [1, 3, -1, 1]) == 2 * T[1] + T[3]).all()
+    assert (O.aggregate_matches(T, [-1]) == 0).all()
+
+
+# ========================================================================== O5 FFN
+def test_ffn_closed_form_scalar():
+    # H = I = 1: g = 1, silu(1) = 1/(1+e^-1), u = 6, o = 4 * silu(1) * 6
+    y = O.swiglu_expert(np.array([2.0]), np.array([[0.5]]), np.array([[3.0]]), np.array([[4.0]]))
+    np.testing.assert_allclose(y, [24.0 / (1.0 + math.exp(-1.0))], rtol=1e-15)
+
+
+def test_ffn_matches_torch_fp64_library_ops():
+    rng = np.random.default_rng(10)
+    H, I = 24, 40                               # H != I: a transposed operand cannot pass
+    x = rng.standard_normal(H)
+    ex = [(rng.standard_normal((I, H)), rng.standard_normal((I, H)), rng.standard_normal((H, I))) for _ in range(3)]
+    gates = [0.5, 0.25, 1.0]
+    y = O.expert_ffn(x, ex, gates)
+    xt = torch.from_numpy(x)
+    ref = sum(w * (torch.from_numpy(Wd) @ (torch.nn.functional.silu(torch.from_numpy(Wg) @ xt) * (torch.from_numpy(Wu) @ xt)))
+              for (Wg, Wu, Wd), w in zip(ex, gates))
+    np.testing.assert_allclose(y, ref.numpy(), rtol=1e-12, atol=1e-12)
+    # gate and up are not interchangeable: swapping them changes the result
+    y_sw = O.expert_ffn(x, [(Wu, Wg, Wd) for Wg, Wu, Wd in ex], gates)
+    assert np.abs(y - y_sw).max() > 1e-3
+
+
+def test_ffn_special_cases():
+    rng = np.random.default_rng(11)
+    H, I = 8, 12
+    x = rng.standard_normal(H)
+    Wg, Wu, Wd = rng.standard_normal((I, H)), rng.standard_normal((I, H)), rng.standard_normal((H, I))
+    assert (O.expert_ffn(x, [(np.zeros((I, H)), Wu, Wd)], [1.0]) == 0).all()     # silu(0) = 0
+    y1 = O.expert_ffn(x, [(Wg, Wu, Wd)], [1.0])
+    np.testing.assert_allclose(O.expert_ffn(x, [(Wg, Wu, Wd)], [0.3]), 0.3 * y1, rtol=1e-14)  # linear in w_e
+    np.testing.assert_allclose(O.expert_ffn(x, [(Wg, Wu, Wd)] * 2, [0.3, 0.7]), y1, rtol=1e-14)
+    assert (O.expert_ffn(x, [], []) == 0).all()
+    # stored bf16 inputs: decoded exactly, then plain fp64
+    from moei_inputs import f32_to_bf16_bits, bf16_bits_to_f32
+    xb = f32_to_bf16_bits(x.astype(np.float32))
+    Wb = [f32_to_bf16_bits(w.astype(np.float32)) for w in (Wg, Wu, Wd)]
+    yb = O.expert_ffn(xb, [tuple(Wb)], [1.0])
+    yf = O.expert_ffn(bf16_bits_to_f32(xb).astype(np.float64), [tuple(bf16_bits_to_f32(w).astype(np.float64) for w in Wb)], [1.0])
+    np.testing.assert_array_equal(yb, yf)
+
+
+# ============================================================== O6 cache retrieval
+def _simulate_dict(L, E, S, steps):
+    """Independent dictionary-based replay of Alg. 1 (cache: id -> slot)."""
+    cache = {f: f for f in range(min(S, L * E))}
+    log = []
+    for layer, picks, ev in steps:
+        need = {layer * E + p for p in picks}
+        evq = list(ev)
+        for p in picks:
+            fid = layer * E + p
+            if fid in cache:                                   # Alg. 1 steps 1-3
+                log.append((fid, True, -1, cache[fid])); continue
+            used = set(cache.values())
+            if len(cache) < S:                                 # steps 4-7
+                slot = min(s for s in range(S) if s not in used); victim = -1
+            else:                                              # steps 8-19
+                victim = next((c for c in evq if c in cache and c not in need), None)
+                if victim is None:
+                    victim = next(o for o in (next(k for k, v in cache.items() if v == s) for s in range(S)) if o not in need)
+                else:
+                    evq = evq[evq.index(victim) + 1:]
+                slot = cache.pop(victim)
+            cache[fid] = slot
+            log.append((fid, False, victim, slot))
+    return log, cache
+
+
+def test_cache_retrieval_against_independent_simulation_and_invariants():
+    rng = np.random.default_rng(12)
+    for S, warm in [(12, True), (5, False), (3, True)]:
+        L, E, k = 4, 8, 2
+        c = O.ExpertCache(L, E, S, warm=warm)
+        steps, got = [], []
+        for it in range(40):
+            for layer in range(L):
+                picks = rng.choice(E, size=k, replace=False).tolist()
+                resident = [f for f in range(L * E) if c.slot_of[f] >= 0 and f not in {layer * E + p for p in picks}]
+                ev = rng.permutation(resident).tolist()
+                if it % 7 == 3:
+                    ev = ev[:1]                                # exhausted order -> fallback rule
+                steps.append((layer, picks, ev))
+                ev_now = c.retrieve(layer, picks, ev)
+                got += ev_now
+                # invariants: capacity, inverse maps, picks resident, victim never a current pick
+                assert (c.slot_of >= 0).sum() <= S
+                for f in range(L * E):
+                    if c.slot_of[f] >= 0:
+                        assert c.owner[c.slot_of[f]] == f
+                for s in range(S):
+                    if c.owner[s] >= 0:
+                        assert c.slot_of[c.owner[s]] == s
+                for p in picks:
+                    assert c.slot_of[layer * E + p] >= 0
+                for fid, hit, victim, slot in ev_now:
+                    assert victim not in {layer * E + p for p in picks}
+        if warm:                                               # the dictionary replay starts full too
+            log, _ = _simulate_dict(L, E, S, steps)
+            assert log == got
+    with pytest.raises(ValueError):
+        O.ExpertCache(2, 4, 1).retrieve(0, [0, 1], [])
+
+
+def test_cache_cold_start_fills_lowest_free_slots():
+    c = O.ExpertCache(2, 4, 3, warm=False)
+    ev = c.retrieve(0, [2, 0], [])
+    assert ev == [(2, False, -1, 0), (0, False, -1, 1)]
+    ev = c.retrieve(1, [1, 3], [2, 0])
+    assert ev == [(5, False, -1, 2), (7, False, 2, 0)]       # one free slot, then evict the order's head
+    ev = c.retrieve(1, [1, 2], [0, 7])
+    assert ev == [(5, True, -1, 2), (6, False, 0, 1)]
+
+
+# ============================================================ composite (via parts)
+def test_decode_layer_composes_its_parts():
+    from moei_inputs import get_config, eamc_traces, make_request, router_weights, expert_weights
+    cfg = get_config("C1")
+    T, _, _ = eamc_traces(cfg, threads=1)
+    req = make_request(cfg, 0)
+    eam = req.prefill_eam.astype(np.int64).copy()
+    cache = O.ExpertCache(cfg.L, cfg.E, cfg.S)
+    H, I = cfg.H, cfg.I
+
+    def expert_of(fid):
+        w = expert_weights(cfg, fid)
+        return w[:I * H].reshape(I, H), w[I * H:2 * I * H].reshape(I, H), w[2 * I * H:].reshape(H, I)
+
+    row0 = eam[0].sum()
+    out = O.decode_layer(T, eam, cache, 0, router_weights(cfg, 0), req.bias[0], req.x[0, 0], expert_of,
+                         lambda l: [], cfg.k, bool(cfg.renorm), 2.0 ** -20)
+    assert eam[0].sum() == row0 + cfg.k
+    idx, w = O.route_topk(out["logits"], cfg.k, True)
+    assert (idx[0] == out["idx"]).all()
+    y = O.expert_ffn(req.x[0, 0], [expert_of(int(j)) for j in idx[0]], w[0])
+    np.testing.assert_array_equal(y, out["y"])
+    assert out["best"] == O.eamc_match(T, eam)[0]
