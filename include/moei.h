@@ -1,0 +1,201 @@
+/*
+ * moei.h -- C ABI of the MI355X (gfx950) decode hot path of a sparsity-aware
+ * MoE expert cache (arXiv 2401.14361, "MoE-Infinity").
+ *
+ * One batch-1 decode iteration runs, per MoE layer: router top-k, EAM update,
+ * EAMC cosine match, prefetch/eviction priorities, Alg. 1 cache retrieval and
+ * the activated experts' FFN over weights held in HBM cache slots.
+ *
+ * Conventions
+ *   - Every function returns 0 (MOEI_OK) or a negative MOEI_E* code and never
+ *     aborts; moei_last_error() returns a message for the calling thread's last
+ *     failure.
+ *   - Pointer names: d_* = device memory, h_* = host memory.  The caller owns
+ *     every buffer it passes in; the library owns what *_create allocates and
+ *     frees it in *_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls are asynchronous on it unless they fill h_* outputs, in which case
+ *     they synchronise as documented per function.
+ *   - Matrices are row-major and dense.  Layer indices are 0-based.
+ *   - Notation (Sec. 4.3 of the paper): L MoE layers, E routed experts per
+ *     layer, k experts per token, EAM = L x E matrix of token counts; H hidden
+ *     width, I expert intermediate width, N traces in the EAMC, S cache slots.
+ */
+#ifndef MOEI_H
+#define MOEI_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOEI_OK          0
+#define MOEI_EINVAL    (-1)   /* bad argument: null pointer, shape or range */
+#define MOEI_ENOMEM    (-2)   /* host or device allocation failed */
+#define MOEI_EHIP      (-3)   /* a HIP runtime call failed */
+#define MOEI_ESTATE    (-4)   /* object not in a state that allows the call */
+#define MOEI_ECAPACITY (-5)   /* a fixed capacity would be exceeded */
+
+#define MOEI_WDTYPE_FP32 0
+#define MOEI_WDTYPE_BF16 1
+
+/* Largest count an EAM cell may hold anywhere in this library (2^24 - 1). */
+#define MOEI_MAX_COUNT 16777215
+
+typedef struct moei_model_desc {
+    int32_t L, E, k, n_shared;  /* MoE layers, routed experts/layer, top-k, always-on shared experts/layer */
+    int32_t H, I;               /* hidden width, expert intermediate width */
+    int32_t wdtype;             /* MOEI_WDTYPE_*: storage type of expert/router weights and of x */
+    int32_t renorm_topk;        /* 1: gate weights are renormalised over the k picks */
+    float   eps;                /* epsilon of Alg. 1's priority score */
+} moei_model_desc;
+
+typedef struct moei_eamc  moei_eamc;   /* the EAM collection on the device */
+typedef struct moei_cache moei_cache;  /* HBM slot pool + slot table + per-layer scratch */
+
+const char* moei_last_error(void);
+const char* moei_version(void);
+
+/* ------------------------------------------------------------------ EAMC (Sec. 4.5)
+ * Expert Activation Matrix Collection: up to n_cap request-level EAMs kept on the
+ * device, stored layer-major [L][n_cap][E] in cells of `cell_bytes` (4 = int32,
+ * 2 = uint16) together with each trace's squared norm.
+ */
+int moei_eamc_create(const moei_model_desc* desc, int32_t n_cap, int32_t cell_bytes, moei_eamc** out);
+/* Replaces the contents with N traces given trace-major, h_traces[N][L][E] (host).
+ * Cells must lie in [0, MOEI_MAX_COUNT] (and <= 65535 for 2-byte cells), else
+ * MOEI_EINVAL and the collection is left empty.  N = 0 empties it.  Synchronous. */
+int moei_eamc_load(moei_eamc* c, const int32_t* h_traces, int32_t N);
+/* Sec. B.1 replacement rule: stores one finished request-level EAM (host, [L][E]).
+ * While N < n_cap it is appended; at capacity it overwrites trace `victim`, which
+ * the caller obtains from eamc_match on that EAM (the most similar stored trace).
+ * victim is ignored while not full.  Synchronous. */
+int moei_eamc_insert(moei_eamc* c, const int32_t* h_eam, int32_t victim);
+/* Failure recovery (Sec. B.2): trace-major dump of the collection to host memory,
+ * h_traces[N][L][E]; pass the result to moei_eamc_load to restore.  Synchronous. */
+int moei_eamc_export(const moei_eamc* c, int32_t* h_traces, int32_t max_traces);
+int moei_eamc_size(const moei_eamc* c);            /* N, or MOEI_EINVAL */
+int moei_eamc_destroy(moei_eamc* c);
+
+/* -------------------------------------------------------- hot-path steps, one by one */
+
+/* Step 1, router decision (Sec. 2): per token softmax over the E logits, the k most
+ * probable experts in descending order (ties to the lower index), and their gate
+ * weights (softmax probabilities; divided by their sum if renorm != 0).
+ * d_logits[B][E] fp32 -> d_idx[B][k] int32, d_w[B][k] fp32.  Needs 1 <= k <= E <= 4096.
+ * Logits must not be NaN. */
+int moe_route_topk(const float* d_logits, int32_t B, int32_t E, int32_t k, int32_t renorm,
+                   int32_t* d_idx, float* d_w, void* stream);
+
+/* Step 2, EAM update (Sec. 4.3): d_eam[b][layer][d_idx[b][j]] += 1 for every pick.
+ * d_eam[B][L][E] int32 in place; picks of one token must be distinct; indices outside
+ * [0,E) are ignored. */
+int eam_update(int32_t* d_eam, int32_t B, int32_t L, int32_t E, int32_t layer,
+               const int32_t* d_idx, int32_t k, void* stream);
+
+/* Step 3, EAMC match (Sec. 4.5): cosine similarity between each of the B flattened
+ * EAMs d_eam[B][L][E] (int32, cells in [0, MOEI_MAX_COUNT]) and every stored trace;
+ * d_best[b] = index of the most similar trace (smallest cosine distance; equal
+ * similarities go to the lowest index; decided in exact integer arithmetic),
+ * d_best_sim[b] = its similarity (fp32), d_sims[B][N] = all similarities (may be NULL).
+ * A zero vector has similarity 0 to everything.  Empty collection: best = -1, sim = 0.
+ * layer_hi: the caller promises rows > layer_hi of every query are zero, so only
+ * layers 0..layer_hi are scanned (L-1 scans everything); norms are always those of
+ * the full matrices.  B <= 16. */
+int eamc_match(const moei_eamc* c, const int32_t* d_eam, int32_t B, int32_t layer_hi,
+               int32_t* d_best, float* d_best_sim, float* d_sims, void* stream);
+
+/* Step 4, PredictEAM + priorities (Sec. 4.5 steps 2-3; Alg. 1 priority score).
+ * T = sum over b of trace d_best[b] (entries < 0 skipped), R_i = row sums of T.
+ *   prefetch  P[i][j] = T[i][j] (L - i + l) / (R_i L)   for l < i < L, else 0 (0 if R_i = 0)
+ *   eviction  V[i][j] = (T[i][j] + eps)(L - i) / (R_i L)  (R_i := 1 for an empty row)
+ * with l = cur_layer in [-1, L-1]; each is one fp64 division of exact products,
+ * written out in fp32 to d_prefetch[L][E] / d_evict[L][E].
+ * d_pf_order: flat ids i*E+j with i > l, P > 0 and d_slot_of[i*E+j] < 0, by P
+ *   descending; d_ev_order: flat ids with d_slot_of >= 0, except the picks
+ *   d_cur_idx[B][k] of layer l (may be NULL), by V ascending; ties to the lowest
+ *   flat id in both.  Counts go to d_n_pf / d_n_ev; each order buffer holds L*E ints. */
+int expert_priority(const moei_eamc* c, const int32_t* d_best, int32_t B, int32_t cur_layer,
+                    const int32_t* d_slot_of, float eps, const int32_t* d_cur_idx, int32_t k,
+                    float* d_prefetch, float* d_evict,
+                    int32_t* d_pf_order, int32_t* d_n_pf, int32_t* d_ev_order, int32_t* d_n_ev,
+                    void* stream);
+
+/* --------------------------------------------------------- expert cache (Sec. 4.7, Alg. 1)
+ * A pool of n_slots cache slots in HBM for routed experts plus L*n_shared pinned
+ * slots for the always-on shared experts.  One slot holds one expert, contiguous:
+ * W_gate[I][H], W_up[I][H], W_down[H][I] in desc->wdtype.
+ * Slot ids: 0..n_slots-1 routed, n_slots + layer*n_shared + s shared.
+ * h_experts: host copy of the routed experts (pinned memory for asynchronous fills),
+ *   n_host_experts rows of 3*H*I elements; expert (l, j) is row (l*E + j) %
+ *   n_host_experts.  NULL = no host copy: slots are filled by the caller
+ *   (moei_cache_slot_ptr) and a miss is an error.
+ * h_shared: [L*n_shared][3*H*I] or NULL (then shared slots are left for the caller).
+ * Needs n_slots >= k, else MOEI_ECAPACITY. */
+int moei_cache_create(const moei_model_desc* desc, int32_t n_slots,
+                      const void* h_experts, int32_t n_host_experts, const void* h_shared,
+                      moei_cache** out);
+int moei_cache_destroy(moei_cache* c);
+/* Initial residency: n_resident (<= n_slots, <= L*E) experts with flat ids
+ * 0..n_resident-1 in slots of the same number, the rest free.  Copies them from
+ * h_experts when there is one.  Synchronous. */
+int moei_cache_reset(moei_cache* c, int32_t n_resident);
+/* Device address of a slot's weights (any slot id, shared included). */
+int moei_cache_slot_ptr(moei_cache* c, int32_t slot, void** d_ptr);
+/* Device slot table d_slot_of[L*E] (-1 = not resident), for expert_priority. */
+int moei_cache_slot_table(moei_cache* c, const int32_t** d_slot_of);
+/* Host copy of the slot table, h_slot_of[L*E]. */
+int moei_cache_get_slots(const moei_cache* c, int32_t* h_slot_of);
+/* Alg. 1 for one layer's picks, in order: a hit keeps its slot; otherwise the
+ * expert goes to the lowest free slot or, when full, to the slot of the first entry
+ * of h_ev_order that is resident and not one of these picks (if the order runs out:
+ * the lowest slot whose owner is not one of these picks).  Misses are copied from
+ * h_experts on the cache's copy stream; `stream` then waits for them.  Per pick:
+ * h_slots[n] = slot, h_victims[n] = evicted flat id or -1; *h_n_miss = misses.
+ * The device slot table is updated on `stream`. */
+int moei_cache_retrieve(moei_cache* c, int32_t layer, const int32_t* h_idx, int32_t n,
+                        const int32_t* h_ev_order, int32_t n_ev,
+                        int32_t* h_slots, int32_t* h_victims, int32_t* h_n_miss, void* stream);
+
+/* Step 5, expert FFN (Sec. 2; SwiGLU):
+ *   y = sum_e w_e * W_down,e ( silu(W_gate,e x) * (W_up,e x) ),  silu(g) = g / (1 + exp(-g))
+ * over the n_act slots d_slot_ids[n_act] with weights d_gate_w[n_act]; weights are
+ * streamed from the slot pool, sums are fp32.  d_x[H] in desc->wdtype, d_y[H] fp32.
+ * A slot id outside the pool contributes nothing and raises the cache's error flag.
+ * n_act <= k + n_shared. */
+int expert_ffn_gemv(moei_cache* c, const int32_t* d_slot_ids, const float* d_gate_w,
+                    int32_t n_act, const void* d_x, float* d_y, void* stream);
+/* Device-side error flags raised by kernels since the last call (bit 0: bad slot id,
+ * bit 1: a routed expert was not resident in a step without host retrieval).
+ * Synchronises `stream`. */
+int moei_cache_error_flags(moei_cache* c, int32_t* h_flags, void* stream);
+
+/* ------------------------------------------------------------------ the fused layer step
+ * One MoE layer of one decode iteration for one request:
+ *   logits = W_r x + b -> top-k -> EAM row update -> (EAMC match -> priorities) on a
+ *   side stream, while Alg. 1 retrieval and the expert FFNs run on `stream`.
+ * d_router_w[E][H] in wdtype, d_router_bias[E] fp32 or NULL, d_eam[L][E] int32.
+ * The eviction order used for this layer's misses is the one computed from the EAM
+ * that already contains this layer's routing.
+ * If all three h_* outputs are NULL the call is fully asynchronous: slots are looked
+ * up on the device and a non-resident pick raises error flag bit 1.  Otherwise the
+ * call waits for the routing decision, serves misses from the host copy, and fills
+ * h_topk_idx[k], *h_best (matched trace, waits for the side stream) and *h_n_miss
+ * (each may be NULL). */
+int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d_eam, int32_t layer,
+                     const void* d_router_w, const float* d_router_bias,
+                     const void* d_x, float* d_y,
+                     int32_t* h_topk_idx, int32_t* h_best, int32_t* h_n_miss, void* stream);
+/* Results of the most recent moe_decode_layer on this cache, copied to the host
+ * (any pointer may be NULL): gate weights [k], best similarity, score matrices [L*E],
+ * orders [L*E] and their lengths.  Synchronises both streams. */
+int moei_cache_last_step(moei_cache* c, float* h_gate_w, float* h_best_sim,
+                         float* h_prefetch, float* h_evict,
+                         int32_t* h_pf_order, int32_t* h_n_pf, int32_t* h_ev_order, int32_t* h_n_ev,
+                         void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOEI_H */

@@ -1,0 +1,474 @@
+// The expert cache (Sec. 4.7, Alg. 1 of the paper) as a pool of HBM slots with a
+// host-side slot table, miss fills from pinned host memory on a copy stream, and the
+// fused per-layer decode step that strings the five steps together.
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "kernels.hpp"
+
+namespace moei {
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+constexpr int kMaxAct = 64;  // k + n_shared never exceeds one wavefront
+
+struct SlotUpdates {
+    int n;
+    int32_t fid[2 * kMaxAct];
+    int32_t slot[2 * kMaxAct];
+};
+
+__global__ void apply_slot_updates_kernel(int32_t* __restrict__ slot_of, SlotUpdates u) {
+    int t = threadIdx.x;
+    if (t < u.n) slot_of[u.fid[t]] = u.slot[t];
+}
+
+// Host mirrors in pinned memory so that the device-to-host copies are asynchronous.
+struct Pinned {
+    int32_t idx[kMaxAct];
+    float w[kMaxAct];
+    int32_t ev_head[kMaxAct];
+    int32_t best;
+    float best_sim;
+    int32_t n_ev;
+    int32_t flags;
+};
+
+}  // namespace
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int check_desc(const moei_model_desc* d) {
+    MOEI_REQUIRE(d->L >= 1 && d->E >= 1 && d->H >= 1 && d->I >= 1, "model: L, E, H, I must be positive");
+    MOEI_REQUIRE(d->k >= 1 && d->k <= d->E, "model: k = %d outside [1, E = %d]", d->k, d->E);
+    MOEI_REQUIRE(d->n_shared >= 0 && d->k + d->n_shared <= kMaxAct, "model: k + n_shared = %d exceeds %d",
+                 d->k + d->n_shared, kMaxAct);
+    MOEI_REQUIRE(d->wdtype == MOEI_WDTYPE_FP32 || d->wdtype == MOEI_WDTYPE_BF16, "model: unknown wdtype %d", d->wdtype);
+    MOEI_REQUIRE(d->H <= 16384, "model: H = %d exceeds 16384", d->H);
+    MOEI_REQUIRE((long long)d->L * d->E <= (1 << 24), "model: L*E too large");
+    MOEI_REQUIRE(d->eps >= 0.f, "model: eps must not be negative");
+    return MOEI_OK;
+}
+
+}  // namespace moei
+
+using namespace moei;
+
+struct moei_cache {
+    moei_model_desc d{};
+    int S = 0, n_total = 0, wb = 2;
+    size_t slot_elems = 0, slot_bytes = 0;
+    unsigned char* d_pool = nullptr;
+    const unsigned char* h_experts = nullptr;
+    int n_host = 0;
+    std::vector<int32_t> slot_of, owner;
+    int32_t* d_slot_of = nullptr;
+    int32_t* d_flags = nullptr;
+    hipStream_t copy_stream = nullptr, side_stream = nullptr;
+    hipEvent_t ev_copy = nullptr, ev_routed = nullptr, ev_side = nullptr, ev_main = nullptr;
+    bool side_pending = false;
+    FfnScratch ffn;
+    float* d_logits = nullptr;
+    int32_t* d_idx = nullptr;
+    float* d_w = nullptr;
+    int32_t* d_slot_ids = nullptr;
+    float* d_gate = nullptr;
+    int32_t* d_best = nullptr;
+    float* d_best_sim = nullptr;
+    float *d_P = nullptr, *d_V = nullptr;
+    int32_t *d_pf_order = nullptr, *d_ev_order = nullptr, *d_n_pf = nullptr, *d_n_ev = nullptr;
+    Pinned* pin = nullptr;
+};
+
+extern "C" const char* moei_last_error(void) { return g_err; }
+extern "C" const char* moei_version(void) { return "moei 0.1 (gfx950)"; }
+
+extern "C" int moei_cache_destroy(moei_cache* c) {
+    if (!c) return MOEI_OK;
+    if (c->copy_stream) (void)hipStreamSynchronize(c->copy_stream);
+    if (c->side_stream) (void)hipStreamSynchronize(c->side_stream);
+    (void)hipFree(c->d_pool);
+    (void)hipFree(c->d_slot_of);
+    (void)hipFree(c->d_flags);
+    ffn_scratch_free(&c->ffn);
+    (void)hipFree(c->d_logits);
+    (void)hipFree(c->d_idx);
+    (void)hipFree(c->d_w);
+    (void)hipFree(c->d_slot_ids);
+    (void)hipFree(c->d_gate);
+    (void)hipFree(c->d_best);
+    (void)hipFree(c->d_best_sim);
+    (void)hipFree(c->d_P);
+    (void)hipFree(c->d_V);
+    (void)hipFree(c->d_pf_order);
+    (void)hipFree(c->d_ev_order);
+    (void)hipFree(c->d_n_pf);
+    (void)hipFree(c->d_n_ev);
+    if (c->pin) (void)hipHostFree(c->pin);
+    if (c->ev_copy) (void)hipEventDestroy(c->ev_copy);
+    if (c->ev_routed) (void)hipEventDestroy(c->ev_routed);
+    if (c->ev_side) (void)hipEventDestroy(c->ev_side);
+    if (c->ev_main) (void)hipEventDestroy(c->ev_main);
+    if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
+    if (c->side_stream) (void)hipStreamDestroy(c->side_stream);
+    delete c;
+    return MOEI_OK;
+}
+
+namespace {
+
+int upload_slot_table(moei_cache* c) {
+    MOEI_HIP(hipMemcpy(c->d_slot_of, c->slot_of.data(), c->slot_of.size() * 4, hipMemcpyHostToDevice));
+    return MOEI_OK;
+}
+
+int cache_alloc(moei_cache* c) {
+    const moei_model_desc& d = c->d;
+    const size_t LE = (size_t)d.L * d.E;
+    const int na = d.k + d.n_shared;
+#define MOEI_DMALLOC(ptr, bytes)                                                                           \
+    do {                                                                                                   \
+        hipError_t e__ = hipMalloc((void**)&(ptr), (bytes));                                               \
+        if (e__ != hipSuccess)                                                                             \
+            MOEI_FAIL(MOEI_ENOMEM, "moei_cache_create: device allocation of %zu bytes failed: %s",        \
+                      (size_t)(bytes), hipGetErrorString(e__));                                            \
+    } while (0)
+    MOEI_DMALLOC(c->d_pool, (size_t)c->n_total * c->slot_bytes);
+    MOEI_DMALLOC(c->d_slot_of, LE * 4);
+    MOEI_DMALLOC(c->d_flags, 4);
+    MOEI_DMALLOC(c->d_logits, (size_t)d.E * 4);
+    MOEI_DMALLOC(c->d_idx, (size_t)kMaxAct * 4);
+    MOEI_DMALLOC(c->d_w, (size_t)kMaxAct * 4);
+    MOEI_DMALLOC(c->d_slot_ids, (size_t)kMaxAct * 4);
+    MOEI_DMALLOC(c->d_gate, (size_t)kMaxAct * 4);
+    MOEI_DMALLOC(c->d_best, 4);
+    MOEI_DMALLOC(c->d_best_sim, 4);
+    MOEI_DMALLOC(c->d_P, LE * 4);
+    MOEI_DMALLOC(c->d_V, LE * 4);
+    MOEI_DMALLOC(c->d_pf_order, LE * 4);
+    MOEI_DMALLOC(c->d_ev_order, LE * 4);
+    MOEI_DMALLOC(c->d_n_pf, 4);
+    MOEI_DMALLOC(c->d_n_ev, 4);
+#undef MOEI_DMALLOC
+    MOEI_HIP(hipMemset(c->d_flags, 0, 4));
+    MOEI_HIP(hipMemset(c->d_n_pf, 0, 4));
+    MOEI_HIP(hipMemset(c->d_n_ev, 0, 4));
+    MOEI_HIP(hipMemset(c->d_best, 0xff, 4));
+    int rc = ffn_scratch_alloc(d, na, &c->ffn);
+    if (rc) return rc;
+    MOEI_HIP(hipHostMalloc((void**)&c->pin, sizeof(Pinned), hipHostMallocDefault));
+    memset(c->pin, 0, sizeof(Pinned));
+    MOEI_HIP(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
+    MOEI_HIP(hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking));
+    MOEI_HIP(hipEventCreateWithFlags(&c->ev_copy, hipEventDisableTiming));
+    MOEI_HIP(hipEventCreateWithFlags(&c->ev_routed, hipEventDisableTiming));
+    MOEI_HIP(hipEventCreateWithFlags(&c->ev_side, hipEventDisableTiming));
+    MOEI_HIP(hipEventCreateWithFlags(&c->ev_main, hipEventDisableTiming));
+    return MOEI_OK;
+}
+
+}  // namespace
+
+extern "C" int moei_cache_create(const moei_model_desc* desc, int32_t n_slots, const void* h_experts,
+                                 int32_t n_host_experts, const void* h_shared, moei_cache** out) {
+    MOEI_REQUIRE(desc && out, "moei_cache_create: null pointer");
+    *out = nullptr;
+    int rc = check_desc(desc);
+    if (rc) return rc;
+    MOEI_REQUIRE(n_slots >= 1, "moei_cache_create: n_slots = %d must be positive", n_slots);
+    if (n_slots < desc->k)
+        MOEI_FAIL(MOEI_ECAPACITY, "moei_cache_create: %d slots cannot hold one layer's %d picks", n_slots, desc->k);
+    MOEI_REQUIRE(!h_experts || n_host_experts >= 1, "moei_cache_create: n_host_experts must be positive");
+    moei_cache* c = new (std::nothrow) moei_cache();
+    if (!c) MOEI_FAIL(MOEI_ENOMEM, "moei_cache_create: out of host memory");
+    c->d = *desc;
+    c->S = n_slots;
+    c->n_total = n_slots + desc->L * desc->n_shared;
+    c->wb = desc->wdtype == MOEI_WDTYPE_BF16 ? 2 : 4;
+    c->slot_elems = (size_t)3 * desc->H * desc->I;
+    c->slot_bytes = c->slot_elems * c->wb;
+    c->h_experts = reinterpret_cast<const unsigned char*>(h_experts);
+    c->n_host = h_experts ? n_host_experts : 0;
+    try {
+        c->slot_of.assign((size_t)desc->L * desc->E, -1);
+        c->owner.assign((size_t)n_slots, -1);
+    } catch (...) {
+        delete c;
+        MOEI_FAIL(MOEI_ENOMEM, "moei_cache_create: out of host memory");
+    }
+    rc = cache_alloc(c);
+    if (rc == MOEI_OK) rc = upload_slot_table(c);
+    if (rc == MOEI_OK && h_shared && desc->n_shared > 0) {
+        hipError_t e = hipMemcpy(c->d_pool + (size_t)n_slots * c->slot_bytes, h_shared,
+                                 (size_t)desc->L * desc->n_shared * c->slot_bytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            set_error("moei_cache_create: copying the shared experts failed: %s", hipGetErrorString(e));
+            rc = MOEI_EHIP;
+        }
+    }
+    if (rc) {
+        char keep[sizeof(g_err)];
+        memcpy(keep, g_err, sizeof(keep));
+        moei_cache_destroy(c);
+        memcpy(g_err, keep, sizeof(keep));
+        return rc;
+    }
+    *out = c;
+    return MOEI_OK;
+}
+
+extern "C" int moei_cache_reset(moei_cache* c, int32_t n_resident) {
+    MOEI_REQUIRE(c, "moei_cache_reset: null pointer");
+    const int LE = c->d.L * c->d.E;
+    MOEI_REQUIRE(n_resident >= 0 && n_resident <= c->S && n_resident <= LE,
+                 "moei_cache_reset: n_resident = %d outside [0, min(S, L*E)]", n_resident);
+    MOEI_HIP(hipDeviceSynchronize());
+    c->side_pending = false;
+    std::fill(c->slot_of.begin(), c->slot_of.end(), -1);
+    std::fill(c->owner.begin(), c->owner.end(), -1);
+    for (int s = 0; s < n_resident; ++s) {
+        c->slot_of[s] = s;
+        c->owner[s] = s;
+        if (c->h_experts)
+            MOEI_HIP(hipMemcpy(c->d_pool + (size_t)s * c->slot_bytes,
+                               c->h_experts + (size_t)(s % c->n_host) * c->slot_bytes, c->slot_bytes,
+                               hipMemcpyHostToDevice));
+    }
+    MOEI_HIP(hipMemset(c->d_flags, 0, 4));
+    return upload_slot_table(c);
+}
+
+extern "C" int moei_cache_slot_ptr(moei_cache* c, int32_t slot, void** d_ptr) {
+    MOEI_REQUIRE(c && d_ptr, "moei_cache_slot_ptr: null pointer");
+    MOEI_REQUIRE(slot >= 0 && slot < c->n_total, "moei_cache_slot_ptr: slot %d outside [0, %d)", slot, c->n_total);
+    *d_ptr = c->d_pool + (size_t)slot * c->slot_bytes;
+    return MOEI_OK;
+}
+
+extern "C" int moei_cache_slot_table(moei_cache* c, const int32_t** d_slot_of) {
+    MOEI_REQUIRE(c && d_slot_of, "moei_cache_slot_table: null pointer");
+    *d_slot_of = c->d_slot_of;
+    return MOEI_OK;
+}
+
+extern "C" int moei_cache_get_slots(const moei_cache* c, int32_t* h_slot_of) {
+    MOEI_REQUIRE(c && h_slot_of, "moei_cache_get_slots: null pointer");
+    memcpy(h_slot_of, c->slot_of.data(), c->slot_of.size() * 4);
+    return MOEI_OK;
+}
+
+extern "C" int moei_cache_retrieve(moei_cache* c, int32_t layer, const int32_t* h_idx, int32_t n,
+                                   const int32_t* h_ev_order, int32_t n_ev, int32_t* h_slots, int32_t* h_victims,
+                                   int32_t* h_n_miss, void* stream) {
+    MOEI_REQUIRE(c && h_idx && h_slots, "moei_cache_retrieve: null pointer");
+    MOEI_REQUIRE(layer >= 0 && layer < c->d.L, "moei_cache_retrieve: layer %d outside [0, %d)", layer, c->d.L);
+    MOEI_REQUIRE(n >= 0 && n <= kMaxAct, "moei_cache_retrieve: n = %d outside [0, %d]", n, kMaxAct);
+    MOEI_REQUIRE(n_ev >= 0 && (n_ev == 0 || h_ev_order), "moei_cache_retrieve: bad eviction order");
+    const int E = c->d.E, LE = c->d.L * c->d.E;
+    hipStream_t s = as_stream(stream);
+    int n_miss = 0;
+    for (int j = 0; j < n; ++j) {
+        MOEI_REQUIRE(h_idx[j] >= 0 && h_idx[j] < E, "moei_cache_retrieve: expert index %d outside [0, %d)", h_idx[j], E);
+        for (int m = 0; m < j; ++m)
+            MOEI_REQUIRE(h_idx[m] != h_idx[j], "moei_cache_retrieve: expert %d picked twice", h_idx[j]);
+        if (c->slot_of[layer * E + h_idx[j]] < 0) ++n_miss;
+    }
+    if (n > c->S) MOEI_FAIL(MOEI_ECAPACITY, "moei_cache_retrieve: %d picks exceed the %d slots", n, c->S);
+    if (n_miss > 0 && !c->h_experts)
+        MOEI_FAIL(MOEI_ESTATE, "moei_cache_retrieve: %d expert(s) not resident and the cache has no host copy", n_miss);
+    auto needed = [&](int fid) {
+        if (fid < layer * E || fid >= (layer + 1) * E) return false;
+        for (int j = 0; j < n; ++j)
+            if (h_idx[j] == fid - layer * E) return true;
+        return false;
+    };
+    SlotUpdates upd{};
+    int pos = 0;
+    bool waited = false;
+    for (int j = 0; j < n; ++j) {
+        const int fid = layer * E + h_idx[j];
+        int slot = c->slot_of[fid];
+        int victim = -1;
+        if (slot < 0) {
+            for (int t = 0; t < c->S; ++t)
+                if (c->owner[t] < 0) {
+                    slot = t;
+                    break;
+                }
+            if (slot < 0) {
+                while (pos < n_ev) {
+                    int cand = h_ev_order[pos++];
+                    if (cand >= 0 && cand < LE && c->slot_of[cand] >= 0 && !needed(cand)) {
+                        victim = cand;
+                        break;
+                    }
+                }
+                if (victim < 0)
+                    for (int t = 0; t < c->S; ++t)
+                        if (!needed(c->owner[t])) {
+                            victim = c->owner[t];
+                            break;
+                        }
+                slot = c->slot_of[victim];
+                c->slot_of[victim] = -1;
+                upd.fid[upd.n] = victim;
+                upd.slot[upd.n++] = -1;
+            }
+            c->slot_of[fid] = slot;
+            c->owner[slot] = fid;
+            upd.fid[upd.n] = fid;
+            upd.slot[upd.n++] = slot;
+            if (!waited) {  // the slot may still be read by work queued on `stream`
+                MOEI_HIP(hipEventRecord(c->ev_main, s));
+                MOEI_HIP(hipStreamWaitEvent(c->copy_stream, c->ev_main, 0));
+                waited = true;
+            }
+            MOEI_HIP(hipMemcpyAsync(c->d_pool + (size_t)slot * c->slot_bytes,
+                                    c->h_experts + (size_t)(fid % c->n_host) * c->slot_bytes, c->slot_bytes,
+                                    hipMemcpyHostToDevice, c->copy_stream));
+        }
+        h_slots[j] = slot;
+        if (h_victims) h_victims[j] = victim;
+    }
+    if (n_miss > 0) {
+        MOEI_HIP(hipEventRecord(c->ev_copy, c->copy_stream));
+        MOEI_HIP(hipStreamWaitEvent(s, c->ev_copy, 0));
+        apply_slot_updates_kernel<<<1, 2 * kMaxAct, 0, s>>>(c->d_slot_of, upd);
+        MOEI_LAUNCH_CHECK();
+    }
+    if (h_n_miss) *h_n_miss = n_miss;
+    return MOEI_OK;
+}
+
+extern "C" int expert_ffn_gemv(moei_cache* c, const int32_t* d_slot_ids, const float* d_gate_w, int32_t n_act,
+                               const void* d_x, float* d_y, void* stream) {
+    MOEI_REQUIRE(c && d_x && d_y, "expert_ffn_gemv: null pointer");
+    MOEI_REQUIRE(n_act >= 0 && n_act <= c->ffn.n_act_max, "expert_ffn_gemv: n_act = %d outside [0, k + n_shared = %d]",
+                 n_act, c->ffn.n_act_max);
+    MOEI_REQUIRE(n_act == 0 || (d_slot_ids && d_gate_w), "expert_ffn_gemv: null slot ids or gate weights");
+    return launch_expert_ffn(c->d, c->d_pool, c->slot_elems, c->n_total, c->ffn, d_slot_ids, d_gate_w, n_act, d_x, d_y,
+                             c->d_flags, as_stream(stream));
+}
+
+extern "C" int moei_cache_error_flags(moei_cache* c, int32_t* h_flags, void* stream) {
+    MOEI_REQUIRE(c && h_flags, "moei_cache_error_flags: null pointer");
+    hipStream_t s = as_stream(stream);
+    MOEI_HIP(hipMemcpyAsync(&c->pin->flags, c->d_flags, 4, hipMemcpyDeviceToHost, s));
+    MOEI_HIP(hipStreamSynchronize(s));
+    *h_flags = c->pin->flags;
+    if (c->pin->flags) {
+        MOEI_HIP(hipMemsetAsync(c->d_flags, 0, 4, s));
+        MOEI_HIP(hipStreamSynchronize(s));
+    }
+    return MOEI_OK;
+}
+
+extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d_eam, int32_t layer,
+                                const void* d_router_w, const float* d_router_bias, const void* d_x, float* d_y,
+                                int32_t* h_topk_idx, int32_t* h_best, int32_t* h_n_miss, void* stream) {
+    MOEI_REQUIRE(c && eamc && d_eam && d_router_w && d_x && d_y, "moe_decode_layer: null pointer");
+    const moei_model_desc& d = c->d;
+    MOEI_REQUIRE(eamc->d.L == d.L && eamc->d.E == d.E, "moe_decode_layer: EAMC is %dx%d, cache is %dx%d", eamc->d.L,
+                 eamc->d.E, d.L, d.E);
+    MOEI_REQUIRE(layer >= 0 && layer < d.L, "moe_decode_layer: layer %d outside [0, %d)", layer, d.L);
+    hipStream_t s = as_stream(stream);
+    const bool sync_mode = h_topk_idx || h_best || h_n_miss;
+    const int k = d.k, E = d.E;
+    int rc;
+
+    // the previous step's match/priority work still reads d_eam and the pick buffer
+    if (c->side_pending) MOEI_HIP(hipStreamWaitEvent(s, c->ev_side, 0));
+
+    rc = launch_router_gemv(d_router_w, d_router_bias, d_x, E, d.H, d.wdtype, c->d_logits, s);
+    if (rc) return rc;
+    RouteFusedArgs ra{};
+    ra.logits = c->d_logits;
+    ra.E = E;
+    ra.k = k;
+    ra.renorm = d.renorm_topk != 0;
+    ra.idx = c->d_idx;
+    ra.w = c->d_w;
+    ra.eam_row = d_eam + (size_t)layer * E;
+    ra.slot_of_row = c->d_slot_of + (size_t)layer * E;
+    ra.n_shared = d.n_shared;
+    ra.shared_base = c->S + layer * d.n_shared;
+    ra.slot_ids = c->d_slot_ids;
+    ra.gate = c->d_gate;
+    ra.flags = sync_mode ? nullptr : c->d_flags;
+    rc = launch_route_fused(ra, s);
+    if (rc) return rc;
+    if (sync_mode) MOEI_HIP(hipMemcpyAsync(c->pin->idx, c->d_idx, (size_t)k * 4, hipMemcpyDeviceToHost, s));
+    MOEI_HIP(hipEventRecord(c->ev_routed, s));
+
+    // side stream: EAMC match and priorities from the EAM that now holds this layer's routing
+    hipStream_t side = c->side_stream;
+    MOEI_HIP(hipStreamWaitEvent(side, c->ev_routed, 0));
+    rc = eamc_match(eamc, d_eam, 1, d.L - 1, c->d_best, c->d_best_sim, nullptr, side);
+    if (rc) return rc;
+    rc = expert_priority(eamc, c->d_best, 1, layer, c->d_slot_of, d.eps, c->d_idx, k, c->d_P, c->d_V, c->d_pf_order,
+                         c->d_n_pf, c->d_ev_order, c->d_n_ev, side);
+    if (rc) return rc;
+    if (sync_mode) {
+        MOEI_HIP(hipMemcpyAsync(&c->pin->best, c->d_best, 4, hipMemcpyDeviceToHost, side));
+        MOEI_HIP(hipMemcpyAsync(&c->pin->n_ev, c->d_n_ev, 4, hipMemcpyDeviceToHost, side));
+        MOEI_HIP(hipMemcpyAsync(c->pin->ev_head, c->d_ev_order, (size_t)k * 4, hipMemcpyDeviceToHost, side));
+    }
+    MOEI_HIP(hipEventRecord(c->ev_side, side));
+    c->side_pending = true;
+
+    if (sync_mode) {
+        MOEI_HIP(hipEventSynchronize(c->ev_routed));
+        int n_miss = 0;
+        for (int j = 0; j < k; ++j) {
+            int e = c->pin->idx[j];
+            if (e < 0 || e >= E) MOEI_FAIL(MOEI_ESTATE, "moe_decode_layer: router produced expert %d", e);
+            if (c->slot_of[layer * E + e] < 0) ++n_miss;
+        }
+        bool side_done = false;
+        if (n_miss > 0) {
+            MOEI_HIP(hipEventSynchronize(c->ev_side));
+            side_done = true;
+            int n_ev = c->pin->n_ev < k ? c->pin->n_ev : k;
+            int32_t slots[kMaxAct];
+            rc = moei_cache_retrieve(c, layer, c->pin->idx, k, c->pin->ev_head, n_ev, slots, nullptr, nullptr, s);
+            if (rc) return rc;
+            rc = launch_gather_slots(c->d_idx, k, c->d_slot_of + (size_t)layer * E, c->d_slot_ids, c->d_flags, s);
+            if (rc) return rc;
+        }
+        if (h_topk_idx) memcpy(h_topk_idx, c->pin->idx, (size_t)k * 4);
+        if (h_n_miss) *h_n_miss = n_miss;
+        if (h_best) {
+            if (!side_done) MOEI_HIP(hipEventSynchronize(c->ev_side));
+            *h_best = c->pin->best;
+        }
+    }
+    return launch_expert_ffn(d, c->d_pool, c->slot_elems, c->n_total, c->ffn, c->d_slot_ids, c->d_gate,
+                             k + d.n_shared, d_x, d_y, c->d_flags, s);
+}
+
+extern "C" int moei_cache_last_step(moei_cache* c, float* h_gate_w, float* h_best_sim, float* h_prefetch,
+                                    float* h_evict, int32_t* h_pf_order, int32_t* h_n_pf, int32_t* h_ev_order,
+                                    int32_t* h_n_ev, void* stream) {
+    MOEI_REQUIRE(c, "moei_cache_last_step: null pointer");
+    MOEI_HIP(hipStreamSynchronize(as_stream(stream)));
+    MOEI_HIP(hipStreamSynchronize(c->side_stream));
+    const size_t LE = (size_t)c->d.L * c->d.E;
+    if (h_gate_w) MOEI_HIP(hipMemcpy(h_gate_w, c->d_w, (size_t)c->d.k * 4, hipMemcpyDeviceToHost));
+    if (h_best_sim) MOEI_HIP(hipMemcpy(h_best_sim, c->d_best_sim, 4, hipMemcpyDeviceToHost));
+    if (h_prefetch) MOEI_HIP(hipMemcpy(h_prefetch, c->d_P, LE * 4, hipMemcpyDeviceToHost));
+    if (h_evict) MOEI_HIP(hipMemcpy(h_evict, c->d_V, LE * 4, hipMemcpyDeviceToHost));
+    if (h_pf_order) MOEI_HIP(hipMemcpy(h_pf_order, c->d_pf_order, LE * 4, hipMemcpyDeviceToHost));
+    if (h_n_pf) MOEI_HIP(hipMemcpy(h_n_pf, c->d_n_pf, 4, hipMemcpyDeviceToHost));
+    if (h_ev_order) MOEI_HIP(hipMemcpy(h_ev_order, c->d_ev_order, LE * 4, hipMemcpyDeviceToHost));
+    if (h_n_ev) MOEI_HIP(hipMemcpy(h_n_ev, c->d_n_ev, 4, hipMemcpyDeviceToHost));
+    return MOEI_OK;
+}

@@ -1,0 +1,61 @@
+// Internal interfaces between the translation units of the moei library.
+#pragma once
+
+#include <vector>
+
+#include "common.hpp"
+
+namespace moei {
+
+// ----------------------------------------------------------------- route.hip
+struct RouteFusedArgs {
+    const float* logits;         // [E]
+    int E, k, renorm;
+    int32_t* idx;                // [k] out
+    float* w;                    // [k] out
+    int32_t* eam_row;            // eam + layer*E, updated in place
+    const int32_t* slot_of_row;  // slot_of + layer*E
+    int n_shared, shared_base;   // shared slot ids: shared_base + s
+    int32_t* slot_ids;           // [k + n_shared] out
+    float* gate;                 // [k + n_shared] out
+    int32_t* flags;              // error flags (bit 1: pick not resident)
+};
+int launch_router_gemv(const void* d_W, const float* d_bias, const void* d_x, int E, int H, int wdtype,
+                       float* d_logits, hipStream_t s);
+int launch_route_fused(const RouteFusedArgs& a, hipStream_t s);
+int launch_gather_slots(const int32_t* d_idx, int k, const int32_t* d_slot_of_row, int32_t* d_slot_ids,
+                        int32_t* d_flags, hipStream_t s);
+
+// ------------------------------------------------------------------ ffn.hip
+struct FfnScratch {
+    float* d_act = nullptr;   // [n_act_max][I] intermediate silu(g)*u
+    float* d_part = nullptr;  // [n_act_max * ksplit_max][H] partial down-projections
+    int n_act_max = 0;
+    int ksplit_max = 0;
+};
+int ffn_scratch_alloc(const moei_model_desc& d, int n_act_max, FfnScratch* out);
+void ffn_scratch_free(FfnScratch* s);
+int launch_expert_ffn(const moei_model_desc& d, const void* d_pool, size_t slot_elems, int n_slots_total,
+                      const FfnScratch& scr, const int32_t* d_slot_ids, const float* d_gate_w, int n_act,
+                      const void* d_x, float* d_y, int32_t* d_flags, hipStream_t s);
+
+}  // namespace moei
+
+// The EAM collection (Sec. 4.5): traces layer-major on the device.
+struct moei_eamc {
+    moei_model_desc d{};
+    int32_t n_cap = 0;
+    int32_t N = 0;
+    int32_t cell_bytes = 4;
+    void* d_traces = nullptr;            // [L][n_cap][E] cells
+    unsigned long long* d_norm2 = nullptr;  // [n_cap] squared norms of the flattened traces
+    unsigned long long* d_part = nullptr;   // [B_max][lsplit_max][n_cap] partial dot products
+    int32_t lsplit_max = 0;
+    // priority scratch: compacted candidate lists
+    unsigned long long* d_keys = nullptr;  // [2][L*E] sort keys (prefetch, evict)
+    int32_t* d_ids = nullptr;              // [2][L*E] flat ids of the candidates
+};
+
+namespace moei {
+constexpr int kMaxMatchBatch = 16;
+}

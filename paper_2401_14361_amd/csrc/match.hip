@@ -1,0 +1,490 @@
+// Step 3 of the layer step: the EAMC match (Sec. 4.5 of the paper).
+//
+// Every stored request-level EAM is compared with the current EAM by the cosine of
+// the flattened matrices; the closest one wins.  On the device this is a streaming
+// reduction over the whole collection: traces are stored layer-major
+// [L][n_cap][E], a workgroup owns a tile of consecutive traces and walks the layers,
+// so each step reads one contiguous run of cells with 16-byte loads.  The query's
+// rows sit in LDS.  Dot products are exact 64-bit integers; the arg-max compares
+// dot_a^2 * |T_b|^2 with dot_b^2 * |T_a|^2 in 192-bit integer arithmetic, so the
+// winner does not depend on floating-point rounding.
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "kernels.hpp"
+
+namespace moei {
+
+namespace {
+
+constexpr int kDotThreads = 256;
+constexpr int kMaxE = 2048;
+constexpr int kArgmaxThreads = 1024;
+typedef unsigned long long u64;
+typedef unsigned __int128 u128;
+
+struct DotArgs {
+    const void* traces;   // [L][n_cap][E]
+    const int32_t* q;     // [B][L][E]
+    u64* part;            // [B][n_lsplit][n_cap]
+    int n_cap, N, L, E;
+    int L_scan;           // layers 0..L_scan-1 are read
+    int lper;             // layers per split
+    int n_lsplit;
+    int TN;               // traces per tile
+    int rowV;             // vectors per trace row
+};
+
+template <typename CT, int VEC>
+struct CellVec;
+
+template <>
+struct CellVec<int32_t, 4> {
+    using raw = int4;
+    static __device__ __forceinline__ raw load(const int32_t* p) { return *reinterpret_cast<const int4*>(p); }
+    static __device__ __forceinline__ u64 dot(raw v, const int32_t* q, u64 acc) {
+        int4 qq = *reinterpret_cast<const int4*>(q);
+        acc += (u64)(uint32_t)v.x * (uint32_t)qq.x;
+        acc += (u64)(uint32_t)v.y * (uint32_t)qq.y;
+        acc += (u64)(uint32_t)v.z * (uint32_t)qq.z;
+        acc += (u64)(uint32_t)v.w * (uint32_t)qq.w;
+        return acc;
+    }
+};
+
+template <>
+struct CellVec<int32_t, 1> {
+    using raw = int32_t;
+    static __device__ __forceinline__ raw load(const int32_t* p) { return *p; }
+    static __device__ __forceinline__ u64 dot(raw v, const int32_t* q, u64 acc) {
+        return acc + (u64)(uint32_t)v * (uint32_t)q[0];
+    }
+};
+
+template <>
+struct CellVec<uint16_t, 8> {
+    using raw = uint4;
+    static __device__ __forceinline__ raw load(const uint16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+    static __device__ __forceinline__ u64 dot(raw v, const int32_t* q, u64 acc) {
+        int4 q0 = *reinterpret_cast<const int4*>(q);
+        int4 q1 = *reinterpret_cast<const int4*>(q + 4);
+        acc += (u64)(v.x & 0xffffu) * (uint32_t)q0.x;
+        acc += (u64)(v.x >> 16) * (uint32_t)q0.y;
+        acc += (u64)(v.y & 0xffffu) * (uint32_t)q0.z;
+        acc += (u64)(v.y >> 16) * (uint32_t)q0.w;
+        acc += (u64)(v.z & 0xffffu) * (uint32_t)q1.x;
+        acc += (u64)(v.z >> 16) * (uint32_t)q1.y;
+        acc += (u64)(v.w & 0xffffu) * (uint32_t)q1.z;
+        acc += (u64)(v.w >> 16) * (uint32_t)q1.w;
+        return acc;
+    }
+};
+
+template <>
+struct CellVec<uint16_t, 1> {
+    using raw = uint16_t;
+    static __device__ __forceinline__ raw load(const uint16_t* p) { return *p; }
+    static __device__ __forceinline__ u64 dot(raw v, const int32_t* q, u64 acc) {
+        return acc + (u64)v * (uint32_t)q[0];
+    }
+};
+
+// grid (tiles, layer splits, B).  Thread t owns vectors p = j*256 + t (j < J) of its
+// tile; vector p belongs to trace p / rowV of the tile in EVERY layer, so the J
+// accumulators live in registers across the whole layer walk.
+template <typename CT, int VEC, int J>
+__global__ void __launch_bounds__(kDotThreads) eamc_dot_kernel(DotArgs a) {
+    using CV = CellVec<CT, VEC>;
+    extern __shared__ __align__(16) unsigned char smem[];
+    int32_t* qs = reinterpret_cast<int32_t*>(smem);
+    const int q_bytes = ((a.lper * a.E * 4) + 15) & ~15;
+    u64* rowsum = reinterpret_cast<u64*>(smem + q_bytes);
+
+    const int tid = threadIdx.x;
+    const int split = blockIdx.y;
+    const int b = blockIdx.z;
+    const int l0 = split * a.lper;
+    int nl = min(l0 + a.lper, a.L_scan) - l0;
+    if (nl < 0) nl = 0;
+    const int n0 = blockIdx.x * a.TN;
+    const int tn = min(a.TN, a.N - n0);
+
+    const int32_t* qsrc = a.q + ((size_t)b * a.L + l0) * a.E;
+    for (int i = tid; i < nl * a.E; i += kDotThreads) qs[i] = qsrc[i];
+    for (int i = tid; i < a.TN; i += kDotThreads) rowsum[i] = 0;
+    __syncthreads();
+
+    bool valid[J];
+    int row[J], col[J];
+    u64 acc[J];
+    const int nvec = tn * a.rowV;
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        int p = j * kDotThreads + tid;
+        valid[j] = p < nvec;
+        row[j] = valid[j] ? p / a.rowV : 0;
+        col[j] = valid[j] ? (p - row[j] * a.rowV) * VEC : 0;
+        acc[j] = 0;
+    }
+    const size_t lstride = (size_t)a.n_cap * a.E;
+    const CT* base = reinterpret_cast<const CT*>(a.traces) + ((size_t)l0 * a.n_cap + n0) * a.E + (size_t)tid * VEC;
+    const int32_t* ql = qs;
+#pragma unroll 2
+    for (int l = 0; l < nl; ++l) {
+        typename CV::raw v[J];
+#pragma unroll
+        for (int j = 0; j < J; ++j)
+            if (valid[j]) v[j] = CV::load(base + (size_t)j * kDotThreads * VEC);
+#pragma unroll
+        for (int j = 0; j < J; ++j)
+            if (valid[j]) acc[j] = CV::dot(v[j], ql + col[j], acc[j]);
+        base += lstride;
+        ql += a.E;
+    }
+#pragma unroll
+    for (int j = 0; j < J; ++j)
+        if (valid[j] && acc[j] != 0) atomicAdd(&rowsum[row[j]], acc[j]);
+    __syncthreads();
+    u64* out = a.part + ((size_t)b * a.n_lsplit + split) * a.n_cap + n0;
+    for (int i = tid; i < tn; i += kDotThreads) out[i] = rowsum[i];
+}
+
+struct Best {
+    u64 dot;  // <q, T>
+    u64 nt;   // |T|^2, never 0 here (an all-zero trace enters as dot 0, nt 1)
+    int idx;  // -1: none
+};
+
+// a.dot^2 * b.nt  vs  b.dot^2 * a.nt, exactly, as 192-bit integers.
+__device__ __forceinline__ int cmp_sim(const Best& a, const Best& b) {
+    u128 a2 = (u128)a.dot * a.dot, b2 = (u128)b.dot * b.dot;
+    u128 al = (u128)(u64)a2 * b.nt, ah = (u128)(u64)(a2 >> 64) * b.nt + (al >> 64);
+    u128 bl = (u128)(u64)b2 * a.nt, bh = (u128)(u64)(b2 >> 64) * a.nt + (bl >> 64);
+    if (ah != bh) return ah > bh ? 1 : -1;
+    u64 all = (u64)al, bll = (u64)bl;
+    if (all != bll) return all > bll ? 1 : -1;
+    return 0;
+}
+
+__device__ __forceinline__ Best pick(const Best& a, const Best& b) {
+    if (b.idx < 0) return a;
+    if (a.idx < 0) return b;
+    int c = cmp_sim(a, b);
+    if (c > 0) return a;
+    if (c < 0) return b;
+    return a.idx < b.idx ? a : b;  // equal similarity: lowest trace index
+}
+
+__device__ __forceinline__ u64 shfl_xor_u64(u64 v, int off) {
+    unsigned lo = __shfl_xor((unsigned)(v & 0xffffffffull), off, 64);
+    unsigned hi = __shfl_xor((unsigned)(v >> 32), off, 64);
+    return ((u64)hi << 32) | lo;
+}
+
+__device__ __forceinline__ double cosine(u64 dot, u64 nq, u64 nt) {
+    if (nq == 0 || nt == 0) return 0.0;
+    return (double)dot / (sqrt((double)nq) * sqrt((double)nt));
+}
+
+// One workgroup per query: sums the split partials, writes similarities, block arg-max.
+__global__ void __launch_bounds__(kArgmaxThreads)
+    eamc_argmax_kernel(const u64* __restrict__ part, int n_lsplit, int n_cap, int N, const u64* __restrict__ norm2,
+                       const int32_t* __restrict__ q, int LE, int32_t* __restrict__ best, float* __restrict__ best_sim,
+                       float* __restrict__ sims) {
+    __shared__ u64 s_dot[kArgmaxThreads / kWave];
+    __shared__ u64 s_nt[kArgmaxThreads / kWave];
+    __shared__ int s_idx[kArgmaxThreads / kWave];
+    __shared__ u64 s_nq;
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wv = tid / kWave;
+
+    u64 nq = 0;
+    for (int i = tid; i < LE; i += kArgmaxThreads) {
+        u64 v = (uint32_t)q[(size_t)b * LE + i];
+        nq += v * v;
+    }
+    nq = wave_sum_u64(nq);
+    if (lane == 0) s_dot[wv] = nq;
+    __syncthreads();
+    if (tid == 0) {
+        u64 t = 0;
+        for (int i = 0; i < kArgmaxThreads / kWave; ++i) t += s_dot[i];
+        s_nq = t;
+    }
+    __syncthreads();
+    nq = s_nq;
+    __syncthreads();
+
+    Best me{0, 1, -1};
+    for (int n = tid; n < N; n += kArgmaxThreads) {
+        u64 dot = 0;
+        for (int s = 0; s < n_lsplit; ++s) dot += part[((size_t)b * n_lsplit + s) * n_cap + n];
+        u64 nt = norm2[n];
+        if (sims) sims[(size_t)b * N + n] = (float)cosine(dot, nq, nt);
+        Best c{nt ? dot : 0, nt ? nt : 1, n};
+        me = pick(me, c);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        Best o;
+        o.dot = shfl_xor_u64(me.dot, off);
+        o.nt = shfl_xor_u64(me.nt, off);
+        o.idx = __shfl_xor(me.idx, off, 64);
+        me = pick(me, o);
+    }
+    if (lane == 0) {
+        s_dot[wv] = me.dot;
+        s_nt[wv] = me.nt;
+        s_idx[wv] = me.idx;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        Best r{s_dot[0], s_nt[0], s_idx[0]};
+        for (int i = 1; i < kArgmaxThreads / kWave; ++i) r = pick(r, Best{s_dot[i], s_nt[i], s_idx[i]});
+        best[b] = r.idx;
+        if (best_sim) best_sim[b] = r.idx >= 0 ? (float)cosine(r.dot, nq, norm2[r.idx]) : 0.f;
+    }
+}
+
+struct Plan {
+    int VEC, J, TN, rowV, n_tiles, n_lsplit, lper;
+    size_t smem;
+};
+
+Plan make_plan(const moei_eamc* c, int L_scan) {
+    Plan p{};
+    const int E = c->d.E;
+    const int full = 16 / c->cell_bytes;
+    p.VEC = (E % full == 0) ? full : 1;
+    p.rowV = E / p.VEC;
+    const long total_vec = (long)c->N * L_scan * p.rowV;
+    const int jt = total_vec >= (1L << 20) ? 4 : 1;  // fewer vectors per thread when the whole scan is small
+    p.TN = (kDotThreads * jt) / p.rowV;
+    if (p.TN < 1) p.TN = 1;
+    p.J = (p.TN * p.rowV + kDotThreads - 1) / kDotThreads;
+    p.n_tiles = (c->N + p.TN - 1) / p.TN;
+    int want = (1024 + p.n_tiles - 1) / p.n_tiles;  // aim at >= 1024 workgroups
+    int lmax = L_scan < c->lsplit_max ? L_scan : c->lsplit_max;
+    p.n_lsplit = want < 1 ? 1 : (want > lmax ? lmax : want);
+    // LDS: the query rows of one split must fit in 48 KiB
+    int min_split = (int)(((size_t)L_scan * E * 4 + 49151) / 49152);
+    if (p.n_lsplit < min_split) p.n_lsplit = min_split;
+    p.lper = (L_scan + p.n_lsplit - 1) / p.n_lsplit;
+    p.n_lsplit = (L_scan + p.lper - 1) / p.lper;
+    p.smem = (((size_t)p.lper * E * 4 + 15) & ~(size_t)15) + (size_t)p.TN * 8;
+    return p;
+}
+
+template <typename CT, int VEC>
+int launch_dot_j(const Plan& p, const DotArgs& a, dim3 grid, hipStream_t s) {
+#define MOEI_DOT_CASE(JJ)                                                                  \
+    case JJ:                                                                               \
+        eamc_dot_kernel<CT, VEC, JJ><<<grid, kDotThreads, p.smem, s>>>(a);                 \
+        break;
+    switch (p.J) {
+        MOEI_DOT_CASE(1)
+        MOEI_DOT_CASE(2)
+        MOEI_DOT_CASE(3)
+        MOEI_DOT_CASE(4)
+        MOEI_DOT_CASE(5)
+        MOEI_DOT_CASE(6)
+        MOEI_DOT_CASE(7)
+        MOEI_DOT_CASE(8)
+        default:
+            MOEI_FAIL(MOEI_EINVAL, "eamc_match: no kernel for %d vectors per thread", p.J);
+    }
+#undef MOEI_DOT_CASE
+    MOEI_LAUNCH_CHECK();
+    return MOEI_OK;
+}
+
+size_t cells(const moei_eamc* c) { return (size_t)c->d.L * c->n_cap * c->d.E; }
+
+}  // namespace
+
+}  // namespace moei
+
+using namespace moei;
+
+extern "C" int moei_eamc_create(const moei_model_desc* desc, int32_t n_cap, int32_t cell_bytes, moei_eamc** out) {
+    MOEI_REQUIRE(desc && out, "moei_eamc_create: null pointer");
+    *out = nullptr;
+    int rc = check_desc(desc);
+    if (rc) return rc;
+    MOEI_REQUIRE(n_cap >= 1, "moei_eamc_create: n_cap = %d must be positive", n_cap);
+    MOEI_REQUIRE(cell_bytes == 4 || cell_bytes == 2, "moei_eamc_create: cell_bytes must be 4 or 2");
+    MOEI_REQUIRE(desc->E <= kMaxE, "moei_eamc_create: E = %d exceeds %d", desc->E, kMaxE);
+    moei_eamc* c = new (std::nothrow) moei_eamc();
+    if (!c) MOEI_FAIL(MOEI_ENOMEM, "moei_eamc_create: out of host memory");
+    c->d = *desc;
+    c->n_cap = n_cap;
+    c->cell_bytes = cell_bytes;
+    c->lsplit_max = desc->L < 32 ? desc->L : 32;
+    const size_t LE = (size_t)desc->L * desc->E;
+    hipError_t e = hipMalloc(&c->d_traces, cells(c) * cell_bytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&c->d_norm2, (size_t)n_cap * 8);
+    if (e == hipSuccess) e = hipMalloc((void**)&c->d_part, (size_t)kMaxMatchBatch * c->lsplit_max * n_cap * 8);
+    if (e == hipSuccess) e = hipMalloc((void**)&c->d_keys, 2 * LE * 8);
+    if (e == hipSuccess) e = hipMalloc((void**)&c->d_ids, 2 * LE * 4);
+    if (e != hipSuccess) {
+        moei_eamc_destroy(c);
+        MOEI_FAIL(MOEI_ENOMEM, "moei_eamc_create: device allocation failed: %s", hipGetErrorString(e));
+    }
+    *out = c;
+    return MOEI_OK;
+}
+
+extern "C" int moei_eamc_destroy(moei_eamc* c) {
+    if (!c) return MOEI_OK;
+    (void)hipFree(c->d_traces);
+    (void)hipFree(c->d_norm2);
+    (void)hipFree(c->d_part);
+    (void)hipFree(c->d_keys);
+    (void)hipFree(c->d_ids);
+    delete c;
+    return MOEI_OK;
+}
+
+extern "C" int moei_eamc_size(const moei_eamc* c) {
+    MOEI_REQUIRE(c, "moei_eamc_size: null pointer");
+    return c->N;
+}
+
+namespace {
+
+int check_cells(const int32_t* p, size_t n, int cell_bytes) {
+    const int32_t hi = cell_bytes == 2 ? 65535 : MOEI_MAX_COUNT;
+    for (size_t i = 0; i < n; ++i)
+        if (p[i] < 0 || p[i] > hi)
+            MOEI_FAIL(MOEI_EINVAL, "EAM cell %zu holds %d, outside [0, %d]", i, p[i], hi);
+    return MOEI_OK;
+}
+
+unsigned long long norm2_of(const int32_t* p, size_t n) {
+    unsigned long long s = 0;
+    for (size_t i = 0; i < n; ++i) s += (unsigned long long)p[i] * (unsigned long long)p[i];
+    return s;
+}
+
+}  // namespace
+
+extern "C" int moei_eamc_load(moei_eamc* c, const int32_t* h_traces, int32_t N) {
+    MOEI_REQUIRE(c, "moei_eamc_load: null pointer");
+    MOEI_REQUIRE(N >= 0, "moei_eamc_load: N = %d is negative", N);
+    if (N > c->n_cap) MOEI_FAIL(MOEI_ECAPACITY, "moei_eamc_load: N = %d exceeds the capacity %d", N, c->n_cap);
+    MOEI_REQUIRE(N == 0 || h_traces, "moei_eamc_load: null traces");
+    c->N = 0;
+    if (N == 0) return MOEI_OK;
+    const int L = c->d.L, E = c->d.E;
+    const size_t LE = (size_t)L * E;
+    int rc = check_cells(h_traces, (size_t)N * LE, c->cell_bytes);
+    if (rc) return rc;
+    // trace-major -> layer-major staging, one layer at a time
+    std::vector<unsigned long long> norm((size_t)N);
+    for (int n = 0; n < N; ++n) norm[n] = norm2_of(h_traces + (size_t)n * LE, LE);
+    std::vector<unsigned char> stage;
+    try {
+        stage.resize((size_t)N * E * c->cell_bytes);
+    } catch (...) {
+        MOEI_FAIL(MOEI_ENOMEM, "moei_eamc_load: out of host memory");
+    }
+    for (int l = 0; l < L; ++l) {
+        if (c->cell_bytes == 4) {
+            int32_t* dst = reinterpret_cast<int32_t*>(stage.data());
+            for (int n = 0; n < N; ++n) memcpy(dst + (size_t)n * E, h_traces + (size_t)n * LE + (size_t)l * E, (size_t)E * 4);
+        } else {
+            uint16_t* dst = reinterpret_cast<uint16_t*>(stage.data());
+            for (int n = 0; n < N; ++n) {
+                const int32_t* src = h_traces + (size_t)n * LE + (size_t)l * E;
+                for (int e = 0; e < E; ++e) dst[(size_t)n * E + e] = (uint16_t)src[e];
+            }
+        }
+        unsigned char* d = reinterpret_cast<unsigned char*>(c->d_traces) + (size_t)l * c->n_cap * E * c->cell_bytes;
+        MOEI_HIP(hipMemcpy(d, stage.data(), stage.size(), hipMemcpyHostToDevice));
+    }
+    MOEI_HIP(hipMemcpy(c->d_norm2, norm.data(), (size_t)N * 8, hipMemcpyHostToDevice));
+    c->N = N;
+    return MOEI_OK;
+}
+
+extern "C" int moei_eamc_insert(moei_eamc* c, const int32_t* h_eam, int32_t victim) {
+    MOEI_REQUIRE(c && h_eam, "moei_eamc_insert: null pointer");
+    const int L = c->d.L, E = c->d.E;
+    const size_t LE = (size_t)L * E;
+    int rc = check_cells(h_eam, LE, c->cell_bytes);
+    if (rc) return rc;
+    int pos;
+    if (c->N < c->n_cap) {
+        pos = c->N;
+    } else {
+        MOEI_REQUIRE(victim >= 0 && victim < c->N, "moei_eamc_insert: victim %d outside [0, %d)", victim, c->N);
+        pos = victim;
+    }
+    const size_t cb = c->cell_bytes;
+    std::vector<uint16_t> narrow;
+    const void* src = h_eam;
+    if (cb == 2) {
+        narrow.resize(LE);
+        for (size_t i = 0; i < LE; ++i) narrow[i] = (uint16_t)h_eam[i];
+        src = narrow.data();
+    }
+    unsigned char* dst = reinterpret_cast<unsigned char*>(c->d_traces) + (size_t)pos * E * cb;
+    MOEI_HIP(hipMemcpy2D(dst, (size_t)c->n_cap * E * cb, src, (size_t)E * cb, (size_t)E * cb, L, hipMemcpyHostToDevice));
+    unsigned long long n2 = norm2_of(h_eam, LE);
+    MOEI_HIP(hipMemcpy(c->d_norm2 + pos, &n2, 8, hipMemcpyHostToDevice));
+    if (pos == c->N) c->N += 1;
+    return MOEI_OK;
+}
+
+extern "C" int moei_eamc_export(const moei_eamc* c, int32_t* h_traces, int32_t max_traces) {
+    MOEI_REQUIRE(c && (h_traces || c->N == 0), "moei_eamc_export: null pointer");
+    if (max_traces < c->N) MOEI_FAIL(MOEI_ECAPACITY, "moei_eamc_export: room for %d traces, %d stored", max_traces, c->N);
+    const int L = c->d.L, E = c->d.E, N = c->N;
+    if (N == 0) return MOEI_OK;
+    const size_t cb = c->cell_bytes;
+    std::vector<unsigned char> stage((size_t)N * E * cb);
+    for (int l = 0; l < L; ++l) {
+        const unsigned char* d = reinterpret_cast<const unsigned char*>(c->d_traces) + (size_t)l * c->n_cap * E * cb;
+        MOEI_HIP(hipMemcpy(stage.data(), d, stage.size(), hipMemcpyDeviceToHost));
+        for (int n = 0; n < N; ++n) {
+            int32_t* dst = h_traces + ((size_t)n * L + l) * E;
+            if (cb == 4) {
+                memcpy(dst, stage.data() + (size_t)n * E * 4, (size_t)E * 4);
+            } else {
+                const uint16_t* s16 = reinterpret_cast<const uint16_t*>(stage.data()) + (size_t)n * E;
+                for (int e = 0; e < E; ++e) dst[e] = s16[e];
+            }
+        }
+    }
+    return MOEI_OK;
+}
+
+extern "C" int eamc_match(const moei_eamc* c, const int32_t* d_eam, int32_t B, int32_t layer_hi, int32_t* d_best,
+                          float* d_best_sim, float* d_sims, void* stream) {
+    MOEI_REQUIRE(c && d_eam && d_best, "eamc_match: null pointer");
+    MOEI_REQUIRE(B >= 0 && B <= kMaxMatchBatch, "eamc_match: B = %d outside [0, %d]", B, kMaxMatchBatch);
+    MOEI_REQUIRE(layer_hi >= 0 && layer_hi < c->d.L, "eamc_match: layer_hi = %d outside [0, %d)", layer_hi, c->d.L);
+    if (B == 0) return MOEI_OK;
+    hipStream_t s = as_stream(stream);
+    const int L = c->d.L, E = c->d.E;
+    int n_lsplit = 0;
+    if (c->N > 0) {
+        Plan p = make_plan(c, layer_hi + 1);
+        n_lsplit = p.n_lsplit;
+        DotArgs a{c->d_traces, d_eam, c->d_part, c->n_cap, c->N, L, E, layer_hi + 1, p.lper, p.n_lsplit, p.TN, p.rowV};
+        dim3 grid(p.n_tiles, p.n_lsplit, B);
+        int rc;
+        if (c->cell_bytes == 4)
+            rc = p.VEC == 4 ? launch_dot_j<int32_t, 4>(p, a, grid, s) : launch_dot_j<int32_t, 1>(p, a, grid, s);
+        else
+            rc = p.VEC == 8 ? launch_dot_j<uint16_t, 8>(p, a, grid, s) : launch_dot_j<uint16_t, 1>(p, a, grid, s);
+        if (rc) return rc;
+    }
+    eamc_argmax_kernel<<<B, kArgmaxThreads, 0, s>>>(c->d_part, n_lsplit, c->n_cap, c->N, c->d_norm2, d_eam, L * E,
+                                                    d_best, d_best_sim, d_sims);
+    MOEI_LAUNCH_CHECK();
+    return MOEI_OK;
+}

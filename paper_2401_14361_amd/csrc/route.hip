@@ -1,0 +1,288 @@
+// Step 1 and 2 of the layer step: router GEMV, softmax + top-k, EAM update.
+//
+// The router assigns each token to k of the E experts of a layer (Sec. 2 of the
+// paper); every assignment increments the request's Expert Activation Matrix
+// (Sec. 4.3).  One wavefront serves one token: the E logits sit in LDS, each of
+// the k rounds is a 64-lane butterfly arg-max.
+#include "kernels.hpp"
+#include "wtypes.hpp"
+
+namespace moei {
+
+namespace {
+
+constexpr int kMaxE = 4096;
+
+struct Cand {
+    float v;
+    int e;  // -1: none
+};
+
+__device__ __forceinline__ Cand better(Cand a, Cand b) {
+    // larger logit first; equal logits go to the lower expert index
+    if (b.e < 0) return a;
+    if (a.e < 0) return b;
+    if (a.v > b.v) return a;
+    if (b.v > a.v) return b;
+    return (a.e < b.e) ? a : b;
+}
+
+// Softmax + top-k of z[0..E) (LDS or global, read-only here) by one wavefront.
+// Lane j < k returns pick j in (idx, w); other lanes return idx = -1.
+__device__ __forceinline__ void wave_topk(const float* z, int E, int k, int renorm, int lane, int& idx_out,
+                                          float& w_out) {
+    const int per = (E + kWave - 1) / kWave;  // <= 64, so one 64-bit mask per lane marks taken entries
+    float m = -INFINITY;
+    for (int r = 0; r < per; ++r) {
+        int e = lane + r * kWave;
+        if (e < E) m = fmaxf(m, z[e]);
+    }
+    m = wave_max(m);
+    float s = 0.f;
+    for (int r = 0; r < per; ++r) {
+        int e = lane + r * kWave;
+        if (e < E) s += expf(z[e] - m);
+    }
+    s = wave_sum(s);
+
+    unsigned long long taken = 0ull;
+    idx_out = -1;
+    w_out = 0.f;
+    float sel_sum = 0.f;
+    for (int j = 0; j < k; ++j) {
+        Cand c{0.f, -1};
+        for (int r = 0; r < per; ++r) {
+            int e = lane + r * kWave;
+            if (e < E && !((taken >> r) & 1ull)) {
+                float v = z[e];
+                if (c.e < 0 || v > c.v) c = Cand{v, e};
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            Cand o;
+            o.v = __shfl_xor(c.v, off, 64);
+            o.e = __shfl_xor(c.e, off, 64);
+            c = better(c, o);
+        }
+        // c is now identical in all lanes; k <= E guarantees c.e >= 0
+        if ((c.e & (kWave - 1)) == lane) taken |= 1ull << (c.e / kWave);
+        float p = expf(c.v - m) / s;
+        sel_sum += p;
+        if (lane == j) {
+            idx_out = c.e;
+            w_out = p;
+        }
+    }
+    if (renorm) w_out = w_out / sel_sum;
+}
+
+__global__ void __launch_bounds__(kWave) route_topk_kernel(const float* __restrict__ logits, int E, int k,
+                                                           int renorm, int32_t* __restrict__ idx,
+                                                           float* __restrict__ w) {
+    extern __shared__ float z[];
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x;
+    for (int e = lane; e < E; e += kWave) z[e] = logits[(size_t)b * E + e];
+    __syncthreads();
+    int my_idx;
+    float my_w;
+    wave_topk(z, E, k, renorm, lane, my_idx, my_w);
+    // k may exceed 64: picks are produced in rounds of 64 lanes
+    if (k <= kWave) {
+        if (lane < k) {
+            idx[(size_t)b * k + lane] = my_idx;
+            w[(size_t)b * k + lane] = my_w;
+        }
+    }
+}
+
+// k > 64: serial rounds writing straight to memory (rare: k is 1..8 in practice).
+__global__ void __launch_bounds__(kWave) route_topk_wide_kernel(const float* __restrict__ logits, int E, int k,
+                                                                int renorm, int32_t* __restrict__ idx,
+                                                                float* __restrict__ w) {
+    extern __shared__ float z[];
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x;
+    for (int e = lane; e < E; e += kWave) z[e] = logits[(size_t)b * E + e];
+    __syncthreads();
+    const int per = (E + kWave - 1) / kWave;
+    float m = -INFINITY;
+    for (int r = 0; r < per; ++r) {
+        int e = lane + r * kWave;
+        if (e < E) m = fmaxf(m, z[e]);
+    }
+    m = wave_max(m);
+    float s = 0.f;
+    for (int r = 0; r < per; ++r) {
+        int e = lane + r * kWave;
+        if (e < E) s += expf(z[e] - m);
+    }
+    s = wave_sum(s);
+    unsigned long long taken = 0ull;
+    float sel_sum = 0.f;
+    for (int j = 0; j < k; ++j) {
+        Cand c{0.f, -1};
+        for (int r = 0; r < per; ++r) {
+            int e = lane + r * kWave;
+            if (e < E && !((taken >> r) & 1ull)) {
+                float v = z[e];
+                if (c.e < 0 || v > c.v) c = Cand{v, e};
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            Cand o;
+            o.v = __shfl_xor(c.v, off, 64);
+            o.e = __shfl_xor(c.e, off, 64);
+            c = better(c, o);
+        }
+        if ((c.e & (kWave - 1)) == lane) taken |= 1ull << (c.e / kWave);
+        float p = expf(c.v - m) / s;
+        sel_sum += p;
+        if (lane == 0) {
+            idx[(size_t)b * k + j] = c.e;
+            w[(size_t)b * k + j] = p;
+        }
+    }
+    if (renorm) {
+        __syncthreads();
+        for (int j = lane; j < k; j += kWave) w[(size_t)b * k + j] = w[(size_t)b * k + j] / sel_sum;
+    }
+}
+
+__global__ void eam_update_kernel(int32_t* __restrict__ eam, int B, int L, int E, int layer,
+                                  const int32_t* __restrict__ idx, int k) {
+    int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= B * k) return;
+    int b = t / k;
+    int e = idx[t];
+    // picks of one token are distinct and every token has its own matrix: no two
+    // threads touch the same cell
+    if (e >= 0 && e < E) eam[((size_t)b * L + layer) * E + e] += 1;
+}
+
+// logits[e] = <W[e][:], x> + bias[e]; one wavefront per expert row.
+template <typename WT>
+__global__ void __launch_bounds__(kWave) router_gemv_kernel(const WT* __restrict__ W, const float* __restrict__ bias,
+                                                            const WT* __restrict__ x, int E, int H, int vec_ok,
+                                                            float* __restrict__ logits) {
+    using V = WVec<WT>;
+    const int e = blockIdx.x;
+    const int lane = threadIdx.x;
+    const WT* row = W + (size_t)e * H;
+    float acc = 0.f;
+    if (vec_ok) {
+        for (int c = lane * V::N; c < H; c += kWave * V::N) {
+            typename V::raw wv = V::load(row + c);
+            typename V::raw xv = V::load(x + c);
+            float xf[V::N];
+            V::unpack(xv, xf);
+            acc = V::dot(wv, xf, acc);
+        }
+    } else {
+        for (int c = lane; c < H; c += kWave) acc = __builtin_fmaf(V::one(row + c), V::one(x + c), acc);
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) logits[e] = acc + (bias ? bias[e] : 0.f);
+}
+
+// Routing decision of the fused layer step for one token: top-k, EAM row update and
+// the slot ids / gate weights the FFN kernels read.
+__global__ void __launch_bounds__(kWave) route_fused_kernel(RouteFusedArgs a) {
+    extern __shared__ float z[];
+    const int lane = threadIdx.x;
+    for (int e = lane; e < a.E; e += kWave) z[e] = a.logits[e];
+    __syncthreads();
+    int my_idx;
+    float my_w;
+    wave_topk(z, a.E, a.k, a.renorm, lane, my_idx, my_w);
+    if (lane < a.k) {
+        a.idx[lane] = my_idx;
+        a.w[lane] = my_w;
+        a.eam_row[my_idx] += 1;
+        int slot = a.slot_of_row[my_idx];
+        a.slot_ids[lane] = slot;
+        a.gate[lane] = my_w;
+        if (slot < 0 && a.flags) atomicOr(a.flags, 2);
+    } else if (lane < a.k + a.n_shared) {
+        a.slot_ids[lane] = a.shared_base + (lane - a.k);
+        a.gate[lane] = 1.0f;
+    }
+}
+
+// Slot ids of already chosen picks (after the host has served the misses).
+__global__ void gather_slots_kernel(const int32_t* __restrict__ idx, int k, const int32_t* __restrict__ slot_of_row,
+                                    int32_t* __restrict__ slot_ids, int32_t* __restrict__ flags) {
+    int j = threadIdx.x;
+    if (j < k) {
+        int slot = slot_of_row[idx[j]];
+        slot_ids[j] = slot;
+        if (slot < 0) atomicOr(flags, 2);
+    }
+}
+
+}  // namespace
+
+int launch_router_gemv(const void* d_W, const float* d_bias, const void* d_x, int E, int H, int wdtype,
+                       float* d_logits, hipStream_t s) {
+    if (wdtype == MOEI_WDTYPE_BF16) {
+        int vec_ok = (H % 8 == 0) && ((uintptr_t)d_W % 16 == 0) && ((uintptr_t)d_x % 16 == 0);
+        router_gemv_kernel<uint16_t><<<E, kWave, 0, s>>>((const uint16_t*)d_W, d_bias, (const uint16_t*)d_x, E, H,
+                                                        vec_ok, d_logits);
+    } else {
+        int vec_ok = (H % 4 == 0) && ((uintptr_t)d_W % 16 == 0) && ((uintptr_t)d_x % 16 == 0);
+        router_gemv_kernel<float><<<E, kWave, 0, s>>>((const float*)d_W, d_bias, (const float*)d_x, E, H, vec_ok,
+                                                      d_logits);
+    }
+    MOEI_LAUNCH_CHECK();
+    return MOEI_OK;
+}
+
+int launch_route_fused(const RouteFusedArgs& a, hipStream_t s) {
+    if (a.E > kMaxE || a.k > kWave || a.k + a.n_shared > kWave)
+        MOEI_FAIL(MOEI_EINVAL, "fused routing needs E <= %d and k + n_shared <= %d", kMaxE, kWave);
+    route_fused_kernel<<<1, kWave, a.E * sizeof(float), s>>>(a);
+    MOEI_LAUNCH_CHECK();
+    return MOEI_OK;
+}
+
+int launch_gather_slots(const int32_t* d_idx, int k, const int32_t* d_slot_of_row, int32_t* d_slot_ids,
+                        int32_t* d_flags, hipStream_t s) {
+    gather_slots_kernel<<<1, kWave, 0, s>>>(d_idx, k, d_slot_of_row, d_slot_ids, d_flags);
+    MOEI_LAUNCH_CHECK();
+    return MOEI_OK;
+}
+
+}  // namespace moei
+
+using namespace moei;
+
+extern "C" int moe_route_topk(const float* d_logits, int32_t B, int32_t E, int32_t k, int32_t renorm, int32_t* d_idx,
+                              float* d_w, void* stream) {
+    MOEI_REQUIRE(d_logits && d_idx && d_w, "moe_route_topk: null pointer");
+    MOEI_REQUIRE(B >= 0, "moe_route_topk: B = %d is negative", B);
+    MOEI_REQUIRE(E >= 1 && E <= kMaxE, "moe_route_topk: E = %d outside [1, %d]", E, kMaxE);
+    MOEI_REQUIRE(k >= 1 && k <= E, "moe_route_topk: k = %d outside [1, E = %d]", k, E);
+    if (B == 0) return MOEI_OK;
+    hipStream_t s = as_stream(stream);
+    if (k <= kWave)
+        route_topk_kernel<<<B, kWave, E * sizeof(float), s>>>(d_logits, E, k, renorm != 0, d_idx, d_w);
+    else
+        route_topk_wide_kernel<<<B, kWave, E * sizeof(float), s>>>(d_logits, E, k, renorm != 0, d_idx, d_w);
+    MOEI_LAUNCH_CHECK();
+    return MOEI_OK;
+}
+
+extern "C" int eam_update(int32_t* d_eam, int32_t B, int32_t L, int32_t E, int32_t layer, const int32_t* d_idx,
+                          int32_t k, void* stream) {
+    MOEI_REQUIRE(d_eam && d_idx, "eam_update: null pointer");
+    MOEI_REQUIRE(B >= 0 && L >= 1 && E >= 1 && k >= 1 && k <= E, "eam_update: bad shape B=%d L=%d E=%d k=%d", B, L, E,
+                 k);
+    MOEI_REQUIRE(layer >= 0 && layer < L, "eam_update: layer %d outside [0, %d)", layer, L);
+    if (B == 0) return MOEI_OK;
+    int n = B * k;
+    eam_update_kernel<<<(n + 255) / 256, 256, 0, as_stream(stream)>>>(d_eam, B, L, E, layer, d_idx, k);
+    MOEI_LAUNCH_CHECK();
+    return MOEI_OK;
+}

@@ -1,0 +1,184 @@
+"""Cache retrieval (Alg. 1) and the fused layer step against the oracle, state carried
+across a whole request: routing, EAM, matched trace, both orders and the hit/miss/victim
+sequence must agree exactly at every layer step; FFN outputs within tolerance.
+Layer inputs are teacher-forced (each (token, layer) has its own pre-drawn x), so a
+rounding difference in one FFN output cannot change a later routing decision.
+"""
+import numpy as np
+import pytest
+import torch
+
+import moei_inputs as mi
+from oracle import moei_oracle as O
+from tests.helpers import EPS, dev, pick_clear_tokens, pinned, rel_max_err, split_expert
+
+pytestmark = pytest.mark.gpu
+
+FFN_TOL = 2e-2
+FFN_TOL_FP32ACC = 2e-4
+
+
+@pytest.fixture(scope="module")
+def m():
+    import paper_2401_14361_amd as mod
+    mod.lib()
+    return mod
+
+
+def test_cache_retrieve_sequence_and_slot_contents(m):
+    cfg = mi.get_config("C1").scaled(H=64, I=32)
+    L, E, k, S = cfg.L, cfg.E, cfg.k, 6
+    bank = mi.expert_bank(cfg, L * E, threads=2)
+    host = pinned(bank)
+    cache = m.Cache(m.ModelDesc.from_config(cfg), S, host)
+    for warm in (True, False):
+        cache.reset(S if warm else 0)
+        ref = O.ExpertCache(L, E, S, warm=warm)
+        rng = np.random.default_rng(11)
+        for it in range(30):
+            for layer in range(L):
+                picks = rng.choice(E, size=k, replace=False)
+                need = {layer * E + int(p) for p in picks}
+                resident = [f for f in range(L * E) if ref.slot_of[f] >= 0 and f not in need]
+                ev = rng.permutation(resident)[: (1 if it % 5 == 0 else len(resident))]
+                want = ref.retrieve(layer, picks, ev)
+                slots, victims, n_miss = cache.retrieve(layer, picks, ev)
+                assert slots.tolist() == [w[3] for w in want]
+                assert victims.tolist() == [w[2] for w in want]
+                assert n_miss == sum(1 for w in want if not w[1])
+                assert (cache.get_slots() == ref.slot_of).all()
+        torch.cuda.synchronize()
+        # every resident slot holds its owner's weights; the device table mirrors the host's
+        for f in range(L * E):
+            s = int(ref.slot_of[f])
+            if s >= 0:
+                got = cache.slot_tensor(s).cpu().numpy()
+                assert (got == bank[f]).all()
+    with pytest.raises(m.MoeiError):
+        cache.retrieve(0, [1, 1], [])
+    with pytest.raises(m.MoeiError):
+        cache.retrieve(L, [0, 1], [])
+    cache.close()
+    # without a host copy a miss is an error, not a silent zero
+    c2 = m.Cache(m.ModelDesc.from_config(cfg), S)
+    c2.reset(S)
+    with pytest.raises(m.MoeiError):
+        c2.retrieve(L - 1, [0, 1], [0])
+    c2.close()
+
+
+def _replay(m, cfg, S, n_tokens, n_unique, cell_bytes, rid=0):
+    L, E, k = cfg.L, cfg.E, cfg.k
+    T, _, _ = mi.eamc_traces(cfg, threads=4)
+    req = mi.make_request(cfg, rid, decode=n_tokens + 8)
+    tokens = pick_clear_tokens(cfg, req, n_tokens)
+    bank = mi.expert_bank(cfg, n_unique, threads=4)
+    shared = mi.expert_bank(cfg.scaled(cid=cfg.cid + 50), max(L * cfg.n_shared, 1), threads=2)
+    routers = [mi.router_weights(cfg, l) for l in range(L)]
+
+    desc = m.ModelDesc.from_config(cfg)
+    eamc = m.Eamc(desc, cfg.N, cell_bytes)
+    eamc.load(T)
+    cache = m.Cache(desc, S, pinned(bank), pinned(shared) if cfg.n_shared else None)
+    cache.reset(min(S, L * E))
+    d_eam = dev(req.prefill_eam.astype(np.int32))
+    d_routers = [dev(w) for w in routers]
+    d_bias = dev(req.bias)
+    d_x = dev(req.x)
+    y = torch.empty(cfg.H, dtype=torch.float32, device="cuda")
+
+    ref_eam = req.prefill_eam.astype(np.int64).copy()
+    ref_cache = O.ExpertCache(L, E, S)
+
+    def expert_of(fid):
+        return split_expert(cfg, bank[fid % n_unique])
+
+    def shared_of(layer):
+        return [split_expert(cfg, shared[layer * cfg.n_shared + s]) for s in range(cfg.n_shared)]
+
+    n_miss_total, worst = 0, 0.0
+    for t in tokens:
+        for l in range(L):
+            idx, best, n_miss = m.moe_decode_layer(cache, eamc, d_eam, l, d_routers[l], d_bias[l], d_x[t, l], y)
+            last = cache.last_step()
+            ref = O.decode_layer(T, ref_eam, ref_cache, l, routers[l], req.bias[l], req.x[t, l], expert_of, shared_of,
+                                 k, bool(cfg.renorm), EPS)
+            where = f"token {t} layer {l}"
+            assert idx.tolist() == ref["idx"].tolist(), where
+            np.testing.assert_allclose(last["w"], ref["w"], rtol=1e-4, err_msg=where)
+            assert (d_eam.cpu().numpy() == ref_eam).all(), where
+            assert best == ref["best"], where
+            np.testing.assert_allclose(last["sim"], ref["sim"], rtol=1e-5, err_msg=where)
+            assert last["ev_order"].tolist() == ref["ev_order"], where
+            assert last["pf_order"].tolist() == ref["pf_order"], where
+            np.testing.assert_allclose(last["P"], ref["P"], rtol=1e-6, err_msg=where)
+            np.testing.assert_allclose(last["V"], ref["V"], rtol=1e-6, err_msg=where)
+            assert n_miss == sum(1 for e in ref["events"] if not e[1]), where
+            assert (cache.get_slots() == ref_cache.slot_of).all(), where
+            worst = max(worst, rel_max_err(y.cpu().numpy(), ref["y"]))
+            n_miss_total += n_miss
+    assert cache.error_flags() == 0
+    assert worst <= FFN_TOL_FP32ACC <= FFN_TOL, worst
+    eamc.close()
+    cache.close()
+    return n_miss_total
+
+
+def test_decode_request_tiny_config(m):
+    # configuration 1 as specified: 4 layers x 8 experts, top-2, fp32, 12 of 32 slots, 16 decode tokens
+    cfg = mi.get_config("C1")
+    misses = _replay(m, cfg, cfg.S, cfg.decode, cfg.L * cfg.E, 4)
+    assert misses > 0                                   # the capped cache really evicts
+
+
+@pytest.mark.parametrize("cell_bytes", [4, 2])
+def test_decode_request_reduced_deepseek_shape(m, cell_bytes):
+    # DeepSeek-V2-Lite structure (top-6 of 64 + 2 shared, bf16, 25 % of experts cached), narrow matrices
+    cfg = mi.get_config("C2").scaled(L=6, H=256, I=192, N=120, prompt=64)
+    misses = _replay(m, cfg, (cfg.L * cfg.E) // 4, 10, 48, cell_bytes)
+    assert misses > 0
+
+
+def test_decode_request_reduced_mixtral_shape(m):
+    cfg = mi.get_config("C3").scaled(L=5, H=512, I=1792, N=80, prompt=32)
+    misses = _replay(m, cfg, 15, 10, cfg.L * cfg.E, 4)
+    assert misses > 0
+
+
+def test_async_layer_step_matches_sync_and_flags_a_miss(m):
+    cfg = mi.get_config("C2").scaled(L=3, H=128, I=64, N=40, prompt=16, E=16, k=3)
+    L, E = cfg.L, cfg.E
+    T, _, _ = mi.eamc_traces(cfg, threads=2)
+    req = mi.make_request(cfg, 2, decode=4)
+    bank = mi.expert_bank(cfg, L * E, threads=2)
+    shared = mi.expert_bank(cfg.scaled(cid=77), L * cfg.n_shared, threads=2)
+    desc = m.ModelDesc.from_config(cfg)
+    eamc = m.Eamc(desc, cfg.N)
+    eamc.load(T)
+    outs = {}
+    for mode in ("sync", "async"):
+        cache = m.Cache(desc, L * E, pinned(bank), pinned(shared))
+        cache.reset(L * E)                               # fully resident: no host round trip needed
+        d_eam = dev(req.prefill_eam.astype(np.int32))
+        ys = []
+        for t in range(4):
+            for l in range(L):
+                y = torch.empty(cfg.H, dtype=torch.float32, device="cuda")
+                m.moe_decode_layer(cache, eamc, d_eam, l, dev(mi.router_weights(cfg, l)), dev(req.bias[l]),
+                                   dev(req.x[t, l]), y, sync=(mode == "sync"))
+                ys.append(y)
+        torch.cuda.synchronize()
+        assert cache.error_flags() == 0
+        outs[mode] = (torch.stack(ys).cpu().numpy(), d_eam.cpu().numpy(), cache.last_step())
+        cache.close()
+    assert (outs["sync"][0] == outs["async"][0]).all() and (outs["sync"][1] == outs["async"][1]).all()
+    assert outs["sync"][2]["ev_order"].tolist() == outs["async"][2]["ev_order"].tolist()
+    # a pick that is not resident cannot be served without the host: the flag says so
+    cache = m.Cache(desc, cfg.k, pinned(bank), pinned(shared))
+    cache.reset(0)
+    y = torch.empty(cfg.H, dtype=torch.float32, device="cuda")
+    m.moe_decode_layer(cache, eamc, dev(req.prefill_eam.astype(np.int32)), 0, dev(mi.router_weights(cfg, 0)),
+                       dev(req.bias[0]), dev(req.x[0, 0]), y, sync=False)
+    assert cache.error_flags() & 2
+    cache.close()
+    eamc.close()

@@ -1,0 +1,285 @@
+"""Per-step parity of the HIP path against the CPU oracle, through the C ABI.
+
+Bars: bit-exact for top-k indices, EAM counts, best-match index and the
+prefetch / eviction orders; 1e-5 relative for similarities and gate weights;
+max|y - y_ref| / max|y_ref| <= 2e-2 for FFN outputs (and a much tighter bound that
+fp32 accumulation actually meets, asserted alongside).
+"""
+import numpy as np
+import pytest
+import torch
+
+import moei_inputs as mi
+from oracle import moei_oracle as O
+from tests.helpers import EPS, dev, pinned, rel_max_err, split_expert
+
+pytestmark = pytest.mark.gpu
+
+SIM_RTOL = 1e-5
+FFN_TOL = 2e-2          # stated bar
+FFN_TOL_FP32ACC = 2e-4  # what fp32 accumulation of <= 16K terms of bf16/fp32 products meets
+
+
+@pytest.fixture(scope="module")
+def m():
+    import paper_2401_14361_amd as mod
+    mod.lib()
+    return mod
+
+
+# ----------------------------------------------------------------------- step 1
+@pytest.mark.parametrize("B,E,k,renorm", [
+    (1, 8, 2, True), (5, 64, 6, False), (3, 160, 6, False), (2, 1, 1, True), (4, 7, 7, True),
+    (2, 4096, 8, False), (2, 130, 70, True), (16, 64, 6, True), (0, 8, 2, False),
+])
+def test_route_topk(m, B, E, k, renorm):
+    rng = np.random.default_rng(100 + E + k)
+    z = rng.standard_normal((B, E)).astype(np.float32) * 3
+    if B and E >= 6:
+        z[0, 1] = z[0, 4] = z[0, 5] = z[0].max() + 1          # exact ties in the top set
+    idx, w = m.moe_route_topk(dev(z), k, renorm)
+    torch.cuda.synchronize()
+    if B == 0:
+        return
+    ridx, rw = O.route_topk(z, k, renorm)
+    assert (idx.cpu().numpy() == ridx).all()
+    np.testing.assert_allclose(w.cpu().numpy(), rw, rtol=SIM_RTOL, atol=1e-30)
+
+
+def test_route_topk_all_equal_and_neg_inf(m):
+    z = np.zeros((1, 10), dtype=np.float32)
+    idx, w = m.moe_route_topk(dev(z), 4, False)
+    assert idx.cpu().numpy().tolist() == [[0, 1, 2, 3]]
+    np.testing.assert_allclose(w.cpu().numpy(), 0.1, rtol=1e-6)
+    z = np.array([[0.5, -np.inf, 2.0, -np.inf, 1.0]], dtype=np.float32)
+    idx, w = m.moe_route_topk(dev(z), 4, True)
+    ridx, rw = O.route_topk(z, 4, True)
+    assert (idx.cpu().numpy() == ridx).all()
+    np.testing.assert_allclose(w.cpu().numpy(), rw, rtol=SIM_RTOL)
+
+
+# ----------------------------------------------------------------------- step 2
+def test_eam_update(m):
+    rng = np.random.default_rng(7)
+    B, L, E, k = 3, 5, 11, 4
+    eam = rng.integers(0, 9, size=(B, L, E)).astype(np.int32)
+    d_eam = dev(eam)
+    ref = eam.astype(np.int64)
+    for step in range(12):
+        layer = step % L
+        idx = np.stack([rng.choice(E, size=k, replace=False) for _ in range(B)]).astype(np.int32)
+        m.eam_update(d_eam, layer, dev(idx))
+        for b in range(B):
+            O.eam_update(ref[b], layer, idx[b])
+    assert (d_eam.cpu().numpy() == ref).all()
+    with pytest.raises(m.MoeiError):
+        m.eam_update(d_eam, L, dev(idx))
+
+
+# ----------------------------------------------------------------------- step 3
+def _check_match(m, T, Q, cell_bytes, layer_hi=None):
+    N, L, E = T.shape
+    desc = m.ModelDesc(L, E, 1, 0, 8, 8, m.WDTYPE_BF16, 0, EPS)
+    eamc = m.Eamc(desc, max(N, 1) + 3, cell_bytes)       # capacity above N: the stride is not N
+    eamc.load(T)
+    best, sim, sims = m.eamc_match(eamc, dev(Q.astype(np.int32)), layer_hi=layer_hi, want_sims=True)
+    torch.cuda.synchronize()
+    best, sim, sims = best.cpu().numpy(), sim.cpu().numpy(), sims.cpu().numpy()
+    for b in range(Q.shape[0]):
+        rb, rs, rsims = O.eamc_match(T, Q[b])
+        assert best[b] == rb, (b, best[b], rb)
+        np.testing.assert_allclose(sims[b], rsims, rtol=SIM_RTOL, atol=1e-30)
+        np.testing.assert_allclose(sim[b], rs, rtol=SIM_RTOL, atol=1e-30)
+    eamc.close()
+
+
+@pytest.mark.parametrize("N,L,E", [(64, 4, 8), (1000, 26, 64), (37, 3, 6), (1, 1, 1), (300, 5, 160),
+                                   (513, 7, 12), (70, 2, 2048), (9, 33, 100)])
+@pytest.mark.parametrize("cell_bytes", [4, 2])
+def test_eamc_match_shapes(m, N, L, E, cell_bytes):
+    rng = np.random.default_rng(N * 7 + E)
+    T = (rng.integers(0, 600, size=(N, L, E)) * (rng.random((N, L, E)) < 0.4)).astype(np.int32)
+    Q = (rng.integers(0, 100, size=(3, L, E)) * (rng.random((3, L, E)) < 0.5)).astype(np.int32)
+    if N > 6:
+        T[5] = 3 * T[2]                                   # exact tie between traces 2 and 5
+        Q[1] = T[2] * 2
+        T[4] = 0                                          # an empty trace
+    Q[2] = 0                                              # an empty query
+    _check_match(m, T, Q, cell_bytes)
+
+
+def test_eamc_match_workload_traces_and_partial_rows(m):
+    cfg = mi.get_config("C2").scaled(N=300)
+    T, _, _ = mi.eamc_traces(cfg)
+    req = mi.make_request(cfg, 1, decode=1)
+    Q = np.stack([req.prefill_eam, T[17], req.prefill_eam // 3])
+    _check_match(m, T, Q, 4)
+    _check_match(m, T, Q, 2)
+    # iteration-level reading (Sec. 4.3): rows above the current layer are zero and are not scanned
+    Qp = Q.copy()
+    Qp[:, 9:] = 0
+    _check_match(m, T, Qp, 4, layer_hi=8)
+    _check_match(m, T, Qp, 2, layer_hi=8)
+
+
+def test_eamc_match_large_counts_and_empty_collection(m):
+    rng = np.random.default_rng(3)
+    T = rng.integers(0, 16777215, size=(40, 3, 16), dtype=np.int64).astype(np.int32)
+    Q = rng.integers(0, 16777215, size=(2, 3, 16), dtype=np.int64).astype(np.int32)
+    _check_match(m, T, Q, 4)
+    desc = m.ModelDesc(3, 16, 1, 0, 8, 8, m.WDTYPE_BF16, 0, EPS)
+    eamc = m.Eamc(desc, 5, 4)
+    best, sim, _ = m.eamc_match(eamc, dev(Q), want_sims=True)
+    assert best.cpu().numpy().tolist() == [-1, -1] and sim.cpu().numpy().tolist() == [0.0, 0.0]
+    bad = T.copy(); bad[3, 1, 2] = -1
+    with pytest.raises(m.MoeiError):
+        eamc.load(bad[:5])
+    assert eamc.size == 0
+
+
+def test_eamc_insert_replace_and_export(m):
+    # App. B.1: at capacity the incoming EAM replaces the stored one it is most similar to
+    rng = np.random.default_rng(5)
+    L, E, cap = 4, 8, 6
+    desc = m.ModelDesc(L, E, 1, 0, 8, 8, m.WDTYPE_BF16, 0, EPS)
+    for cb in (4, 2):
+        eamc = m.Eamc(desc, cap, cb)
+        ref = []
+        for t in range(10):
+            eam = rng.integers(0, 50, size=(L, E)).astype(np.int32)
+            if len(ref) < cap:
+                eamc.insert(eam)
+                ref.append(eam)
+            else:
+                best, _, _ = m.eamc_match(eamc, dev(eam))
+                victim = int(best.cpu()[0])
+                assert victim == O.eamc_match(np.stack(ref), eam)[0]
+                eamc.insert(eam, victim)
+                ref[victim] = eam
+            assert (eamc.export() == np.stack(ref)).all()
+        q = rng.integers(0, 50, size=(L, E)).astype(np.int32)
+        best, _, _ = m.eamc_match(eamc, dev(q))
+        assert int(best.cpu()[0]) == O.eamc_match(np.stack(ref), q)[0]
+        # failure recovery: a reloaded dump matches identically
+        e2 = m.Eamc(desc, cap, cb)
+        e2.load(eamc.export())
+        b2, s2, _ = m.eamc_match(e2, dev(q))
+        assert int(b2.cpu()[0]) == int(best.cpu()[0])
+
+
+# ----------------------------------------------------------------------- step 4
+@pytest.mark.parametrize("N,L,E,B,cb", [(20, 4, 8, 1, 4), (50, 26, 64, 1, 2), (30, 7, 13, 3, 4), (5, 1, 5, 1, 4),
+                                        (12, 59, 160, 2, 2)])
+def test_expert_priority(m, N, L, E, B, cb):
+    rng = np.random.default_rng(N + L + E)
+    T = (rng.integers(0, 400, size=(N, L, E)) * (rng.random((N, L, E)) < 0.5)).astype(np.int32)
+    T[:, L // 2] = 0 if L > 2 else T[:, L // 2]           # an empty row in every trace
+    if N > 3:
+        T[2] = T[1]                                       # identical traces: exact score ties across...
+    k = min(3, E)
+    desc = m.ModelDesc(L, E, k, 0, 8, 8, m.WDTYPE_BF16, 0, EPS)
+    eamc = m.Eamc(desc, N, cb)
+    eamc.load(T)
+    for trial in range(4):
+        best = rng.integers(-1 if trial == 3 else 0, N, size=B).astype(np.int32)
+        cur = int(rng.integers(-1, L))
+        res = rng.random((L, E)) < 0.4
+        slot_of = np.where(res.reshape(-1), np.arange(L * E), -1).astype(np.int32)
+        cur_idx = None
+        excl = []
+        if cur >= 0:
+            cur_idx = np.stack([rng.choice(E, size=k, replace=False) for _ in range(B)]).astype(np.int32)
+            excl = [cur * E + int(j) for j in cur_idx.reshape(-1)]
+        out = m.expert_priority(eamc, dev(best), cur, dev(slot_of), EPS,
+                                dev(cur_idx) if cur_idx is not None else None)
+        torch.cuda.synchronize()
+        P, V, pf, n_pf, ev, n_ev = [o.cpu().numpy() for o in out]
+        tstar = O.aggregate_matches(T, best)
+        rP, rV, rpf, rev = O.expert_priority(tstar, cur, res, EPS, excl)
+        assert int(n_pf[0]) == len(rpf) and int(n_ev[0]) == len(rev)
+        assert pf[:len(rpf)].tolist() == rpf
+        assert ev[:len(rev)].tolist() == rev
+        np.testing.assert_allclose(P, rP, rtol=1e-6, atol=0)
+        np.testing.assert_allclose(V, rV, rtol=1e-6, atol=0)
+
+
+def test_expert_priority_worked_example(m):
+    # Sec. 4.7 example: EAM [[1,2],[0,3],[0,3]]; E[2,2] (0-based (1,1)) is kept, (1,0) and (2,0) go first
+    T = np.array([[[1, 2], [0, 3], [0, 3]]], dtype=np.int32)
+    desc = m.ModelDesc(3, 2, 1, 0, 8, 8, m.WDTYPE_BF16, 0, EPS)
+    eamc = m.Eamc(desc, 1, 4)
+    eamc.load(T)
+    slot_of = np.arange(6, dtype=np.int32)
+    out = m.expert_priority(eamc, dev(np.zeros(1, np.int32)), 0, dev(slot_of), EPS)
+    ev = out[4].cpu().numpy()[:int(out[5].cpu()[0])].tolist()
+    assert ev == [4, 2, 5, 0, 3, 1]
+    out = m.expert_priority(eamc, dev(np.zeros(1, np.int32)), 0, dev(np.full(6, -1, np.int32)), EPS)
+    assert out[2].cpu().numpy()[:int(out[3].cpu()[0])].tolist() == [3, 5]
+
+
+# ----------------------------------------------------------------------- step 5
+def _ffn_case(m, cfg, n_unique, slot_pick, gates, seed, n_slots=None):
+    bank = mi.expert_bank(cfg, n_unique, threads=4)
+    S = n_slots or n_unique
+    desc = m.ModelDesc.from_config(cfg)
+    cache = m.Cache(desc, S)
+    for s in range(min(S, n_unique)):
+        cache.slot_tensor(s).copy_(dev(bank[s]).view(cache.slot_tensor(s).dtype))
+    n_sh = cfg.L * cfg.n_shared
+    sh = mi.expert_bank(cfg.scaled(cid=cfg.cid + 50), max(n_sh, 1), threads=2)
+    for s in range(n_sh):
+        cache.slot_tensor(S + s).copy_(dev(sh[s]).view(cache.slot_tensor(S + s).dtype))
+    rng = np.random.default_rng(seed)
+    x = mi.to_store(cfg, rng.standard_normal(cfg.H).astype(np.float32))
+    y = m.expert_ffn_gemv(cache, dev(np.asarray(slot_pick, np.int32)), dev(np.asarray(gates, np.float32)), dev(x))
+    torch.cuda.synchronize()
+
+    def weights(s):
+        return split_expert(cfg, bank[s] if s < S else sh[s - S])
+
+    ref = O.expert_ffn(x, [weights(s) for s in slot_pick], gates)
+    err = rel_max_err(y.cpu().numpy(), ref)
+    assert cache.error_flags() == 0
+    return err, cache
+
+
+@pytest.mark.parametrize("wdtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("H,I", [(256, 512), (2048, 1408), (200, 136), (100, 52), (520, 4104), (64, 9000)])
+def test_expert_ffn_shapes(m, wdtype, H, I):
+    cfg = mi.get_config("C1").scaled(H=H, I=I, wdtype=wdtype, L=2, n_shared=1, k=3, E=8)
+    err, cache = _ffn_case(m, cfg, 5, [3, 0, 4, 5 + 1], [0.5, 0.3, 0.2, 1.0], seed=H + I)
+    assert err <= FFN_TOL_FP32ACC <= FFN_TOL, err
+    cache.close()
+
+
+def test_expert_ffn_edge_cases(m):
+    cfg = mi.get_config("C1").scaled(H=128, I=256, wdtype="bf16", L=1, n_shared=0, k=2, E=4)
+    err, cache = _ffn_case(m, cfg, 3, [1], [1.0], seed=1)
+    assert err <= FFN_TOL_FP32ACC
+    x = dev(mi.to_store(cfg, np.ones(cfg.H, np.float32)))
+    # no active expert: y = 0
+    y = m.expert_ffn_gemv(cache, dev(np.zeros(0, np.int32)), dev(np.zeros(0, np.float32)), x)
+    assert (y.cpu().numpy() == 0).all()
+    # a slot id outside the pool contributes nothing and raises the flag
+    y_ok = m.expert_ffn_gemv(cache, dev(np.array([2], np.int32)), dev(np.array([0.7], np.float32)), x).cpu().numpy()
+    y_bad = m.expert_ffn_gemv(cache, dev(np.array([2, 99], np.int32)), dev(np.array([0.7, 1.0], np.float32)), x).cpu().numpy()
+    assert (y_ok == y_bad).all()
+    assert cache.error_flags() & 1
+    assert cache.error_flags() == 0
+    with pytest.raises(m.MoeiError):
+        m.expert_ffn_gemv(cache, dev(np.zeros(3, np.int32)), dev(np.zeros(3, np.float32)), x)
+    # deterministic: repeated runs give identical bits
+    ids, g = dev(np.array([0, 1], np.int32)), dev(np.array([0.4, 0.6], np.float32))
+    y0 = m.expert_ffn_gemv(cache, ids, g, x).cpu().numpy()
+    for _ in range(20):
+        assert (m.expert_ffn_gemv(cache, ids, g, x).cpu().numpy() == y0).all()
+    cache.close()
+
+
+def test_expert_ffn_full_deepseek_v2_lite_layer(m):
+    # the benchmark shape: 6 routed + 2 shared experts of 2048 x 1408, bf16
+    cfg = mi.get_config("C2").scaled(L=1)
+    err, cache = _ffn_case(m, cfg, 7, [5, 0, 3, 6, 1, 2, 7, 8], [0.21, 0.18, 0.12, 0.09, 0.07, 0.05, 1.0, 1.0],
+                           seed=2, n_slots=7)
+    assert err <= FFN_TOL_FP32ACC, err
+    cache.close()
