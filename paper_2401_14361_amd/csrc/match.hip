@@ -474,6 +474,8 @@ extern "C" int eamc_match(const moei_eamc* c, const int32_t* d_eam, int32_t B, i
     if (c->N > 0) {
         Plan p = make_plan(c, layer_hi + 1);
         n_lsplit = p.n_lsplit;
+        if (p.n_lsplit > c->lsplit_max || p.smem > 64 * 1024)
+            MOEI_FAIL(MOEI_ECAPACITY, "eamc_match: L*E = %d is too large for the match kernel's LDS staging", L * E);
         DotArgs a{c->d_traces, d_eam, c->d_part, c->n_cap, c->N, L, E, layer_hi + 1, p.lper, p.n_lsplit, p.TN, p.rowV};
         dim3 grid(p.n_tiles, p.n_lsplit, B);
         int rc;

@@ -260,11 +260,11 @@ using namespace moei;
 
 extern "C" int moe_route_topk(const float* d_logits, int32_t B, int32_t E, int32_t k, int32_t renorm, int32_t* d_idx,
                               float* d_w, void* stream) {
-    MOEI_REQUIRE(d_logits && d_idx && d_w, "moe_route_topk: null pointer");
     MOEI_REQUIRE(B >= 0, "moe_route_topk: B = %d is negative", B);
     MOEI_REQUIRE(E >= 1 && E <= kMaxE, "moe_route_topk: E = %d outside [1, %d]", E, kMaxE);
     MOEI_REQUIRE(k >= 1 && k <= E, "moe_route_topk: k = %d outside [1, E = %d]", k, E);
-    if (B == 0) return MOEI_OK;
+    if (B == 0) return MOEI_OK;  // nothing to route: the (empty) buffers may be null
+    MOEI_REQUIRE(d_logits && d_idx && d_w, "moe_route_topk: null pointer");
     hipStream_t s = as_stream(stream);
     if (k <= kWave)
         route_topk_kernel<<<B, kWave, E * sizeof(float), s>>>(d_logits, E, k, renorm != 0, d_idx, d_w);
@@ -276,11 +276,11 @@ extern "C" int moe_route_topk(const float* d_logits, int32_t B, int32_t E, int32
 
 extern "C" int eam_update(int32_t* d_eam, int32_t B, int32_t L, int32_t E, int32_t layer, const int32_t* d_idx,
                           int32_t k, void* stream) {
-    MOEI_REQUIRE(d_eam && d_idx, "eam_update: null pointer");
     MOEI_REQUIRE(B >= 0 && L >= 1 && E >= 1 && k >= 1 && k <= E, "eam_update: bad shape B=%d L=%d E=%d k=%d", B, L, E,
                  k);
     MOEI_REQUIRE(layer >= 0 && layer < L, "eam_update: layer %d outside [0, %d)", layer, L);
     if (B == 0) return MOEI_OK;
+    MOEI_REQUIRE(d_eam && d_idx, "eam_update: null pointer");
     int n = B * k;
     eam_update_kernel<<<(n + 255) / 256, 256, 0, as_stream(stream)>>>(d_eam, B, L, E, layer, d_idx, k);
     MOEI_LAUNCH_CHECK();
