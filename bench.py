@@ -1,0 +1,328 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE decode layer step on one MI355X.
+
+A "step" is one pass of the whole hot path for one MoE layer of one decode token:
+router top-k, EAM update, EAMC match, priorities, slot lookup and the expert FFNs.
+The default workload is the DeepSeek-V2-Lite-shaped configuration (C2): 26 layers,
+64 routed experts top-6 + 2 shared, hidden 2048, intermediate 1408, bf16 weights,
+EAMC of 1,000 traces, one request of 128 decode tokens.
+
+Legs (all in this one process, so one rocprofv3 run covers them):
+  1. resident replay (value): every expert in HBM, asynchronous layer steps, wall time
+     over exactly --steps steps after --warmup steps;
+  2. the same steps again with a start/stop HIP event pair on every kernel launch:
+     average launch duration per kernel -> the roofline object (dominant kernel);
+  3. eamc_match and expert_ffn_gemv on their own (traces/s, GB/s);
+  4. offload replay: cache capped at 25 % of the routed experts, misses filled from
+     pinned host memory (PCIe-inclusive, reported beside, never as `value`);
+  5. the CPU oracle timed on a bounded sample of the same steps.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None, help="layer steps timed (default: one request's decode, tokens*L)")
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4"])
+    ap.add_argument("--unique", type=int, default=16, help="distinct experts drawn on the host; slots repeat them")
+    ap.add_argument("--offload-tokens", type=int, default=12)
+    ap.add_argument("--cpu-steps", type=int, default=None, help="oracle layer steps timed (default: sized to ~15 s)")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-offload", action="store_true")
+    ap.add_argument("--no-graph", action="store_true")
+    return ap.parse_args()
+
+
+def read_traffic(kernel: str, workload: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    p = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_hbm_traffic.txt")
+    if not os.path.exists(p):
+        return None
+    for line in open(p):
+        if line.startswith("traffic_bytes_per_launch="):
+            return float(line.split("=", 1)[1])
+    return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import moei_inputs as mi
+    import paper_2401_14361_amd as m
+    from tests.helpers import EPS, dev, pack_bank, pinned, split_expert
+
+    if not os.path.exists(m.lib_path()):
+        from paper_2401_14361_amd.build import build
+        build()
+    m.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    cfg = mi.get_config(args.config)
+    L, E, k, H, I = cfg.L, cfg.E, cfg.k, cfg.H, cfg.I
+    n_act = k + cfg.n_shared
+    T_dec = cfg.decode
+    K = args.steps if args.steps is not None else T_dec * L
+    W = args.warmup if args.warmup is not None else 4 * L
+    t_setup = time.time()
+
+    # ------------------------------------------------------------------ inputs
+    log(f"[bench] {cfg.name}: L={L} E={E} k={k}+{cfg.n_shared} H={H} I={I} {cfg.wdtype} N={cfg.N}")
+    traces, _, _ = mi.eamc_traces(cfg, threads=8)
+    req = mi.make_request(cfg, 0)
+    n_unique = min(args.unique, L * E)
+    bank = mi.expert_bank(cfg, n_unique, threads=8)
+    shared = mi.expert_bank(cfg.scaled(cid=cfg.cid + 50), max(min(L * cfg.n_shared, 4), 1), threads=4)
+    routers = [dev(mi.router_weights(cfg, l)) for l in range(L)]
+    d_bias = dev(req.bias)
+    d_x = dev(req.x)
+    desc = m.ModelDesc.from_config(cfg)
+    eamc = m.Eamc(desc, cfg.N, 4)
+    eamc.load(traces)
+    log(f"[bench] inputs drawn in {time.time() - t_setup:.1f}s")
+
+    # resident pool: every routed expert has a slot (MI355X holds the whole model's experts)
+    S_res = L * E if args.config != "C4" else cfg.S
+    cache = m.Cache(desc, S_res)
+    bank_slots, shared_slots = pack_bank(m, cfg, bank), pack_bank(m, cfg, shared)     # slot layout
+    d_bank = [dev(bank_slots[u]) for u in range(n_unique)]
+    d_shared = [dev(shared_slots[u]) for u in range(shared.shape[0])]
+    for s in range(S_res):
+        t = cache.slot_tensor(s)
+        t.copy_(d_bank[s % n_unique].view(t.dtype))
+    for s in range(L * cfg.n_shared):
+        t = cache.slot_tensor(S_res + s)
+        t.copy_(d_shared[s % len(d_shared)].view(t.dtype))
+    cache.reset(min(S_res, L * E))          # marks flat ids 0..S-1 resident (no host copy: nothing is moved)
+    torch.cuda.synchronize()
+    d_eam = dev(req.prefill_eam.astype(np.int32))
+    prefill = d_eam.clone()
+    y = torch.empty(H, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def layer_step(i, sync=False, c=cache):
+        t, l = (i // L) % T_dec, i % L
+        return m.moe_decode_layer(c, eamc, d_eam, l, routers[l], d_bias[l], d_x[t, l], y, sync=sync, stream=stream)
+
+    # ------------------------------------------------ leg 1: resident replay, wall clock
+    for i in range(W):
+        layer_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        layer_step(W + i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    us_step = wall / K * 1e6
+    flags = cache.error_flags()
+    assert flags == 0, f"device error flags {flags}"
+    log(f"[bench] resident replay: {us_step:.1f} us per layer step ({K} steps)")
+
+    # ------------------------------------------------ leg 2: per-kernel durations (HIP events)
+    d_eam.copy_(prefill)
+    n_prof = min(K, 40 * L)
+    m.profile_enable(n_prof * 12)
+    for i in range(n_prof):
+        layer_step(W + i)
+    torch.cuda.synchronize()
+    prof = m.profile_read()
+    m.profile_disable()
+    kern = {name: dict(launches=n, avg_us=(ms / n * 1e3 if n else None)) for name, (n, ms) in prof.items()}
+    wb = cfg.wbytes
+    alg_bytes = {
+        "ffn_fused_kernel": n_act * 3 * H * I * wb,
+        "eamc_dot_kernel": cfg.N * L * E * 4,
+        "router_gemv_kernel": E * H * wb,
+    }
+    for name, b in alg_bytes.items():
+        if kern.get(name, {}).get("avg_us"):
+            kern[name]["alg_bytes"] = b
+            kern[name]["GBps"] = b / kern[name]["avg_us"] / 1e3
+    dom = max((n for n in kern if kern[n]["avg_us"]), key=lambda n: kern[n]["avg_us"] * kern[n]["launches"])
+    achieved = kern[dom].get("GBps")
+    roofline = {
+        "bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": (achieved / HBM_PEAK_GBPS) if achieved else None,
+        "alg_bytes_per_launch": kern[dom].get("alg_bytes"), "avg_launch_us": kern[dom]["avg_us"],
+        "traffic": read_traffic(dom, cfg.name),
+    }
+    ffn_us = sum(kern[n]["avg_us"] or 0 for n in ("ffn_fused_kernel", "ffn_reduce_kernel"))
+    ffn_bytes = n_act * 3 * H * I * wb
+    log(f"[bench] kernels: " + ", ".join(f"{n}={v['avg_us']:.2f}us" for n, v in kern.items() if v["avg_us"]))
+
+    # ------------------------------------------------ leg 3: steps on their own
+    extra = {}
+    # eamc_match alone (launch-inclusive: both of its kernels, back to back)
+    reps = 200
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(10):
+        m.eamc_match(eamc, d_eam, stream=stream)
+    ev0.record(stream)
+    for _ in range(reps):
+        m.eamc_match(eamc, d_eam, stream=stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    match_us = ev0.elapsed_time(ev1) / reps * 1e3
+    extra["eamc_match"] = {
+        "N": cfg.N, "us_per_match": match_us, "traces_per_s": cfg.N / match_us * 1e6,
+        "alg_bytes": cfg.N * L * E * 4 + cfg.N * 8, "GBps": (cfg.N * L * E * 4 + cfg.N * 8) / match_us / 1e3,
+        "note": "scan smaller than launch latency and the 256 MB last-level cache: not an HBM measurement",
+    }
+    # the same shape with the collection grown until the scan cannot stay in cache (> 512 MB)
+    big_n = int(np.ceil(640e6 / (L * E * 4) / cfg.N)) * cfg.N
+    big = np.tile(traces, (big_n // cfg.N, 1, 1))
+    eamc_big = m.Eamc(desc, big_n, 4)
+    eamc_big.load(big)
+    del big
+    for _ in range(3):
+        m.eamc_match(eamc_big, d_eam, stream=stream)
+    m.profile_enable(64)
+    for _ in range(20):
+        m.eamc_match(eamc_big, d_eam, stream=stream)
+    torch.cuda.synchronize()
+    pb = m.profile_read()
+    m.profile_disable()
+    dot_us = pb["eamc_dot_kernel"][1] / pb["eamc_dot_kernel"][0] * 1e3
+    arg_us = pb["eamc_argmax_kernel"][1] / pb["eamc_argmax_kernel"][0] * 1e3
+    big_bytes = big_n * L * E * 4
+    extra["eamc_match_hbm_bound"] = {
+        "N": big_n, "dot_kernel_us": dot_us, "argmax_kernel_us": arg_us, "alg_bytes": big_bytes,
+        "GBps": big_bytes / dot_us / 1e3, "frac_of_peak": big_bytes / dot_us / 1e3 / HBM_PEAK_GBPS,
+        "traces_per_s": big_n / (dot_us + arg_us) * 1e6,
+        "note": f"the {cfg.N} traces tiled {big_n // cfg.N}x so that the scan ({big_bytes / 1e6:.0f} MB) exceeds the cache",
+    }
+    eamc_big.close()
+    # expert_ffn_gemv alone over rotating slots (launch-inclusive)
+    rng = np.random.default_rng(0)
+    n_sets = 64
+    slot_sets = [dev(np.concatenate([rng.choice(S_res, size=k, replace=False),
+                                     S_res + (s % L) * cfg.n_shared + np.arange(cfg.n_shared)]).astype(np.int32))
+                 for s in range(n_sets)]
+    gates = dev(np.full(n_act, 0.125, np.float32))
+    for s in range(8):
+        m.expert_ffn_gemv(cache, slot_sets[s], gates, d_x[0, 0], stream=stream, out=y)
+    ev0.record(stream)
+    for r in range(reps):
+        m.expert_ffn_gemv(cache, slot_sets[r % n_sets], gates, d_x[0, 0], stream=stream, out=y)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    gemv_us = ev0.elapsed_time(ev1) / reps * 1e3
+    extra["expert_ffn_gemv"] = {
+        "us_per_call": gemv_us, "alg_bytes": ffn_bytes, "GBps_launch_inclusive": ffn_bytes / gemv_us / 1e3,
+        "GBps_kernels_only": ffn_bytes / ffn_us / 1e3, "frac_of_peak_kernels_only": ffn_bytes / ffn_us / 1e3 / HBM_PEAK_GBPS,
+        "frac_of_peak_launch_inclusive": ffn_bytes / gemv_us / 1e3 / HBM_PEAK_GBPS,
+    }
+    log(f"[bench] match {match_us:.1f} us; big-N dot {dot_us:.1f} us = {big_bytes / dot_us / 1e3:.0f} GB/s; "
+        f"gemv {gemv_us:.1f} us = {ffn_bytes / gemv_us / 1e3:.0f} GB/s")
+
+    # ------------------------------------------------ leg 4: offload replay (capped cache, PCIe misses)
+    if not args.no_offload and cfg.S < L * E:
+        host_bank = pinned(bank_slots)
+        oc = m.Cache(desc, cfg.S, host_bank, None)
+        for s in range(L * cfg.n_shared):
+            t = oc.slot_tensor(cfg.S + s)
+            t.copy_(d_shared[s % len(d_shared)].view(t.dtype))
+        oc.reset(cfg.S)
+        d_eam.copy_(prefill)
+        n_off = args.offload_tokens * L
+        per = []
+        for i in range(n_off):
+            torch.cuda.synchronize()
+            a = time.perf_counter()
+            idx, best, n_miss = layer_step(i, sync=True, c=oc)
+            torch.cuda.synchronize()
+            per.append((time.perf_counter() - a, n_miss))
+        hit_steps = [t for t, nm in per if nm == 0]
+        miss_steps = [(t, nm) for t, nm in per if nm > 0]
+        tot_miss = sum(nm for _, nm in per)
+        extra["offload"] = {
+            "slots": cfg.S, "layer_steps": n_off, "hit_rate": 1.0 - tot_miss / (n_off * k),
+            "us_per_step_blended": sum(t for t, _ in per) / n_off * 1e6,
+            "us_per_step_all_hit": (sum(hit_steps) / len(hit_steps) * 1e6) if hit_steps else None,
+            "all_hit_steps": len(hit_steps),
+            "us_per_step_with_miss": (sum(t for t, _ in miss_steps) / len(miss_steps) * 1e6) if miss_steps else None,
+            "host_link_GBps": (tot_miss * cfg.expert_bytes / sum(t for t, _ in miss_steps) / 1e9) if miss_steps else None,
+            "note": "synchronous steps, each timed from the host; misses copied from pinned host memory",
+        }
+        log(f"[bench] offload: hit rate {extra['offload']['hit_rate']:.3f}, "
+            f"{extra['offload']['us_per_step_blended']:.0f} us/step blended")
+        oc.close()
+
+    # ------------------------------------------------ leg 5: CPU oracle on a bounded sample
+    cpu = None
+    if not args.no_cpu:
+        from oracle import moei_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            threads = 1
+        ref_eam = req.prefill_eam.astype(np.int64).copy()
+        ref_cache = O.ExpertCache(L, E, L * E)
+        h_routers = [mi.router_weights(cfg, l) for l in range(L)]
+
+        def expert_of(fid):
+            return split_expert(cfg, bank[fid % n_unique])
+
+        def shared_of(layer):
+            return [split_expert(cfg, shared[(layer * cfg.n_shared + s) % shared.shape[0]]) for s in range(cfg.n_shared)]
+
+        n_cpu, spent = 0, 0.0
+        budget = 15.0
+        limit = args.cpu_steps if args.cpu_steps is not None else 10 ** 9
+        while n_cpu < limit and (spent < budget or n_cpu < 2):
+            l = n_cpu % L
+            a = time.perf_counter()
+            O.decode_layer(traces, ref_eam, ref_cache, l, h_routers[l], req.bias[l], req.x[n_cpu // L, l], expert_of,
+                           shared_of, k, bool(cfg.renorm), EPS)
+            spent += time.perf_counter() - a
+            n_cpu += 1
+        cpu = {"value": spent / n_cpu * 1e6, "unit": "us per MoE-layer decode step", "cores": threads, "kind": "oracle",
+               "sample": f"first {n_cpu} layer steps of the same request (all experts resident), {spent:.1f} s of CPU time"}
+        log(f"[bench] oracle: {cpu['value'] / 1e3:.0f} ms per layer step on {threads} thread(s)")
+
+    out = {
+        "metric": "us per MoE-layer decode step (EAMC traces scanned/s and expert GEMV HBM GB/s in `extra`)",
+        "value": us_step, "unit": "us", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": us_step / 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 weights, fp32 accumulate" if cfg.wdtype == "bf16" else "fp32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {L} MoE layers x {E} experts top-{k} + {cfg.n_shared} shared, H={H}, I={I}, "
+                               f"{cfg.wdtype}; EAMC {cfg.N} traces; batch 1, {T_dec} decode tokens; all experts resident "
+                               f"in HBM ({S_res} slots, {n_unique} distinct weight sets repeated)",
+                   "mode": "asynchronous layer steps"},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": kern,
+        "extra": extra,
+        "context": {"paper_tpot_ms_deepseek_v2_lite_a5000": 155, "paper_match_us_1k_cpu": 21, "paper_match_us_10k_cpu": 226},
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -124,11 +124,13 @@ int expert_priority(const moei_eamc* c, const int32_t* d_best, int32_t B, int32_
 
 /* --------------------------------------------------------- expert cache (Sec. 4.7, Alg. 1)
  * A pool of n_slots cache slots in HBM for routed experts plus L*n_shared pinned
- * slots for the always-on shared experts.  One slot holds one expert, contiguous:
- * W_gate[I][H], W_up[I][H], W_down[H][I] in desc->wdtype.
+ * slots for the always-on shared experts.  One slot holds one expert of 3*H*I elements
+ * in desc->wdtype, interleaved by intermediate unit so that the FFN is one stream:
+ *   for i in 0..I-1:  W_gate[i][0..H) | W_up[i][0..H) | W_down[0..H)[i]
+ * (moei_expert_pack builds this from the three plain matrices).
  * Slot ids: 0..n_slots-1 routed, n_slots + layer*n_shared + s shared.
- * h_experts: host copy of the routed experts (pinned memory for asynchronous fills),
- *   n_host_experts rows of 3*H*I elements; expert (l, j) is row (l*E + j) %
+ * h_experts: host copy of the routed experts in slot layout (pinned memory for
+ *   asynchronous fills), n_host_experts rows of 3*H*I elements; expert (l, j) is row (l*E + j) %
  *   n_host_experts.  NULL = no host copy: slots are filled by the caller
  *   (moei_cache_slot_ptr) and a miss is an error.
  * h_shared: [L*n_shared][3*H*I] or NULL (then shared slots are left for the caller).
@@ -137,6 +139,10 @@ int moei_cache_create(const moei_model_desc* desc, int32_t n_slots,
                       const void* h_experts, int32_t n_host_experts, const void* h_shared,
                       moei_cache** out);
 int moei_cache_destroy(moei_cache* c);
+/* Slot layout of one expert from W_gate[I][H], W_up[I][H], W_down[H][I] (all host memory,
+ * desc->wdtype elements); h_slot receives 3*H*I elements.  Pure data movement. */
+int moei_expert_pack(const moei_model_desc* desc, const void* h_gate, const void* h_up, const void* h_down,
+                     void* h_slot);
 /* Initial residency: n_resident (<= n_slots, <= L*E) experts with flat ids
  * 0..n_resident-1 in slots of the same number, the rest free.  Copies them from
  * h_experts when there is one.  Synchronous. */
@@ -161,7 +167,7 @@ int moei_cache_retrieve(moei_cache* c, int32_t layer, const int32_t* h_idx, int3
 /* Step 5, expert FFN (Sec. 2; SwiGLU):
  *   y = sum_e w_e * W_down,e ( silu(W_gate,e x) * (W_up,e x) ),  silu(g) = g / (1 + exp(-g))
  * over the n_act slots d_slot_ids[n_act] with weights d_gate_w[n_act]; weights are
- * streamed from the slot pool, sums are fp32.  d_x[H] in desc->wdtype, d_y[H] fp32.
+ * streamed once from the slot pool, sums are fp32 and bit-reproducible run to run.  d_x[H] in desc->wdtype, d_y[H] fp32.
  * A slot id outside the pool contributes nothing and raises the cache's error flag.
  * n_act <= k + n_shared. */
 int expert_ffn_gemv(moei_cache* c, const int32_t* d_slot_ids, const float* d_gate_w,
@@ -194,6 +200,19 @@ int moei_cache_last_step(moei_cache* c, float* h_gate_w, float* h_best_sim,
                          float* h_prefetch, float* h_evict,
                          int32_t* h_pf_order, int32_t* h_n_pf, int32_t* h_ev_order, int32_t* h_n_ev,
                          void* stream);
+
+/* ------------------------------------------------------------------ kernel timing (diagnostic)
+ * While enabled, every kernel launch of the library carries a start and a stop HIP event
+ * that the runtime stamps with the kernel's own begin and end on its stream (at most
+ * max_samples launches are recorded, later ones are not timed).  moei_profile_read
+ * synchronises the device and returns, for kernel `id` (0 <= id <
+ * moei_profile_kernels()), the number of recorded launches and the sum of their
+ * start-to-stop durations in milliseconds.  Not thread-safe. */
+int moei_profile_enable(int32_t max_samples);
+int moei_profile_disable(void);
+int moei_profile_kernels(void);
+const char* moei_profile_kernel_name(int32_t id);
+int moei_profile_read(int32_t id, double* total_ms, int32_t* count);
 
 #ifdef __cplusplus
 }

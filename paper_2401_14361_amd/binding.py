@@ -16,7 +16,7 @@ import torch
 __all__ = [
     "MoeiError", "ModelDesc", "lib", "lib_path", "Eamc", "Cache",
     "moe_route_topk", "eam_update", "eamc_match", "expert_priority", "expert_ffn_gemv", "moe_decode_layer",
-    "WDTYPE_FP32", "WDTYPE_BF16", "EXPORTS",
+    "WDTYPE_FP32", "WDTYPE_BF16", "EXPORTS", "expert_pack", "profile_enable", "profile_disable", "profile_read",
 ]
 
 WDTYPE_FP32, WDTYPE_BF16 = 0, 1
@@ -26,9 +26,11 @@ EXPORTS = [
     "moei_last_error", "moei_version",
     "moei_eamc_create", "moei_eamc_load", "moei_eamc_insert", "moei_eamc_export", "moei_eamc_size", "moei_eamc_destroy",
     "moe_route_topk", "eam_update", "eamc_match", "expert_priority",
-    "moei_cache_create", "moei_cache_destroy", "moei_cache_reset", "moei_cache_slot_ptr", "moei_cache_slot_table",
+    "moei_cache_create", "moei_cache_destroy", "moei_expert_pack", "moei_cache_reset", "moei_cache_slot_ptr", "moei_cache_slot_table",
     "moei_cache_get_slots", "moei_cache_retrieve", "expert_ffn_gemv", "moei_cache_error_flags",
     "moe_decode_layer", "moei_cache_last_step",
+    "moei_profile_enable", "moei_profile_disable", "moei_profile_kernels", "moei_profile_kernel_name",
+    "moei_profile_read",
 ]
 
 
@@ -69,6 +71,7 @@ def lib() -> C.CDLL:
         L.moei_version.restype = C.c_char_p
         for name in EXPORTS[2:]:
             getattr(L, name).restype = C.c_int
+        L.moei_profile_kernel_name.restype = C.c_char_p
         _lib = L
     return _lib
 
@@ -229,6 +232,24 @@ class Cache:
 
 
 # ------------------------------------------------------------------------ entry points
+def expert_pack(desc: ModelDesc, w_gate: np.ndarray, w_up: np.ndarray, w_down: np.ndarray,
+                out: np.ndarray | None = None) -> np.ndarray:
+    """W_gate [I][H], W_up [I][H], W_down [H][I] (host arrays in the storage dtype) -> one
+    expert in slot layout, flat [3*H*I].  Data movement only."""
+    H, I = desc.H, desc.I
+    dt = np.float32 if desc.wdtype == WDTYPE_FP32 else np.uint16
+    g = np.ascontiguousarray(w_gate, dtype=dt)
+    u = np.ascontiguousarray(w_up, dtype=dt)
+    d = np.ascontiguousarray(w_down, dtype=dt)
+    assert g.shape == (I, H) and u.shape == (I, H) and d.shape == (H, I)
+    if out is None:
+        out = np.empty(3 * H * I, dtype=dt)
+    assert out.dtype == dt and out.size == 3 * H * I and out.flags["C_CONTIGUOUS"]
+    _check(lib().moei_expert_pack(C.byref(desc), _p(g), _p(u), _p(d), _p(out)))
+    return out
+
+
+
 def moe_route_topk(logits: torch.Tensor, k: int, renorm: bool, stream=None):
     """logits [B][E] fp32 (device) -> (idx [B][k] int32, w [B][k] fp32) on the device."""
     _dev(logits, torch.float32)
@@ -313,3 +334,22 @@ def moe_decode_layer(cache: Cache, eamc: Eamc, eam: torch.Tensor, layer: int, ro
     _check(lib().moe_decode_layer(cache.h, eamc.h, _p(eam), layer, _p(router_w), _p(router_bias), _p(x), _p(y),
                                   _p(idx), C.byref(best), C.byref(n_miss), _stream(stream)))
     return idx, best.value, n_miss.value
+
+
+# -------------------------------------------------------------------- kernel timing
+def profile_enable(max_samples: int) -> None:
+    _check(lib().moei_profile_enable(max_samples))
+
+
+def profile_disable() -> None:
+    _check(lib().moei_profile_disable())
+
+
+def profile_read() -> dict:
+    """{kernel name: (launches recorded, total milliseconds between their event brackets)}"""
+    out = {}
+    for i in range(lib().moei_profile_kernels()):
+        t, n = C.c_double(0), C.c_int32(0)
+        _check(lib().moei_profile_read(i, C.byref(t), C.byref(n)))
+        out[lib().moei_profile_kernel_name(i).decode()] = (n.value, t.value)
+    return out

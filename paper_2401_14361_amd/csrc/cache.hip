@@ -342,7 +342,7 @@ extern "C" int moei_cache_retrieve(moei_cache* c, int32_t layer, const int32_t* 
     if (n_miss > 0) {
         MOEI_HIP(hipEventRecord(c->ev_copy, c->copy_stream));
         MOEI_HIP(hipStreamWaitEvent(s, c->ev_copy, 0));
-        apply_slot_updates_kernel<<<1, 2 * kMaxAct, 0, s>>>(c->d_slot_of, upd);
+        launch(K_ROUTE_TOPK, apply_slot_updates_kernel, dim3(1), dim3(2 * kMaxAct), 0, s, c->d_slot_of, upd);
         MOEI_LAUNCH_CHECK();
     }
     if (h_n_miss) *h_n_miss = n_miss;

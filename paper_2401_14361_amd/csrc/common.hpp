@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stdarg.h>
 #include <stdio.h>
@@ -41,8 +42,39 @@ static inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream
 
 constexpr int kWave = 64;
 
+// ------------------------------------------------------------------ kernel timing
+// Optional per-launch start/stop events for every kernel of the library (see
+// moei_profile_enable in moei.h).  Disabled: one predictable branch per launch.
+enum KernelId {
+    K_ROUTER_GEMV = 0,
+    K_ROUTE_TOPK,
+    K_MATCH_DOT,
+    K_MATCH_ARGMAX,
+    K_PRIO_SCORE,
+    K_PRIO_RANK,
+    K_FFN_FUSED,
+    K_FFN_REDUCE,
+    K_COUNT
+};
+extern bool g_prof_on;
+// Hands out the next pre-created event pair for kernel `id`; false when the pool is used up.
+bool prof_take(int id, hipEvent_t* start, hipEvent_t* stop);
+
 // ------------------------------------------------------------------ device helpers
 #if defined(__HIPCC__)
+
+// Every kernel of the library is launched through here.  With timing enabled the
+// launch carries a start/stop event pair that the runtime stamps with the kernel's own
+// begin and end times (no extra packets between kernels).
+template <typename... KArgs, typename... Args>
+inline void launch(int id, void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t smem, hipStream_t s,
+                   Args... args) {
+    hipEvent_t b = nullptr, e = nullptr;
+    if (g_prof_on && prof_take(id, &b, &e))
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)smem, s, b, e, 0u, KArgs(args)...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, (uint32_t)smem, s, KArgs(args)...);
+}
 
 // Butterfly reductions over the 64 lanes of a wavefront; every lane ends with the result.
 template <typename T>

@@ -1,14 +1,23 @@
-// Step 5 of the layer step: the activated experts' FFN as a GEMV over cache slots.
+// Step 5 of the layer step: the activated experts' FFN as ONE streaming pass over
+// their cache slots.
 //
 // An expert is a feed-forward network (Sec. 2 of the paper); here in SwiGLU form,
 //   o = W_down ( silu(W_gate x) * (W_up x) ),  y = sum_e w_e o_e.
-// At batch 1 this is one flop per weight byte, so the kernels are pure weight
-// streams: a wavefront owns a few matrix rows, reads them with 16-byte loads
-// (8 bf16 or 4 fp32 per lane), multiplies with the fp32 copy of the input vector held
-// in LDS, and finishes with a 64-lane butterfly sum.  The down projection is split
-// over (expert, row group, column range); its partial results are added up in a
-// fixed order by a last small kernel, so the output is deterministic.
+// At batch 1 this is one flop per weight byte, so the only thing that matters is how
+// the weight bytes stream out of HBM.  A slot stores an expert row-interleaved,
+//   for i in 0..I-1:  W_gate[i][0..H) | W_up[i][0..H) | W_down[0..H)[i]
+// (the down projection transposed), so that everything intermediate unit i needs is
+// one contiguous run of 3*H values.  A wavefront takes such a run, forms the two dot
+// products with x (held in LDS as fp32), reduces them over its 64 lanes, and adds
+// a_i * W_down[:, i] into a running y kept in registers: no intermediate vector ever
+// leaves the CU and each weight byte is read exactly once.  Work is dealt out
+// statically (unit t goes to wavefront t mod W), one workgroup per compute unit, so
+// the summation order - and with it every output bit - is the same on every run.
+// Workgroup partial sums are added in index order by a small second kernel.
 #include <stdlib.h>
+#include <string.h>
+
+#include <type_traits>
 
 #include "kernels.hpp"
 #include "wtypes.hpp"
@@ -17,9 +26,6 @@ namespace moei {
 
 namespace {
 
-constexpr int kFfnThreads = 256;
-constexpr int kWavesPerBlock = kFfnThreads / kWave;
-
 struct FfnArgs {
     const void* pool;
     size_t slot_elems;
@@ -27,146 +33,272 @@ struct FfnArgs {
     const int32_t* slot_ids;
     const float* gate_w;
     const void* x;
-    float* act;   // [n_act][I]
-    float* part;  // [n_act * ksplit][H]
-    int H, I, ksplit, iper;
+    float* part;  // [gridDim.x][H] workgroup partial sums
+    int H, I, n_act;
+    int waves;    // wavefronts per workgroup
+    int ygroup;   // wavefronts whose y rows fit in LDS together
     int32_t* flags;
 };
 
-// act[e][i] = silu(<W_gate[i], x>) * <W_up[i], x>;  grid (ceil(I / (4R)), n_act)
-template <typename WT, int R, bool VEC>
-__global__ void __launch_bounds__(kFfnThreads) ffn_gate_up_kernel(FfnArgs a) {
+// Sum over the 64 lanes, same value returned to every lane: DPP inside each row of 16
+// lanes, then the four row totals are read through scalar registers.
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, false));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, false));
+    const int b = __builtin_bit_cast(int, v);
+    float r = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+    r += __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+    r += __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+    r += __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+    return r;
+}
+
+__device__ __forceinline__ float silu(float g) { return g / (1.0f + expf(-g)); }
+
+// Adds the wavefronts' y rows in wavefront order and writes the workgroup's partial row.
+// Rows go through LDS `ygroup` at a time; `store_my_row` writes the calling wavefront's.
+template <typename Store>
+__device__ __forceinline__ void block_sum_rows(float* yp, int H, int waves, int ygroup, int wv, float* out,
+                                               Store store_my_row) {
+    const int tid = threadIdx.x, nthr = blockDim.x;
+    for (int g0 = 0; g0 < waves; g0 += ygroup) {
+        if (wv >= g0 && wv < g0 + ygroup) store_my_row(yp + (size_t)(wv - g0) * H);
+        __syncthreads();
+        const int ng = min(ygroup, waves - g0);
+        for (int c = tid; c < H; c += nthr) {
+            float s = g0 == 0 ? 0.f : out[c];  // each column is owned by one thread across rounds
+            for (int k = 0; k < ng; ++k) s += yp[(size_t)k * H + c];
+            out[c] = s;
+        }
+        __syncthreads();
+    }
+}
+
+// Fast path: H is NCH chunks of 64 lanes x 16 bytes, so unit i is a run of 3*NCH
+// 16-byte loads per lane (gate and up chunks interleaved, then the down chunks).  The
+// wavefront keeps a rolling window of PF loads in flight: each step consumes the oldest
+// load and issues the one PF steps ahead, across unit boundaries, so its stream never
+// drains.  grid = one workgroup per compute unit, block = waves * 64 threads,
+// LDS = x (H floats) + ygroup y rows.
+template <int NCH>
+struct StreamShape {
+    static constexpr int kSteps = 3 * NCH;
+    // window depth: the largest divisor-quotient of the step count that is <= 16
+    static constexpr int kWindow = kSteps <= 16 ? kSteps : (kSteps / 2 <= 16 && kSteps % 2 == 0 ? kSteps / 2 : kSteps / 3);
+    // register budget: window + y accumulators decide how many wavefronts fit a SIMD
+    static constexpr int kMaxWaves = NCH <= 4 ? 16 : (NCH <= 10 ? 12 : 8);
+};
+
+template <typename WT, int NCH>
+__global__ void __launch_bounds__((StreamShape<NCH>::kMaxWaves * kWave)) ffn_fused_kernel(FfnArgs a) {
     using V = WVec<WT>;
-    extern __shared__ __align__(16) float xs[];
-    const int e = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    using Raw = typename V::raw;
+    constexpr int N = V::N;
+    constexpr int CW = kWave * N;  // columns per chunk
+    constexpr int STEPS = StreamShape<NCH>::kSteps;
+    constexpr int PF = StreamShape<NCH>::kWindow;
+    static_assert(STEPS % PF == 0, "the window must divide the steps of a unit");
+    extern __shared__ __align__(16) float smem[];
+    float* xs = smem;
+    float* yp = smem + a.H;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    // the wavefront index in a scalar register: unit ids, slot ids and base addresses are
+    // then scalar too
+    const int wv = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int H = a.H, I = a.I;
-    const int i0 = (blockIdx.x * kWavesPerBlock + wv) * R;
-    const int slot = a.slot_ids[e];
-    if (slot < 0 || slot >= a.n_slots_total) {  // uniform over the workgroup
-        if (lane == 0)
-            for (int r = 0; r < R; ++r)
-                if (i0 + r < I) a.act[(size_t)e * I + i0 + r] = 0.f;
-        if (tid == 0) atomicOr(a.flags, 1);
-        return;
+    const int W = gridDim.x * a.waves;
+    const int NT = a.n_act * I;
+    const WT* pool = reinterpret_cast<const WT*>(a.pool);
+    const unsigned lane_off = (unsigned)lane * N;  // this lane's elements inside a chunk
+    int* s_slot = reinterpret_cast<int*>(yp);      // slot ids and gate weights of the call, staged
+    float* s_gate = yp + 64;                       // in LDS (the y rows are not in use before the end)
+
+    auto scalar = [](size_t v) -> size_t {
+        uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+        uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+        return (size_t)(((uint64_t)hi << 32) | lo);
+    };
+    // element offset of unit t in the pool; a bad slot id reads slot 0 and is weighted by zero
+    auto unit_off = [&](int slot, int i, bool& ok) -> size_t {
+        ok = slot >= 0 && slot < a.n_slots_total;
+        if (!ok && lane == 0) atomicOr(a.flags, 1);
+        return scalar((size_t)(ok ? slot : 0) * a.slot_elems + (size_t)i * 3 * H);
+    };
+    // element offset of load step s inside a unit: g0 u0 g1 u1 ... then d0 d1 ...
+    auto step_off = [&](int s) -> int {
+        return s < 2 * NCH ? ((s & 1) ? H : 0) + (s >> 1) * CW : 2 * H + (s - 2 * NCH) * CW;
+    };
+    auto ld = [&](size_t unit, int off) -> Raw { return V::load(pool + unit + off + lane_off); };
+
+    float acc[NCH * N];
+#pragma unroll
+    for (int k = 0; k < NCH * N; ++k) acc[k] = 0.f;
+    Raw win[PF];
+
+    int t = blockIdx.x * a.waves + wv;
+    float gate = 0.f, gate_n = 0.f;
+    bool ok = false, ok_n = false;
+    size_t p = 0;
+    if (t < NT) {  // the first loads are on their way while x is staged
+        const int e = t / I;
+        p = unit_off(a.slot_ids[e], t - e * I, ok);
+        gate = a.gate_w[e];
+#pragma unroll
+        for (int s = 0; s < PF; ++s) win[s] = ld(p, step_off(s));
     }
     stage_as_f32(reinterpret_cast<const WT*>(a.x), xs, H);
+    if (tid < a.n_act) {
+        s_slot[tid] = a.slot_ids[tid];
+        s_gate[tid] = a.gate_w[tid];
+    }
     __syncthreads();
-    if (i0 >= I) return;
-    const WT* Wg = reinterpret_cast<const WT*>(a.pool) + (size_t)slot * a.slot_elems;
-    const WT* Wu = Wg + (size_t)I * H;
-    const WT* rg[R];
-    const WT* ru[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        int row = min(i0 + r, I - 1);  // tail rows recompute the last row and are not written
-        rg[r] = Wg + (size_t)row * H;
-        ru[r] = Wu + (size_t)row * H;
-    }
-    float ag[R], au[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) ag[r] = au[r] = 0.f;
-    if (VEC) {
-#pragma unroll 2
-        for (int c = lane * V::N; c < H; c += kWave * V::N) {
-            typename V::raw wg[R], wu[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                wg[r] = V::load(rg[r] + c);
-                wu[r] = V::load(ru[r] + c);
-            }
-            float xf[V::N];
-#pragma unroll
-            for (int i = 0; i < V::N; i += 4) *reinterpret_cast<float4*>(xf + i) = *reinterpret_cast<const float4*>(xs + c + i);
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                ag[r] = V::dot(wg[r], xf, ag[r]);
-                au[r] = V::dot(wu[r], xf, au[r]);
-            }
+
+    while (t < NT) {
+        const int tn = t + W;
+        const bool more = tn < NT;
+        size_t pn = p;
+        if (more) {
+            const int e = tn / I;
+            pn = unit_off(s_slot[e], tn - e * I, ok_n);
+            gate_n = s_gate[e];
         }
-    } else {
-        for (int c = lane; c < H; c += kWave) {
-            float xv = xs[c];
+        float g = 0.f, u = 0.f, ai = 0.f;
+        float xf[N];
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                ag[r] = __builtin_fmaf(V::one(rg[r] + c), xv, ag[r]);
-                au[r] = __builtin_fmaf(V::one(ru[r] + c), xv, au[r]);
+        for (int s = 0; s < STEPS; ++s) {
+            const Raw cur = win[s % PF];
+            if (s < 2 * NCH) {
+                if ((s & 1) == 0) {
+#pragma unroll
+                    for (int k = 0; k < N; k += 4)
+                        *reinterpret_cast<float4*>(xf + k) =
+                            *reinterpret_cast<const float4*>(xs + (s >> 1) * CW + lane * N + k);
+                    g = V::dot(cur, xf, g);
+                } else {
+                    u = V::dot(cur, xf, u);
+                }
+            } else {
+                if (s == 2 * NCH) {
+                    g = wave_sum_dpp(g);
+                    u = wave_sum_dpp(u);
+                    ai = ok ? silu(g) * u * gate : 0.f;
+                }
+                float d[N];
+                V::unpack(cur, d);
+#pragma unroll
+                for (int k = 0; k < N; ++k)
+                    acc[(s - 2 * NCH) * N + k] = __builtin_fmaf(ai, d[k], acc[(s - 2 * NCH) * N + k]);
             }
+            // The consumed slot is free again: refill it with the load PF steps ahead.  After
+            // the last unit the refills re-read one already cached chunk, so that every step
+            // issues exactly one load and the loop body has no branch.  The scheduling barriers
+            // keep the compiler from hoisting refills and growing the window.
+            __builtin_amdgcn_sched_barrier(0);
+            if (s + PF < STEPS)
+                win[s % PF] = ld(p, step_off(s + PF));
+            else
+                win[s % PF] = ld(pn, more ? step_off(s + PF - STEPS) : 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        t = tn;
+        p = pn;
+        gate = gate_n;
+        ok = ok_n;
     }
+    __syncthreads();  // the LDS behind the y rows held the slot ids until here
+    float* out = a.part + (size_t)blockIdx.x * H;
+    block_sum_rows(yp, H, a.waves, a.ygroup, wv, out, [&](float* row) {
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        float g = wave_sum(ag[r]);
-        float u = wave_sum(au[r]);
-        if (lane == 0 && i0 + r < I) a.act[(size_t)e * I + i0 + r] = g / (1.0f + expf(-g)) * u;
-    }
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int k = 0; k < N; k += 4)
+                *reinterpret_cast<float4*>(row + c * CW + lane * N + k) =
+                    make_float4(acc[c * N + k], acc[c * N + k + 1], acc[c * N + k + 2], acc[c * N + k + 3]);
+    });
 }
 
-// part[e*ksplit + ks][h] = w_e * <W_down[h][i_lo:i_hi], act[e][i_lo:i_hi]>;
-// grid (ceil(H / (4R)), ksplit, n_act)
-template <typename WT, int R, bool VEC>
-__global__ void __launch_bounds__(kFfnThreads) ffn_down_kernel(FfnArgs a) {
+// Any H: the same dealing of units to wavefronts, scalar loads, y rows accumulated in LDS.
+template <typename WT>
+__global__ void __launch_bounds__(1024) ffn_fused_generic_kernel(FfnArgs a) {
     using V = WVec<WT>;
-    extern __shared__ __align__(16) float as[];
-    const int e = blockIdx.z, ks = blockIdx.y;
+    extern __shared__ __align__(16) float smem[];
+    float* xs = smem;
+    float* yp = smem + a.H;  // [waves][H]
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const int H = a.H, I = a.I;
-    const int h0 = (blockIdx.x * kWavesPerBlock + wv) * R;
-    float* out = a.part + ((size_t)e * a.ksplit + ks) * H;
-    const int slot = a.slot_ids[e];
-    const int i_lo = ks * a.iper;
-    const int i_hi = min(I, i_lo + a.iper);
-    if (slot < 0 || slot >= a.n_slots_total || i_lo >= i_hi) {  // uniform over the workgroup
-        if (lane == 0)
-            for (int r = 0; r < R; ++r)
-                if (h0 + r < H) out[h0 + r] = 0.f;
-        return;
-    }
-    const float gw = a.gate_w[e];
-    const int ni = i_hi - i_lo;
-    for (int i = tid; i < ni; i += kFfnThreads) as[i] = a.act[(size_t)e * I + i_lo + i] * gw;
+    const int W = gridDim.x * a.waves;
+    const int NT = a.n_act * I;
+    const WT* pool = reinterpret_cast<const WT*>(a.pool);
+    float* my = yp + (size_t)wv * H;
+    stage_as_f32(reinterpret_cast<const WT*>(a.x), xs, H);
+    for (int c = lane; c < H; c += kWave) my[c] = 0.f;
     __syncthreads();
-    if (h0 >= H) return;
-    const WT* Wd = reinterpret_cast<const WT*>(a.pool) + (size_t)slot * a.slot_elems + (size_t)2 * I * H;
-    const WT* rd[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) rd[r] = Wd + (size_t)min(h0 + r, H - 1) * I + i_lo;
-    float acc[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) acc[r] = 0.f;
-    if (VEC) {
-#pragma unroll 2
-        for (int c = lane * V::N; c < ni; c += kWave * V::N) {
-            typename V::raw w[R];
-#pragma unroll
-            for (int r = 0; r < R; ++r) w[r] = V::load(rd[r] + c);
-            float xf[V::N];
-#pragma unroll
-            for (int i = 0; i < V::N; i += 4) *reinterpret_cast<float4*>(xf + i) = *reinterpret_cast<const float4*>(as + c + i);
-#pragma unroll
-            for (int r = 0; r < R; ++r) acc[r] = V::dot(w[r], xf, acc[r]);
+    for (int t = blockIdx.x * a.waves + wv; t < NT; t += W) {
+        const int e = t / I, i = t - e * I;
+        const int slot = a.slot_ids[e];
+        if (slot < 0 || slot >= a.n_slots_total) {
+            if (lane == 0) atomicOr(a.flags, 1);
+            continue;
         }
-    } else {
-        for (int c = lane; c < ni; c += kWave) {
-            float xv = as[c];
-#pragma unroll
-            for (int r = 0; r < R; ++r) acc[r] = __builtin_fmaf(V::one(rd[r] + c), xv, acc[r]);
+        const WT* p = pool + (size_t)slot * a.slot_elems + (size_t)i * 3 * H;
+        float g = 0.f, u = 0.f;
+        for (int c = lane; c < H; c += kWave) {
+            g = __builtin_fmaf(V::one(p + c), xs[c], g);
+            u = __builtin_fmaf(V::one(p + H + c), xs[c], u);
         }
+        g = wave_sum_dpp(g);
+        u = wave_sum_dpp(u);
+        const float ai = silu(g) * u * a.gate_w[e];
+        for (int c = lane; c < H; c += kWave) my[c] = __builtin_fmaf(ai, V::one(p + 2 * H + c), my[c]);
     }
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        float s = wave_sum(acc[r]);
-        if (lane == 0 && h0 + r < H) out[h0 + r] = s;
+    __syncthreads();
+    float* out = a.part + (size_t)blockIdx.x * H;
+    for (int c = tid; c < H; c += blockDim.x) {
+        float s = 0.f;
+        for (int k = 0; k < a.waves; ++k) s += yp[(size_t)k * H + c];
+        out[c] = s;
     }
 }
 
-// y[h] = sum of the n_part partial rows, in index order.
-__global__ void ffn_reduce_kernel(const float* __restrict__ part, int n_part, int H, float* __restrict__ y) {
-    int h = blockIdx.x * blockDim.x + threadIdx.x;
-    if (h >= H) return;
-    float s = 0.f;
-    for (int p = 0; p < n_part; ++p) s += part[(size_t)p * H + h];
-    y[h] = s;
+// y[h] = sum of the n_part workgroup partials.  A workgroup owns 32 columns; its 256
+// threads are 8 column quads x 32 slices of the partial list; every thread adds its
+// slice in index order, then the 32 slice sums are added in slice order.
+__global__ void __launch_bounds__(256) ffn_reduce_kernel(const float* __restrict__ part, int n_part, int H,
+                                                         float* __restrict__ y) {
+    __shared__ float s_sum[32][32];
+    const int cq = threadIdx.x & 7, sl = threadIdx.x >> 3;
+    const int h = blockIdx.x * 32 + cq * 4;
+    const int per = (n_part + 31) / 32;
+    const int p0 = sl * per, p1 = min(n_part, p0 + per);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (h + 3 < H) {
+#pragma unroll 8
+        for (int p = p0; p < p1; ++p) {
+            const float4 v = *reinterpret_cast<const float4*>(part + (size_t)p * H + h);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+    } else {
+        for (int p = p0; p < p1; ++p) {
+            const float* r = part + (size_t)p * H;
+            if (h < H) acc.x += r[h];
+            if (h + 1 < H) acc.y += r[h + 1];
+            if (h + 2 < H) acc.z += r[h + 2];
+        }
+    }
+    s_sum[sl][cq * 4 + 0] = acc.x;
+    s_sum[sl][cq * 4 + 1] = acc.y;
+    s_sum[sl][cq * 4 + 2] = acc.z;
+    s_sum[sl][cq * 4 + 3] = acc.w;
+    __syncthreads();
+    if (threadIdx.x < 32) {
+        const int hh = blockIdx.x * 32 + threadIdx.x;
+        float t = 0.f;
+#pragma unroll
+        for (int k = 0; k < 32; ++k) t += s_sum[k][threadIdx.x];
+        if (hh < H) y[hh] = t;
+    }
 }
 
 int env_int(const char* name, int dflt) {
@@ -175,69 +307,122 @@ int env_int(const char* name, int dflt) {
     return atoi(v);
 }
 
-template <typename WT, bool VEC>
-int launch_ffn_typed(const FfnArgs& a, int n_act, int r1, int r2, float* d_y, hipStream_t s) {
-    const int H = a.H, I = a.I;
-    dim3 g1((I + kWavesPerBlock * r1 - 1) / (kWavesPerBlock * r1), n_act);
-    size_t sm1 = (size_t)H * sizeof(float);
-    switch (r1) {
-        case 1: ffn_gate_up_kernel<WT, 1, VEC><<<g1, kFfnThreads, sm1, s>>>(a); break;
-        case 2: ffn_gate_up_kernel<WT, 2, VEC><<<g1, kFfnThreads, sm1, s>>>(a); break;
-        default: ffn_gate_up_kernel<WT, 4, VEC><<<g1, kFfnThreads, sm1, s>>>(a); break;
+int g_cus = 0;
+int compute_units() {
+    if (g_cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        g_cus = n;
     }
-    MOEI_LAUNCH_CHECK();
-    dim3 g2((H + kWavesPerBlock * r2 - 1) / (kWavesPerBlock * r2), a.ksplit, n_act);
-    size_t sm2 = (size_t)a.iper * sizeof(float);
-    switch (r2) {
-        case 1: ffn_down_kernel<WT, 1, VEC><<<g2, kFfnThreads, sm2, s>>>(a); break;
-        case 2: ffn_down_kernel<WT, 2, VEC><<<g2, kFfnThreads, sm2, s>>>(a); break;
-        default: ffn_down_kernel<WT, 4, VEC><<<g2, kFfnThreads, sm2, s>>>(a); break;
+    return g_cus;
+}
+
+constexpr size_t kLdsBudget = 150 * 1024;  // of the 160 KiB per compute unit
+
+// Wavefronts per workgroup: the count in [4, max_waves] that wastes the fewest unit slots when
+// n_units are dealt out to blocks * waves wavefronts (ties go to more wavefronts).
+int plan_waves(int n_units, int blocks, int max_waves) {
+    int forced = env_int("MOEI_FFN_WAVES", 0);
+    if (forced >= 1 && forced <= max_waves) return forced;
+    int best = max_waves;
+    double best_eff = -1.0;
+    for (int m = max_waves; m >= (max_waves < 4 ? 1 : 4); --m) {
+        long per = ((long)n_units + (long)blocks * m - 1) / ((long)blocks * m);
+        double eff = (double)n_units / ((double)per * blocks * m);
+        if (eff > best_eff + 1e-9) {
+            best_eff = eff;
+            best = m;
+        }
     }
-    MOEI_LAUNCH_CHECK();
-    ffn_reduce_kernel<<<(H + 255) / 256, 256, 0, s>>>(a.part, n_act * a.ksplit, H, d_y);
-    MOEI_LAUNCH_CHECK();
+    return best;
+}
+
+template <typename K>
+int allow_big_lds(K kernel, size_t bytes) {
+    if (bytes > 64 * 1024)
+        MOEI_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)bytes));
     return MOEI_OK;
 }
 
-// Column ranges of the down projection: at most 4096 intermediate values per range,
-// a multiple of 512 (one 16-byte load per lane of a wavefront covers 512 bf16).
-int plan_ksplit(int I, int ksplit_max, int* iper) {
-    int ks = (I + 4095) / 4096;
-    ks = env_int("MOEI_FFN_KSPLIT", ks);
-    if (ks < 1) ks = 1;
-    if (ks > ksplit_max) ks = ksplit_max;
-    int per = (I + ks - 1) / ks;
-    per = (per + 511) / 512 * 512;
-    *iper = per;
-    return (I + per - 1) / per;
+template <typename WT>
+int launch_ffn_typed(FfnArgs a, bool fast, int grid, float* d_y, hipStream_t s) {
+    using V = WVec<WT>;
+    const int H = a.H;
+    int rc = MOEI_OK;
+    const int nch = H / (kWave * V::N);
+    const size_t row = (size_t)H * sizeof(float);
+    if (fast) {
+#define MOEI_FFN_CASE(N_)                                                                            \
+    case N_: {                                                                                       \
+        a.waves = plan_waves(a.n_act * a.I, grid, StreamShape<N_>::kMaxWaves);                       \
+        int yg = (int)((kLdsBudget - row) / row);                                                    \
+        a.ygroup = yg < 1 ? 1 : (yg > a.waves ? a.waves : yg);                                       \
+        const size_t smem = row * (1 + a.ygroup);                                                    \
+        rc = allow_big_lds(ffn_fused_kernel<WT, N_>, smem);                                          \
+        if (rc) return rc;                                                                           \
+        launch(K_FFN_FUSED, ffn_fused_kernel<WT, N_>, dim3(grid), dim3(a.waves * kWave), smem, s, a); \
+        break;                                                                                       \
+    }
+        switch (nch) {
+            MOEI_FFN_CASE(1)
+            MOEI_FFN_CASE(2)
+            MOEI_FFN_CASE(3)
+            MOEI_FFN_CASE(4)
+            MOEI_FFN_CASE(5)
+            MOEI_FFN_CASE(6)
+            MOEI_FFN_CASE(8)
+            MOEI_FFN_CASE(10)
+            MOEI_FFN_CASE(12)
+            MOEI_FFN_CASE(16)
+            default:
+                fast = false;
+        }
+#undef MOEI_FFN_CASE
+    }
+    if (!fast) {
+        int m = (int)((kLdsBudget - row) / row);
+        if (m > 8) m = 8;
+        if (m < 1) MOEI_FAIL(MOEI_ECAPACITY, "expert_ffn_gemv: H = %d does not fit the LDS staging", H);
+        a.waves = m;
+        a.ygroup = m;
+        const size_t smem = row * (1 + m);
+        rc = allow_big_lds(ffn_fused_generic_kernel<WT>, smem);
+        if (rc) return rc;
+        launch(K_FFN_FUSED, ffn_fused_generic_kernel<WT>, dim3(grid), dim3(m * kWave), smem, s, a);
+    }
+    MOEI_LAUNCH_CHECK();
+    launch(K_FFN_REDUCE, ffn_reduce_kernel, dim3((H + 31) / 32), dim3(256), 0, s, (const float*)a.part, grid, H, d_y);
+    MOEI_LAUNCH_CHECK();
+    return MOEI_OK;
 }
 
 }  // namespace
 
 int ffn_scratch_alloc(const moei_model_desc& d, int n_act_max, FfnScratch* out) {
     out->n_act_max = n_act_max;
-    out->ksplit_max = (d.I + 511) / 512;
-    hipError_t e = hipMalloc((void**)&out->d_act, (size_t)n_act_max * d.I * sizeof(float));
-    if (e == hipSuccess)
-        e = hipMalloc((void**)&out->d_part, (size_t)n_act_max * out->ksplit_max * d.H * sizeof(float));
+    out->n_part = compute_units();
+    hipError_t e = hipMalloc((void**)&out->d_part, (size_t)out->n_part * d.H * sizeof(float));
     if (e != hipSuccess) {
-        ffn_scratch_free(out);
+        out->d_part = nullptr;
         MOEI_FAIL(MOEI_ENOMEM, "FFN scratch allocation failed: %s", hipGetErrorString(e));
     }
     return MOEI_OK;
 }
 
 void ffn_scratch_free(FfnScratch* s) {
-    (void)hipFree(s->d_act);
     (void)hipFree(s->d_part);
-    s->d_act = s->d_part = nullptr;
+    s->d_part = nullptr;
 }
 
 int launch_expert_ffn(const moei_model_desc& d, const void* d_pool, size_t slot_elems, int n_slots_total,
                       const FfnScratch& scr, const int32_t* d_slot_ids, const float* d_gate_w, int n_act,
                       const void* d_x, float* d_y, int32_t* d_flags, hipStream_t s) {
     if (n_act == 0) {  // an empty sum: the reduction over zero partial rows writes zeros
-        ffn_reduce_kernel<<<(d.H + 255) / 256, 256, 0, s>>>(scr.d_part, 0, d.H, d_y);
+        launch(K_FFN_REDUCE, ffn_reduce_kernel, dim3((d.H + 31) / 32), dim3(256), 0, s, (const float*)scr.d_part, 0, d.H,
+               d_y);
         MOEI_LAUNCH_CHECK();
         return MOEI_OK;
     }
@@ -248,23 +433,49 @@ int launch_expert_ffn(const moei_model_desc& d, const void* d_pool, size_t slot_
     a.slot_ids = d_slot_ids;
     a.gate_w = d_gate_w;
     a.x = d_x;
-    a.act = scr.d_act;
     a.part = scr.d_part;
     a.H = d.H;
     a.I = d.I;
+    a.n_act = n_act;
     a.flags = d_flags;
-    a.ksplit = plan_ksplit(d.I, scr.ksplit_max, &a.iper);
     const int wb = d.wdtype == MOEI_WDTYPE_BF16 ? 2 : 4;
     const int n = 16 / wb;
-    const bool vec = (d.H % n == 0) && (d.I % n == 0) && ((uintptr_t)d_pool % 16 == 0) && ((slot_elems * wb) % 16 == 0);
-    auto rows = [](int r) { return r >= 4 ? 4 : (r >= 2 ? 2 : 1); };
-    static const int r1 = rows(env_int("MOEI_FFN_R1", 2));
-    static const int r2 = rows(env_int("MOEI_FFN_R2", 4));
-    if (d.wdtype == MOEI_WDTYPE_BF16)
-        return vec ? launch_ffn_typed<uint16_t, true>(a, n_act, r1, r2, d_y, s)
-                   : launch_ffn_typed<uint16_t, false>(a, n_act, r1, r2, d_y, s);
-    return vec ? launch_ffn_typed<float, true>(a, n_act, r1, r2, d_y, s)
-               : launch_ffn_typed<float, false>(a, n_act, r1, r2, d_y, s);
+    const bool fast = (d.H % (kWave * n) == 0) && ((uintptr_t)d_pool % 16 == 0) && ((slot_elems * wb) % 16 == 0) &&
+                      env_int("MOEI_FFN_GENERIC", 0) == 0;
+    if (d.wdtype == MOEI_WDTYPE_BF16) return launch_ffn_typed<uint16_t>(a, fast, scr.n_part, d_y, s);
+    return launch_ffn_typed<float>(a, fast, scr.n_part, d_y, s);
 }
 
 }  // namespace moei
+
+using namespace moei;
+
+// Slot layout from the three plain matrices (host memory, desc->wdtype elements).
+extern "C" int moei_expert_pack(const moei_model_desc* desc, const void* h_gate, const void* h_up, const void* h_down,
+                                void* h_slot) {
+    MOEI_REQUIRE(desc && h_gate && h_up && h_down && h_slot, "moei_expert_pack: null pointer");
+    int rc = check_desc(desc);
+    if (rc) return rc;
+    const size_t H = desc->H, I = desc->I;
+    const size_t wb = desc->wdtype == MOEI_WDTYPE_BF16 ? 2 : 4;
+    const unsigned char* g = static_cast<const unsigned char*>(h_gate);
+    const unsigned char* u = static_cast<const unsigned char*>(h_up);
+    const unsigned char* dn = static_cast<const unsigned char*>(h_down);
+    unsigned char* out = static_cast<unsigned char*>(h_slot);
+    for (size_t i = 0; i < I; ++i) {
+        unsigned char* row = out + i * 3 * H * wb;
+        memcpy(row, g + i * H * wb, H * wb);
+        memcpy(row + H * wb, u + i * H * wb, H * wb);
+        unsigned char* dcol = row + 2 * H * wb;
+        if (wb == 2) {
+            const uint16_t* src = reinterpret_cast<const uint16_t*>(dn) + i;
+            uint16_t* dst = reinterpret_cast<uint16_t*>(dcol);
+            for (size_t h = 0; h < H; ++h) dst[h] = src[h * I];
+        } else {
+            const uint32_t* src = reinterpret_cast<const uint32_t*>(dn) + i;
+            uint32_t* dst = reinterpret_cast<uint32_t*>(dcol);
+            for (size_t h = 0; h < H; ++h) dst[h] = src[h * I];
+        }
+    }
+    return MOEI_OK;
+}

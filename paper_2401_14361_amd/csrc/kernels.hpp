@@ -28,10 +28,9 @@ int launch_gather_slots(const int32_t* d_idx, int k, const int32_t* d_slot_of_ro
 
 // ------------------------------------------------------------------ ffn.hip
 struct FfnScratch {
-    float* d_act = nullptr;   // [n_act_max][I] intermediate silu(g)*u
-    float* d_part = nullptr;  // [n_act_max * ksplit_max][H] partial down-projections
+    float* d_part = nullptr;  // [n_part][H] workgroup partial sums of y
+    int n_part = 0;           // = workgroups of the fused kernel (one per compute unit)
     int n_act_max = 0;
-    int ksplit_max = 0;
 };
 int ffn_scratch_alloc(const moei_model_desc& d, int n_act_max, FfnScratch* out);
 void ffn_scratch_free(FfnScratch* s);

@@ -280,9 +280,9 @@ Plan make_plan(const moei_eamc* c, int L_scan) {
 
 template <typename CT, int VEC>
 int launch_dot_j(const Plan& p, const DotArgs& a, dim3 grid, hipStream_t s) {
-#define MOEI_DOT_CASE(JJ)                                                                  \
-    case JJ:                                                                               \
-        eamc_dot_kernel<CT, VEC, JJ><<<grid, kDotThreads, p.smem, s>>>(a);                 \
+#define MOEI_DOT_CASE(JJ)                                                                          \
+    case JJ:                                                                                       \
+        launch(K_MATCH_DOT, eamc_dot_kernel<CT, VEC, JJ>, grid, dim3(kDotThreads), p.smem, s, a);  \
         break;
     switch (p.J) {
         MOEI_DOT_CASE(1)
@@ -485,8 +485,8 @@ extern "C" int eamc_match(const moei_eamc* c, const int32_t* d_eam, int32_t B, i
             rc = p.VEC == 8 ? launch_dot_j<uint16_t, 8>(p, a, grid, s) : launch_dot_j<uint16_t, 1>(p, a, grid, s);
         if (rc) return rc;
     }
-    eamc_argmax_kernel<<<B, kArgmaxThreads, 0, s>>>(c->d_part, n_lsplit, c->n_cap, c->N, c->d_norm2, d_eam, L * E,
-                                                    d_best, d_best_sim, d_sims);
+    launch(K_MATCH_ARGMAX, eamc_argmax_kernel, dim3(B), dim3(kArgmaxThreads), 0, s, (const u64*)c->d_part, n_lsplit,
+           c->n_cap, c->N, (const u64*)c->d_norm2, d_eam, L * E, d_best, d_best_sim, d_sims);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
 }

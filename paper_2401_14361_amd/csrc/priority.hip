@@ -182,10 +182,11 @@ extern "C" int expert_priority(const moei_eamc* c, const int32_t* d_best, int32_
     const size_t LE = (size_t)c->d.L * c->d.E;
     ScoreArgs a{c->d_traces, c->cell_bytes, c->n_cap, c->N, c->d.L, c->d.E, d_best, B, cur_layer, d_slot_of,
                 (double)eps, d_cur_idx, d_cur_idx ? B * k : 0, d_prefetch, d_evict, c->d_keys, c->d_ids, d_n_pf, d_n_ev};
-    priority_score_kernel<<<1, kScoreThreads, 0, s>>>(a);
+    launch(K_PRIO_SCORE, priority_score_kernel, dim3(1), dim3(kScoreThreads), 0, s, a);
     MOEI_LAUNCH_CHECK();
     dim3 grid((unsigned)((LE + kWave - 1) / kWave), 2);
-    priority_rank_kernel<<<grid, kRankThreads, 0, s>>>(c->d_keys, c->d_ids, LE, d_n_pf, d_n_ev, d_pf_order, d_ev_order);
+    launch(K_PRIO_RANK, priority_rank_kernel, grid, dim3(kRankThreads), 0, s, (const u64*)c->d_keys,
+           (const int32_t*)c->d_ids, LE, (const int32_t*)d_n_pf, (const int32_t*)d_n_ev, d_pf_order, d_ev_order);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
 }

@@ -228,12 +228,12 @@ int launch_router_gemv(const void* d_W, const float* d_bias, const void* d_x, in
                        float* d_logits, hipStream_t s) {
     if (wdtype == MOEI_WDTYPE_BF16) {
         int vec_ok = (H % 8 == 0) && ((uintptr_t)d_W % 16 == 0) && ((uintptr_t)d_x % 16 == 0);
-        router_gemv_kernel<uint16_t><<<E, kWave, 0, s>>>((const uint16_t*)d_W, d_bias, (const uint16_t*)d_x, E, H,
-                                                        vec_ok, d_logits);
+        launch(K_ROUTER_GEMV, router_gemv_kernel<uint16_t>, dim3(E), dim3(kWave), 0, s, (const uint16_t*)d_W, d_bias,
+               (const uint16_t*)d_x, E, H, vec_ok, d_logits);
     } else {
         int vec_ok = (H % 4 == 0) && ((uintptr_t)d_W % 16 == 0) && ((uintptr_t)d_x % 16 == 0);
-        router_gemv_kernel<float><<<E, kWave, 0, s>>>((const float*)d_W, d_bias, (const float*)d_x, E, H, vec_ok,
-                                                      d_logits);
+        launch(K_ROUTER_GEMV, router_gemv_kernel<float>, dim3(E), dim3(kWave), 0, s, (const float*)d_W, d_bias,
+               (const float*)d_x, E, H, vec_ok, d_logits);
     }
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
@@ -242,14 +242,14 @@ int launch_router_gemv(const void* d_W, const float* d_bias, const void* d_x, in
 int launch_route_fused(const RouteFusedArgs& a, hipStream_t s) {
     if (a.E > kMaxE || a.k > kWave || a.k + a.n_shared > kWave)
         MOEI_FAIL(MOEI_EINVAL, "fused routing needs E <= %d and k + n_shared <= %d", kMaxE, kWave);
-    route_fused_kernel<<<1, kWave, a.E * sizeof(float), s>>>(a);
+    launch(K_ROUTE_TOPK, route_fused_kernel, dim3(1), dim3(kWave), a.E * sizeof(float), s, a);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
 }
 
 int launch_gather_slots(const int32_t* d_idx, int k, const int32_t* d_slot_of_row, int32_t* d_slot_ids,
                         int32_t* d_flags, hipStream_t s) {
-    gather_slots_kernel<<<1, kWave, 0, s>>>(d_idx, k, d_slot_of_row, d_slot_ids, d_flags);
+    launch(K_ROUTE_TOPK, gather_slots_kernel, dim3(1), dim3(kWave), 0, s, d_idx, k, d_slot_of_row, d_slot_ids, d_flags);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
 }
@@ -266,10 +266,8 @@ extern "C" int moe_route_topk(const float* d_logits, int32_t B, int32_t E, int32
     if (B == 0) return MOEI_OK;  // nothing to route: the (empty) buffers may be null
     MOEI_REQUIRE(d_logits && d_idx && d_w, "moe_route_topk: null pointer");
     hipStream_t s = as_stream(stream);
-    if (k <= kWave)
-        route_topk_kernel<<<B, kWave, E * sizeof(float), s>>>(d_logits, E, k, renorm != 0, d_idx, d_w);
-    else
-        route_topk_wide_kernel<<<B, kWave, E * sizeof(float), s>>>(d_logits, E, k, renorm != 0, d_idx, d_w);
+    launch(K_ROUTE_TOPK, k <= kWave ? route_topk_kernel : route_topk_wide_kernel, dim3(B), dim3(kWave),
+           E * sizeof(float), s, d_logits, E, k, (int)(renorm != 0), d_idx, d_w);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
 }
@@ -282,7 +280,8 @@ extern "C" int eam_update(int32_t* d_eam, int32_t B, int32_t L, int32_t E, int32
     if (B == 0) return MOEI_OK;
     MOEI_REQUIRE(d_eam && d_idx, "eam_update: null pointer");
     int n = B * k;
-    eam_update_kernel<<<(n + 255) / 256, 256, 0, as_stream(stream)>>>(d_eam, B, L, E, layer, d_idx, k);
+    launch(K_ROUTE_TOPK, eam_update_kernel, dim3((n + 255) / 256), dim3(256), 0, as_stream(stream), d_eam, B, L, E, layer,
+           d_idx, k);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
 }

@@ -24,6 +24,15 @@ def split_expert(cfg, w: np.ndarray):
     return w[:I * H].reshape(I, H), w[I * H:2 * I * H].reshape(I, H), w[2 * I * H:].reshape(H, I)
 
 
+def pack_bank(m, cfg, bank: np.ndarray) -> np.ndarray:
+    """Experts drawn as plain matrices -> the library's slot layout (its own packer; data movement)."""
+    desc = m.ModelDesc.from_config(cfg)
+    out = np.empty_like(bank)
+    for u in range(bank.shape[0]):
+        m.expert_pack(desc, *split_expert(cfg, bank[u]), out=out[u])
+    return out
+
+
 def pinned(a: np.ndarray) -> torch.Tensor:
     """A pinned host copy (the library reads misses from it asynchronously)."""
     src = torch.from_numpy(np.ascontiguousarray(a).view(np.int16) if a.dtype == np.uint16 else np.ascontiguousarray(a))

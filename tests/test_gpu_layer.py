@@ -10,7 +10,7 @@ import torch
 
 import moei_inputs as mi
 from oracle import moei_oracle as O
-from tests.helpers import EPS, dev, pick_clear_tokens, pinned, rel_max_err, split_expert
+from tests.helpers import EPS, dev, pack_bank, pick_clear_tokens, pinned, rel_max_err, split_expert
 
 pytestmark = pytest.mark.gpu
 
@@ -29,7 +29,8 @@ def test_cache_retrieve_sequence_and_slot_contents(m):
     cfg = mi.get_config("C1").scaled(H=64, I=32)
     L, E, k, S = cfg.L, cfg.E, cfg.k, 6
     bank = mi.expert_bank(cfg, L * E, threads=2)
-    host = pinned(bank)
+    packed = pack_bank(m, cfg, bank)
+    host = pinned(packed)
     cache = m.Cache(m.ModelDesc.from_config(cfg), S, host)
     for warm in (True, False):
         cache.reset(S if warm else 0)
@@ -53,7 +54,7 @@ def test_cache_retrieve_sequence_and_slot_contents(m):
             s = int(ref.slot_of[f])
             if s >= 0:
                 got = cache.slot_tensor(s).cpu().numpy()
-                assert (got == bank[f]).all()
+                assert (got == packed[f]).all()
     with pytest.raises(m.MoeiError):
         cache.retrieve(0, [1, 1], [])
     with pytest.raises(m.MoeiError):
@@ -79,7 +80,7 @@ def _replay(m, cfg, S, n_tokens, n_unique, cell_bytes, rid=0):
     desc = m.ModelDesc.from_config(cfg)
     eamc = m.Eamc(desc, cfg.N, cell_bytes)
     eamc.load(T)
-    cache = m.Cache(desc, S, pinned(bank), pinned(shared) if cfg.n_shared else None)
+    cache = m.Cache(desc, S, pinned(pack_bank(m, cfg, bank)), pinned(pack_bank(m, cfg, shared)) if cfg.n_shared else None)
     cache.reset(min(S, L * E))
     d_eam = dev(req.prefill_eam.astype(np.int32))
     d_routers = [dev(w) for w in routers]
@@ -155,6 +156,7 @@ def test_async_layer_step_matches_sync_and_flags_a_miss(m):
     desc = m.ModelDesc.from_config(cfg)
     eamc = m.Eamc(desc, cfg.N)
     eamc.load(T)
+    bank, shared = pack_bank(m, cfg, bank), pack_bank(m, cfg, shared)
     outs = {}
     for mode in ("sync", "async"):
         cache = m.Cache(desc, L * E, pinned(bank), pinned(shared))

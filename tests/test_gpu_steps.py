@@ -11,7 +11,7 @@ import torch
 
 import moei_inputs as mi
 from oracle import moei_oracle as O
-from tests.helpers import EPS, dev, pinned, rel_max_err, split_expert
+from tests.helpers import EPS, dev, pack_bank, pinned, rel_max_err, split_expert
 
 pytestmark = pytest.mark.gpu
 
@@ -223,12 +223,14 @@ def _ffn_case(m, cfg, n_unique, slot_pick, gates, seed, n_slots=None):
     S = n_slots or n_unique
     desc = m.ModelDesc.from_config(cfg)
     cache = m.Cache(desc, S)
+    packed = pack_bank(m, cfg, bank)
     for s in range(min(S, n_unique)):
-        cache.slot_tensor(s).copy_(dev(bank[s]).view(cache.slot_tensor(s).dtype))
+        cache.slot_tensor(s).copy_(dev(packed[s]).view(cache.slot_tensor(s).dtype))
     n_sh = cfg.L * cfg.n_shared
     sh = mi.expert_bank(cfg.scaled(cid=cfg.cid + 50), max(n_sh, 1), threads=2)
+    sh_packed = pack_bank(m, cfg, sh)
     for s in range(n_sh):
-        cache.slot_tensor(S + s).copy_(dev(sh[s]).view(cache.slot_tensor(S + s).dtype))
+        cache.slot_tensor(S + s).copy_(dev(sh_packed[s]).view(cache.slot_tensor(S + s).dtype))
     rng = np.random.default_rng(seed)
     x = mi.to_store(cfg, rng.standard_normal(cfg.H).astype(np.float32))
     y = m.expert_ffn_gemv(cache, dev(np.asarray(slot_pick, np.int32)), dev(np.asarray(gates, np.float32)), dev(x))
@@ -244,7 +246,8 @@ def _ffn_case(m, cfg, n_unique, slot_pick, gates, seed, n_slots=None):
 
 
 @pytest.mark.parametrize("wdtype", ["bf16", "fp32"])
-@pytest.mark.parametrize("H,I", [(256, 512), (2048, 1408), (200, 136), (100, 52), (520, 4104), (64, 9000)])
+@pytest.mark.parametrize("H,I", [(256, 512), (2048, 1408), (200, 136), (100, 52), (520, 4104), (64, 9000),
+                                 (1536, 40), (4096, 96), (5120, 48), (8192, 16), (3584, 24)])
 def test_expert_ffn_shapes(m, wdtype, H, I):
     cfg = mi.get_config("C1").scaled(H=H, I=I, wdtype=wdtype, L=2, n_shared=1, k=3, E=8)
     err, cache = _ffn_case(m, cfg, 5, [3, 0, 4, 5 + 1], [0.5, 0.3, 0.2, 1.0], seed=H + I)
