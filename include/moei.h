@@ -193,6 +193,16 @@ int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d_eam, int32
                      const void* d_router_w, const float* d_router_bias,
                      const void* d_x, float* d_y,
                      int32_t* h_topk_idx, int32_t* h_best, int32_t* h_n_miss, void* stream);
+/* Makes `stream` wait for the match/priority work that the last moe_decode_layer put on
+ * the cache's side stream (the next moe_decode_layer does this by itself).  Call it
+ * before ending a stream capture that contains asynchronous layer steps, so that the
+ * side stream has joined `stream` again. */
+int moei_cache_join(moei_cache* c, void* stream);
+/* Waits on the host for the cache's own streams (match/priority work, miss fills) and
+ * forgets any pending cross-stream dependency.  Call it before beginning and after
+ * ending a stream capture, so that no wait inside the capture refers to work outside
+ * it and vice versa. */
+int moei_cache_sync(moei_cache* c);
 /* Results of the most recent moe_decode_layer on this cache, copied to the host
  * (any pointer may be NULL): gate weights [k], best similarity, score matrices [L*E],
  * orders [L*E] and their lengths.  Synchronises both streams. */

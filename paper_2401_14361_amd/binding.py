@@ -28,7 +28,7 @@ EXPORTS = [
     "moe_route_topk", "eam_update", "eamc_match", "expert_priority",
     "moei_cache_create", "moei_cache_destroy", "moei_expert_pack", "moei_cache_reset", "moei_cache_slot_ptr", "moei_cache_slot_table",
     "moei_cache_get_slots", "moei_cache_retrieve", "expert_ffn_gemv", "moei_cache_error_flags",
-    "moe_decode_layer", "moei_cache_last_step",
+    "moe_decode_layer", "moei_cache_last_step", "moei_cache_join", "moei_cache_sync",
     "moei_profile_enable", "moei_profile_disable", "moei_profile_kernels", "moei_profile_kernel_name",
     "moei_profile_read",
 ]
@@ -204,6 +204,12 @@ class Cache:
         f = C.c_int32(0)
         _check(lib().moei_cache_error_flags(self.h, C.byref(f), _stream(stream)))
         return f.value
+
+    def join(self, stream=None) -> None:
+        _check(lib().moei_cache_join(self.h, _stream(stream)))
+
+    def sync(self) -> None:
+        _check(lib().moei_cache_sync(self.h))
 
     def last_step(self, stream=None) -> dict:
         LE, k = self.desc.L * self.desc.E, self.desc.k

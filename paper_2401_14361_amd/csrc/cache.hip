@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "kernels.hpp"
+#include "score.hpp"
 
 namespace moei {
 
@@ -15,6 +16,7 @@ namespace {
 thread_local char g_err[512] = "";
 
 constexpr int kMaxAct = 64;  // k + n_shared never exceeds one wavefront
+constexpr int kRing = 4;     // buffer sets handed from the routing to the side stream, used in turn
 
 struct SlotUpdates {
     int n;
@@ -73,12 +75,20 @@ struct moei_cache {
     std::vector<int32_t> slot_of, owner;
     int32_t* d_slot_of = nullptr;
     int32_t* d_flags = nullptr;
+    unsigned* d_ticket = nullptr;
     hipStream_t copy_stream = nullptr, side_stream = nullptr;
     hipEvent_t ev_copy = nullptr, ev_routed = nullptr, ev_side = nullptr, ev_main = nullptr;
+    hipEvent_t ev_match[kRing] = {};             // end of the side chain of the last step with this parity;
+                                                  // ev_side aliases the most recent of the two
+    bool match_pending[kRing] = {};
     bool side_pending = false;
+    int parity = 0;  // which buffer set the current step writes
     FfnScratch ffn;
     float* d_logits = nullptr;
-    int32_t* d_idx = nullptr;
+    int32_t* d_idx2[kRing] = {};  // picks of the last kRing steps (the side stream reads one set while the
+                                  // routing of later steps writes the others)
+    int32_t* d_idx = nullptr;                 // = d_idx2[parity] of the most recent step
+    int32_t* d_snap[kRing] = {};  // EAM snapshots the match reads, same rotation
     float* d_w = nullptr;
     int32_t* d_slot_ids = nullptr;
     float* d_gate = nullptr;
@@ -99,9 +109,14 @@ extern "C" int moei_cache_destroy(moei_cache* c) {
     (void)hipFree(c->d_pool);
     (void)hipFree(c->d_slot_of);
     (void)hipFree(c->d_flags);
+    (void)hipFree(c->d_ticket);
     ffn_scratch_free(&c->ffn);
     (void)hipFree(c->d_logits);
-    (void)hipFree(c->d_idx);
+    for (int r = 0; r < kRing; ++r) {
+        (void)hipFree(c->d_idx2[r]);
+        (void)hipFree(c->d_snap[r]);
+        if (c->ev_match[r]) (void)hipEventDestroy(c->ev_match[r]);
+    }
     (void)hipFree(c->d_w);
     (void)hipFree(c->d_slot_ids);
     (void)hipFree(c->d_gate);
@@ -116,7 +131,6 @@ extern "C" int moei_cache_destroy(moei_cache* c) {
     if (c->pin) (void)hipHostFree(c->pin);
     if (c->ev_copy) (void)hipEventDestroy(c->ev_copy);
     if (c->ev_routed) (void)hipEventDestroy(c->ev_routed);
-    if (c->ev_side) (void)hipEventDestroy(c->ev_side);
     if (c->ev_main) (void)hipEventDestroy(c->ev_main);
     if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
     if (c->side_stream) (void)hipStreamDestroy(c->side_stream);
@@ -145,8 +159,13 @@ int cache_alloc(moei_cache* c) {
     MOEI_DMALLOC(c->d_pool, (size_t)c->n_total * c->slot_bytes);
     MOEI_DMALLOC(c->d_slot_of, LE * 4);
     MOEI_DMALLOC(c->d_flags, 4);
+    MOEI_DMALLOC(c->d_ticket, 4);
     MOEI_DMALLOC(c->d_logits, (size_t)d.E * 4);
-    MOEI_DMALLOC(c->d_idx, (size_t)kMaxAct * 4);
+    for (int r = 0; r < kRing; ++r) {
+        MOEI_DMALLOC(c->d_idx2[r], (size_t)kMaxAct * 4);
+        MOEI_DMALLOC(c->d_snap[r], LE * 4);
+    }
+    c->d_idx = c->d_idx2[0];
     MOEI_DMALLOC(c->d_w, (size_t)kMaxAct * 4);
     MOEI_DMALLOC(c->d_slot_ids, (size_t)kMaxAct * 4);
     MOEI_DMALLOC(c->d_gate, (size_t)kMaxAct * 4);
@@ -160,6 +179,7 @@ int cache_alloc(moei_cache* c) {
     MOEI_DMALLOC(c->d_n_ev, 4);
 #undef MOEI_DMALLOC
     MOEI_HIP(hipMemset(c->d_flags, 0, 4));
+    MOEI_HIP(hipMemset(c->d_ticket, 0, 4));
     MOEI_HIP(hipMemset(c->d_n_pf, 0, 4));
     MOEI_HIP(hipMemset(c->d_n_ev, 0, 4));
     MOEI_HIP(hipMemset(c->d_best, 0xff, 4));
@@ -171,7 +191,7 @@ int cache_alloc(moei_cache* c) {
     MOEI_HIP(hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking));
     MOEI_HIP(hipEventCreateWithFlags(&c->ev_copy, hipEventDisableTiming));
     MOEI_HIP(hipEventCreateWithFlags(&c->ev_routed, hipEventDisableTiming));
-    MOEI_HIP(hipEventCreateWithFlags(&c->ev_side, hipEventDisableTiming));
+    for (int r = 0; r < kRing; ++r) MOEI_HIP(hipEventCreateWithFlags(&c->ev_match[r], hipEventDisableTiming));
     MOEI_HIP(hipEventCreateWithFlags(&c->ev_main, hipEventDisableTiming));
     return MOEI_OK;
 }
@@ -233,6 +253,7 @@ extern "C" int moei_cache_reset(moei_cache* c, int32_t n_resident) {
                  "moei_cache_reset: n_resident = %d outside [0, min(S, L*E)]", n_resident);
     MOEI_HIP(hipDeviceSynchronize());
     c->side_pending = false;
+    for (int r = 0; r < kRing; ++r) c->match_pending[r] = false;
     std::fill(c->slot_of.begin(), c->slot_of.end(), -1);
     std::fill(c->owner.begin(), c->owner.end(), -1);
     for (int s = 0; s < n_resident; ++s) {
@@ -385,47 +406,76 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
     const int k = d.k, E = d.E;
     int rc;
 
-    // the previous step's match/priority work still reads d_eam and the pick buffer
-    if (c->side_pending) MOEI_HIP(hipStreamWaitEvent(s, c->ev_side, 0));
+    // Routing hands the side stream a snapshot of the updated EAM and its picks in one of
+    // kRing buffer sets used in turn, so the main stream never waits for the match and scoring
+    // of recent steps: it only must not overwrite a set that the step kRing steps back still
+    // reads (a wait that has long been satisfied unless the side stream falls far behind).
+    c->parity = (c->parity + 1) % kRing;
+    if (c->match_pending[c->parity]) MOEI_HIP(hipStreamWaitEvent(s, c->ev_match[c->parity], 0));
+    c->d_idx = c->d_idx2[c->parity];
+    int32_t* d_snap = c->d_snap[c->parity];
 
-    rc = launch_router_gemv(d_router_w, d_router_bias, d_x, E, d.H, d.wdtype, c->d_logits, s);
-    if (rc) return rc;
     RouteFusedArgs ra{};
+    ra.W = d_router_w;
+    ra.bias = d_router_bias;
+    ra.x = d_x;
+    ra.H = d.H;
     ra.logits = c->d_logits;
+    ra.ticket = c->d_ticket;
     ra.E = E;
     ra.k = k;
     ra.renorm = d.renorm_topk != 0;
     ra.idx = c->d_idx;
     ra.w = c->d_w;
-    ra.eam_row = d_eam + (size_t)layer * E;
+    ra.eam = d_eam;
+    ra.snap = d_snap;
+    ra.LE = d.L * E;
+    ra.layer = layer;
     ra.slot_of_row = c->d_slot_of + (size_t)layer * E;
     ra.n_shared = d.n_shared;
     ra.shared_base = c->S + layer * d.n_shared;
     ra.slot_ids = c->d_slot_ids;
     ra.gate = c->d_gate;
     ra.flags = sync_mode ? nullptr : c->d_flags;
-    rc = launch_route_fused(ra, s);
+    rc = launch_route_fused(ra, d.wdtype, s);
     if (rc) return rc;
     if (sync_mode) MOEI_HIP(hipMemcpyAsync(c->pin->idx, c->d_idx, (size_t)k * 4, hipMemcpyDeviceToHost, s));
     MOEI_HIP(hipEventRecord(c->ev_routed, s));
+    // Asynchronous step: the expert FFNs go onto the main stream right behind the routing,
+    // before any side-stream work is enqueued, so that neither the host-side enqueue time of
+    // the match nor a captured graph's branch placement comes between routing and FFN.
+    if (!sync_mode) {
+        rc = launch_expert_ffn(d, c->d_pool, c->slot_elems, c->n_total, c->ffn, c->d_slot_ids, c->d_gate,
+                               k + d.n_shared, d_x, d_y, c->d_flags, s);
+        if (rc) return rc;
+    }
 
     // side stream: EAMC match and priorities from the EAM that now holds this layer's routing
     hipStream_t side = c->side_stream;
     MOEI_HIP(hipStreamWaitEvent(side, c->ev_routed, 0));
-    rc = eamc_match(eamc, d_eam, 1, d.L - 1, c->d_best, c->d_best_sim, nullptr, side);
+    // match and scoring in one launch sequence (the workgroup that finishes the match scores
+    // the matched trace), then the two orders
+    ScoreArgs sc = make_score_args(eamc, c->d_best, 1, layer, c->d_slot_of, d.eps, c->d_idx, k, c->d_P, c->d_V,
+                                   c->d_n_pf, c->d_n_ev);
+    rc = launch_match(eamc, d_snap, 1, d.L - 1, c->d_best, c->d_best_sim, nullptr, &sc, side);
     if (rc) return rc;
-    rc = expert_priority(eamc, c->d_best, 1, layer, c->d_slot_of, d.eps, c->d_idx, k, c->d_P, c->d_V, c->d_pf_order,
-                         c->d_n_pf, c->d_ev_order, c->d_n_ev, side);
+    rc = launch_priority_rank(eamc, c->d_n_pf, c->d_n_ev, c->d_pf_order, c->d_ev_order, side);
     if (rc) return rc;
     if (sync_mode) {
         MOEI_HIP(hipMemcpyAsync(&c->pin->best, c->d_best, 4, hipMemcpyDeviceToHost, side));
         MOEI_HIP(hipMemcpyAsync(&c->pin->n_ev, c->d_n_ev, 4, hipMemcpyDeviceToHost, side));
         MOEI_HIP(hipMemcpyAsync(c->pin->ev_head, c->d_ev_order, (size_t)k * 4, hipMemcpyDeviceToHost, side));
     }
-    MOEI_HIP(hipEventRecord(c->ev_side, side));
+    // one event per step at the end of the side chain (an event record between two kernels
+    // costs a few microseconds on its stream): it releases this step's buffer set and is what
+    // a join or a host-side wait refers to
+    MOEI_HIP(hipEventRecord(c->ev_match[c->parity], side));
+    c->match_pending[c->parity] = true;
+    c->ev_side = c->ev_match[c->parity];
     c->side_pending = true;
 
-    if (sync_mode) {
+    if (!sync_mode) return MOEI_OK;
+    {
         MOEI_HIP(hipEventSynchronize(c->ev_routed));
         int n_miss = 0;
         for (int j = 0; j < k; ++j) {
@@ -453,6 +503,21 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
     }
     return launch_expert_ffn(d, c->d_pool, c->slot_elems, c->n_total, c->ffn, c->d_slot_ids, c->d_gate,
                              k + d.n_shared, d_x, d_y, c->d_flags, s);
+}
+
+extern "C" int moei_cache_join(moei_cache* c, void* stream) {
+    MOEI_REQUIRE(c, "moei_cache_join: null pointer");
+    if (c->side_pending) MOEI_HIP(hipStreamWaitEvent(as_stream(stream), c->ev_side, 0));
+    return MOEI_OK;
+}
+
+extern "C" int moei_cache_sync(moei_cache* c) {
+    MOEI_REQUIRE(c, "moei_cache_sync: null pointer");
+    MOEI_HIP(hipStreamSynchronize(c->side_stream));
+    MOEI_HIP(hipStreamSynchronize(c->copy_stream));
+    c->side_pending = false;
+    for (int r = 0; r < kRing; ++r) c->match_pending[r] = false;
+    return MOEI_OK;
 }
 
 extern "C" int moei_cache_last_step(moei_cache* c, float* h_gate_w, float* h_best_sim, float* h_prefetch,

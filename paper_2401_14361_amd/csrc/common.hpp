@@ -46,8 +46,7 @@ constexpr int kWave = 64;
 // Optional per-launch start/stop events for every kernel of the library (see
 // moei_profile_enable in moei.h).  Disabled: one predictable branch per launch.
 enum KernelId {
-    K_ROUTER_GEMV = 0,
-    K_ROUTE_TOPK,
+    K_ROUTE_TOPK = 0,
     K_MATCH_DOT,
     K_MATCH_ARGMAX,
     K_PRIO_SCORE,
@@ -98,6 +97,54 @@ __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
     return v;
+}
+
+// The same reductions without LDS traffic: DPP inside each row of 16 lanes, then the four
+// row results are read through scalar registers.  Every lane gets the result.
+#define MOEI_DPP_F32(v, ctrl) \
+    __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, (v)), (ctrl), 0xF, 0xF, false))
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+    v += MOEI_DPP_F32(v, 0xB1);   // quad_perm [1,0,3,2]
+    v += MOEI_DPP_F32(v, 0x4E);   // quad_perm [2,3,0,1]
+    v += MOEI_DPP_F32(v, 0x141);  // row_half_mirror
+    v += MOEI_DPP_F32(v, 0x140);  // row_mirror
+    const int b = __builtin_bit_cast(int, v);
+    float r = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+    r += __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+    r += __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+    r += __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+    return r;
+}
+__device__ __forceinline__ float wave_max_dpp(float v) {
+    v = fmaxf(v, MOEI_DPP_F32(v, 0xB1));
+    v = fmaxf(v, MOEI_DPP_F32(v, 0x4E));
+    v = fmaxf(v, MOEI_DPP_F32(v, 0x141));
+    v = fmaxf(v, MOEI_DPP_F32(v, 0x140));
+    const int b = __builtin_bit_cast(int, v);
+    float r = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+    r = fmaxf(r, __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16)));
+    r = fmaxf(r, __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32)));
+    r = fmaxf(r, __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48)));
+    return r;
+}
+
+#define MOEI_DPP_U32(v, ctrl) ((unsigned)__builtin_amdgcn_update_dpp(0, (int)(v), (ctrl), 0xF, 0xF, false))
+__device__ __forceinline__ unsigned wave_sum_u32_dpp(unsigned v) {
+    v += MOEI_DPP_U32(v, 0xB1);
+    v += MOEI_DPP_U32(v, 0x4E);
+    v += MOEI_DPP_U32(v, 0x141);
+    v += MOEI_DPP_U32(v, 0x140);
+    return (unsigned)__builtin_amdgcn_readlane((int)v, 0) + (unsigned)__builtin_amdgcn_readlane((int)v, 16) +
+           (unsigned)__builtin_amdgcn_readlane((int)v, 32) + (unsigned)__builtin_amdgcn_readlane((int)v, 48);
+}
+// Exact 64-bit sum over the wavefront: four 16-bit digits are summed separately (each digit
+// sum stays below 2^22) and recombined.
+__device__ __forceinline__ unsigned long long wave_sum_u64_dpp(unsigned long long v) {
+    const unsigned long long d0 = wave_sum_u32_dpp((unsigned)(v & 0xffffu));
+    const unsigned long long d1 = wave_sum_u32_dpp((unsigned)((v >> 16) & 0xffffu));
+    const unsigned long long d2 = wave_sum_u32_dpp((unsigned)((v >> 32) & 0xffffu));
+    const unsigned long long d3 = wave_sum_u32_dpp((unsigned)(v >> 48));
+    return d0 + (d1 << 16) + (d2 << 32) + (d3 << 48);
 }
 
 // bf16 pair packed in a 32-bit word (element 0 in the low half) -> two fp32, exactly.

@@ -40,21 +40,6 @@ struct FfnArgs {
     int32_t* flags;
 };
 
-// Sum over the 64 lanes, same value returned to every lane: DPP inside each row of 16
-// lanes, then the four row totals are read through scalar registers.
-__device__ __forceinline__ float wave_sum_dpp(float v) {
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, false));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, false));
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, false));
-    const int b = __builtin_bit_cast(int, v);
-    float r = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
-    r += __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
-    r += __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
-    r += __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
-    return r;
-}
-
 __device__ __forceinline__ float silu(float g) { return g / (1.0f + expf(-g)); }
 
 // Adds the wavefronts' y rows in wavefront order and writes the workgroup's partial row.
@@ -339,11 +324,22 @@ int plan_waves(int n_units, int blocks, int max_waves) {
     return best;
 }
 
+// Raises a kernel's dynamic-LDS limit above 64 KiB, once per kernel and size (the call
+// is not a stream operation, so it stays out of the per-launch path and of captures).
 template <typename K>
 int allow_big_lds(K kernel, size_t bytes) {
-    if (bytes > 64 * 1024)
-        MOEI_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)bytes));
+    static const void* seen_fn[64];
+    static size_t seen_bytes[64];
+    static int n_seen = 0;
+    if (bytes <= 64 * 1024) return MOEI_OK;
+    const void* fn = reinterpret_cast<const void*>(kernel);
+    for (int i = 0; i < n_seen; ++i)
+        if (seen_fn[i] == fn && seen_bytes[i] >= bytes) return MOEI_OK;
+    MOEI_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    if (n_seen < 64) {
+        seen_fn[n_seen] = fn;
+        seen_bytes[n_seen++] = bytes;
+    }
     return MOEI_OK;
 }
 

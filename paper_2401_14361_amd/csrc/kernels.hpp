@@ -9,20 +9,25 @@ namespace moei {
 
 // ----------------------------------------------------------------- route.hip
 struct RouteFusedArgs {
-    const float* logits;         // [E]
+    const void* W;               // router matrix [E][H] in the weight dtype
+    const float* bias;           // [E] or null
+    const void* x;               // [H] in the weight dtype
+    int H, vec_ok;
+    float* logits;               // [E] scratch, written then read by the last wavefront
+    unsigned* ticket;            // arrival counter, zero between launches
     int E, k, renorm;
     int32_t* idx;                // [k] out
     float* w;                    // [k] out
-    int32_t* eam_row;            // eam + layer*E, updated in place
+    int32_t* eam;                // the request's EAM [L*E]; row `layer` is updated in place
+    int32_t* snap;               // [L*E] copy of the updated EAM for the match on the side stream
+    int LE, layer;
     const int32_t* slot_of_row;  // slot_of + layer*E
     int n_shared, shared_base;   // shared slot ids: shared_base + s
     int32_t* slot_ids;           // [k + n_shared] out
     float* gate;                 // [k + n_shared] out
     int32_t* flags;              // error flags (bit 1: pick not resident)
 };
-int launch_router_gemv(const void* d_W, const float* d_bias, const void* d_x, int E, int H, int wdtype,
-                       float* d_logits, hipStream_t s);
-int launch_route_fused(const RouteFusedArgs& a, hipStream_t s);
+int launch_route_fused(RouteFusedArgs a, int wdtype, hipStream_t s);
 int launch_gather_slots(const int32_t* d_idx, int k, const int32_t* d_slot_of_row, int32_t* d_slot_ids,
                         int32_t* d_flags, hipStream_t s);
 
@@ -50,9 +55,11 @@ struct moei_eamc {
     unsigned long long* d_norm2 = nullptr;  // [n_cap] squared norms of the flattened traces
     unsigned long long* d_part = nullptr;   // [B_max][lsplit_max][n_cap] partial dot products
     int32_t lsplit_max = 0;
-    // priority scratch: compacted candidate lists
+    unsigned long long* d_cand = nullptr;   // [B_max][workgroups][2] per-workgroup winners (dot, norm)
+    int32_t* d_cand_idx = nullptr;          // [B_max][workgroups] their trace indices
+    unsigned* d_ticket = nullptr;           // [B_max] arrival counters of the final pick
+    // priority scratch
     unsigned long long* d_keys = nullptr;  // [2][L*E] sort keys (prefetch, evict)
-    int32_t* d_ids = nullptr;              // [2][L*E] flat ids of the candidates
 };
 
 namespace moei {

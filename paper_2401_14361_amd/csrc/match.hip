@@ -8,12 +8,14 @@
 // rows sit in LDS.  Dot products are exact 64-bit integers; the arg-max compares
 // dot_a^2 * |T_b|^2 with dot_b^2 * |T_a|^2 in 192-bit integer arithmetic, so the
 // winner does not depend on floating-point rounding.
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
 #include <vector>
 
 #include "kernels.hpp"
+#include "score.hpp"
 
 namespace moei {
 
@@ -21,8 +23,6 @@ namespace {
 
 constexpr int kDotThreads = 256;
 constexpr int kMaxE = 2048;
-constexpr int kArgmaxThreads = 1024;
-typedef unsigned long long u64;
 typedef unsigned __int128 u128;
 
 struct DotArgs {
@@ -152,29 +152,59 @@ __global__ void __launch_bounds__(kDotThreads) eamc_dot_kernel(DotArgs a) {
 }
 
 struct Best {
-    u64 dot;  // <q, T>
-    u64 nt;   // |T|^2, never 0 here (an all-zero trace enters as dot 0, nt 1)
-    int idx;  // -1: none
+    u64 dot;     // <q, T>
+    u64 nt;      // |T|^2, never 0 here (an all-zero trace enters as dot 0, nt 1)
+    double key;  // dot^2 / nt in fp64: decides all but near ties
+    int idx;     // -1: none
 };
 
+__device__ __forceinline__ Best make_best(u64 dot, u64 nt, int idx) {
+    Best b;
+    b.dot = nt ? dot : 0;
+    b.nt = nt ? nt : 1;
+    b.key = ((double)b.dot * (double)b.dot) / (double)b.nt;
+    b.idx = idx;
+    return b;
+}
+
 // a.dot^2 * b.nt  vs  b.dot^2 * a.nt, exactly, as 192-bit integers.
-__device__ __forceinline__ int cmp_sim(const Best& a, const Best& b) {
-    u128 a2 = (u128)a.dot * a.dot, b2 = (u128)b.dot * b.dot;
-    u128 al = (u128)(u64)a2 * b.nt, ah = (u128)(u64)(a2 >> 64) * b.nt + (al >> 64);
-    u128 bl = (u128)(u64)b2 * a.nt, bh = (u128)(u64)(b2 >> 64) * a.nt + (bl >> 64);
+__device__ __noinline__ int cmp_sim_exact(u64 adot, u64 ant, u64 bdot, u64 bnt) {
+    u128 a2 = (u128)adot * adot, b2 = (u128)bdot * bdot;
+    u128 al = (u128)(u64)a2 * bnt, ah = (u128)(u64)(a2 >> 64) * bnt + (al >> 64);
+    u128 bl = (u128)(u64)b2 * ant, bh = (u128)(u64)(b2 >> 64) * ant + (bl >> 64);
     if (ah != bh) return ah > bh ? 1 : -1;
     u64 all = (u64)al, bll = (u64)bl;
     if (all != bll) return all > bll ? 1 : -1;
     return 0;
 }
 
-__device__ __forceinline__ Best pick(const Best& a, const Best& b) {
-    if (b.idx < 0) return a;
-    if (a.idx < 0) return b;
-    int c = cmp_sim(a, b);
-    if (c > 0) return a;
-    if (c < 0) return b;
-    return a.idx < b.idx ? a : b;  // equal similarity: lowest trace index
+// The fp64 keys carry a relative error below 2^-50; a gap wider than 2^-48 settles the
+// order, anything closer is decided by the exact integer comparison.
+__device__ __forceinline__ int cmp_sim(Best a, Best b) {
+    const double d = a.key - b.key;
+    const double tol = fmax(a.key, b.key) * 0x1p-48;
+    if (d > tol) return 1;
+    if (d < -tol) return -1;
+    return cmp_sim_exact(a.dot, a.nt, b.dot, b.nt);
+}
+
+// The better of two candidates, field by field (the structs stay in registers).
+__device__ __forceinline__ Best pick(Best a, Best b) {
+    bool take_b;
+    if (b.idx < 0) {
+        take_b = false;
+    } else if (a.idx < 0) {
+        take_b = true;
+    } else {
+        const int c = cmp_sim(a, b);
+        take_b = c < 0 || (c == 0 && b.idx < a.idx);  // equal similarity: lowest trace index
+    }
+    Best r;
+    r.dot = take_b ? b.dot : a.dot;
+    r.nt = take_b ? b.nt : a.nt;
+    r.key = take_b ? b.key : a.key;
+    r.idx = take_b ? b.idx : a.idx;
+    return r;
 }
 
 __device__ __forceinline__ u64 shfl_xor_u64(u64 v, int off) {
@@ -183,70 +213,149 @@ __device__ __forceinline__ u64 shfl_xor_u64(u64 v, int off) {
     return ((u64)hi << 32) | lo;
 }
 
-__device__ __forceinline__ double cosine(u64 dot, u64 nq, u64 nt) {
-    if (nq == 0 || nt == 0) return 0.0;
-    return (double)dot / (sqrt((double)nq) * sqrt((double)nt));
-}
-
-// One workgroup per query: sums the split partials, writes similarities, block arg-max.
-__global__ void __launch_bounds__(kArgmaxThreads)
-    eamc_argmax_kernel(const u64* __restrict__ part, int n_lsplit, int n_cap, int N, const u64* __restrict__ norm2,
-                       const int32_t* __restrict__ q, int LE, int32_t* __restrict__ best, float* __restrict__ best_sim,
-                       float* __restrict__ sims) {
-    __shared__ u64 s_dot[kArgmaxThreads / kWave];
-    __shared__ u64 s_nt[kArgmaxThreads / kWave];
-    __shared__ int s_idx[kArgmaxThreads / kWave];
-    __shared__ u64 s_nq;
-    const int b = blockIdx.x;
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1), wv = tid / kWave;
-
-    u64 nq = 0;
-    for (int i = tid; i < LE; i += kArgmaxThreads) {
-        u64 v = (uint32_t)q[(size_t)b * LE + i];
-        nq += v * v;
-    }
-    nq = wave_sum_u64(nq);
-    if (lane == 0) s_dot[wv] = nq;
-    __syncthreads();
-    if (tid == 0) {
-        u64 t = 0;
-        for (int i = 0; i < kArgmaxThreads / kWave; ++i) t += s_dot[i];
-        s_nq = t;
-    }
-    __syncthreads();
-    nq = s_nq;
-    __syncthreads();
-
-    Best me{0, 1, -1};
-    for (int n = tid; n < N; n += kArgmaxThreads) {
-        u64 dot = 0;
-        for (int s = 0; s < n_lsplit; ++s) dot += part[((size_t)b * n_lsplit + s) * n_cap + n];
-        u64 nt = norm2[n];
-        if (sims) sims[(size_t)b * N + n] = (float)cosine(dot, nq, nt);
-        Best c{nt ? dot : 0, nt ? nt : 1, n};
-        me = pick(me, c);
-    }
+__device__ __forceinline__ Best wave_pick(Best me) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         Best o;
         o.dot = shfl_xor_u64(me.dot, off);
         o.nt = shfl_xor_u64(me.nt, off);
+        o.key = __longlong_as_double((long long)shfl_xor_u64((u64)__double_as_longlong(me.key), off));
         o.idx = __shfl_xor(me.idx, off, 64);
         me = pick(me, o);
     }
+    return me;
+}
+
+__device__ __forceinline__ double cosine(u64 dot, u64 nq, u64 nt) {
+    if (nq == 0 || nt == 0) return 0.0;
+    return (double)dot / (sqrt((double)nq) * sqrt((double)nt));
+}
+
+constexpr int kPickThreads = 1024;
+static_assert(kPickThreads == kScoreThreads, "the finishing workgroup of the match also runs the scoring");
+constexpr int kPickChunk = 1024;  // traces per workgroup: one per thread
+constexpr int kPickWaves = kPickThreads / kWave;
+
+struct PickArgs {
+    const u64* part;    // [B][n_lsplit][n_cap]
+    const u64* norm2;   // [n_cap]
+    const int32_t* q;   // [B][L*E]
+    int n_lsplit, n_cap, N, LE;
+    u64* cand;          // [B][gridDim.x][2] winners of the workgroups (dot, nt) ...
+    int32_t* cand_idx;  // [B][gridDim.x] ... and their trace indices
+    unsigned* ticket;   // [B] arrival counters, zero between launches
+    int32_t* best;
+    float* best_sim;
+    float* sims;
+    int do_score;   // the finishing workgroup also scores the matched trace (B = 1)
+    ScoreArgs sc;
+};
+
+// Workgroup winner among its wavefronts' winners; valid in every thread of wavefront 0.
+__device__ __forceinline__ Best block_pick(Best me, u64* s_dot, u64* s_nt, int* s_idx) {
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+    me = wave_pick(me);
+    __syncthreads();
     if (lane == 0) {
         s_dot[wv] = me.dot;
         s_nt[wv] = me.nt;
         s_idx[wv] = me.idx;
     }
     __syncthreads();
-    if (tid == 0) {
-        Best r{s_dot[0], s_nt[0], s_idx[0]};
-        for (int i = 1; i < kArgmaxThreads / kWave; ++i) r = pick(r, Best{s_dot[i], s_nt[i], s_idx[i]});
-        best[b] = r.idx;
-        if (best_sim) best_sim[b] = r.idx >= 0 ? (float)cosine(r.dot, nq, norm2[r.idx]) : 0.f;
+    Best r = make_best(0, 1, -1);
+    if (wv == 0) {
+        if (lane < kPickWaves && s_idx[lane] >= 0) r = make_best(s_dot[lane], s_nt[lane], s_idx[lane]);
+        r = wave_pick(r);
     }
+    return r;
+}
+
+// grid (workgroups over traces, B): sums the layer-split partial dots, writes similarities,
+// picks the workgroup's best trace; the last workgroup to arrive picks among the winners.
+__global__ void __launch_bounds__(kPickThreads) eamc_pick_kernel(PickArgs a) {
+    __shared__ u64 s_dot[kPickWaves];
+    __shared__ u64 s_nt[kPickWaves];
+    __shared__ int s_idx[kPickWaves];
+    __shared__ u64 s_nq;
+    __shared__ unsigned s_ticket;
+    const int b = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wv = tid / kWave;
+
+    u64 nq = 0;
+    for (int i = tid; i < a.LE; i += kPickThreads) {
+        u64 v = (uint32_t)a.q[(size_t)b * a.LE + i];
+        nq += v * v;
+    }
+    nq = wave_sum_u64_dpp(nq);
+    if (lane == 0) s_dot[wv] = nq;
+    __syncthreads();
+    if (tid == 0) {
+        u64 t = 0;
+        for (int i = 0; i < kPickWaves; ++i) t += s_dot[i];
+        s_nq = t;
+    }
+    __syncthreads();
+    nq = s_nq;
+
+    Best me = make_best(0, 1, -1);
+    const int n_end = min(a.N, (int)(blockIdx.x + 1) * kPickChunk);
+    for (int n = blockIdx.x * kPickChunk + tid; n < n_end; n += kPickThreads) {
+        // the split partials are independent loads: issue them four at a time
+        const u64* pp = a.part + (size_t)b * a.n_lsplit * a.n_cap + n;
+        const u64 nt = a.norm2[n];
+        u64 dot = 0;
+        int s = 0;
+        for (; s + 4 <= a.n_lsplit; s += 4) {
+            const u64 v0 = pp[(size_t)s * a.n_cap], v1 = pp[(size_t)(s + 1) * a.n_cap];
+            const u64 v2 = pp[(size_t)(s + 2) * a.n_cap], v3 = pp[(size_t)(s + 3) * a.n_cap];
+            dot += (v0 + v1) + (v2 + v3);
+        }
+        for (; s < a.n_lsplit; ++s) dot += pp[(size_t)s * a.n_cap];
+        if (a.sims) a.sims[(size_t)b * a.N + n] = (float)cosine(dot, nq, nt);
+        me = pick(me, make_best(dot, nt, n));
+    }
+    Best r = block_pick(me, s_dot, s_nt, s_idx);
+    __shared__ int s_sn[2];
+    __shared__ int s_best[kMaxMatchBatch];
+    if (gridDim.x == 1) {
+        if (tid == 0) {
+            a.best[b] = r.idx;
+            if (a.best_sim) a.best_sim[b] = r.idx >= 0 ? (float)cosine(r.dot, nq, a.norm2[r.idx]) : 0.f;
+            s_best[0] = r.idx;
+        }
+        if (a.do_score) score_cells(a.sc, s_sn, s_best, true);
+        return;
+    }
+    // several workgroups: publish this one's winner, the last to arrive finishes
+    const size_t cbase = (size_t)b * gridDim.x;
+    if (tid == 0) {
+        a.cand[(cbase + blockIdx.x) * 2] = r.dot;
+        a.cand[(cbase + blockIdx.x) * 2 + 1] = r.nt;
+        a.cand_idx[cbase + blockIdx.x] = r.idx;
+        __threadfence();
+        s_ticket = __hip_atomic_fetch_add(&a.ticket[b], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (s_ticket != gridDim.x - 1) return;
+    __threadfence();
+    Best fin = make_best(0, 1, -1);
+    for (int i = tid; i < (int)gridDim.x; i += kPickThreads) {
+        const int idx = __hip_atomic_load(&a.cand_idx[cbase + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (idx >= 0) {
+            const u64 d = __hip_atomic_load(&a.cand[(cbase + i) * 2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const u64 t = __hip_atomic_load(&a.cand[(cbase + i) * 2 + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            fin = pick(fin, make_best(d, t, idx));
+        }
+    }
+    fin = block_pick(fin, s_dot, s_nt, s_idx);
+    if (tid == 0) {
+        a.best[b] = fin.idx;
+        if (a.best_sim) a.best_sim[b] = fin.idx >= 0 ? (float)cosine(fin.dot, nq, a.norm2[fin.idx]) : 0.f;
+        a.ticket[b] = 0;  // ready for the next launch on this stream
+        s_best[0] = fin.idx;
+    }
+    if (a.do_score) score_cells(a.sc, s_sn, s_best, true);
 }
 
 struct Plan {
@@ -327,8 +436,12 @@ extern "C" int moei_eamc_create(const moei_model_desc* desc, int32_t n_cap, int3
     hipError_t e = hipMalloc(&c->d_traces, cells(c) * cell_bytes);
     if (e == hipSuccess) e = hipMalloc((void**)&c->d_norm2, (size_t)n_cap * 8);
     if (e == hipSuccess) e = hipMalloc((void**)&c->d_part, (size_t)kMaxMatchBatch * c->lsplit_max * n_cap * 8);
+    const size_t n_blk_max = ((size_t)n_cap + kPickChunk - 1) / kPickChunk;
+    if (e == hipSuccess) e = hipMalloc((void**)&c->d_cand, (size_t)kMaxMatchBatch * n_blk_max * 2 * 8);
+    if (e == hipSuccess) e = hipMalloc((void**)&c->d_cand_idx, (size_t)kMaxMatchBatch * n_blk_max * 4);
+    if (e == hipSuccess) e = hipMalloc((void**)&c->d_ticket, (size_t)kMaxMatchBatch * 4);
+    if (e == hipSuccess) e = hipMemset(c->d_ticket, 0, (size_t)kMaxMatchBatch * 4);
     if (e == hipSuccess) e = hipMalloc((void**)&c->d_keys, 2 * LE * 8);
-    if (e == hipSuccess) e = hipMalloc((void**)&c->d_ids, 2 * LE * 4);
     if (e != hipSuccess) {
         moei_eamc_destroy(c);
         MOEI_FAIL(MOEI_ENOMEM, "moei_eamc_create: device allocation failed: %s", hipGetErrorString(e));
@@ -342,8 +455,10 @@ extern "C" int moei_eamc_destroy(moei_eamc* c) {
     (void)hipFree(c->d_traces);
     (void)hipFree(c->d_norm2);
     (void)hipFree(c->d_part);
+    (void)hipFree(c->d_cand);
+    (void)hipFree(c->d_cand_idx);
+    (void)hipFree(c->d_ticket);
     (void)hipFree(c->d_keys);
-    (void)hipFree(c->d_ids);
     delete c;
     return MOEI_OK;
 }
@@ -462,14 +577,12 @@ extern "C" int moei_eamc_export(const moei_eamc* c, int32_t* h_traces, int32_t m
     return MOEI_OK;
 }
 
-extern "C" int eamc_match(const moei_eamc* c, const int32_t* d_eam, int32_t B, int32_t layer_hi, int32_t* d_best,
-                          float* d_best_sim, float* d_sims, void* stream) {
-    MOEI_REQUIRE(c && d_eam && d_best, "eamc_match: null pointer");
-    MOEI_REQUIRE(B >= 0 && B <= kMaxMatchBatch, "eamc_match: B = %d outside [0, %d]", B, kMaxMatchBatch);
-    MOEI_REQUIRE(layer_hi >= 0 && layer_hi < c->d.L, "eamc_match: layer_hi = %d outside [0, %d)", layer_hi, c->d.L);
-    if (B == 0) return MOEI_OK;
-    hipStream_t s = as_stream(stream);
+namespace moei {
+
+int launch_match(const moei_eamc* c, const int32_t* d_eam, int B, int layer_hi, int32_t* d_best, float* d_best_sim,
+                 float* d_sims, const ScoreArgs* score, hipStream_t s) {
     const int L = c->d.L, E = c->d.E;
+    if (score && B != 1) MOEI_FAIL(MOEI_EINVAL, "match with scoring needs B = 1");
     int n_lsplit = 0;
     if (c->N > 0) {
         Plan p = make_plan(c, layer_hi + 1);
@@ -485,8 +598,21 @@ extern "C" int eamc_match(const moei_eamc* c, const int32_t* d_eam, int32_t B, i
             rc = p.VEC == 8 ? launch_dot_j<uint16_t, 8>(p, a, grid, s) : launch_dot_j<uint16_t, 1>(p, a, grid, s);
         if (rc) return rc;
     }
-    launch(K_MATCH_ARGMAX, eamc_argmax_kernel, dim3(B), dim3(kArgmaxThreads), 0, s, (const u64*)c->d_part, n_lsplit,
-           c->n_cap, c->N, (const u64*)c->d_norm2, d_eam, L * E, d_best, d_best_sim, d_sims);
+    const int n_blk = c->N > 0 ? (c->N + kPickChunk - 1) / kPickChunk : 1;
+    PickArgs pa{c->d_part, c->d_norm2, d_eam, n_lsplit, c->n_cap, c->N, L * E, c->d_cand, c->d_cand_idx,
+                c->d_ticket, d_best, d_best_sim, d_sims, score != nullptr, score ? *score : ScoreArgs{}};
+    launch(K_MATCH_ARGMAX, eamc_pick_kernel, dim3(n_blk, B), dim3(kPickThreads), 0, s, pa);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
+}
+
+}  // namespace moei
+
+extern "C" int eamc_match(const moei_eamc* c, const int32_t* d_eam, int32_t B, int32_t layer_hi, int32_t* d_best,
+                          float* d_best_sim, float* d_sims, void* stream) {
+    MOEI_REQUIRE(c && d_eam && d_best, "eamc_match: null pointer");
+    MOEI_REQUIRE(B >= 0 && B <= kMaxMatchBatch, "eamc_match: B = %d outside [0, %d]", B, kMaxMatchBatch);
+    MOEI_REQUIRE(layer_hi >= 0 && layer_hi < c->d.L, "eamc_match: layer_hi = %d outside [0, %d)", layer_hi, c->d.L);
+    if (B == 0) return MOEI_OK;
+    return launch_match(c, d_eam, B, layer_hi, d_best, d_best_sim, d_sims, nullptr, as_stream(stream));
 }

@@ -17,7 +17,7 @@ std::vector<Sample> g_pool;  // pre-created events: nothing is allocated inside 
 size_t g_used = 0;
 
 const char* const kNames[K_COUNT] = {
-    "router_gemv_kernel", "route_topk_kernel", "eamc_dot_kernel",   "eamc_argmax_kernel", "priority_score_kernel",
+    "route_topk_kernel", "eamc_dot_kernel",   "eamc_pick_kernel", "priority_score_kernel",
     "priority_rank_kernel", "ffn_fused_kernel", "ffn_reduce_kernel",
 };
 

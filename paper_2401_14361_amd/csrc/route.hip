@@ -27,7 +27,52 @@ __device__ __forceinline__ Cand better(Cand a, Cand b) {
     return (a.e < b.e) ? a : b;
 }
 
-// Softmax + top-k of z[0..E) (LDS or global, read-only here) by one wavefront.
+// Softmax + top-k of z[0..E) (in LDS) by one wavefront, k <= 64.  Every expert's rank is
+// the number of experts that come before it (larger logit, or equal logit and lower
+// index), counted against broadcast LDS reads; rank r < k is pick r.  The picks land in
+// s_idx[k] / s_w[k] (LDS); the caller reads them after a __syncthreads().
+constexpr int kRankMaxE = 1024;
+__device__ __forceinline__ void wave_topk_rank(const float* z, int E, int k, int renorm, int lane, int* s_idx,
+                                               float* s_w) {
+    const int per = (E + kWave - 1) / kWave;
+    float m = -INFINITY;
+    for (int r = 0; r < per; ++r) {
+        int e = lane + r * kWave;
+        if (e < E) m = fmaxf(m, z[e]);
+    }
+    m = wave_max_dpp(m);
+    float s = 0.f;
+    for (int r = 0; r < per; ++r) {
+        int e = lane + r * kWave;
+        if (e < E) s += expf(z[e] - m);
+    }
+    s = wave_sum_dpp(s);
+    float sel = 0.f;
+    for (int r = 0; r < per; ++r) {
+        const int e = lane + r * kWave;
+        if (e < E) {
+            const float v = z[e];
+            int rank = 0;
+            for (int j = 0; j < E; ++j) {
+                const float u = z[j];
+                rank += (u > v || (u == v && j < e)) ? 1 : 0;
+            }
+            if (rank < k) {
+                const float p = expf(v - m) / s;
+                s_idx[rank] = e;
+                s_w[rank] = p;
+                sel += p;
+            }
+        }
+    }
+    if (renorm) {
+        sel = wave_sum_dpp(sel);
+        __syncthreads();  // single-wavefront workgroup: orders the LDS writes above with the reads below
+        if (lane < k) s_w[lane] = s_w[lane] / sel;
+    }
+}
+
+// The same by k rounds of a 64-lane butterfly arg-max (any E up to 4096).
 // Lane j < k returns pick j in (idx, w); other lanes return idx = -1.
 __device__ __forceinline__ void wave_topk(const float* z, int E, int k, int renorm, int lane, int& idx_out,
                                           float& w_out) {
@@ -81,19 +126,25 @@ __global__ void __launch_bounds__(kWave) route_topk_kernel(const float* __restri
                                                            int renorm, int32_t* __restrict__ idx,
                                                            float* __restrict__ w) {
     extern __shared__ float z[];
+    __shared__ int s_idx[kWave];
+    __shared__ float s_w[kWave];
     const int b = blockIdx.x;
     const int lane = threadIdx.x;
     for (int e = lane; e < E; e += kWave) z[e] = logits[(size_t)b * E + e];
     __syncthreads();
     int my_idx;
     float my_w;
-    wave_topk(z, E, k, renorm, lane, my_idx, my_w);
-    // k may exceed 64: picks are produced in rounds of 64 lanes
-    if (k <= kWave) {
-        if (lane < k) {
-            idx[(size_t)b * k + lane] = my_idx;
-            w[(size_t)b * k + lane] = my_w;
-        }
+    if (E <= kRankMaxE) {
+        wave_topk_rank(z, E, k, renorm, lane, s_idx, s_w);
+        __syncthreads();
+        my_idx = lane < k ? s_idx[lane] : -1;
+        my_w = lane < k ? s_w[lane] : 0.f;
+    } else {
+        wave_topk(z, E, k, renorm, lane, my_idx, my_w);
+    }
+    if (lane < k) {
+        idx[(size_t)b * k + lane] = my_idx;
+        w[(size_t)b * k + lane] = my_w;
     }
 }
 
@@ -162,18 +213,39 @@ __global__ void eam_update_kernel(int32_t* __restrict__ eam, int B, int L, int E
     if (e >= 0 && e < E) eam[((size_t)b * L + layer) * E + e] += 1;
 }
 
-// logits[e] = <W[e][:], x> + bias[e]; one wavefront per expert row.
+// Routing of the fused layer step for one token in ONE launch: a wavefront per expert
+// forms logit = <W_r[e], x> + b_e; the last wavefront to finish (arrival counter) then takes
+// the top-k, updates the EAM row and writes the slot ids / gate weights the FFN reads.
 template <typename WT>
-__global__ void __launch_bounds__(kWave) router_gemv_kernel(const WT* __restrict__ W, const float* __restrict__ bias,
-                                                            const WT* __restrict__ x, int E, int H, int vec_ok,
-                                                            float* __restrict__ logits) {
+__global__ void __launch_bounds__(kWave) route_fused_kernel(RouteFusedArgs a) {
     using V = WVec<WT>;
+    extern __shared__ float z[];  // E logits, then E slot ids, then the E counts of this layer's EAM row
+    __shared__ unsigned s_ticket;
+    __shared__ int s_pick[kWave];
+    __shared__ float s_pw[kWave];
+    int* s_slot = reinterpret_cast<int*>(z + a.E);
+    int* s_eam = s_slot + a.E;
     const int e = blockIdx.x;
     const int lane = threadIdx.x;
-    const WT* row = W + (size_t)e * H;
+    int32_t* eam_row = a.eam + (size_t)a.layer * a.E;
+    // any wavefront may turn out to be the last: each fetches the layer's slot row and EAM row
+    // now, so that nothing but the logits is left to load after the arrival counter
+    for (int j = lane; j < a.E; j += kWave) {
+        s_slot[j] = a.slot_of_row[j];
+        s_eam[j] = eam_row[j];
+    }
+    // every wavefront copies its share of the EAM into the snapshot the match will read
+    // (this step's k increments are added to the snapshot by the last wavefront)
+    {
+        const int seg = (a.LE + (int)gridDim.x - 1) / (int)gridDim.x;
+        const int i1 = min(a.LE, (e + 1) * seg);
+        for (int i = e * seg + lane; i < i1; i += kWave) a.snap[i] = a.eam[i];
+    }
+    const WT* row = reinterpret_cast<const WT*>(a.W) + (size_t)e * a.H;
+    const WT* x = reinterpret_cast<const WT*>(a.x);
     float acc = 0.f;
-    if (vec_ok) {
-        for (int c = lane * V::N; c < H; c += kWave * V::N) {
+    if (a.vec_ok) {
+        for (int c = lane * V::N; c < a.H; c += kWave * V::N) {
             typename V::raw wv = V::load(row + c);
             typename V::raw xv = V::load(x + c);
             float xf[V::N];
@@ -181,27 +253,37 @@ __global__ void __launch_bounds__(kWave) router_gemv_kernel(const WT* __restrict
             acc = V::dot(wv, xf, acc);
         }
     } else {
-        for (int c = lane; c < H; c += kWave) acc = __builtin_fmaf(V::one(row + c), V::one(x + c), acc);
+        for (int c = lane; c < a.H; c += kWave) acc = __builtin_fmaf(V::one(row + c), V::one(x + c), acc);
     }
-    acc = wave_sum(acc);
-    if (lane == 0) logits[e] = acc + (bias ? bias[e] : 0.f);
-}
-
-// Routing decision of the fused layer step for one token: top-k, EAM row update and
-// the slot ids / gate weights the FFN kernels read.
-__global__ void __launch_bounds__(kWave) route_fused_kernel(RouteFusedArgs a) {
-    extern __shared__ float z[];
-    const int lane = threadIdx.x;
-    for (int e = lane; e < a.E; e += kWave) z[e] = a.logits[e];
+    acc = wave_sum_dpp(acc);
+    if (lane == 0) {
+        a.logits[e] = acc + (a.bias ? a.bias[e] : 0.f);
+        __threadfence();
+        s_ticket = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (s_ticket != gridDim.x - 1) return;
+    __threadfence();
+    for (int j = lane; j < a.E; j += kWave)
+        z[j] = __hip_atomic_load(&a.logits[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     int my_idx;
     float my_w;
-    wave_topk(z, a.E, a.k, a.renorm, lane, my_idx, my_w);
+    if (a.E <= kRankMaxE) {
+        wave_topk_rank(z, a.E, a.k, a.renorm, lane, s_pick, s_pw);
+        __syncthreads();
+        my_idx = lane < a.k ? s_pick[lane] : -1;
+        my_w = lane < a.k ? s_pw[lane] : 0.f;
+    } else {
+        wave_topk(z, a.E, a.k, a.renorm, lane, my_idx, my_w);
+    }
     if (lane < a.k) {
         a.idx[lane] = my_idx;
         a.w[lane] = my_w;
-        a.eam_row[my_idx] += 1;
-        int slot = a.slot_of_row[my_idx];
+        const int cnt = s_eam[my_idx] + 1;  // one writer per cell
+        eam_row[my_idx] = cnt;
+        a.snap[(size_t)a.layer * a.E + my_idx] = cnt;
+        int slot = s_slot[my_idx];
         a.slot_ids[lane] = slot;
         a.gate[lane] = my_w;
         if (slot < 0 && a.flags) atomicOr(a.flags, 2);
@@ -209,6 +291,7 @@ __global__ void __launch_bounds__(kWave) route_fused_kernel(RouteFusedArgs a) {
         a.slot_ids[lane] = a.shared_base + (lane - a.k);
         a.gate[lane] = 1.0f;
     }
+    if (lane == 0) *a.ticket = 0;  // ready for the next launch on this stream
 }
 
 // Slot ids of already chosen picks (after the host has served the misses).
@@ -224,25 +307,15 @@ __global__ void gather_slots_kernel(const int32_t* __restrict__ idx, int k, cons
 
 }  // namespace
 
-int launch_router_gemv(const void* d_W, const float* d_bias, const void* d_x, int E, int H, int wdtype,
-                       float* d_logits, hipStream_t s) {
-    if (wdtype == MOEI_WDTYPE_BF16) {
-        int vec_ok = (H % 8 == 0) && ((uintptr_t)d_W % 16 == 0) && ((uintptr_t)d_x % 16 == 0);
-        launch(K_ROUTER_GEMV, router_gemv_kernel<uint16_t>, dim3(E), dim3(kWave), 0, s, (const uint16_t*)d_W, d_bias,
-               (const uint16_t*)d_x, E, H, vec_ok, d_logits);
-    } else {
-        int vec_ok = (H % 4 == 0) && ((uintptr_t)d_W % 16 == 0) && ((uintptr_t)d_x % 16 == 0);
-        launch(K_ROUTER_GEMV, router_gemv_kernel<float>, dim3(E), dim3(kWave), 0, s, (const float*)d_W, d_bias,
-               (const float*)d_x, E, H, vec_ok, d_logits);
-    }
-    MOEI_LAUNCH_CHECK();
-    return MOEI_OK;
-}
-
-int launch_route_fused(const RouteFusedArgs& a, hipStream_t s) {
+int launch_route_fused(RouteFusedArgs a, int wdtype, hipStream_t s) {
     if (a.E > kMaxE || a.k > kWave || a.k + a.n_shared > kWave)
         MOEI_FAIL(MOEI_EINVAL, "fused routing needs E <= %d and k + n_shared <= %d", kMaxE, kWave);
-    launch(K_ROUTE_TOPK, route_fused_kernel, dim3(1), dim3(kWave), a.E * sizeof(float), s, a);
+    const int n = wdtype == MOEI_WDTYPE_BF16 ? 8 : 4;
+    a.vec_ok = (a.H % n == 0) && ((uintptr_t)a.W % 16 == 0) && ((uintptr_t)a.x % 16 == 0);
+    if (wdtype == MOEI_WDTYPE_BF16)
+        launch(K_ROUTE_TOPK, route_fused_kernel<uint16_t>, dim3(a.E), dim3(kWave), 3 * a.E * sizeof(float), s, a);
+    else
+        launch(K_ROUTE_TOPK, route_fused_kernel<float>, dim3(a.E), dim3(kWave), 3 * a.E * sizeof(float), s, a);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
 }
