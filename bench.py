@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-offload", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 512 MiB device copy (scale for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -207,6 +209,14 @@ def main():
     ffn_bytes = n_act * 3 * H * I * wb
     log(f"[bench] kernels: " + ", ".join(f"{n}={v['avg_us']:.2f}us" for n, v in kern.items() if v["avg_us"]))
 
+    if args.calib_copy:
+        src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ------------------------------------------------ leg 3: steps on their own
     extra = {}
     # eamc_match alone (launch-inclusive: both of its kernels, back to back)
@@ -264,10 +274,31 @@ def main():
     ev1.record(stream)
     torch.cuda.synchronize()
     gemv_us = ev0.elapsed_time(ev1) / reps * 1e3
+    # the same calls with per-launch stamps: the FFN kernel on its own, nothing overlapped; the
+    # call with no active expert launches only an (almost) empty kernel -> the launch floor
+    m.profile_enable(512)
+    for r in range(100):
+        m.expert_ffn_gemv(cache, slot_sets[r % n_sets], gates, d_x[0, 0], stream=stream, out=y)
+    torch.cuda.synchronize()
+    ps = m.profile_read()
+    m.profile_disable()
+    ffn_alone_us = ps["ffn_fused_kernel"][1] / ps["ffn_fused_kernel"][0] * 1e3
+    none_i = torch.zeros(0, dtype=torch.int32, device="cuda")
+    none_f = torch.zeros(0, dtype=torch.float32, device="cuda")
+    m.profile_enable(64)
+    for r in range(50):
+        m.expert_ffn_gemv(cache, none_i, none_f, d_x[0, 0], stream=stream, out=y)
+    torch.cuda.synchronize()
+    pf = m.profile_read()
+    m.profile_disable()
+    floor_us = pf["ffn_reduce_kernel"][1] / pf["ffn_reduce_kernel"][0] * 1e3
     extra["expert_ffn_gemv"] = {
         "us_per_call": gemv_us, "alg_bytes": ffn_bytes, "GBps_launch_inclusive": ffn_bytes / gemv_us / 1e3,
         "GBps_kernels_only": ffn_bytes / ffn_us / 1e3, "frac_of_peak_kernels_only": ffn_bytes / ffn_us / 1e3 / HBM_PEAK_GBPS,
         "frac_of_peak_launch_inclusive": ffn_bytes / gemv_us / 1e3 / HBM_PEAK_GBPS,
+        "ffn_fused_kernel_alone_us": ffn_alone_us, "ffn_fused_kernel_alone_GBps": ffn_bytes / ffn_alone_us / 1e3,
+        "ffn_fused_kernel_alone_frac_of_peak": ffn_bytes / ffn_alone_us / 1e3 / HBM_PEAK_GBPS,
+        "near_empty_kernel_us": floor_us,
     }
     log(f"[bench] match {match_us:.1f} us; big-N dot {dot_us:.1f} us = {big_bytes / dot_us / 1e3:.0f} GB/s; "
         f"gemv {gemv_us:.1f} us = {ffn_bytes / gemv_us / 1e3:.0f} GB/s")

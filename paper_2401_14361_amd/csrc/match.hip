@@ -364,6 +364,7 @@ struct Plan {
 };
 
 Plan make_plan(const moei_eamc* c, int L_scan) {
+    static const int kTargetBlocks = getenv("MOEI_MATCH_BLOCKS") ? atoi(getenv("MOEI_MATCH_BLOCKS")) : 256;
     Plan p{};
     const int E = c->d.E;
     const int full = 16 / c->cell_bytes;
@@ -375,7 +376,7 @@ Plan make_plan(const moei_eamc* c, int L_scan) {
     if (p.TN < 1) p.TN = 1;
     p.J = (p.TN * p.rowV + kDotThreads - 1) / kDotThreads;
     p.n_tiles = (c->N + p.TN - 1) / p.TN;
-    int want = (1024 + p.n_tiles - 1) / p.n_tiles;  // aim at >= 1024 workgroups
+    int want = (kTargetBlocks + p.n_tiles - 1) / p.n_tiles;  // aim at enough workgroups to fill the chip
     int lmax = L_scan < c->lsplit_max ? L_scan : c->lsplit_max;
     p.n_lsplit = want < 1 ? 1 : (want > lmax ? lmax : want);
     // LDS: the query rows of one split must fit in 48 KiB
