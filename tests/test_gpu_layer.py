@@ -184,3 +184,25 @@ def test_async_layer_step_matches_sync_and_flags_a_miss(m):
     assert cache.error_flags() & 2
     cache.close()
     eamc.close()
+
+
+# ------------------------------------------------------------------ full benchmark shapes
+def test_full_size_deepseek_v2_lite_token_with_capped_cache(m):
+    # configuration 2 at full size (26 x 64 experts of 2048 x 1408 bf16, 1,000 traces, 416 slots):
+    # one decode token, every layer step compared in full
+    cfg = mi.get_config("C2")
+    misses = _replay(m, cfg, cfg.S, 1, 24, 4)
+    assert misses > 0
+
+
+def test_full_size_mixtral_layer_steps(m):
+    # configuration 3 at full width (4096 x 14336 bf16 experts, 352 MB each), 3 of its layers
+    cfg = mi.get_config("C3").scaled(L=3, N=200, prompt=64)
+    _replay(m, cfg, 12, 1, 6, 4)
+
+
+def test_full_size_deepseek_v2_slice_steps(m):
+    # configuration 4's shapes: 160 experts per layer top-6 + 2 shared, 5120 x 1536; here 4 of the 59
+    # layers carry weights (the 59 x 160 match and priority sizes are covered in test_gpu_steps.py)
+    cfg = mi.get_config("C4").scaled(L=4, N=300, prompt=32)
+    _replay(m, cfg, cfg.L * cfg.E, 1, 12, 2)

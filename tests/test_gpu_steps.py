@@ -286,3 +286,40 @@ def test_expert_ffn_full_deepseek_v2_lite_layer(m):
                            seed=2, n_slots=7)
     assert err <= FFN_TOL_FP32ACC, err
     cache.close()
+
+
+# ------------------------------------------------------------------ full benchmark sizes
+def test_eamc_match_and_priority_at_deepseek_v2_size(m):
+    # configuration 4 / 5 sizes: 10,000 traces of 59 x 160 (378 MB of int32 cells), batched queries
+    cfg = mi.get_config("C4")
+    T, _, _ = mi.eamc_traces(cfg, threads=16)
+    reqs = [mi.make_request(cfg.scaled(prompt=256), r, decode=1) for r in range(4)]
+    Q = np.stack([r.prefill_eam for r in reqs] + [T[4321], 3 * T[77]]).astype(np.int32)
+    desc = m.ModelDesc.from_config(cfg)
+    for cb in (4, 2):
+        eamc = m.Eamc(desc, cfg.N, cb)
+        eamc.load(T)
+        best, sim, sims = m.eamc_match(eamc, dev(Q), want_sims=True)
+        torch.cuda.synchronize()
+        best, sim, sims = best.cpu().numpy(), sim.cpu().numpy(), sims.cpu().numpy()
+        for b in range(Q.shape[0]):
+            rb, rs, rsims = O.eamc_match(T, Q[b])
+            assert best[b] == rb
+            np.testing.assert_allclose(sims[b], rsims, rtol=SIM_RTOL, atol=1e-30)
+            np.testing.assert_allclose(sim[b], rs, rtol=SIM_RTOL)
+        assert best[4] == 4321 and best[5] == 77
+        # priorities from the first request's match, a third of the experts resident
+        rng = np.random.default_rng(cb)
+        res = rng.random((cfg.L, cfg.E)) < 0.33
+        slot_of = np.where(res.reshape(-1), np.arange(cfg.L * cfg.E), -1).astype(np.int32)
+        cur = 20
+        cur_idx = rng.choice(cfg.E, size=(1, cfg.k), replace=False).astype(np.int32)
+        out = m.expert_priority(eamc, dev(best[:1].astype(np.int32)), cur, dev(slot_of), EPS, dev(cur_idx))
+        torch.cuda.synchronize()
+        P, V, pf, n_pf, ev, n_ev = [o.cpu().numpy() for o in out]
+        rP, rV, rpf, rev = O.expert_priority(O.aggregate_matches(T, best[:1]), cur, res, EPS,
+                                             [cur * cfg.E + int(j) for j in cur_idx[0]])
+        assert pf[:int(n_pf[0])].tolist() == rpf and ev[:int(n_ev[0])].tolist() == rev
+        np.testing.assert_allclose(P, rP, rtol=1e-6)
+        np.testing.assert_allclose(V, rV, rtol=1e-6)
+        eamc.close()
