@@ -172,6 +172,16 @@ int moei_cache_retrieve(moei_cache* c, int32_t layer, const int32_t* h_idx, int3
  * n_act <= k + n_shared. */
 int expert_ffn_gemv(moei_cache* c, const int32_t* d_slot_ids, const float* d_gate_w,
                     int32_t n_act, const void* d_x, float* d_y, void* stream);
+/* Step 5 for a decode batch of B independent requests (B <= 16): for every token b,
+ *   y[b] = sum_j d_w[b][j] * expert(layer, d_idx[b][j])(x[b]) + sum over the layer's shared experts,
+ * with the picks' slots looked up in the device slot table.  Tokens are grouped per activated
+ * expert on the device and an expert's weights are streamed once per group of up to 4 of its
+ * tokens, so bytes read grow with the number of distinct experts, not with B.
+ * d_idx[B][k] int32, d_w[B][k] fp32, d_x[B][H] in desc->wdtype, d_y[B][H] fp32.  A pick that is
+ * not resident contributes nothing and raises error flag bit 1.  Needs H to be a multiple of
+ * 64 lanes x 16 bytes.  Results are bit-reproducible run to run. */
+int expert_ffn_grouped(moei_cache* c, int32_t layer, const int32_t* d_idx, const float* d_w, int32_t B,
+                       const void* d_x, float* d_y, void* stream);
 /* Device-side error flags raised by kernels since the last call (bit 0: bad slot id,
  * bit 1: a routed expert was not resident in a step without host retrieval).
  * Synchronises `stream`. */

@@ -16,7 +16,7 @@ import torch
 __all__ = [
     "MoeiError", "ModelDesc", "lib", "lib_path", "Eamc", "Cache",
     "moe_route_topk", "eam_update", "eamc_match", "expert_priority", "expert_ffn_gemv", "moe_decode_layer",
-    "WDTYPE_FP32", "WDTYPE_BF16", "EXPORTS", "expert_pack", "profile_enable", "profile_disable", "profile_read",
+    "expert_ffn_grouped", "WDTYPE_FP32", "WDTYPE_BF16", "EXPORTS", "expert_pack", "profile_enable", "profile_disable", "profile_read",
 ]
 
 WDTYPE_FP32, WDTYPE_BF16 = 0, 1
@@ -27,7 +27,7 @@ EXPORTS = [
     "moei_eamc_create", "moei_eamc_load", "moei_eamc_insert", "moei_eamc_export", "moei_eamc_size", "moei_eamc_destroy",
     "moe_route_topk", "eam_update", "eamc_match", "expert_priority",
     "moei_cache_create", "moei_cache_destroy", "moei_expert_pack", "moei_cache_reset", "moei_cache_slot_ptr", "moei_cache_slot_table",
-    "moei_cache_get_slots", "moei_cache_retrieve", "expert_ffn_gemv", "moei_cache_error_flags",
+    "moei_cache_get_slots", "moei_cache_retrieve", "expert_ffn_gemv", "expert_ffn_grouped", "moei_cache_error_flags",
     "moe_decode_layer", "moei_cache_last_step", "moei_cache_join", "moei_cache_sync",
     "moei_profile_enable", "moei_profile_disable", "moei_profile_kernels", "moei_profile_kernel_name",
     "moei_profile_read",
@@ -322,6 +322,18 @@ def expert_ffn_gemv(cache: Cache, slot_ids: torch.Tensor, gate_w: torch.Tensor, 
     assert x.is_cuda and x.is_contiguous() and x.numel() == cache.desc.H
     y = out if out is not None else torch.empty(cache.desc.H, dtype=torch.float32, device=x.device)
     _check(lib().expert_ffn_gemv(cache.h, _p(slot_ids), _p(gate_w), slot_ids.numel(), _p(x), _p(y), _stream(stream)))
+    return y
+
+
+def expert_ffn_grouped(cache: Cache, layer: int, idx: torch.Tensor, w: torch.Tensor, x: torch.Tensor,
+                       stream=None) -> torch.Tensor:
+    """Decode batch: idx [B][k] int32, w [B][k] fp32, x [B][H] weight dtype (device) -> y [B][H] fp32."""
+    _dev(idx, torch.int32)
+    _dev(w, torch.float32)
+    B = idx.shape[0]
+    assert x.is_cuda and x.is_contiguous() and x.numel() == B * cache.desc.H
+    y = torch.empty((B, cache.desc.H), dtype=torch.float32, device=x.device)
+    _check(lib().expert_ffn_grouped(cache.h, layer, _p(idx), _p(w), B, _p(x), _p(y), _stream(stream)))
     return y
 
 

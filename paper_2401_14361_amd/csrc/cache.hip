@@ -84,6 +84,9 @@ struct moei_cache {
     bool side_pending = false;
     int parity = 0;  // which buffer set the current step writes
     FfnScratch ffn;
+    void* d_items = nullptr;        // batched FFN: token groups, allocated at the first batched call
+    int32_t* d_n_items = nullptr;
+    float* d_gpart = nullptr;
     float* d_logits = nullptr;
     int32_t* d_idx2[kRing] = {};  // picks of the last kRing steps (the side stream reads one set while the
                                   // routing of later steps writes the others)
@@ -111,6 +114,9 @@ extern "C" int moei_cache_destroy(moei_cache* c) {
     (void)hipFree(c->d_flags);
     (void)hipFree(c->d_ticket);
     ffn_scratch_free(&c->ffn);
+    (void)hipFree(c->d_items);
+    (void)hipFree(c->d_n_items);
+    (void)hipFree(c->d_gpart);
     (void)hipFree(c->d_logits);
     for (int r = 0; r < kRing; ++r) {
         (void)hipFree(c->d_idx2[r]);
@@ -378,6 +384,28 @@ extern "C" int expert_ffn_gemv(moei_cache* c, const int32_t* d_slot_ids, const f
     MOEI_REQUIRE(n_act == 0 || (d_slot_ids && d_gate_w), "expert_ffn_gemv: null slot ids or gate weights");
     return launch_expert_ffn(c->d, c->d_pool, c->slot_elems, c->n_total, c->ffn, d_slot_ids, d_gate_w, n_act, d_x, d_y,
                              c->d_flags, as_stream(stream));
+}
+
+extern "C" int expert_ffn_grouped(moei_cache* c, int32_t layer, const int32_t* d_idx, const float* d_w, int32_t B,
+                                  const void* d_x, float* d_y, void* stream) {
+    MOEI_REQUIRE(c && d_idx && d_w && d_x && d_y, "expert_ffn_grouped: null pointer");
+    MOEI_REQUIRE(layer >= 0 && layer < c->d.L, "expert_ffn_grouped: layer %d outside [0, %d)", layer, c->d.L);
+    MOEI_REQUIRE(B >= 1 && B <= 16, "expert_ffn_grouped: B = %d outside [1, 16]", B);
+    if (!c->d_items) {  // scratch of the batched path, on first use
+        hipError_t e = hipMalloc(&c->d_items, (size_t)grouped_max_items(c->d) * grouped_item_bytes());
+        if (e == hipSuccess) e = hipMalloc((void**)&c->d_n_items, 4);
+        if (e == hipSuccess) e = hipMalloc((void**)&c->d_gpart, grouped_part_floats(c->d) * sizeof(float));
+        if (e != hipSuccess) {
+            (void)hipFree(c->d_items);
+            (void)hipFree(c->d_n_items);
+            c->d_items = nullptr;
+            c->d_n_items = nullptr;
+            MOEI_FAIL(MOEI_ENOMEM, "expert_ffn_grouped: scratch allocation failed: %s", hipGetErrorString(e));
+        }
+    }
+    return launch_expert_ffn_grouped(c->d, c->d_pool, c->slot_elems, c->d_items, c->d_n_items, c->d_gpart,
+                                     c->d_slot_of + (size_t)layer * c->d.E, c->S + layer * c->d.n_shared, d_idx, d_w, B,
+                                     d_x, d_y, c->d_flags, as_stream(stream));
 }
 
 extern "C" int moei_cache_error_flags(moei_cache* c, int32_t* h_flags, void* stream) {

@@ -53,6 +53,7 @@ enum KernelId {
     K_PRIO_RANK,
     K_FFN_FUSED,
     K_FFN_REDUCE,
+    K_FFN_GROUP,
     K_COUNT
 };
 extern bool g_prof_on;

@@ -395,6 +395,232 @@ int launch_ffn_typed(FfnArgs a, bool fast, int grid, float* d_y, hipStream_t s) 
     return MOEI_OK;
 }
 
+
+// ------------------------------------------------------------------ decode batch B > 1
+// Tokens are grouped per activated expert; an "item" is one expert with up to kMaxGroup of its
+// tokens, so the expert's weights are streamed once per item.  Items are cut into chunks of
+// kChunkRows intermediate units; chunks are dealt to the workgroups in turn.  A wavefront
+// streams a unit once and uses it for every token of the item; y accumulators exist per token.
+constexpr int kMaxGroup = 4;
+constexpr int kChunkRows = 64;
+constexpr int kGroupedWaves = 8;
+constexpr int kMaxBatch = 16;
+
+struct GroupItem {
+    int32_t slot;
+    int32_t ntok;
+    int32_t tok[kMaxGroup];
+    float w[kMaxGroup];
+};
+
+struct GroupArgs {
+    const int32_t* idx;          // [B][k] picks
+    const float* w;              // [B][k] gate weights
+    const int32_t* slot_of_row;  // slot_of + layer*E
+    int B, k, E, n_shared, shared_base, tb;
+    GroupItem* items;
+    int32_t* n_items;
+    int32_t* flags;
+};
+
+// One workgroup.  Thread e collects the tokens routed to expert e (in token order) and cuts
+// them into items of at most tb tokens; item positions follow expert order, shared experts last.
+__global__ void __launch_bounds__(256) ffn_group_kernel(GroupArgs a) {
+    __shared__ int s_cnt[256];
+    __shared__ int s_base;
+    const int tid = threadIdx.x;
+    const int n_pick = a.B * a.k;
+    int base = 0;
+    for (int e0 = 0; e0 < a.E; e0 += 256) {
+        const int e = e0 + tid;
+        int ntok = 0;
+        int toks[kMaxBatch];
+        float ws[kMaxBatch];
+        if (e < a.E)
+            for (int p = 0; p < n_pick; ++p)
+                if (a.idx[p] == e && ntok < kMaxBatch) {
+                    toks[ntok] = p / a.k;
+                    ws[ntok] = a.w[p];
+                    ++ntok;
+                }
+        int slot = -1;
+        if (ntok > 0) {
+            slot = a.slot_of_row[e];
+            if (slot < 0) {  // not resident: contributes nothing, flagged
+                atomicOr(a.flags, 2);
+                ntok = 0;
+            }
+        }
+        const int my_items = (ntok + a.tb - 1) / a.tb;
+        s_cnt[tid] = my_items;
+        __syncthreads();
+        int before = 0;
+        for (int i = 0; i < tid; ++i) before += s_cnt[i];
+        if (tid == 255) s_base = before + my_items;
+        for (int g = 0; g < my_items; ++g) {
+            GroupItem it;
+            it.slot = slot;
+            it.ntok = min(a.tb, ntok - g * a.tb);
+            for (int j = 0; j < kMaxGroup; ++j) {
+                const bool on = j < it.ntok;
+                it.tok[j] = on ? toks[g * a.tb + j] : 0;
+                it.w[j] = on ? ws[g * a.tb + j] : 0.f;
+            }
+            a.items[base + before + g] = it;
+        }
+        __syncthreads();
+        base += s_base;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        int n = base;
+        for (int s = 0; s < a.n_shared; ++s)
+            for (int t0 = 0; t0 < a.B; t0 += a.tb) {
+                GroupItem it;
+                it.slot = a.shared_base + s;
+                it.ntok = min(a.tb, a.B - t0);
+                for (int j = 0; j < kMaxGroup; ++j) {
+                    it.tok[j] = j < it.ntok ? t0 + j : 0;
+                    it.w[j] = j < it.ntok ? 1.0f : 0.f;
+                }
+                a.items[n++] = it;
+            }
+        *a.n_items = n;
+    }
+}
+
+struct GroupedFfnArgs {
+    const void* pool;
+    size_t slot_elems;
+    const GroupItem* items;
+    const int32_t* n_items;
+    const void* x;  // [B][H]
+    float* part;    // [chunks][TB][H]
+    int H, I;
+};
+
+template <int NCH>
+struct GroupedShape {
+    static constexpr int kTB = NCH <= 4 ? 4 : 1;  // y accumulators per token must fit the register file
+};
+
+template <typename WT, int NCH>
+__global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(GroupedFfnArgs a) {
+    using V = WVec<WT>;
+    using Raw = typename V::raw;
+    constexpr int N = V::N;
+    constexpr int CW = kWave * N;
+    constexpr int TB = GroupedShape<NCH>::kTB;
+    extern __shared__ __align__(16) float smem[];
+    float* xs = smem;              // [TB][H] inputs of the item's tokens, fp32
+    float* yp = smem + TB * a.H;   // [kGroupedWaves][H] y rows of one token, one per wavefront
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int H = a.H, I = a.I;
+    const WT* pool = reinterpret_cast<const WT*>(a.pool);
+    const unsigned lane_off = (unsigned)lane * N;
+    const int n_items = *a.n_items;
+    const int cpi = (I + kChunkRows - 1) / kChunkRows;
+    const int n_chunks = n_items * cpi;
+    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {  // uniform over the workgroup
+        const int item = c / cpi;
+        const int r0 = (c - item * cpi) * kChunkRows;
+        const int r1 = min(I, r0 + kChunkRows);
+        const GroupItem it = a.items[item];
+        __syncthreads();  // the previous chunk is done with xs and yp
+        for (int j = 0; j < TB; ++j)
+            if (j < it.ntok)
+                stage_as_f32(reinterpret_cast<const WT*>(a.x) + (size_t)it.tok[j] * H, xs + (size_t)j * H, H);
+        __syncthreads();
+        float acc[TB][NCH * N];
+#pragma unroll
+        for (int j = 0; j < TB; ++j)
+#pragma unroll
+            for (int q = 0; q < NCH * N; ++q) acc[j][q] = 0.f;
+        for (int i = r0 + wv; i < r1; i += kGroupedWaves) {
+            const WT* p = pool + (size_t)it.slot * a.slot_elems + (size_t)i * 3 * H + lane_off;
+            Raw g[NCH], u[NCH], d[NCH];
+#pragma unroll
+            for (int q = 0; q < NCH; ++q) g[q] = V::load(p + q * CW);
+#pragma unroll
+            for (int q = 0; q < NCH; ++q) u[q] = V::load(p + H + q * CW);
+#pragma unroll
+            for (int q = 0; q < NCH; ++q) d[q] = V::load(p + 2 * H + q * CW);
+#pragma unroll
+            for (int j = 0; j < TB; ++j) {
+                if (j < it.ntok) {  // uniform
+                    float gs = 0.f, us = 0.f;
+#pragma unroll
+                    for (int q = 0; q < NCH; ++q) {
+                        float xf[N];
+#pragma unroll
+                        for (int t = 0; t < N; t += 4)
+                            *reinterpret_cast<float4*>(xf + t) =
+                                *reinterpret_cast<const float4*>(xs + (size_t)j * H + q * CW + lane * N + t);
+                        gs = V::dot(g[q], xf, gs);
+                        us = V::dot(u[q], xf, us);
+                    }
+                    gs = wave_sum_dpp(gs);
+                    us = wave_sum_dpp(us);
+                    const float ai = silu(gs) * us * it.w[j];
+#pragma unroll
+                    for (int q = 0; q < NCH; ++q) {
+                        float df[N];
+                        V::unpack(d[q], df);
+#pragma unroll
+                        for (int t = 0; t < N; ++t) acc[j][q * N + t] = __builtin_fmaf(ai, df[t], acc[j][q * N + t]);
+                    }
+                }
+            }
+        }
+        // the chunk's partial row of every token of the item: wavefront rows added in order
+#pragma unroll
+        for (int j = 0; j < TB; ++j) {
+            if (j < it.ntok) {  // uniform
+                __syncthreads();
+                float* row = yp + (size_t)wv * H;
+#pragma unroll
+                for (int q = 0; q < NCH; ++q)
+#pragma unroll
+                    for (int t = 0; t < N; t += 4)
+                        *reinterpret_cast<float4*>(row + q * CW + lane * N + t) =
+                            make_float4(acc[j][q * N + t], acc[j][q * N + t + 1], acc[j][q * N + t + 2],
+                                        acc[j][q * N + t + 3]);
+                __syncthreads();
+                float* out = a.part + ((size_t)c * TB + j) * H;
+                for (int h = tid; h < H; h += kGroupedWaves * kWave) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int k = 0; k < kGroupedWaves; ++k) s += yp[(size_t)k * H + h];
+                    out[h] = s;
+                }
+            }
+        }
+    }
+}
+
+// y[b][h] = sum, in item and chunk order, of the partial rows of the items that hold token b.
+// grid (ceil(H/256), B)
+__global__ void __launch_bounds__(256) ffn_grouped_reduce_kernel(const float* __restrict__ part,
+                                                                 const GroupItem* __restrict__ items,
+                                                                 const int32_t* __restrict__ n_items, int tb, int I,
+                                                                 int H, float* __restrict__ y) {
+    const int h = blockIdx.x * 256 + threadIdx.x;
+    const int b = blockIdx.y;
+    if (h >= H) return;
+    const int n = *n_items;
+    const int cpi = (I + kChunkRows - 1) / kChunkRows;
+    float s = 0.f;
+    for (int it = 0; it < n; ++it) {
+        int pos = -1;
+        for (int j = 0; j < items[it].ntok; ++j)
+            if (items[it].tok[j] == b) pos = j;
+        if (pos < 0) continue;
+        for (int c = 0; c < cpi; ++c) s += part[((size_t)(it * cpi + c) * tb + pos) * H + h];
+    }
+    y[(size_t)b * H + h] = s;
+}
+
 }  // namespace
 
 int ffn_scratch_alloc(const moei_model_desc& d, int n_act_max, FfnScratch* out) {
@@ -440,6 +666,69 @@ int launch_expert_ffn(const moei_model_desc& d, const void* d_pool, size_t slot_
                       env_int("MOEI_FFN_GENERIC", 0) == 0;
     if (d.wdtype == MOEI_WDTYPE_BF16) return launch_ffn_typed<uint16_t>(a, fast, scr.n_part, d_y, s);
     return launch_ffn_typed<float>(a, fast, scr.n_part, d_y, s);
+}
+
+
+int grouped_max_items(const moei_model_desc& d) { return kMaxBatch * d.k + d.n_shared * kMaxBatch; }
+size_t grouped_item_bytes() { return sizeof(GroupItem); }
+size_t grouped_part_floats(const moei_model_desc& d) {
+    const size_t cpi = ((size_t)d.I + kChunkRows - 1) / kChunkRows;
+    return (size_t)grouped_max_items(d) * cpi * kMaxGroup * d.H;
+}
+
+namespace {
+template <typename WT>
+int launch_grouped_typed(const moei_model_desc& d, const GroupedFfnArgs& ga, GroupArgs gr, int B, float* d_y,
+                         hipStream_t s) {
+    using V = WVec<WT>;
+    const int nch = d.H / (kWave * V::N);
+    const int grid = compute_units();
+    int rc;
+#define MOEI_GROUPED_CASE(N_)                                                                           \
+    case N_: {                                                                                          \
+        gr.tb = GroupedShape<N_>::kTB;                                                                  \
+        launch(K_FFN_GROUP, ffn_group_kernel, dim3(1), dim3(256), 0, s, gr);                            \
+        MOEI_LAUNCH_CHECK();                                                                            \
+        const size_t smem = (size_t)(GroupedShape<N_>::kTB + kGroupedWaves) * d.H * sizeof(float);      \
+        if (smem > kLdsBudget) MOEI_FAIL(MOEI_ECAPACITY, "expert_ffn_grouped: H = %d does not fit the LDS staging", d.H); \
+        rc = allow_big_lds(ffn_grouped_kernel<WT, N_>, smem);                                           \
+        if (rc) return rc;                                                                              \
+        launch(K_FFN_FUSED, ffn_grouped_kernel<WT, N_>, dim3(grid), dim3(kGroupedWaves * kWave), smem, s, ga); \
+        MOEI_LAUNCH_CHECK();                                                                            \
+        break;                                                                                          \
+    }
+    switch (nch) {
+        MOEI_GROUPED_CASE(1)
+        MOEI_GROUPED_CASE(2)
+        MOEI_GROUPED_CASE(4)
+        MOEI_GROUPED_CASE(8)
+        MOEI_GROUPED_CASE(10)
+        default:
+            MOEI_FAIL(MOEI_EINVAL, "expert_ffn_grouped: H = %d is not supported (needs H / %d in {1,2,4,8,10})", d.H,
+                      kWave * V::N);
+    }
+#undef MOEI_GROUPED_CASE
+    launch(K_FFN_REDUCE, ffn_grouped_reduce_kernel, dim3((d.H + 255) / 256, B), dim3(256), 0, s, (const float*)ga.part,
+           ga.items, ga.n_items, gr.tb, d.I, d.H, d_y);
+    MOEI_LAUNCH_CHECK();
+    return MOEI_OK;
+}
+}  // namespace
+
+int launch_expert_ffn_grouped(const moei_model_desc& d, const void* d_pool, size_t slot_elems, void* d_items,
+                              int32_t* d_n_items, float* d_part, const int32_t* d_slot_of_row, int shared_base,
+                              const int32_t* d_idx, const float* d_w, int B, const void* d_x, float* d_y,
+                              int32_t* d_flags, hipStream_t s) {
+    if (B > kMaxBatch) MOEI_FAIL(MOEI_EINVAL, "expert_ffn_grouped: B = %d exceeds %d", B, kMaxBatch);
+    const int wb = d.wdtype == MOEI_WDTYPE_BF16 ? 2 : 4;
+    const int n = 16 / wb;
+    if (d.H % (kWave * n) != 0 || (uintptr_t)d_pool % 16 != 0 || (slot_elems * wb) % 16 != 0)
+        MOEI_FAIL(MOEI_EINVAL, "expert_ffn_grouped: H = %d must be a multiple of %d", d.H, kWave * n);
+    GroupArgs gr{d_idx, d_w, d_slot_of_row, B, d.k, d.E, d.n_shared, shared_base, 0,
+                 reinterpret_cast<GroupItem*>(d_items), d_n_items, d_flags};
+    GroupedFfnArgs ga{d_pool, slot_elems, reinterpret_cast<const GroupItem*>(d_items), d_n_items, d_x, d_part, d.H, d.I};
+    if (d.wdtype == MOEI_WDTYPE_BF16) return launch_grouped_typed<uint16_t>(d, ga, gr, B, d_y, s);
+    return launch_grouped_typed<float>(d, ga, gr, B, d_y, s);
 }
 
 }  // namespace moei

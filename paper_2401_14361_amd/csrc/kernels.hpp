@@ -43,6 +43,15 @@ int launch_expert_ffn(const moei_model_desc& d, const void* d_pool, size_t slot_
                       const FfnScratch& scr, const int32_t* d_slot_ids, const float* d_gate_w, int n_act,
                       const void* d_x, float* d_y, int32_t* d_flags, hipStream_t s);
 
+// decode batch B > 1: tokens grouped per activated expert
+int grouped_max_items(const moei_model_desc& d);
+size_t grouped_item_bytes();
+size_t grouped_part_floats(const moei_model_desc& d);
+int launch_expert_ffn_grouped(const moei_model_desc& d, const void* d_pool, size_t slot_elems, void* d_items,
+                              int32_t* d_n_items, float* d_part, const int32_t* d_slot_of_row, int shared_base,
+                              const int32_t* d_idx, const float* d_w, int B, const void* d_x, float* d_y,
+                              int32_t* d_flags, hipStream_t s);
+
 }  // namespace moei
 
 // The EAM collection (Sec. 4.5): traces layer-major on the device.
