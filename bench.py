@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-offload", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="also time the batched match and grouped FFN for B = 1..16 (EAMC of 10,000 traces)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 512 MiB device copy (scale for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -302,6 +304,43 @@ def main():
     }
     log(f"[bench] match {match_us:.1f} us; big-N dot {dot_us:.1f} us = {big_bytes / dot_us / 1e3:.0f} GB/s; "
         f"gemv {gemv_us:.1f} us = {ffn_bytes / gemv_us / 1e3:.0f} GB/s")
+
+    # ------------------------------------------------ optional: decode batches on this shape
+    if args.batch_sweep:
+        big_cfg = cfg.scaled(cid=5, N=10000)
+        tr10k, _, _ = mi.eamc_traces(big_cfg, threads=16)
+        e10k = m.Eamc(desc, big_cfg.N, 4)
+        e10k.load(tr10k)
+        sweep = []
+        for Bq in (1, 2, 4, 8, 16):
+            rq = [mi.make_request(cfg, 200 + b, decode=1) for b in range(Bq)]
+            q = dev(np.stack([r.prefill_eam for r in rq]).astype(np.int32))
+            xb = dev(np.stack([r.x[0, 0] for r in rq]))
+            lg = dev(np.stack([r.bias[0] for r in rq]).astype(np.float32) + rng.standard_normal((Bq, E)).astype(np.float32))
+            idx_b, w_b = m.moe_route_topk(lg, k, bool(cfg.renorm))
+            distinct = len(set(idx_b.cpu().numpy().reshape(-1).tolist())) + cfg.n_shared
+            for _ in range(5):
+                m.eamc_match(e10k, q, stream=stream)
+                m.expert_ffn_grouped(cache, 0, idx_b, w_b, xb, stream=stream)
+            ev0.record(stream)
+            for _ in range(50):
+                m.eamc_match(e10k, q, stream=stream)
+            ev1.record(stream)
+            torch.cuda.synchronize()
+            t_match = ev0.elapsed_time(ev1) / 50 * 1e3
+            ev0.record(stream)
+            for _ in range(50):
+                m.expert_ffn_grouped(cache, 0, idx_b, w_b, xb, stream=stream)
+            ev1.record(stream)
+            torch.cuda.synchronize()
+            t_ffn = ev0.elapsed_time(ev1) / 50 * 1e3
+            sweep.append({"B": Bq, "match_us": t_match, "match_alg_bytes": big_cfg.N * L * E * 4,
+                          "distinct_experts": distinct, "ffn_us": t_ffn, "ffn_alg_bytes": distinct * cfg.expert_bytes,
+                          "ffn_GBps": distinct * cfg.expert_bytes / t_ffn / 1e3})
+            log(f"[bench] batch {Bq}: match {t_match:.1f} us, grouped FFN {t_ffn:.1f} us over {distinct} experts "
+                f"= {distinct * cfg.expert_bytes / t_ffn / 1e3:.0f} GB/s")
+        extra["batch_sweep"] = sweep
+        e10k.close()
 
     # ------------------------------------------------ leg 4: offload replay (capped cache, PCIe misses)
     if not args.no_offload and cfg.S < L * E:

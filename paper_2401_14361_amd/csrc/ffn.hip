@@ -398,11 +398,10 @@ int launch_ffn_typed(FfnArgs a, bool fast, int grid, float* d_y, hipStream_t s) 
 
 // ------------------------------------------------------------------ decode batch B > 1
 // Tokens are grouped per activated expert; an "item" is one expert with up to kMaxGroup of its
-// tokens, so the expert's weights are streamed once per item.  Items are cut into chunks of
-// kChunkRows intermediate units; chunks are dealt to the workgroups in turn.  A wavefront
-// streams a unit once and uses it for every token of the item; y accumulators exist per token.
+// tokens, so the expert's weights are streamed once per item.  The items' intermediate units
+// are split evenly over the workgroups as contiguous ranges.  A wavefront streams a unit once
+// and uses it for every token of the item; y accumulators exist per token.
 constexpr int kMaxGroup = 4;
-constexpr int kChunkRows = 64;
 constexpr int kGroupedWaves = 8;
 constexpr int kMaxBatch = 16;
 
@@ -495,14 +494,23 @@ struct GroupedFfnArgs {
     const GroupItem* items;
     const int32_t* n_items;
     const void* x;  // [B][H]
-    float* part;    // [chunks][TB][H]
+    float* part;    // [workgroups][seg_max][TB][H]
     int H, I;
+    int seg_max;
 };
 
 template <int NCH>
 struct GroupedShape {
     static constexpr int kTB = NCH <= 4 ? 4 : 1;  // y accumulators per token must fit the register file
 };
+
+// The activated items' intermediate units form one row space of n_items * I rows; workgroup g
+// takes the contiguous range [total*g/G, total*(g+1)/G).  A range crosses at most
+// ceil(n_items / G) item boundaries, so it is cut into at most that many + 1 segments, each
+// inside one item; a segment yields one partial y row per token of the item.
+__device__ __host__ inline long grouped_range_begin(long total, int g, int G) { return total * g / G; }
+
+__host__ inline int grouped_seg_max(int max_items, int G) { return (max_items + G - 1) / G + 1; }
 
 template <typename WT, int NCH>
 __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(GroupedFfnArgs a) {
@@ -511,6 +519,8 @@ __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(Gr
     constexpr int N = V::N;
     constexpr int CW = kWave * N;
     constexpr int TB = GroupedShape<NCH>::kTB;
+    constexpr int STEPS = StreamShape<NCH>::kSteps;
+    constexpr int PF = StreamShape<NCH>::kWindow;
     extern __shared__ __align__(16) float smem[];
     float* xs = smem;              // [TB][H] inputs of the item's tokens, fp32
     float* yp = smem + TB * a.H;   // [kGroupedWaves][H] y rows of one token, one per wavefront
@@ -519,15 +529,36 @@ __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(Gr
     const int H = a.H, I = a.I;
     const WT* pool = reinterpret_cast<const WT*>(a.pool);
     const unsigned lane_off = (unsigned)lane * N;
-    const int n_items = *a.n_items;
-    const int cpi = (I + kChunkRows - 1) / kChunkRows;
-    const int n_chunks = n_items * cpi;
-    for (int c = blockIdx.x; c < n_chunks; c += gridDim.x) {  // uniform over the workgroup
-        const int item = c / cpi;
-        const int r0 = (c - item * cpi) * kChunkRows;
-        const int r1 = min(I, r0 + kChunkRows);
+    const long total = (long)*a.n_items * I;
+    const long R0 = grouped_range_begin(total, blockIdx.x, gridDim.x);
+    const long R1 = grouped_range_begin(total, blockIdx.x + 1, gridDim.x);
+    auto scalar = [](size_t v) -> size_t {
+        uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+        uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+        return (size_t)(((uint64_t)hi << 32) | lo);
+    };
+    auto step_off = [&](int s) -> int {
+        return s < 2 * NCH ? ((s & 1) ? H : 0) + (s >> 1) * CW : 2 * H + (s - 2 * NCH) * CW;
+    };
+    auto ld = [&](size_t unit, int off) -> Raw { return V::load(pool + unit + off + lane_off); };
+
+    int seg = 0;
+    for (long row = R0; row < R1 && seg < a.seg_max; ++seg) {  // uniform over the workgroup
+        const int item = (int)(row / I);
+        const int r0 = (int)(row - (long)item * I);
+        const int r1 = (int)min((long)I, r0 + (R1 - row));
+        row += r1 - r0;
         const GroupItem it = a.items[item];
-        __syncthreads();  // the previous chunk is done with xs and yp
+        // this wavefront's rows of the segment: r0 + wv, r0 + wv + 8, ...
+        const int nr = (r1 - r0 - wv + kGroupedWaves - 1) / kGroupedWaves;  // may be <= 0
+        const size_t row_stride = (size_t)kGroupedWaves * 3 * H;
+        size_t p = scalar((size_t)it.slot * a.slot_elems + (size_t)(r0 + wv) * 3 * H);
+        Raw win[PF];
+        if (nr > 0) {  // the first window is on its way while the inputs are staged
+#pragma unroll
+            for (int s = 0; s < PF; ++s) win[s] = ld(p, step_off(s));
+        }
+        __syncthreads();  // the previous segment is done with xs and yp
         for (int j = 0; j < TB; ++j)
             if (j < it.ntok)
                 stage_as_f32(reinterpret_cast<const WT*>(a.x) + (size_t)it.tok[j] * H, xs + (size_t)j * H, H);
@@ -537,57 +568,68 @@ __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(Gr
         for (int j = 0; j < TB; ++j)
 #pragma unroll
             for (int q = 0; q < NCH * N; ++q) acc[j][q] = 0.f;
-        for (int i = r0 + wv; i < r1; i += kGroupedWaves) {
-            const WT* p = pool + (size_t)it.slot * a.slot_elems + (size_t)i * 3 * H + lane_off;
-            Raw g[NCH], u[NCH], d[NCH];
+        for (int r = 0; r < nr; ++r) {
+            const bool more = r + 1 < nr;
+            const size_t pn = more ? p + row_stride : p;
+            float gs[TB], us[TB], ai[TB];
 #pragma unroll
-            for (int q = 0; q < NCH; ++q) g[q] = V::load(p + q * CW);
+            for (int j = 0; j < TB; ++j) gs[j] = us[j] = ai[j] = 0.f;
 #pragma unroll
-            for (int q = 0; q < NCH; ++q) u[q] = V::load(p + H + q * CW);
+            for (int s = 0; s < STEPS; ++s) {
+                const Raw cur = win[s % PF];
+                if (s < 2 * NCH) {
 #pragma unroll
-            for (int q = 0; q < NCH; ++q) d[q] = V::load(p + 2 * H + q * CW);
+                    for (int j = 0; j < TB; ++j) {
+                        if (j < it.ntok) {  // uniform
+                            float xf[N];
 #pragma unroll
-            for (int j = 0; j < TB; ++j) {
-                if (j < it.ntok) {  // uniform
-                    float gs = 0.f, us = 0.f;
-#pragma unroll
-                    for (int q = 0; q < NCH; ++q) {
-                        float xf[N];
-#pragma unroll
-                        for (int t = 0; t < N; t += 4)
-                            *reinterpret_cast<float4*>(xf + t) =
-                                *reinterpret_cast<const float4*>(xs + (size_t)j * H + q * CW + lane * N + t);
-                        gs = V::dot(g[q], xf, gs);
-                        us = V::dot(u[q], xf, us);
+                            for (int t = 0; t < N; t += 4)
+                                *reinterpret_cast<float4*>(xf + t) = *reinterpret_cast<const float4*>(
+                                    xs + (size_t)j * H + (s >> 1) * CW + lane * N + t);
+                            if ((s & 1) == 0)
+                                gs[j] = V::dot(cur, xf, gs[j]);
+                            else
+                                us[j] = V::dot(cur, xf, us[j]);
+                        }
                     }
-                    gs = wave_sum_dpp(gs);
-                    us = wave_sum_dpp(us);
-                    const float ai = silu(gs) * us * it.w[j];
+                } else {
+                    if (s == 2 * NCH) {
 #pragma unroll
-                    for (int q = 0; q < NCH; ++q) {
-                        float df[N];
-                        V::unpack(d[q], df);
-#pragma unroll
-                        for (int t = 0; t < N; ++t) acc[j][q * N + t] = __builtin_fmaf(ai, df[t], acc[j][q * N + t]);
+                        for (int j = 0; j < TB; ++j)
+                            if (j < it.ntok) ai[j] = silu(wave_sum_dpp(gs[j])) * wave_sum_dpp(us[j]) * it.w[j];
                     }
+                    float df[N];
+                    V::unpack(cur, df);
+#pragma unroll
+                    for (int j = 0; j < TB; ++j)
+#pragma unroll
+                        for (int t = 0; t < N; ++t)
+                            acc[j][(s - 2 * NCH) * N + t] = __builtin_fmaf(ai[j], df[t], acc[j][(s - 2 * NCH) * N + t]);
                 }
+                __builtin_amdgcn_sched_barrier(0);
+                if (s + PF < STEPS)
+                    win[s % PF] = ld(p, step_off(s + PF));
+                else
+                    win[s % PF] = ld(pn, more ? step_off(s + PF - STEPS) : 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
+            p = pn;
         }
-        // the chunk's partial row of every token of the item: wavefront rows added in order
+        // the segment's partial row of every token of the item: wavefront rows added in order
 #pragma unroll
         for (int j = 0; j < TB; ++j) {
             if (j < it.ntok) {  // uniform
                 __syncthreads();
-                float* row = yp + (size_t)wv * H;
+                float* rowp = yp + (size_t)wv * H;
 #pragma unroll
                 for (int q = 0; q < NCH; ++q)
 #pragma unroll
                     for (int t = 0; t < N; t += 4)
-                        *reinterpret_cast<float4*>(row + q * CW + lane * N + t) =
+                        *reinterpret_cast<float4*>(rowp + q * CW + lane * N + t) =
                             make_float4(acc[j][q * N + t], acc[j][q * N + t + 1], acc[j][q * N + t + 2],
                                         acc[j][q * N + t + 3]);
                 __syncthreads();
-                float* out = a.part + ((size_t)c * TB + j) * H;
+                float* out = a.part + (((size_t)blockIdx.x * a.seg_max + seg) * TB + j) * H;
                 for (int h = tid; h < H; h += kGroupedWaves * kWave) {
                     float s = 0.f;
 #pragma unroll
@@ -599,26 +641,66 @@ __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(Gr
     }
 }
 
-// y[b][h] = sum, in item and chunk order, of the partial rows of the items that hold token b.
-// grid (ceil(H/256), B)
+// y[b][h] = sum of the partial rows of the segments whose item holds token b: 16 slices take
+// the segments in turn (workgroup-major order) and are then added in slice order.
+// grid (H / 64, B), 256 threads = 16 slices x 16 float4 columns; dynamic LDS: n_blocks * seg_max ints.
 __global__ void __launch_bounds__(256) ffn_grouped_reduce_kernel(const float* __restrict__ part,
                                                                  const GroupItem* __restrict__ items,
                                                                  const int32_t* __restrict__ n_items, int tb, int I,
-                                                                 int H, float* __restrict__ y) {
-    const int h = blockIdx.x * 256 + threadIdx.x;
+                                                                 int H, int n_blocks, int seg_max,
+                                                                 float* __restrict__ y) {
+    extern __shared__ __align__(16) int32_t s_rows[];  // partial row of each segment for this token, or -1
+    __shared__ float4 s_red[16][16];
     const int b = blockIdx.y;
-    if (h >= H) return;
-    const int n = *n_items;
-    const int cpi = (I + kChunkRows - 1) / kChunkRows;
-    float s = 0.f;
-    for (int it = 0; it < n; ++it) {
-        int pos = -1;
-        for (int j = 0; j < items[it].ntok; ++j)
-            if (items[it].tok[j] == b) pos = j;
-        if (pos < 0) continue;
-        for (int c = 0; c < cpi; ++c) s += part[((size_t)(it * cpi + c) * tb + pos) * H + h];
+    const long total = (long)*n_items * I;
+    for (int g = threadIdx.x; g < n_blocks; g += 256) {
+        long row = grouped_range_begin(total, g, n_blocks);
+        const long R1 = grouped_range_begin(total, g + 1, n_blocks);
+        for (int seg = 0; seg < seg_max; ++seg) {
+            int entry = -1;
+            if (row < R1) {
+                const int item = (int)(row / I);
+                const int r0 = (int)(row - (long)item * I);
+                row += min((long)I, r0 + (R1 - row)) - r0;
+                for (int j = 0; j < items[item].ntok; ++j)
+                    if (items[item].tok[j] == b) entry = (g * seg_max + seg) * tb + j;
+            }
+            s_rows[g * seg_max + seg] = entry;
+        }
     }
-    y[(size_t)b * H + h] = s;
+    __syncthreads();
+    const int slice = threadIdx.x >> 4, col = threadIdx.x & 15;
+    const int h = blockIdx.x * 64 + col * 4;
+    const int n = n_blocks * seg_max;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int e0 = slice; e0 < n; e0 += 64) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = e0 + 16 * u;
+            const int r = e < n ? s_rows[e] : -1;
+            v[u] = r >= 0 ? *reinterpret_cast<const float4*>(part + (size_t)r * H + h) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            acc.x += v[u].x;
+            acc.y += v[u].y;
+            acc.z += v[u].z;
+            acc.w += v[u].w;
+        }
+    }
+    s_red[slice][col] = acc;
+    __syncthreads();
+    if (slice == 0) {
+        float4 t = s_red[0][col];
+        for (int k = 1; k < 16; ++k) {
+            t.x += s_red[k][col].x;
+            t.y += s_red[k][col].y;
+            t.z += s_red[k][col].z;
+            t.w += s_red[k][col].w;
+        }
+        *reinterpret_cast<float4*>(y + (size_t)b * H + h) = t;
+    }
 }
 
 }  // namespace
@@ -672,17 +754,18 @@ int launch_expert_ffn(const moei_model_desc& d, const void* d_pool, size_t slot_
 int grouped_max_items(const moei_model_desc& d) { return kMaxBatch * d.k + d.n_shared * kMaxBatch; }
 size_t grouped_item_bytes() { return sizeof(GroupItem); }
 size_t grouped_part_floats(const moei_model_desc& d) {
-    const size_t cpi = ((size_t)d.I + kChunkRows - 1) / kChunkRows;
-    return (size_t)grouped_max_items(d) * cpi * kMaxGroup * d.H;
+    const int G = compute_units();
+    return (size_t)G * grouped_seg_max(grouped_max_items(d), G) * kMaxGroup * d.H;
 }
 
 namespace {
 template <typename WT>
-int launch_grouped_typed(const moei_model_desc& d, const GroupedFfnArgs& ga, GroupArgs gr, int B, float* d_y,
+int launch_grouped_typed(const moei_model_desc& d, GroupedFfnArgs ga, GroupArgs gr, int B, float* d_y,
                          hipStream_t s) {
     using V = WVec<WT>;
     const int nch = d.H / (kWave * V::N);
     const int grid = compute_units();
+    ga.seg_max = grouped_seg_max(grouped_max_items(d), grid);
     int rc;
 #define MOEI_GROUPED_CASE(N_)                                                                           \
     case N_: {                                                                                          \
@@ -708,8 +791,9 @@ int launch_grouped_typed(const moei_model_desc& d, const GroupedFfnArgs& ga, Gro
                       kWave * V::N);
     }
 #undef MOEI_GROUPED_CASE
-    launch(K_FFN_REDUCE, ffn_grouped_reduce_kernel, dim3((d.H + 255) / 256, B), dim3(256), 0, s, (const float*)ga.part,
-           ga.items, ga.n_items, gr.tb, d.I, d.H, d_y);
+    launch(K_FFN_REDUCE, ffn_grouped_reduce_kernel, dim3(d.H / 64, B), dim3(256),
+           (size_t)grid * ga.seg_max * sizeof(int32_t), s, (const float*)ga.part, ga.items, ga.n_items, gr.tb, d.I, d.H,
+           grid, ga.seg_max, d_y);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
 }
@@ -726,7 +810,7 @@ int launch_expert_ffn_grouped(const moei_model_desc& d, const void* d_pool, size
         MOEI_FAIL(MOEI_EINVAL, "expert_ffn_grouped: H = %d must be a multiple of %d", d.H, kWave * n);
     GroupArgs gr{d_idx, d_w, d_slot_of_row, B, d.k, d.E, d.n_shared, shared_base, 0,
                  reinterpret_cast<GroupItem*>(d_items), d_n_items, d_flags};
-    GroupedFfnArgs ga{d_pool, slot_elems, reinterpret_cast<const GroupItem*>(d_items), d_n_items, d_x, d_part, d.H, d.I};
+    GroupedFfnArgs ga{d_pool, slot_elems, reinterpret_cast<const GroupItem*>(d_items), d_n_items, d_x, d_part, d.H, d.I, 0};
     if (d.wdtype == MOEI_WDTYPE_BF16) return launch_grouped_typed<uint16_t>(d, ga, gr, B, d_y, s);
     return launch_grouped_typed<float>(d, ga, gr, B, d_y, s);
 }

@@ -29,7 +29,7 @@ struct DotArgs {
     const void* traces;   // [L][n_cap][E]
     const int32_t* q;     // [B][L][E]
     u64* part;            // [B][n_lsplit][n_cap]
-    int n_cap, N, L, E;
+    int n_cap, N, L, E, B;
     int L_scan;           // layers 0..L_scan-1 are read
     int lper;             // layers per split
     int n_lsplit;
@@ -91,34 +91,41 @@ struct CellVec<uint16_t, 1> {
     }
 };
 
-// grid (tiles, layer splits, B).  Thread t owns vectors p = j*256 + t (j < J) of its
-// tile; vector p belongs to trace p / rowV of the tile in EVERY layer, so the J
-// accumulators live in registers across the whole layer walk.
-template <typename CT, int VEC, int J>
+// grid (tiles, layer splits, query groups).  Thread t owns vectors p = j*256 + t (j < J) of its
+// tile; vector p belongs to trace p / rowV of the tile in EVERY layer, so the accumulators
+// live in registers across the whole layer walk.  A workgroup serves NB queries at once:
+// every loaded vector is multiplied with all of them, so a batch reads the traces once per
+// group of NB queries.
+template <typename CT, int VEC, int J, int NB>
 __global__ void __launch_bounds__(kDotThreads) eamc_dot_kernel(DotArgs a) {
     using CV = CellVec<CT, VEC>;
     extern __shared__ __align__(16) unsigned char smem[];
-    int32_t* qs = reinterpret_cast<int32_t*>(smem);
-    const int q_bytes = ((a.lper * a.E * 4) + 15) & ~15;
-    u64* rowsum = reinterpret_cast<u64*>(smem + q_bytes);
+    int32_t* qs = reinterpret_cast<int32_t*>(smem);  // [NB][lper*E]
+    const int q_stride = a.lper * a.E;
+    const int q_bytes = ((NB * q_stride * 4) + 15) & ~15;
+    u64* rowsum = reinterpret_cast<u64*>(smem + q_bytes);  // [NB][TN]
 
     const int tid = threadIdx.x;
     const int split = blockIdx.y;
-    const int b = blockIdx.z;
+    const int b0 = blockIdx.z * NB;
     const int l0 = split * a.lper;
     int nl = min(l0 + a.lper, a.L_scan) - l0;
     if (nl < 0) nl = 0;
     const int n0 = blockIdx.x * a.TN;
     const int tn = min(a.TN, a.N - n0);
 
-    const int32_t* qsrc = a.q + ((size_t)b * a.L + l0) * a.E;
-    for (int i = tid; i < nl * a.E; i += kDotThreads) qs[i] = qsrc[i];
-    for (int i = tid; i < a.TN; i += kDotThreads) rowsum[i] = 0;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const bool on = b0 + b < a.B;
+        const int32_t* qsrc = a.q + ((size_t)(on ? b0 + b : 0) * a.L + l0) * a.E;
+        for (int i = tid; i < nl * a.E; i += kDotThreads) qs[b * q_stride + i] = on ? qsrc[i] : 0;
+    }
+    for (int i = tid; i < NB * a.TN; i += kDotThreads) rowsum[i] = 0;
     __syncthreads();
 
     bool valid[J];
     int row[J], col[J];
-    u64 acc[J];
+    u64 acc[J][NB];
     const int nvec = tn * a.rowV;
 #pragma unroll
     for (int j = 0; j < J; ++j) {
@@ -126,7 +133,8 @@ __global__ void __launch_bounds__(kDotThreads) eamc_dot_kernel(DotArgs a) {
         valid[j] = p < nvec;
         row[j] = valid[j] ? p / a.rowV : 0;
         col[j] = valid[j] ? (p - row[j] * a.rowV) * VEC : 0;
-        acc[j] = 0;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) acc[j][b] = 0;
     }
     const size_t lstride = (size_t)a.n_cap * a.E;
     const CT* base = reinterpret_cast<const CT*>(a.traces) + ((size_t)l0 * a.n_cap + n0) * a.E + (size_t)tid * VEC;
@@ -139,16 +147,25 @@ __global__ void __launch_bounds__(kDotThreads) eamc_dot_kernel(DotArgs a) {
             if (valid[j]) v[j] = CV::load(base + (size_t)j * kDotThreads * VEC);
 #pragma unroll
         for (int j = 0; j < J; ++j)
-            if (valid[j]) acc[j] = CV::dot(v[j], ql + col[j], acc[j]);
+            if (valid[j]) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b) acc[j][b] = CV::dot(v[j], ql + b * q_stride + col[j], acc[j][b]);
+            }
         base += lstride;
         ql += a.E;
     }
 #pragma unroll
     for (int j = 0; j < J; ++j)
-        if (valid[j] && acc[j] != 0) atomicAdd(&rowsum[row[j]], acc[j]);
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+            if (valid[j] && acc[j][b] != 0) atomicAdd(&rowsum[b * a.TN + row[j]], acc[j][b]);
     __syncthreads();
-    u64* out = a.part + ((size_t)b * a.n_lsplit + split) * a.n_cap + n0;
-    for (int i = tid; i < tn; i += kDotThreads) out[i] = rowsum[i];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        if (b0 + b >= a.B) break;
+        u64* out = a.part + ((size_t)(b0 + b) * a.n_lsplit + split) * a.n_cap + n0;
+        for (int i = tid; i < tn; i += kDotThreads) out[i] = rowsum[b * a.TN + i];
+    }
 }
 
 struct Best {
@@ -359,13 +376,14 @@ __global__ void __launch_bounds__(kPickThreads) eamc_pick_kernel(PickArgs a) {
 }
 
 struct Plan {
-    int VEC, J, TN, rowV, n_tiles, n_lsplit, lper;
+    int VEC, J, TN, rowV, n_tiles, n_lsplit, lper, NB;
     size_t smem;
 };
 
-Plan make_plan(const moei_eamc* c, int L_scan) {
-    static const int kTargetBlocks = getenv("MOEI_MATCH_BLOCKS") ? atoi(getenv("MOEI_MATCH_BLOCKS")) : 256;
+Plan make_plan(const moei_eamc* c, int L_scan, int B) {
+    static const int kTargetBlocks = getenv("MOEI_MATCH_BLOCKS") ? atoi(getenv("MOEI_MATCH_BLOCKS")) : 0;
     Plan p{};
+    p.NB = B >= 3 ? 4 : (B == 2 ? 2 : 1);  // queries served by one pass over the traces
     const int E = c->d.E;
     const int full = 16 / c->cell_bytes;
     p.VEC = (E % full == 0) ? full : 1;
@@ -376,23 +394,27 @@ Plan make_plan(const moei_eamc* c, int L_scan) {
     if (p.TN < 1) p.TN = 1;
     p.J = (p.TN * p.rowV + kDotThreads - 1) / kDotThreads;
     p.n_tiles = (c->N + p.TN - 1) / p.TN;
-    int want = (kTargetBlocks + p.n_tiles - 1) / p.n_tiles;  // aim at enough workgroups to fill the chip
+    // aim at enough workgroups to fill the chip (two rounds of them when the scan is long);
+    // the query groups multiply the grid as well
+    const int target = kTargetBlocks > 0 ? kTargetBlocks : (jt > 1 ? 512 : 256);
+    const int per_split = p.n_tiles * ((B + p.NB - 1) / p.NB);
+    int want = (target + per_split - 1) / per_split;
     int lmax = L_scan < c->lsplit_max ? L_scan : c->lsplit_max;
     p.n_lsplit = want < 1 ? 1 : (want > lmax ? lmax : want);
-    // LDS: the query rows of one split must fit in 48 KiB
-    int min_split = (int)(((size_t)L_scan * E * 4 + 49151) / 49152);
+    // LDS: the query rows of one split (for all NB queries) must fit in 48 KiB
+    int min_split = (int)(((size_t)p.NB * L_scan * E * 4 + 49151) / 49152);
     if (p.n_lsplit < min_split) p.n_lsplit = min_split;
     p.lper = (L_scan + p.n_lsplit - 1) / p.n_lsplit;
     p.n_lsplit = (L_scan + p.lper - 1) / p.lper;
-    p.smem = (((size_t)p.lper * E * 4 + 15) & ~(size_t)15) + (size_t)p.TN * 8;
+    p.smem = (((size_t)p.NB * p.lper * E * 4 + 15) & ~(size_t)15) + (size_t)p.NB * p.TN * 8;
     return p;
 }
 
-template <typename CT, int VEC>
-int launch_dot_j(const Plan& p, const DotArgs& a, dim3 grid, hipStream_t s) {
-#define MOEI_DOT_CASE(JJ)                                                                          \
-    case JJ:                                                                                       \
-        launch(K_MATCH_DOT, eamc_dot_kernel<CT, VEC, JJ>, grid, dim3(kDotThreads), p.smem, s, a);  \
+template <typename CT, int VEC, int NB>
+int launch_dot_nb(const Plan& p, const DotArgs& a, dim3 grid, hipStream_t s) {
+#define MOEI_DOT_CASE(JJ)                                                                              \
+    case JJ:                                                                                           \
+        launch(K_MATCH_DOT, eamc_dot_kernel<CT, VEC, JJ, NB>, grid, dim3(kDotThreads), p.smem, s, a);  \
         break;
     switch (p.J) {
         MOEI_DOT_CASE(1)
@@ -409,6 +431,13 @@ int launch_dot_j(const Plan& p, const DotArgs& a, dim3 grid, hipStream_t s) {
 #undef MOEI_DOT_CASE
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
+}
+
+template <typename CT, int VEC>
+int launch_dot_j(const Plan& p, const DotArgs& a, dim3 grid, hipStream_t s) {
+    if (p.NB == 4) return launch_dot_nb<CT, VEC, 4>(p, a, grid, s);
+    if (p.NB == 2) return launch_dot_nb<CT, VEC, 2>(p, a, grid, s);
+    return launch_dot_nb<CT, VEC, 1>(p, a, grid, s);
 }
 
 size_t cells(const moei_eamc* c) { return (size_t)c->d.L * c->n_cap * c->d.E; }
@@ -586,12 +615,12 @@ int launch_match(const moei_eamc* c, const int32_t* d_eam, int B, int layer_hi, 
     if (score && B != 1) MOEI_FAIL(MOEI_EINVAL, "match with scoring needs B = 1");
     int n_lsplit = 0;
     if (c->N > 0) {
-        Plan p = make_plan(c, layer_hi + 1);
+        Plan p = make_plan(c, layer_hi + 1, B);
         n_lsplit = p.n_lsplit;
         if (p.n_lsplit > c->lsplit_max || p.smem > 64 * 1024)
             MOEI_FAIL(MOEI_ECAPACITY, "eamc_match: L*E = %d is too large for the match kernel's LDS staging", L * E);
-        DotArgs a{c->d_traces, d_eam, c->d_part, c->n_cap, c->N, L, E, layer_hi + 1, p.lper, p.n_lsplit, p.TN, p.rowV};
-        dim3 grid(p.n_tiles, p.n_lsplit, B);
+        DotArgs a{c->d_traces, d_eam, c->d_part, c->n_cap, c->N, L, E, B, layer_hi + 1, p.lper, p.n_lsplit, p.TN, p.rowV};
+        dim3 grid(p.n_tiles, p.n_lsplit, (B + p.NB - 1) / p.NB);
         int rc;
         if (c->cell_bytes == 4)
             rc = p.VEC == 4 ? launch_dot_j<int32_t, 4>(p, a, grid, s) : launch_dot_j<int32_t, 1>(p, a, grid, s);
