@@ -25,7 +25,7 @@ import numpy as np
 
 __all__ = [
     "to_f64", "router_logits", "softmax", "route_topk", "eam_update", "eamc_match",
-    "aggregate_matches", "expert_priority", "swiglu_expert", "expert_ffn",
+    "eamc_match_topm", "aggregate_matches", "expert_priority", "swiglu_expert", "expert_ffn",
     "ExpertCache", "decode_layer",
 ]
 
@@ -130,6 +130,37 @@ def eamc_match(traces, q):
         if best_key is None or key > best_key:
             best, best_key = t, key
     return best, float(sims[best]), sims
+
+
+def eamc_match_topm(traces, q, m: int):
+    """The m most similar stored EAMs (Sec. 4.5: the match may hand back several EAMs,
+    which PredictEAM then aggregates).
+
+    reading: the paper does not say how many matches are returned or by what rule;
+    here the caller fixes m and the m traces of largest cosine similarity are taken,
+    most similar first, equal similarities by ascending trace index -- the same total
+    order whose first element ``eamc_match`` returns.  Decided with exact fractions
+    (dot^2 / |T|^2).  Returns (idx list, sims list) of length min(m, N).
+    """
+    if m < 0:
+        raise ValueError("m must be >= 0")
+    T = np.asarray(traces)
+    N = T.shape[0]
+    if N == 0 or m == 0:
+        return [], []
+    qv = np.asarray(q).reshape(-1).astype(np.int64)
+    Tv = T.reshape(N, -1).astype(np.int64)
+    nq = int((qv * qv).sum())
+    keyed = []
+    for t in range(N):
+        d = sum(int(a) * int(b) for a, b in zip(Tv[t], qv))
+        n = sum(int(a) * int(a) for a in Tv[t])
+        key = Fraction(d * d, n) if (n > 0 and nq > 0) else Fraction(0)
+        sim = d / (math.sqrt(nq) * math.sqrt(n)) if (n > 0 and nq > 0) else 0.0
+        keyed.append((key, t, sim))
+    keyed.sort(key=lambda e: (-e[0], e[1]))
+    top = keyed[:m]
+    return [t for _, t, _ in top], [s for _, _, s in top]
 
 
 # -------------------------------------------------------- step 4: PredictEAM
@@ -285,14 +316,15 @@ class ExpertCache:
 
 # ----------------------------------------------------------------- whole layer step
 def decode_layer(traces, eam, cache: ExpertCache, layer: int, W_r, bias, x, expert_of, shared_of,
-                 k: int, renorm: bool, eps: float):
+                 k: int, renorm: bool, eps: float, m: int = 1):
     """One MoE layer of one decode iteration, in the order of Sec. 4.3-4.7:
     routing decision, EAM update, EAMC match, priorities, Alg. 1 retrieval, expert FFNs.
 
     ``expert_of(flat_id)`` / ``shared_of(layer)`` hand back weight triples.  The
     eviction order used for this layer's misses is the one computed from the EAM
     that already holds this layer's routing (Alg. 1 calls PredictEAM with the
-    current EAM).  Composite: pinned only through its parts.
+    current EAM).  With m > 1 the m most similar traces are aggregated.
+    Composite: pinned only through its parts.
     """
     L, E = eam.shape
     z = router_logits(W_r, x, bias)
@@ -300,7 +332,8 @@ def decode_layer(traces, eam, cache: ExpertCache, layer: int, W_r, bias, x, expe
     idx, w = idx[0], w[0]
     eam_update(eam, layer, idx)
     best, sim, _ = eamc_match(traces, eam)
-    tstar = aggregate_matches(traces, [best])
+    matched = [best] if m == 1 else eamc_match_topm(traces, eam, m)[0]
+    tstar = aggregate_matches(traces, matched)
     excl = [layer * E + int(j) for j in idx]
     P, V, pf, ev = expert_priority(tstar, layer, cache.resident(), eps, excl)
     events = cache.retrieve(layer, idx, ev)
@@ -310,5 +343,5 @@ def decode_layer(traces, eam, cache: ExpertCache, layer: int, W_r, bias, x, expe
         experts.append(sh)
         gates.append(1.0)
     y = expert_ffn(x, experts, gates)
-    return dict(logits=z, idx=idx, w=w, best=best, sim=sim, P=P, V=V, pf_order=pf, ev_order=ev,
-                events=events, y=y)
+    return dict(logits=z, idx=idx, w=w, best=best, sim=sim, matched=list(matched), P=P, V=V, pf_order=pf,
+                ev_order=ev, events=events, y=y)

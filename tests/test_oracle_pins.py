@@ -202,6 +202,61 @@ def test_match_exact_rank_agrees_with_fp64_and_finds_planted_group():
     assert sim > 0.9
 
 
+def test_match_topm_against_library_sort_and_brute_force():
+    rng = np.random.default_rng(81)
+    # distinct similarities: the order is that of a library cosine + stable sort
+    T = rng.integers(0, 300, size=(40, 4, 8))
+    q = rng.integers(0, 40, size=(4, 8))
+    Tn = torch.nn.functional.normalize(torch.from_numpy(T.reshape(40, -1)).double(), dim=1)
+    qn = torch.nn.functional.normalize(torch.from_numpy(q.reshape(-1)).double(), dim=0)
+    lib = (Tn @ qn).numpy()
+    assert np.unique(lib).size == 40
+    order = np.argsort(-lib, kind="stable")
+    for m in (1, 2, 5, 16, 40, 64):
+        idx, sims = O.eamc_match_topm(T, q, m)
+        assert idx == order[:m].tolist()
+        np.testing.assert_allclose(sims, lib[order[:m]], rtol=1e-13)
+    assert O.eamc_match_topm(T, q, 1)[0] == [O.eamc_match(T, q)[0]]
+    # tiny cases with many exact ties: exact fractions, ties by ascending index
+    for trial in range(150):
+        N, L, E = rng.integers(1, 9), rng.integers(1, 3), rng.integers(1, 4)
+        T = rng.integers(0, 3, size=(N, L, E))
+        q = rng.integers(0, 3, size=(L, E))
+        keys = [_brute_cosine(q, T[t])[0] for t in range(N)]
+        want = sorted(range(N), key=lambda t: (-keys[t], t))
+        for m in (1, 3, N, N + 2):
+            assert O.eamc_match_topm(T, q, m)[0] == want[:m]
+
+
+def test_match_topm_ties_prefix_and_degenerate_inputs():
+    rng = np.random.default_rng(82)
+    T = rng.integers(1, 50, size=(10, 2, 6))
+    q = T[6].copy()
+    T[2] = 3 * T[6]                          # scaled copies tie exactly at similarity 1
+    T[9] = 5 * T[6]
+    idx, sims = O.eamc_match_topm(T, q, 4)
+    assert idx[:3] == [2, 6, 9] and all(abs(s - 1.0) < 1e-15 for s in sims[:3])
+    for m in range(1, 10):                   # each list is a prefix of the next
+        assert O.eamc_match_topm(T, q, m + 1)[0][:m] == O.eamc_match_topm(T, q, m)[0]
+    assert sorted(O.eamc_match_topm(T, q, 99)[0]) == list(range(10))
+    assert O.eamc_match_topm(np.zeros((0, 2, 3), dtype=np.int32), np.ones((2, 3)), 3) == ([], [])
+    assert O.eamc_match_topm(T, q, 0) == ([], [])
+    # an all-zero query: every similarity is 0, the order is the index order
+    assert O.eamc_match_topm(T, np.zeros((2, 6), dtype=np.int64), 3) == ([0, 1, 2], [0.0, 0.0, 0.0])
+
+
+def test_aggregated_matches_hand_worked_priorities():
+    # two matched EAMs, cells summed, rows normalised, proximity applied (Sec. 4.5, steps 2-3)
+    Ta = np.array([[1, 0], [1, 1], [4, 0]])
+    Tb = np.array([[1, 2], [0, 2], [0, 4]])
+    agg = O.aggregate_matches(np.stack([Ta, Tb]), [0, 1])
+    assert agg.tolist() == [[2, 2], [1, 3], [4, 4]]
+    P, V, pf, ev = O.expert_priority(agg, 0, np.zeros((3, 2), dtype=bool), 0.0)
+    # layer 1: (1/4, 3/4) * (1 - 1/3); layer 2: (1/2, 1/2) * (1 - 2/3)
+    np.testing.assert_allclose(P, [[0, 0], [1 / 6, 1 / 2], [1 / 6, 1 / 6]], rtol=1e-15)
+    assert pf == [3, 2, 4, 5]                # 1/2 first; the three equal 1/6 cells by flat id
+
+
 # ==================================================================== O4 priorities
 def test_priority_worked_example_from_the_paper():
     g = json.load(open(os.path.join(GOLD, "alg1_worked_example.json")))
