@@ -106,6 +106,16 @@ int eam_update(int32_t* d_eam, int32_t B, int32_t L, int32_t E, int32_t layer,
 int eamc_match(const moei_eamc* c, const int32_t* d_eam, int32_t B, int32_t layer_hi,
                int32_t* d_best, float* d_best_sim, float* d_sims, void* stream);
 
+/* Step 3 with several matches (Sec. 4.5: the match may return several EAMs, which the
+ * prediction aggregates): d_top[m] = the m most similar traces to the single query
+ * d_eam[L][E], most similar first, equal similarities by ascending index (the total
+ * order whose first element eamc_match returns; exact integer arithmetic);
+ * d_top_sim[m] (may be NULL) their similarities, d_sims[N] (may be NULL) all of them.
+ * Entries beyond the stored traces are -1 / 0.  1 <= m <= 16; MOEI_ECAPACITY when
+ * ceil(N / 1024) * m exceeds 4096.  Feed d_top to expert_priority with B = m. */
+int eamc_match_topm(const moei_eamc* c, const int32_t* d_eam, int32_t layer_hi, int32_t m,
+                    int32_t* d_top, float* d_top_sim, float* d_sims, void* stream);
+
 /* Step 4, PredictEAM + priorities (Sec. 4.5 steps 2-3; Alg. 1 priority score).
  * T = sum over b of trace d_best[b] (entries < 0 skipped), R_i = row sums of T.
  *   prefetch  P[i][j] = T[i][j] (L - i + l) / (R_i L)   for l < i < L, else 0 (0 if R_i = 0)
@@ -113,11 +123,12 @@ int eamc_match(const moei_eamc* c, const int32_t* d_eam, int32_t B, int32_t laye
  * with l = cur_layer in [-1, L-1]; each is one fp64 division of exact products,
  * written out in fp32 to d_prefetch[L][E] / d_evict[L][E].
  * d_pf_order: flat ids i*E+j with i > l, P > 0 and d_slot_of[i*E+j] < 0, by P
- *   descending; d_ev_order: flat ids with d_slot_of >= 0, except the picks
- *   d_cur_idx[B][k] of layer l (may be NULL), by V ascending; ties to the lowest
+ *   descending; d_ev_order: flat ids with d_slot_of >= 0, except the n_cur experts
+ *   d_cur_idx[n_cur] of layer l that are about to run (may be NULL; a list, repeats
+ *   allowed: one query's k picks, or all picks of a batch), by V ascending; ties to the lowest
  *   flat id in both.  Counts go to d_n_pf / d_n_ev; each order buffer holds L*E ints. */
 int expert_priority(const moei_eamc* c, const int32_t* d_best, int32_t B, int32_t cur_layer,
-                    const int32_t* d_slot_of, float eps, const int32_t* d_cur_idx, int32_t k,
+                    const int32_t* d_slot_of, float eps, const int32_t* d_cur_idx, int32_t n_cur,
                     float* d_prefetch, float* d_evict,
                     int32_t* d_pf_order, int32_t* d_n_pf, int32_t* d_ev_order, int32_t* d_n_ev,
                     void* stream);
@@ -203,6 +214,13 @@ int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d_eam, int32
                      const void* d_router_w, const float* d_router_bias,
                      const void* d_x, float* d_y,
                      int32_t* h_topk_idx, int32_t* h_best, int32_t* h_n_miss, void* stream);
+/* Number of most-similar traces the layer step's prediction aggregates (default 1; Sec. 4.5
+ * step 2).  Takes effect from the next moe_decode_layer; *h_best stays the most similar. */
+int moei_cache_set_match_count(moei_cache* c, int32_t m);
+/* The matched traces of the last layer step, most similar first, after both streams have
+ * drained: h_top[cap] / h_top_sim[cap] (either may be NULL), *h_m = how many. */
+int moei_cache_last_matches(moei_cache* c, int32_t* h_top, float* h_top_sim, int32_t cap,
+                            int32_t* h_m, void* stream);
 /* Makes `stream` wait for the match/priority work that the last moe_decode_layer put on
  * the cache's side stream (the next moe_decode_layer does this by itself).  Call it
  * before ending a stream capture that contains asynchronous layer steps, so that the

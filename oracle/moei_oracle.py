@@ -151,10 +151,11 @@ def eamc_match_topm(traces, q, m: int):
     qv = np.asarray(q).reshape(-1).astype(np.int64)
     Tv = T.reshape(N, -1).astype(np.int64)
     nq = int((qv * qv).sum())
+    dots = Tv @ qv
+    nts = (Tv * Tv).sum(axis=1)
     keyed = []
     for t in range(N):
-        d = sum(int(a) * int(b) for a, b in zip(Tv[t], qv))
-        n = sum(int(a) * int(a) for a in Tv[t])
+        d, n = int(dots[t]), int(nts[t])
         key = Fraction(d * d, n) if (n > 0 and nq > 0) else Fraction(0)
         sim = d / (math.sqrt(nq) * math.sqrt(n)) if (n > 0 and nq > 0) else 0.0
         keyed.append((key, t, sim))

@@ -15,8 +15,8 @@ import torch
 
 __all__ = [
     "MoeiError", "ModelDesc", "lib", "lib_path", "Eamc", "Cache",
-    "moe_route_topk", "eam_update", "eamc_match", "expert_priority", "expert_ffn_gemv", "moe_decode_layer",
-    "expert_ffn_grouped", "WDTYPE_FP32", "WDTYPE_BF16", "EXPORTS", "expert_pack", "profile_enable", "profile_disable", "profile_read",
+    "moe_route_topk", "eam_update", "eamc_match", "eamc_match_topm", "expert_priority", "expert_ffn_gemv",
+    "moe_decode_layer", "expert_ffn_grouped", "WDTYPE_FP32", "WDTYPE_BF16", "EXPORTS", "expert_pack", "profile_enable", "profile_disable", "profile_read",
 ]
 
 WDTYPE_FP32, WDTYPE_BF16 = 0, 1
@@ -25,10 +25,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 EXPORTS = [
     "moei_last_error", "moei_version",
     "moei_eamc_create", "moei_eamc_load", "moei_eamc_insert", "moei_eamc_export", "moei_eamc_size", "moei_eamc_destroy",
-    "moe_route_topk", "eam_update", "eamc_match", "expert_priority",
+    "moe_route_topk", "eam_update", "eamc_match", "eamc_match_topm", "expert_priority",
     "moei_cache_create", "moei_cache_destroy", "moei_expert_pack", "moei_cache_reset", "moei_cache_slot_ptr", "moei_cache_slot_table",
     "moei_cache_get_slots", "moei_cache_retrieve", "expert_ffn_gemv", "expert_ffn_grouped", "moei_cache_error_flags",
     "moe_decode_layer", "moei_cache_last_step", "moei_cache_join", "moei_cache_sync",
+    "moei_cache_set_match_count", "moei_cache_last_matches",
     "moei_profile_enable", "moei_profile_disable", "moei_profile_kernels", "moei_profile_kernel_name",
     "moei_profile_read",
 ]
@@ -225,6 +226,18 @@ class Cache:
         return dict(w=w, sim=sim.value, P=P.reshape(self.desc.L, self.desc.E), V=V.reshape(self.desc.L, self.desc.E),
                     pf_order=pf[:n_pf.value].copy(), ev_order=ev[:n_ev.value].copy())
 
+    def set_match_count(self, m: int) -> None:
+        """Traces aggregated by the layer step's prediction (Sec. 4.5 step 2); default 1."""
+        _check(lib().moei_cache_set_match_count(self.h, int(m)))
+
+    def last_matches(self, stream=None):
+        """(trace indices, similarities) matched by the last layer step, most similar first."""
+        top = np.empty(16, dtype=np.int32)
+        sim = np.empty(16, dtype=np.float32)
+        m = C.c_int32(0)
+        _check(lib().moei_cache_last_matches(self.h, _p(top), _p(sim), 16, C.byref(m), _stream(stream)))
+        return top[:m.value].copy(), sim[:m.value].copy()
+
     def close(self) -> None:
         if self.h:
             lib().moei_cache_destroy(self.h)
@@ -292,6 +305,21 @@ def eamc_match(eamc: Eamc, eam: torch.Tensor, layer_hi: int | None = None, want_
     return best, sim, sims
 
 
+def eamc_match_topm(eamc: Eamc, eam: torch.Tensor, m: int, layer_hi: int | None = None, want_sims: bool = False,
+                    stream=None):
+    """eam [L][E] int32 (device) -> (top [m] int32, top_sim [m] fp32, sims [N] fp32 or None): the m most
+    similar traces, most similar first; entries beyond the stored traces are -1."""
+    _dev(eam, torch.int32)
+    assert tuple(eam.shape) == (eamc.desc.L, eamc.desc.E)
+    n = max(int(m), 1)
+    top = torch.empty(n, dtype=torch.int32, device=eam.device)
+    sim = torch.empty(n, dtype=torch.float32, device=eam.device)
+    sims = torch.empty(eamc.size, dtype=torch.float32, device=eam.device) if want_sims else None
+    lh = eamc.desc.L - 1 if layer_hi is None else layer_hi
+    _check(lib().eamc_match_topm(eamc.h, _p(eam), lh, int(m), _p(top), _p(sim), _p(sims), _stream(stream)))
+    return top, sim, sims
+
+
 def expert_priority(eamc: Eamc, best: torch.Tensor, cur_layer: int, slot_of, eps: float,
                     cur_idx: torch.Tensor | None = None, stream=None):
     """-> (P [L][E] fp32, V [L][E] fp32, pf_order, n_pf, ev_order, n_ev), all device tensors.
@@ -308,7 +336,7 @@ def expert_priority(eamc: Eamc, best: torch.Tensor, cur_layer: int, slot_of, eps
     k = 0
     if cur_idx is not None:
         _dev(cur_idx, torch.int32)
-        k = cur_idx.shape[-1]
+        k = cur_idx.numel()
     _check(lib().expert_priority(eamc.h, _p(best), best.shape[0], cur_layer, _p(slot_of), C.c_float(eps),
                                  _p(cur_idx), k, _p(P), _p(V), _p(pf), _p(n_pf), _p(ev), _p(n_ev), _stream(stream)))
     return P, V, pf, n_pf, ev, n_ev

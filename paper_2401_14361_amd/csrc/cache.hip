@@ -95,7 +95,8 @@ struct moei_cache {
     float* d_w = nullptr;
     int32_t* d_slot_ids = nullptr;
     float* d_gate = nullptr;
-    int32_t* d_best = nullptr;
+    int32_t* d_best = nullptr;  // [kMaxMatchBatch] matched traces of the last step, most similar first
+    int match_m = 1;            // traces aggregated by the layer step's prediction
     float* d_best_sim = nullptr;
     float *d_P = nullptr, *d_V = nullptr;
     int32_t *d_pf_order = nullptr, *d_ev_order = nullptr, *d_n_pf = nullptr, *d_n_ev = nullptr;
@@ -175,8 +176,8 @@ int cache_alloc(moei_cache* c) {
     MOEI_DMALLOC(c->d_w, (size_t)kMaxAct * 4);
     MOEI_DMALLOC(c->d_slot_ids, (size_t)kMaxAct * 4);
     MOEI_DMALLOC(c->d_gate, (size_t)kMaxAct * 4);
-    MOEI_DMALLOC(c->d_best, 4);
-    MOEI_DMALLOC(c->d_best_sim, 4);
+    MOEI_DMALLOC(c->d_best, kMaxMatchBatch * 4);
+    MOEI_DMALLOC(c->d_best_sim, kMaxMatchBatch * 4);
     MOEI_DMALLOC(c->d_P, LE * 4);
     MOEI_DMALLOC(c->d_V, LE * 4);
     MOEI_DMALLOC(c->d_pf_order, LE * 4);
@@ -188,7 +189,7 @@ int cache_alloc(moei_cache* c) {
     MOEI_HIP(hipMemset(c->d_ticket, 0, 4));
     MOEI_HIP(hipMemset(c->d_n_pf, 0, 4));
     MOEI_HIP(hipMemset(c->d_n_ev, 0, 4));
-    MOEI_HIP(hipMemset(c->d_best, 0xff, 4));
+    MOEI_HIP(hipMemset(c->d_best, 0xff, kMaxMatchBatch * 4));
     int rc = ffn_scratch_alloc(d, na, &c->ffn);
     if (rc) return rc;
     MOEI_HIP(hipHostMalloc((void**)&c->pin, sizeof(Pinned), hipHostMallocDefault));
@@ -483,9 +484,12 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
     MOEI_HIP(hipStreamWaitEvent(side, c->ev_routed, 0));
     // match and scoring in one launch sequence (the workgroup that finishes the match scores
     // the matched trace), then the two orders
-    ScoreArgs sc = make_score_args(eamc, c->d_best, 1, layer, c->d_slot_of, d.eps, c->d_idx, k, c->d_P, c->d_V,
-                                   c->d_n_pf, c->d_n_ev);
-    rc = launch_match(eamc, d_snap, 1, d.L - 1, c->d_best, c->d_best_sim, nullptr, &sc, side);
+    ScoreArgs sc = make_score_args(eamc, c->d_best, c->match_m, layer, c->d_slot_of, d.eps, c->d_idx, k, c->d_P,
+                                   c->d_V, c->d_n_pf, c->d_n_ev);
+    if (c->match_m == 1)
+        rc = launch_match(eamc, d_snap, 1, d.L - 1, c->d_best, c->d_best_sim, nullptr, &sc, side);
+    else
+        rc = launch_match_topm(eamc, d_snap, d.L - 1, c->match_m, c->d_best, c->d_best_sim, nullptr, &sc, side);
     if (rc) return rc;
     rc = launch_priority_rank(eamc, c->d_n_pf, c->d_n_ev, c->d_pf_order, c->d_ev_order, side);
     if (rc) return rc;
@@ -531,6 +535,25 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
     }
     return launch_expert_ffn(d, c->d_pool, c->slot_elems, c->n_total, c->ffn, c->d_slot_ids, c->d_gate,
                              k + d.n_shared, d_x, d_y, c->d_flags, s);
+}
+
+extern "C" int moei_cache_set_match_count(moei_cache* c, int32_t m) {
+    MOEI_REQUIRE(c, "moei_cache_set_match_count: null pointer");
+    MOEI_REQUIRE(m >= 1 && m <= kMaxMatchBatch, "moei_cache_set_match_count: m = %d outside [1, %d]", m, kMaxMatchBatch);
+    c->match_m = m;
+    return MOEI_OK;
+}
+
+extern "C" int moei_cache_last_matches(moei_cache* c, int32_t* h_top, float* h_top_sim, int32_t cap, int32_t* h_m,
+                                       void* stream) {
+    MOEI_REQUIRE(c && h_m, "moei_cache_last_matches: null pointer");
+    MOEI_REQUIRE(cap >= c->match_m, "moei_cache_last_matches: room for %d entries, %d needed", cap, c->match_m);
+    MOEI_HIP(hipStreamSynchronize(as_stream(stream)));
+    MOEI_HIP(hipStreamSynchronize(c->side_stream));
+    if (h_top) MOEI_HIP(hipMemcpy(h_top, c->d_best, (size_t)c->match_m * 4, hipMemcpyDeviceToHost));
+    if (h_top_sim) MOEI_HIP(hipMemcpy(h_top_sim, c->d_best_sim, (size_t)c->match_m * 4, hipMemcpyDeviceToHost));
+    *h_m = c->match_m;
+    return MOEI_OK;
 }
 
 extern "C" int moei_cache_join(moei_cache* c, void* stream) {

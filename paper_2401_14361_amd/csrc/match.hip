@@ -375,6 +375,127 @@ __global__ void __launch_bounds__(kPickThreads) eamc_pick_kernel(PickArgs a) {
     if (a.do_score) score_cells(a.sc, s_sn, s_best, true);
 }
 
+// ---- the m most similar traces of ONE query, most similar first (ties: lowest index)
+constexpr int kTopmPerThread = 4;  // candidates a thread of the finishing workgroup may hold
+
+struct TopmArgs {
+    const u64* part;   // [n_lsplit][n_cap]
+    const u64* norm2;  // [n_cap]
+    const int32_t* q;  // [L*E]
+    int n_lsplit, n_cap, N, LE, m;
+    u64* cand;          // [gridDim.x * m][2]
+    int32_t* cand_idx;  // [gridDim.x * m]
+    unsigned* ticket;   // one arrival counter, zero between launches
+    int32_t* top;       // [m], -1 beyond the stored traces
+    float* top_sim;     // [m] or null
+    float* sims;        // [N] or null
+    int do_score;       // the finishing workgroup also scores the aggregate of the m traces
+    ScoreArgs sc;
+};
+
+// grid (workgroups over traces): each workgroup extracts the m best of its 1024 traces by m
+// rounds of the exact pick; the last workgroup to arrive extracts the m best of all winners.
+__global__ void __launch_bounds__(kPickThreads) eamc_topm_kernel(TopmArgs a) {
+    __shared__ u64 s_dot[kPickWaves];
+    __shared__ u64 s_nt[kPickWaves];
+    __shared__ int s_idx[kPickWaves];
+    __shared__ u64 s_nq;
+    __shared__ unsigned s_ticket;
+    __shared__ int s_win;
+    __shared__ int s_sn[2];
+    __shared__ int s_best[kMaxMatchBatch];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wv = tid / kWave;
+    const bool single = gridDim.x == 1;
+
+    u64 nq = 0;
+    for (int i = tid; i < a.LE; i += kPickThreads) {
+        u64 v = (uint32_t)a.q[i];
+        nq += v * v;
+    }
+    nq = wave_sum_u64_dpp(nq);
+    if (lane == 0) s_dot[wv] = nq;
+    __syncthreads();
+    if (tid == 0) {
+        u64 t = 0;
+        for (int i = 0; i < kPickWaves; ++i) t += s_dot[i];
+        s_nq = t;
+    }
+    __syncthreads();
+    nq = s_nq;
+
+    Best me = make_best(0, 1, -1);
+    const int n = blockIdx.x * kPickChunk + tid;  // one trace per thread
+    if (n < a.N) {
+        const u64* pp = a.part + n;
+        u64 dot = 0;
+        for (int s = 0; s < a.n_lsplit; ++s) dot += pp[(size_t)s * a.n_cap];
+        const u64 nt = a.norm2[n];
+        if (a.sims) a.sims[n] = (float)cosine(dot, nq, nt);
+        me = make_best(dot, nt, n);
+    }
+    for (int r = 0; r < a.m; ++r) {
+        const Best w = block_pick(me, s_dot, s_nt, s_idx);
+        if (tid == 0) {
+            s_win = w.idx;
+            if (single) {
+                a.top[r] = w.idx;
+                if (a.top_sim) a.top_sim[r] = w.idx >= 0 ? (float)cosine(w.dot, nq, w.nt) : 0.f;
+                s_best[r] = w.idx;
+            } else {
+                const size_t ci = (size_t)blockIdx.x * a.m + r;
+                a.cand[ci * 2] = w.dot;
+                a.cand[ci * 2 + 1] = w.nt;
+                a.cand_idx[ci] = w.idx;
+            }
+        }
+        __syncthreads();
+        if (s_win >= 0 && me.idx == s_win) me = make_best(0, 1, -1);  // taken: out of the next rounds
+    }
+    if (!single) {
+        if (tid == 0) {
+            __threadfence();
+            s_ticket = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        if (s_ticket != gridDim.x - 1) return;
+        __threadfence();
+        const int total = (int)gridDim.x * a.m;  // the host keeps this within kTopmPerThread per thread
+        Best mine[kTopmPerThread];
+#pragma unroll
+        for (int u = 0; u < kTopmPerThread; ++u) {
+            const int i = tid + u * kPickThreads;
+            mine[u] = make_best(0, 1, -1);
+            if (i < total) {
+                const int idx = __hip_atomic_load(&a.cand_idx[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (idx >= 0) {
+                    const u64 d = __hip_atomic_load(&a.cand[(size_t)i * 2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const u64 t = __hip_atomic_load(&a.cand[(size_t)i * 2 + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    mine[u] = make_best(d, t, idx);
+                }
+            }
+        }
+        for (int r = 0; r < a.m; ++r) {
+            Best loc = mine[0];
+#pragma unroll
+            for (int u = 1; u < kTopmPerThread; ++u) loc = pick(loc, mine[u]);
+            const Best w = block_pick(loc, s_dot, s_nt, s_idx);
+            if (tid == 0) {
+                s_win = w.idx;
+                a.top[r] = w.idx;
+                if (a.top_sim) a.top_sim[r] = w.idx >= 0 ? (float)cosine(w.dot, nq, w.nt) : 0.f;
+                s_best[r] = w.idx;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < kTopmPerThread; ++u)
+                if (s_win >= 0 && mine[u].idx == s_win) mine[u] = make_best(0, 1, -1);
+        }
+        if (tid == 0) *a.ticket = 0;  // ready for the next launch on this stream
+    }
+    if (a.do_score) score_cells(a.sc, s_sn, s_best, true);
+}
+
 struct Plan {
     int VEC, J, TN, rowV, n_tiles, n_lsplit, lper, NB;
     size_t smem;
@@ -609,29 +730,53 @@ extern "C" int moei_eamc_export(const moei_eamc* c, int32_t* h_traces, int32_t m
 
 namespace moei {
 
+namespace {
+// The partial dot products of B queries against every stored trace (layers 0..layer_hi).
+int launch_dots(const moei_eamc* c, const int32_t* d_eam, int B, int layer_hi, int* n_lsplit, hipStream_t s) {
+    const int L = c->d.L, E = c->d.E;
+    *n_lsplit = 0;
+    if (c->N == 0) return MOEI_OK;
+    Plan p = make_plan(c, layer_hi + 1, B);
+    *n_lsplit = p.n_lsplit;
+    if (p.n_lsplit > c->lsplit_max || p.smem > 64 * 1024)
+        MOEI_FAIL(MOEI_ECAPACITY, "eamc_match: L*E = %d is too large for the match kernel's LDS staging", L * E);
+    DotArgs a{c->d_traces, d_eam, c->d_part, c->n_cap, c->N, L, E, B, layer_hi + 1, p.lper, p.n_lsplit, p.TN, p.rowV};
+    dim3 grid(p.n_tiles, p.n_lsplit, (B + p.NB - 1) / p.NB);
+    if (c->cell_bytes == 4)
+        return p.VEC == 4 ? launch_dot_j<int32_t, 4>(p, a, grid, s) : launch_dot_j<int32_t, 1>(p, a, grid, s);
+    return p.VEC == 8 ? launch_dot_j<uint16_t, 8>(p, a, grid, s) : launch_dot_j<uint16_t, 1>(p, a, grid, s);
+}
+}  // namespace
+
 int launch_match(const moei_eamc* c, const int32_t* d_eam, int B, int layer_hi, int32_t* d_best, float* d_best_sim,
                  float* d_sims, const ScoreArgs* score, hipStream_t s) {
     const int L = c->d.L, E = c->d.E;
     if (score && B != 1) MOEI_FAIL(MOEI_EINVAL, "match with scoring needs B = 1");
     int n_lsplit = 0;
-    if (c->N > 0) {
-        Plan p = make_plan(c, layer_hi + 1, B);
-        n_lsplit = p.n_lsplit;
-        if (p.n_lsplit > c->lsplit_max || p.smem > 64 * 1024)
-            MOEI_FAIL(MOEI_ECAPACITY, "eamc_match: L*E = %d is too large for the match kernel's LDS staging", L * E);
-        DotArgs a{c->d_traces, d_eam, c->d_part, c->n_cap, c->N, L, E, B, layer_hi + 1, p.lper, p.n_lsplit, p.TN, p.rowV};
-        dim3 grid(p.n_tiles, p.n_lsplit, (B + p.NB - 1) / p.NB);
-        int rc;
-        if (c->cell_bytes == 4)
-            rc = p.VEC == 4 ? launch_dot_j<int32_t, 4>(p, a, grid, s) : launch_dot_j<int32_t, 1>(p, a, grid, s);
-        else
-            rc = p.VEC == 8 ? launch_dot_j<uint16_t, 8>(p, a, grid, s) : launch_dot_j<uint16_t, 1>(p, a, grid, s);
-        if (rc) return rc;
-    }
+    int rc = launch_dots(c, d_eam, B, layer_hi, &n_lsplit, s);
+    if (rc) return rc;
     const int n_blk = c->N > 0 ? (c->N + kPickChunk - 1) / kPickChunk : 1;
     PickArgs pa{c->d_part, c->d_norm2, d_eam, n_lsplit, c->n_cap, c->N, L * E, c->d_cand, c->d_cand_idx,
                 c->d_ticket, d_best, d_best_sim, d_sims, score != nullptr, score ? *score : ScoreArgs{}};
     launch(K_MATCH_ARGMAX, eamc_pick_kernel, dim3(n_blk, B), dim3(kPickThreads), 0, s, pa);
+    MOEI_LAUNCH_CHECK();
+    return MOEI_OK;
+}
+
+int launch_match_topm(const moei_eamc* c, const int32_t* d_eam, int layer_hi, int m, int32_t* d_top, float* d_top_sim,
+                      float* d_sims, const ScoreArgs* score, hipStream_t s) {
+    const int L = c->d.L, E = c->d.E;
+    if (m < 1 || m > kMaxMatchBatch) MOEI_FAIL(MOEI_EINVAL, "eamc_match_topm: m = %d outside [1, %d]", m, kMaxMatchBatch);
+    const int n_blk = c->N > 0 ? (c->N + kPickChunk - 1) / kPickChunk : 1;
+    if ((long)n_blk * m > (long)kTopmPerThread * kPickThreads)
+        MOEI_FAIL(MOEI_ECAPACITY, "eamc_match_topm: %d traces x m = %d exceed the finishing workgroup's %d candidates",
+                  c->N, m, kTopmPerThread * kPickThreads);
+    int n_lsplit = 0;
+    int rc = launch_dots(c, d_eam, 1, layer_hi, &n_lsplit, s);
+    if (rc) return rc;
+    TopmArgs ta{c->d_part, c->d_norm2, d_eam, n_lsplit, c->n_cap, c->N, L * E, m, c->d_cand, c->d_cand_idx,
+                c->d_ticket, d_top, d_top_sim, d_sims, score != nullptr, score ? *score : ScoreArgs{}};
+    launch(K_MATCH_ARGMAX, eamc_topm_kernel, dim3(n_blk), dim3(kPickThreads), 0, s, ta);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
 }
@@ -645,4 +790,11 @@ extern "C" int eamc_match(const moei_eamc* c, const int32_t* d_eam, int32_t B, i
     MOEI_REQUIRE(layer_hi >= 0 && layer_hi < c->d.L, "eamc_match: layer_hi = %d outside [0, %d)", layer_hi, c->d.L);
     if (B == 0) return MOEI_OK;
     return launch_match(c, d_eam, B, layer_hi, d_best, d_best_sim, d_sims, nullptr, as_stream(stream));
+}
+
+extern "C" int eamc_match_topm(const moei_eamc* c, const int32_t* d_eam, int32_t layer_hi, int32_t m, int32_t* d_top,
+                               float* d_top_sim, float* d_sims, void* stream) {
+    MOEI_REQUIRE(c && d_eam && d_top, "eamc_match_topm: null pointer");
+    MOEI_REQUIRE(layer_hi >= 0 && layer_hi < c->d.L, "eamc_match_topm: layer_hi = %d outside [0, %d)", layer_hi, c->d.L);
+    return launch_match_topm(c, d_eam, layer_hi, m, d_top, d_top_sim, d_sims, nullptr, as_stream(stream));
 }

@@ -77,10 +77,10 @@ __global__ void __launch_bounds__(kRankThreads)
 namespace moei {
 
 ScoreArgs make_score_args(const moei_eamc* c, const int32_t* d_best, int B, int cur_layer, const int32_t* d_slot_of,
-                          float eps, const int32_t* d_cur_idx, int k, float* d_prefetch, float* d_evict,
+                          float eps, const int32_t* d_cur_idx, int n_cur, float* d_prefetch, float* d_evict,
                           int32_t* d_n_pf, int32_t* d_n_ev) {
     return ScoreArgs{c->d_traces, c->cell_bytes, c->n_cap, c->N, c->d.L, c->d.E, d_best, B, cur_layer, d_slot_of,
-                     (double)eps, d_cur_idx, d_cur_idx ? B * k : 0, d_prefetch, d_evict, c->d_keys, d_n_pf, d_n_ev};
+                     (double)eps, d_cur_idx, d_cur_idx ? n_cur : 0, d_prefetch, d_evict, c->d_keys, d_n_pf, d_n_ev};
 }
 
 // The two orders from the keys that score_cells left in c->d_keys.
@@ -110,7 +110,7 @@ int launch_priority_rank(const moei_eamc* c, const int32_t* d_n_pf, const int32_
 using namespace moei;
 
 extern "C" int expert_priority(const moei_eamc* c, const int32_t* d_best, int32_t B, int32_t cur_layer,
-                               const int32_t* d_slot_of, float eps, const int32_t* d_cur_idx, int32_t k,
+                               const int32_t* d_slot_of, float eps, const int32_t* d_cur_idx, int32_t n_cur,
                                float* d_prefetch, float* d_evict, int32_t* d_pf_order, int32_t* d_n_pf,
                                int32_t* d_ev_order, int32_t* d_n_ev, void* stream) {
     MOEI_REQUIRE(c && d_best && d_slot_of && d_prefetch && d_evict && d_pf_order && d_n_pf && d_ev_order && d_n_ev,
@@ -119,9 +119,10 @@ extern "C" int expert_priority(const moei_eamc* c, const int32_t* d_best, int32_
     MOEI_REQUIRE(cur_layer >= -1 && cur_layer < c->d.L, "expert_priority: cur_layer = %d outside [-1, %d)", cur_layer,
                  c->d.L);
     MOEI_REQUIRE(eps >= 0.f, "expert_priority: eps must not be negative");
-    MOEI_REQUIRE(!d_cur_idx || (k >= 1 && k <= c->d.E), "expert_priority: k = %d outside [1, E]", k);
+    MOEI_REQUIRE(!d_cur_idx || (n_cur >= 0 && n_cur <= kMaxMatchBatch * c->d.E),
+                 "expert_priority: n_cur = %d outside [0, %d]", n_cur, kMaxMatchBatch * c->d.E);
     hipStream_t s = as_stream(stream);
-    ScoreArgs a = make_score_args(c, d_best, B, cur_layer, d_slot_of, eps, d_cur_idx, k, d_prefetch, d_evict, d_n_pf,
+    ScoreArgs a = make_score_args(c, d_best, B, cur_layer, d_slot_of, eps, d_cur_idx, n_cur, d_prefetch, d_evict, d_n_pf,
                                   d_n_ev);
     launch(K_PRIO_SCORE, priority_score_kernel, dim3(1), dim3(kScoreThreads), 0, s, a);
     MOEI_LAUNCH_CHECK();

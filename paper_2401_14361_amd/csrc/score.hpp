@@ -19,7 +19,7 @@ struct ScoreArgs {
     int B, cur_layer;
     const int32_t* slot_of;  // [L*E]
     double eps;
-    const int32_t* cur_idx;  // [B*k] or null
+    const int32_t* cur_idx;  // [n_cur] experts of the current layer that are about to run, or null
     int n_cur;
     float* P;  // [L*E]
     float* V;  // [L*E]
@@ -133,7 +133,7 @@ __device__ __forceinline__ void score_cells(const ScoreArgs& a, int* s_n, int* s
 
 // priority.hip
 ScoreArgs make_score_args(const moei_eamc* c, const int32_t* d_best, int B, int cur_layer, const int32_t* d_slot_of,
-                          float eps, const int32_t* d_cur_idx, int k, float* d_prefetch, float* d_evict,
+                          float eps, const int32_t* d_cur_idx, int n_cur, float* d_prefetch, float* d_evict,
                           int32_t* d_n_pf, int32_t* d_n_ev);
 int launch_priority_rank(const moei_eamc* c, const int32_t* d_n_pf, const int32_t* d_n_ev, int32_t* d_pf_order,
                          int32_t* d_ev_order, hipStream_t s);
@@ -141,5 +141,8 @@ int launch_priority_rank(const moei_eamc* c, const int32_t* d_n_pf, const int32_
 // trace by the workgroup that finishes the match, in the same launch
 int launch_match(const moei_eamc* c, const int32_t* d_eam, int B, int layer_hi, int32_t* d_best, float* d_best_sim,
                  float* d_sims, const ScoreArgs* score, hipStream_t s);
+// the m most similar traces of one query; `score` (with B = m) scores their aggregate
+int launch_match_topm(const moei_eamc* c, const int32_t* d_eam, int layer_hi, int m, int32_t* d_top, float* d_top_sim,
+                      float* d_sims, const ScoreArgs* score, hipStream_t s);
 
 }  // namespace moei

@@ -68,7 +68,7 @@ def test_cache_retrieve_sequence_and_slot_contents(m):
     c2.close()
 
 
-def _replay(m, cfg, S, n_tokens, n_unique, cell_bytes, rid=0):
+def _replay(m, cfg, S, n_tokens, n_unique, cell_bytes, rid=0, match_m=1):
     L, E, k = cfg.L, cfg.E, cfg.k
     T, _, _ = mi.eamc_traces(cfg, threads=4)
     req = mi.make_request(cfg, rid, decode=n_tokens + 8)
@@ -82,6 +82,7 @@ def _replay(m, cfg, S, n_tokens, n_unique, cell_bytes, rid=0):
     eamc.load(T)
     cache = m.Cache(desc, S, pinned(pack_bank(m, cfg, bank)), pinned(pack_bank(m, cfg, shared)) if cfg.n_shared else None)
     cache.reset(min(S, L * E))
+    cache.set_match_count(match_m)
     d_eam = dev(req.prefill_eam.astype(np.int32))
     d_routers = [dev(w) for w in routers]
     d_bias = dev(req.bias)
@@ -103,12 +104,13 @@ def _replay(m, cfg, S, n_tokens, n_unique, cell_bytes, rid=0):
             idx, best, n_miss = m.moe_decode_layer(cache, eamc, d_eam, l, d_routers[l], d_bias[l], d_x[t, l], y)
             last = cache.last_step()
             ref = O.decode_layer(T, ref_eam, ref_cache, l, routers[l], req.bias[l], req.x[t, l], expert_of, shared_of,
-                                 k, bool(cfg.renorm), EPS)
+                                 k, bool(cfg.renorm), EPS, m=match_m)
             where = f"token {t} layer {l}"
             assert idx.tolist() == ref["idx"].tolist(), where
             np.testing.assert_allclose(last["w"], ref["w"], rtol=1e-4, err_msg=where)
             assert (d_eam.cpu().numpy() == ref_eam).all(), where
             assert best == ref["best"], where
+            assert cache.last_matches()[0].tolist() == ref["matched"], where
             np.testing.assert_allclose(last["sim"], ref["sim"], rtol=1e-5, err_msg=where)
             assert last["ev_order"].tolist() == ref["ev_order"], where
             assert last["pf_order"].tolist() == ref["pf_order"], where
@@ -144,6 +146,17 @@ def test_decode_request_reduced_mixtral_shape(m):
     cfg = mi.get_config("C3").scaled(L=5, H=512, I=1792, N=80, prompt=32)
     misses = _replay(m, cfg, 15, 10, cfg.L * cfg.E, 4)
     assert misses > 0
+
+
+def test_decode_request_with_aggregated_matches(m):
+    # PredictEAM over the 3 / 16 most similar traces (Sec. 4.5 step 2) inside the fused layer step
+    cfg = mi.get_config("C2").scaled(L=6, H=256, I=192, N=120, prompt=64)
+    assert _replay(m, cfg, (cfg.L * cfg.E) // 4, 6, 48, 4, match_m=3) > 0
+    cfg = mi.get_config("C1")
+    assert _replay(m, cfg, cfg.S, 8, cfg.L * cfg.E, 2, rid=1, match_m=16) > 0
+    # more traces than one workgroup scans: the finishing workgroup merges the winners
+    cfg = mi.get_config("C1").scaled(N=2300)
+    _replay(m, cfg, cfg.S, 3, cfg.L * cfg.E, 4, rid=2, match_m=5)
 
 
 def test_async_layer_step_matches_sync_and_flags_a_miss(m):
