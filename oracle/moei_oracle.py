@@ -258,17 +258,33 @@ class ExpertCache:
     reading: the cache starts full of the experts with flat ids 0..S-1 in slots
     0..S-1 (``warm=True``) or empty.  ``retrieve`` serves one layer's picks in
     router order: a hit returns the slot; with a free slot the expert is fetched
-    into the lowest free slot; otherwise the victim is the first entry of
-    ``ev_order`` (lowest eviction priority first) that is still resident and is
-    not one of this layer's picks, and the expert is fetched into its slot.  If
-    ``ev_order`` runs out, the lowest slot whose owner is not a current pick is
-    taken.
+    into the lowest free slot; otherwise a victim chosen by the policy gives up its
+    slot.  The victim is never one of this layer's picks.
+
+    policy "eam" (the paper's, Alg. 1): the first entry of ``ev_order`` (lowest
+    eviction priority first) that is still resident; if ``ev_order`` runs out, the
+    lowest slot whose owner is not a current pick.
+    The two policies the paper compares against (Sec. 4.7, the example with three
+    caches; Sec. 6), as plain eviction rules, for the hit-rate comparison only:
+    policy "lru": the slot used least recently; every pick, hit or miss, stamps
+      its slot with a running clock; slots never used (warm start) carry stamp 0;
+      ties to the lowest slot.
+    policy "count": the resident expert activated least often so far (a
+      model-level count over everything this cache has served); ties to the lowest
+      flat id.
     """
 
-    def __init__(self, L: int, E: int, S: int, warm: bool = True):
-        self.L, self.E, self.S = L, E, S
+    POLICIES = ("eam", "lru", "count")
+
+    def __init__(self, L: int, E: int, S: int, warm: bool = True, policy: str = "eam"):
+        if policy not in self.POLICIES:
+            raise ValueError("unknown policy")
+        self.L, self.E, self.S, self.policy = L, E, S, policy
         self.slot_of = np.full(L * E, -1, dtype=np.int64)
         self.owner = np.full(S, -1, dtype=np.int64)
+        self.stamp = np.zeros(S, dtype=np.int64)
+        self.clock = 0
+        self.count = np.zeros(L * E, dtype=np.int64)
         if warm:
             for s in range(min(S, L * E)):
                 self.slot_of[s] = s
@@ -277,7 +293,35 @@ class ExpertCache:
     def resident(self) -> np.ndarray:
         return (self.slot_of >= 0).reshape(self.L, self.E)
 
-    def retrieve(self, layer: int, picks, ev_order):
+    def _victim(self, needed, ev, pos):
+        """(victim flat id, new position in ev) for a full cache."""
+        if self.policy == "lru":
+            best = None
+            for s in range(self.S):
+                if int(self.owner[s]) in needed:
+                    continue
+                if best is None or self.stamp[s] < self.stamp[best]:
+                    best = s
+            return int(self.owner[best]), pos
+        if self.policy == "count":
+            best = None
+            for s in range(self.S):
+                f = int(self.owner[s])
+                if f in needed:
+                    continue
+                if best is None or (self.count[f], f) < (self.count[best], best):
+                    best = f
+            return best, pos
+        while pos < len(ev):
+            c = int(ev[pos]); pos += 1
+            if self.slot_of[c] >= 0 and c not in needed:
+                return c, pos
+        for s2 in range(self.S):
+            if int(self.owner[s2]) not in needed:
+                return int(self.owner[s2]), pos
+        raise AssertionError("no victim")
+
+    def retrieve(self, layer: int, picks, ev_order=()):
         """Returns a list of (flat id, hit, victim flat id or -1, slot), one per pick."""
         picks = [int(p) for p in picks]
         needed = set(layer * self.E + p for p in picks)
@@ -288,43 +332,81 @@ class ExpertCache:
         out = []
         for p in picks:
             fid = layer * self.E + p
+            self.count[fid] += 1
             s = int(self.slot_of[fid])
-            if s >= 0:
-                out.append((fid, True, -1, s))
+            hit = s >= 0
+            victim = -1
+            if not hit:
+                free = np.nonzero(self.owner < 0)[0]
+                if free.size:
+                    s = int(free[0])
+                else:
+                    victim, pos = self._victim(needed, ev, pos)
+                    s = int(self.slot_of[victim])
+                    self.slot_of[victim] = -1
+                self.slot_of[fid] = s
+                self.owner[s] = fid
+            self.clock += 1
+            self.stamp[s] = self.clock
+            out.append((fid, hit, victim, s))
+        return out
+
+    def prefetch(self, pf_order, ev_order, V, depth: int, protect=()):
+        """Prefetching into the cache (Sec. 4.6, "enhancing the cache with prefetching").
+
+        reading (the paper leaves the mechanism out): after a layer's retrieval the
+        first ``depth`` entries of ``pf_order`` (most likely future experts first)
+        are considered in turn.  A candidate that is not resident takes the lowest
+        free slot; with a full cache it may displace the cheapest victim -- the
+        first entry of ``ev_order`` that is still resident and not in ``protect``
+        -- but only if that improves the cache by Alg. 1's own measure: the
+        candidate's eviction score must exceed the victim's, compared in fp32 (the
+        precision the scores are handed over in).  A candidate that is not
+        admitted is skipped and the same victim is offered to the next one.
+        A prefetched expert counts as a use for the "lru" stamps, not for the
+        activation counts.  Returns a list of (flat id, victim or -1, slot).
+        """
+        Vf = np.asarray(V, dtype=np.float64).reshape(-1).astype(np.float32)
+        ev = [int(e) for e in ev_order]
+        prot = set(int(p) for p in protect)
+        pos = 0
+        out = []
+        for c in [int(c) for c in list(pf_order)[:max(depth, 0)]]:
+            if self.slot_of[c] >= 0:
                 continue
             free = np.nonzero(self.owner < 0)[0]
             victim = -1
             if free.size:
                 s = int(free[0])
             else:
-                while pos < len(ev):
-                    c = int(ev[pos]); pos += 1
-                    if self.slot_of[c] >= 0 and c not in needed:
-                        victim = c
-                        break
-                if victim < 0:
-                    for s2 in range(self.S):
-                        if int(self.owner[s2]) not in needed:
-                            victim = int(self.owner[s2])
-                            break
+                while pos < len(ev) and (self.slot_of[ev[pos]] < 0 or ev[pos] in prot):
+                    pos += 1
+                if pos >= len(ev):
+                    break
+                if not (Vf[c] > Vf[ev[pos]]):
+                    continue
+                victim = ev[pos]; pos += 1
                 s = int(self.slot_of[victim])
                 self.slot_of[victim] = -1
-            self.slot_of[fid] = s
-            self.owner[s] = fid
-            out.append((fid, False, victim, s))
+            self.slot_of[c] = s
+            self.owner[s] = c
+            self.clock += 1
+            self.stamp[s] = self.clock
+            out.append((c, victim, s))
         return out
 
 
 # ----------------------------------------------------------------- whole layer step
 def decode_layer(traces, eam, cache: ExpertCache, layer: int, W_r, bias, x, expert_of, shared_of,
-                 k: int, renorm: bool, eps: float, m: int = 1):
+                 k: int, renorm: bool, eps: float, m: int = 1, prefetch_depth: int = 0):
     """One MoE layer of one decode iteration, in the order of Sec. 4.3-4.7:
     routing decision, EAM update, EAMC match, priorities, Alg. 1 retrieval, expert FFNs.
 
     ``expert_of(flat_id)`` / ``shared_of(layer)`` hand back weight triples.  The
     eviction order used for this layer's misses is the one computed from the EAM
     that already holds this layer's routing (Alg. 1 calls PredictEAM with the
-    current EAM).  With m > 1 the m most similar traces are aggregated.
+    current EAM).  With m > 1 the m most similar traces are aggregated; with
+    prefetch_depth > 0 the layer's retrieval is followed by ``ExpertCache.prefetch``.
     Composite: pinned only through its parts.
     """
     L, E = eam.shape
@@ -338,6 +420,7 @@ def decode_layer(traces, eam, cache: ExpertCache, layer: int, W_r, bias, x, expe
     excl = [layer * E + int(j) for j in idx]
     P, V, pf, ev = expert_priority(tstar, layer, cache.resident(), eps, excl)
     events = cache.retrieve(layer, idx, ev)
+    prefetched = cache.prefetch(pf, ev, V, prefetch_depth, excl) if prefetch_depth > 0 else []
     experts = [expert_of(layer * E + int(j)) for j in idx]
     gates = [float(v) for v in w]
     for sh in shared_of(layer):
@@ -345,4 +428,4 @@ def decode_layer(traces, eam, cache: ExpertCache, layer: int, W_r, bias, x, expe
         gates.append(1.0)
     y = expert_ffn(x, experts, gates)
     return dict(logits=z, idx=idx, w=w, best=best, sim=sim, matched=list(matched), P=P, V=V, pf_order=pf,
-                ev_order=ev, events=events, y=y)
+                ev_order=ev, events=events, prefetched=prefetched, y=y)

@@ -446,6 +446,121 @@ def test_cache_retrieval_against_independent_simulation_and_invariants():
         O.ExpertCache(2, 4, 1).retrieve(0, [0, 1], [])
 
 
+def test_lru_policy_equals_textbook_ordered_dict_lru():
+    # one pick per call: no pick protection comes into play and the rule is the textbook one
+    from collections import OrderedDict
+    rng = np.random.default_rng(21)
+    L, E, S = 3, 6, 5
+    c = O.ExpertCache(L, E, S, warm=False, policy="lru")
+    book = OrderedDict()
+    for step in range(600):
+        layer = step % L
+        p = int(rng.integers(0, E)) if rng.random() < 0.7 else int(rng.integers(0, 2))
+        fid = layer * E + p
+        hit_book = fid in book
+        if hit_book:
+            book.move_to_end(fid)
+        else:
+            if len(book) == S:
+                book.popitem(last=False)
+            book[fid] = True
+        (f, hit, victim, slot), = c.retrieve(layer, [p])
+        assert hit == hit_book
+        assert set(np.nonzero(c.slot_of >= 0)[0].tolist()) == set(book.keys())
+    # several picks per call: a resident later pick is never the victim of an earlier one
+    c = O.ExpertCache(2, 4, 2, warm=False, policy="lru")
+    c.retrieve(0, [0, 1])                      # slots: 0 -> e0, 1 -> e1; e0 is the older
+    ev = c.retrieve(0, [2, 0])                 # e2 misses; the LRU slot holds e0, a current pick -> e1 goes
+    assert ev[0][2] == 1 and ev[1][1] is True
+    # warm start: all stamps equal, ties to the lowest slot
+    c = O.ExpertCache(2, 4, 3, warm=True, policy="lru")
+    assert c.retrieve(1, [3])[0][2:] == (0, 0)
+
+
+def test_count_policy_hand_worked_and_brute_force():
+    c = O.ExpertCache(1, 6, 3, warm=False, policy="count")
+    for p in (0, 0, 0, 1, 2, 2):
+        c.retrieve(0, [p])
+    assert c.retrieve(0, [3])[0][2] == 1        # counts 3, 1, 2 -> expert 1 leaves
+    assert c.retrieve(0, [4])[0][2] == 3        # counts 3, 2, 1(new) -> the newcomer leaves
+    c.retrieve(0, [4])                          # now e4 has count 2 = e2's: tie -> lowest id
+    assert c.retrieve(0, [5])[0][2] == 2
+    rng = np.random.default_rng(22)
+    L, E, S, k = 3, 5, 4, 2
+    c = O.ExpertCache(L, E, S, warm=True, policy="count")
+    counts = {}
+    res = set(range(S))
+    for step in range(300):
+        layer = step % L
+        picks = rng.choice(E, size=k, replace=False).tolist()
+        need = {layer * E + p for p in picks}
+        want = []
+        for p in picks:
+            f = layer * E + p
+            counts[f] = counts.get(f, 0) + 1
+            if f in res:
+                want.append(-1); continue
+            v = min((x for x in res if x not in need), key=lambda x: (counts.get(x, 0), x))
+            res.remove(v); res.add(f); want.append(v)
+        assert [e[2] for e in c.retrieve(layer, picks)] == want
+        assert set(np.nonzero(c.slot_of >= 0)[0].tolist()) == res
+    with pytest.raises(ValueError):
+        O.ExpertCache(1, 2, 1, policy="fifo")
+
+
+def test_prefetch_hand_worked_admission_rule():
+    # 3 layers x 2 experts, 3 slots holding experts 0, 1 and 4
+    c = O.ExpertCache(3, 2, 3, warm=False)
+    for layer, p in ((0, 0), (0, 1), (2, 0)):
+        c.retrieve(layer, [p], [])
+    V = np.array([0.9, 0.1, 0.5, 0.3, 0.2, 0.6])
+    # candidates 5 then 2 then 3; victims cheapest first: 1 (0.1), 4 (0.2), 0 (0.9)
+    got = c.prefetch([5, 2, 3], [1, 4, 0], V, depth=3)
+    #  5 (0.6) > 1 (0.1): takes slot of 1.  2 (0.5) > 4 (0.2): takes slot of 4.  3 (0.3) < 0 (0.9): skipped
+    assert got == [(5, 1, 1), (2, 4, 2)]
+    assert sorted(np.nonzero(c.slot_of >= 0)[0].tolist()) == [0, 2, 5]
+    # depth limits the candidates considered; a resident candidate is passed over
+    c2 = O.ExpertCache(3, 2, 3, warm=True)                   # holds 0, 1, 2
+    assert c2.prefetch([2, 5, 4], [1, 0], V, depth=2) == [(5, 1, 1)]
+    # a protected victim and a victim that has left are passed over
+    c3 = O.ExpertCache(3, 2, 3, warm=True)
+    c3.retrieve(1, [1], [1])                                 # expert 3 replaces expert 1 in slot 1
+    assert c3.prefetch([5], [1, 0, 2], V, depth=1, protect=[0]) == [(5, 2, 2)]
+    # free slots are used first, lowest first, and need no admission
+    c4 = O.ExpertCache(3, 2, 3, warm=False)
+    assert c4.prefetch([1, 0], [], np.zeros(6), depth=5) == [(1, -1, 0), (0, -1, 1)]
+    # scores that differ only below fp32 resolution do not admit (compared as handed over, in fp32)
+    Vt = np.array([0.5, 0.5 + 1e-12, 0.0, 0.0, 0.0, 0.0])
+    c5 = O.ExpertCache(3, 2, 1, warm=True)                   # holds expert 0
+    assert c5.prefetch([1], [0], Vt, depth=1) == []
+    assert O.ExpertCache(3, 2, 1, warm=True).prefetch([1], [0], np.array([0.5, 0.5001, 0, 0, 0, 0]), 1) == [(1, 0, 0)]
+
+
+def test_prefetch_invariants_random():
+    rng = np.random.default_rng(23)
+    L, E, S, k = 4, 6, 7, 2
+    c = O.ExpertCache(L, E, S, warm=True)
+    for step in range(300):
+        layer = step % L
+        picks = rng.choice(E, size=k, replace=False).tolist()
+        need = [layer * E + p for p in picks]
+        V = rng.random(L * E)
+        res = [f for f in range(L * E) if c.slot_of[f] >= 0 and f not in need]
+        ev = sorted(res, key=lambda f: (V[f], f))
+        c.retrieve(layer, picks, ev)
+        pf = [f for f in rng.permutation(L * E).tolist() if f // E > layer and c.slot_of[f] < 0]
+        before = set(np.nonzero(c.slot_of >= 0)[0].tolist())
+        out = c.prefetch(pf, ev, V, depth=3, protect=need)
+        after = set(np.nonzero(c.slot_of >= 0)[0].tolist())
+        assert len(out) <= 3 and len(after) <= S and all(f in after for f in need)
+        for fid, victim, slot in out:
+            assert fid not in before and c.owner[slot] == fid and victim not in need
+            if victim >= 0:
+                assert np.float32(V[fid]) > np.float32(V[victim]) and victim not in after
+        for f in after:
+            assert c.owner[c.slot_of[f]] == f
+
+
 def test_cache_cold_start_fills_lowest_free_slots():
     c = O.ExpertCache(2, 4, 3, warm=False)
     ev = c.retrieve(0, [2, 0], [])
