@@ -214,6 +214,43 @@ int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d_eam, int32
                      const void* d_router_w, const float* d_router_bias,
                      const void* d_x, float* d_y,
                      int32_t* h_topk_idx, int32_t* h_best, int32_t* h_n_miss, void* stream);
+/* Eviction rule of moei_cache_retrieve / moe_decode_layer when the cache is full:
+ * MOEI_POLICY_EAM (default) is Alg. 1, driven by the eviction order; the other two are the
+ * rules the paper compares against (Sec. 4.7 example, Sec. 6), for hit-rate comparisons:
+ * MOEI_POLICY_LRU evicts the slot used least recently (every pick stamps its slot; never
+ * used = oldest; ties to the lowest slot), MOEI_POLICY_COUNT the resident expert activated
+ * least often since the last reset (ties to the lowest id).  A victim is never one of the
+ * current picks.  Under these two the eviction order is ignored. */
+#define MOEI_POLICY_EAM 0
+#define MOEI_POLICY_LRU 1
+#define MOEI_POLICY_COUNT 2
+int moei_cache_set_policy(moei_cache* c, int32_t policy);
+
+/* Prefetching into the cache (Sec. 4.6).  The first `depth` (<= 32) entries of
+ * h_pf_order[n_pf] are considered in turn; one that is not resident goes to the lowest
+ * free slot or, when the cache is full, displaces the first entry of h_ev_order[n_ev]
+ * that is still resident and not in h_protect[n_protect] - but only if its own eviction
+ * score h_V[fid] exceeds that victim's (fp32 compare; h_V[L*E] as written by
+ * expert_priority); otherwise it is skipped and the victim is offered to the next one.
+ * Copies run on the cache's prefetch stream after everything already queued on `stream`;
+ * they are NOT waited for here: moei_cache_retrieve and the synchronous moe_decode_layer
+ * make the reading stream wait when a prefetched expert is picked or replaced,
+ * moei_cache_join does so for all of them (needed before expert_ffn_gemv / asynchronous
+ * layer steps that may touch such a slot).  The slot tables name the new owners at once.
+ * Outputs (each may be NULL): h_fids / h_victims (-1 = free slot) / h_slots [depth],
+ * *h_n_issued.  All arrays are host memory.  MOEI_ESTATE without a host copy. */
+int moei_cache_prefetch(moei_cache* c, const int32_t* h_pf_order, int32_t n_pf,
+                        const int32_t* h_ev_order, int32_t n_ev, const float* h_V, int32_t depth,
+                        const int32_t* h_protect, int32_t n_protect,
+                        int32_t* h_fids, int32_t* h_victims, int32_t* h_slots, int32_t* h_n_issued,
+                        void* stream);
+/* Prefetch candidates the synchronous moe_decode_layer considers after each layer's
+ * retrieval (0 = off, the default; needs MOEI_POLICY_EAM): moei_cache_prefetch with the
+ * step's own orders and scores, protecting the layer's picks.  Asynchronous steps never
+ * prefetch. */
+int moei_cache_set_prefetch(moei_cache* c, int32_t depth);
+/* What the last synchronous layer step prefetched: h_fids[cap] / h_victims[cap], *h_n. */
+int moei_cache_last_prefetch(moei_cache* c, int32_t* h_fids, int32_t* h_victims, int32_t cap, int32_t* h_n);
 /* Number of most-similar traces the layer step's prediction aggregates (default 1; Sec. 4.5
  * step 2).  Takes effect from the next moe_decode_layer; *h_best stays the most similar. */
 int moei_cache_set_match_count(moei_cache* c, int32_t m);
@@ -222,7 +259,8 @@ int moei_cache_set_match_count(moei_cache* c, int32_t m);
 int moei_cache_last_matches(moei_cache* c, int32_t* h_top, float* h_top_sim, int32_t cap,
                             int32_t* h_m, void* stream);
 /* Makes `stream` wait for the match/priority work that the last moe_decode_layer put on
- * the cache's side stream (the next moe_decode_layer does this by itself).  Call it
+ * the cache's side stream (the next moe_decode_layer does this by itself) and for every
+ * prefetch copy that no stream has waited for yet.  Call it
  * before ending a stream capture that contains asynchronous layer steps, so that the
  * side stream has joined `stream` again. */
 int moei_cache_join(moei_cache* c, void* stream);

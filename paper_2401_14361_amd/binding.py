@@ -30,6 +30,7 @@ EXPORTS = [
     "moei_cache_get_slots", "moei_cache_retrieve", "expert_ffn_gemv", "expert_ffn_grouped", "moei_cache_error_flags",
     "moe_decode_layer", "moei_cache_last_step", "moei_cache_join", "moei_cache_sync",
     "moei_cache_set_match_count", "moei_cache_last_matches",
+    "moei_cache_set_policy", "moei_cache_prefetch", "moei_cache_set_prefetch", "moei_cache_last_prefetch",
     "moei_profile_enable", "moei_profile_disable", "moei_profile_kernels", "moei_profile_kernel_name",
     "moei_profile_read",
 ]
@@ -225,6 +226,38 @@ class Cache:
                                           C.byref(n_ev), _stream(stream)))
         return dict(w=w, sim=sim.value, P=P.reshape(self.desc.L, self.desc.E), V=V.reshape(self.desc.L, self.desc.E),
                     pf_order=pf[:n_pf.value].copy(), ev_order=ev[:n_ev.value].copy())
+
+    POLICIES = {"eam": 0, "lru": 1, "count": 2}
+
+    def set_policy(self, policy: str) -> None:
+        """Eviction rule: "eam" (Alg. 1, default), "lru" or "count" (the comparison rules)."""
+        _check(lib().moei_cache_set_policy(self.h, self.POLICIES[policy]))
+
+    def set_prefetch(self, depth: int) -> None:
+        """Prefetch candidates considered after each synchronous layer step (0 = off)."""
+        _check(lib().moei_cache_set_prefetch(self.h, int(depth)))
+
+    def prefetch(self, pf_order, ev_order, V, depth: int, protect=(), stream=None):
+        """Sec. 4.6 prefetch step from host-side orders and fp32 scores -> list of (fid, victim, slot)."""
+        pf = np.ascontiguousarray(np.asarray(pf_order, dtype=np.int32).reshape(-1))
+        ev = np.ascontiguousarray(np.asarray(ev_order, dtype=np.int32).reshape(-1))
+        Vf = np.ascontiguousarray(np.asarray(V, dtype=np.float32).reshape(-1))
+        assert Vf.size == self.desc.L * self.desc.E
+        pr = np.ascontiguousarray(np.asarray(list(protect), dtype=np.int32).reshape(-1))
+        n = max(int(depth), 1)
+        fids, vic, slots = (np.empty(n, dtype=np.int32) for _ in range(3))
+        issued = C.c_int32(0)
+        _check(lib().moei_cache_prefetch(self.h, _p(pf) if pf.size else None, pf.size, _p(ev) if ev.size else None,
+                                         ev.size, _p(Vf), int(depth), _p(pr) if pr.size else None, pr.size,
+                                         _p(fids), _p(vic), _p(slots), C.byref(issued), _stream(stream)))
+        m = issued.value
+        return [(int(fids[i]), int(vic[i]), int(slots[i])) for i in range(m)]
+
+    def last_prefetch(self):
+        fids, vic = np.empty(32, dtype=np.int32), np.empty(32, dtype=np.int32)
+        n = C.c_int32(0)
+        _check(lib().moei_cache_last_prefetch(self.h, _p(fids), _p(vic), 32, C.byref(n)))
+        return [(int(fids[i]), int(vic[i])) for i in range(n.value)]
 
     def set_match_count(self, m: int) -> None:
         """Traces aggregated by the layer step's prediction (Sec. 4.5 step 2); default 1."""

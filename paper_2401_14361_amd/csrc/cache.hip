@@ -17,6 +17,9 @@ thread_local char g_err[512] = "";
 
 constexpr int kMaxAct = 64;  // k + n_shared never exceeds one wavefront
 constexpr int kRing = 4;     // buffer sets handed from the routing to the side stream, used in turn
+constexpr int kMaxPrefetch = 32;  // prefetch candidates considered per layer step
+
+enum Policy { kPolicyEam = 0, kPolicyLru = 1, kPolicyCount = 2 };
 
 struct SlotUpdates {
     int n;
@@ -33,10 +36,12 @@ __global__ void apply_slot_updates_kernel(int32_t* __restrict__ slot_of, SlotUpd
 struct Pinned {
     int32_t idx[kMaxAct];
     float w[kMaxAct];
-    int32_t ev_head[kMaxAct];
+    int32_t ev_head[kMaxAct + kMaxPrefetch];
+    int32_t pf_head[kMaxPrefetch];
     int32_t best;
     float best_sim;
     int32_t n_ev;
+    int32_t n_pf;
     int32_t flags;
 };
 
@@ -101,6 +106,22 @@ struct moei_cache {
     float *d_P = nullptr, *d_V = nullptr;
     int32_t *d_pf_order = nullptr, *d_ev_order = nullptr, *d_n_pf = nullptr, *d_n_ev = nullptr;
     Pinned* pin = nullptr;
+    float* pin_V = nullptr;  // [L*E] eviction scores of the last step (pinned), for the prefetch admission
+    // eviction policy and its host-side state
+    int policy = kPolicyEam;
+    std::vector<int64_t> stamp;  // per slot: clock value of its last use (0 = never)
+    std::vector<int64_t> count;  // per expert: activations served so far
+    int64_t clock = 0;
+    // prefetching: copies on their own stream; a slot is "pending" until some stream that reads
+    // it has been made to wait for its copy
+    int pf_depth = 0;
+    hipStream_t pf_stream = nullptr;
+    std::vector<hipEvent_t> slot_ev;
+    std::vector<char> slot_pending;
+    int n_pending = 0;
+    long n_prefetched = 0;
+    int32_t last_pf_fid[kMaxPrefetch] = {}, last_pf_victim[kMaxPrefetch] = {};
+    int32_t last_n_pf = 0;  // prefetches issued by the last layer step
 };
 
 extern "C" const char* moei_last_error(void) { return g_err; }
@@ -136,6 +157,13 @@ extern "C" int moei_cache_destroy(moei_cache* c) {
     (void)hipFree(c->d_n_pf);
     (void)hipFree(c->d_n_ev);
     if (c->pin) (void)hipHostFree(c->pin);
+    if (c->pin_V) (void)hipHostFree(c->pin_V);
+    if (c->pf_stream) {
+        (void)hipStreamSynchronize(c->pf_stream);
+        (void)hipStreamDestroy(c->pf_stream);
+    }
+    for (hipEvent_t e : c->slot_ev)
+        if (e) (void)hipEventDestroy(e);
     if (c->ev_copy) (void)hipEventDestroy(c->ev_copy);
     if (c->ev_routed) (void)hipEventDestroy(c->ev_routed);
     if (c->ev_main) (void)hipEventDestroy(c->ev_main);
@@ -194,6 +222,8 @@ int cache_alloc(moei_cache* c) {
     if (rc) return rc;
     MOEI_HIP(hipHostMalloc((void**)&c->pin, sizeof(Pinned), hipHostMallocDefault));
     memset(c->pin, 0, sizeof(Pinned));
+    MOEI_HIP(hipHostMalloc((void**)&c->pin_V, LE * sizeof(float), hipHostMallocDefault));
+    MOEI_HIP(hipStreamCreateWithFlags(&c->pf_stream, hipStreamNonBlocking));
     MOEI_HIP(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
     MOEI_HIP(hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking));
     MOEI_HIP(hipEventCreateWithFlags(&c->ev_copy, hipEventDisableTiming));
@@ -228,6 +258,10 @@ extern "C" int moei_cache_create(const moei_model_desc* desc, int32_t n_slots, c
     try {
         c->slot_of.assign((size_t)desc->L * desc->E, -1);
         c->owner.assign((size_t)n_slots, -1);
+        c->stamp.assign((size_t)n_slots, 0);
+        c->count.assign((size_t)desc->L * desc->E, 0);
+        c->slot_ev.assign((size_t)n_slots, nullptr);
+        c->slot_pending.assign((size_t)n_slots, 0);
     } catch (...) {
         delete c;
         MOEI_FAIL(MOEI_ENOMEM, "moei_cache_create: out of host memory");
@@ -263,6 +297,12 @@ extern "C" int moei_cache_reset(moei_cache* c, int32_t n_resident) {
     for (int r = 0; r < kRing; ++r) c->match_pending[r] = false;
     std::fill(c->slot_of.begin(), c->slot_of.end(), -1);
     std::fill(c->owner.begin(), c->owner.end(), -1);
+    std::fill(c->stamp.begin(), c->stamp.end(), 0);
+    std::fill(c->count.begin(), c->count.end(), 0);
+    std::fill(c->slot_pending.begin(), c->slot_pending.end(), 0);
+    c->clock = 0;
+    c->n_pending = 0;
+    c->n_prefetched = 0;
     for (int s = 0; s < n_resident; ++s) {
         c->slot_of[s] = s;
         c->owner[s] = s;
@@ -294,6 +334,21 @@ extern "C" int moei_cache_get_slots(const moei_cache* c, int32_t* h_slot_of) {
     return MOEI_OK;
 }
 
+namespace {
+
+// A stream that is about to read or overwrite `slot` first waits for a prefetch copy into it
+// that nobody has waited for yet.
+int settle_pending(moei_cache* c, int slot, hipStream_t waiter) {
+    if (slot >= 0 && slot < c->S && c->slot_pending[slot]) {
+        MOEI_HIP(hipStreamWaitEvent(waiter, c->slot_ev[slot], 0));
+        c->slot_pending[slot] = 0;
+        --c->n_pending;
+    }
+    return MOEI_OK;
+}
+
+}  // namespace
+
 extern "C" int moei_cache_retrieve(moei_cache* c, int32_t layer, const int32_t* h_idx, int32_t n,
                                    const int32_t* h_ev_order, int32_t n_ev, int32_t* h_slots, int32_t* h_victims,
                                    int32_t* h_n_miss, void* stream) {
@@ -319,33 +374,51 @@ extern "C" int moei_cache_retrieve(moei_cache* c, int32_t layer, const int32_t* 
             if (h_idx[j] == fid - layer * E) return true;
         return false;
     };
-    SlotUpdates upd{};
     int pos = 0;
+    // the expert that gives up its slot when the cache is full (never one of these picks)
+    auto pick_victim = [&]() -> int {
+        if (c->policy == kPolicyLru) {  // least recently used slot, ties to the lowest slot
+            int best = -1;
+            for (int t = 0; t < c->S; ++t)
+                if (!needed(c->owner[t]) && (best < 0 || c->stamp[t] < c->stamp[best])) best = t;
+            return c->owner[best];
+        }
+        if (c->policy == kPolicyCount) {  // least often activated expert, ties to the lowest id
+            int best = -1;
+            for (int t = 0; t < c->S; ++t) {
+                const int f = c->owner[t];
+                if (needed(f)) continue;
+                if (best < 0 || c->count[f] < c->count[best] || (c->count[f] == c->count[best] && f < best)) best = f;
+            }
+            return best;
+        }
+        while (pos < n_ev) {  // Alg. 1: lowest eviction priority first
+            int cand = h_ev_order[pos++];
+            if (cand >= 0 && cand < LE && c->slot_of[cand] >= 0 && !needed(cand)) return cand;
+        }
+        for (int t = 0; t < c->S; ++t)
+            if (!needed(c->owner[t])) return c->owner[t];
+        return -1;
+    };
+    SlotUpdates upd{};
     bool waited = false;
     for (int j = 0; j < n; ++j) {
         const int fid = layer * E + h_idx[j];
+        ++c->count[fid];
         int slot = c->slot_of[fid];
         int victim = -1;
-        if (slot < 0) {
+        if (slot >= 0) {
+            int rc = settle_pending(c, slot, s);  // a hit on a prefetched expert whose copy may be in flight
+            if (rc) return rc;
+        } else {
             for (int t = 0; t < c->S; ++t)
                 if (c->owner[t] < 0) {
                     slot = t;
                     break;
                 }
             if (slot < 0) {
-                while (pos < n_ev) {
-                    int cand = h_ev_order[pos++];
-                    if (cand >= 0 && cand < LE && c->slot_of[cand] >= 0 && !needed(cand)) {
-                        victim = cand;
-                        break;
-                    }
-                }
-                if (victim < 0)
-                    for (int t = 0; t < c->S; ++t)
-                        if (!needed(c->owner[t])) {
-                            victim = c->owner[t];
-                            break;
-                        }
+                victim = pick_victim();
+                if (victim < 0) MOEI_FAIL(MOEI_ESTATE, "moei_cache_retrieve: no slot can be freed");
                 slot = c->slot_of[victim];
                 c->slot_of[victim] = -1;
                 upd.fid[upd.n] = victim;
@@ -360,10 +433,13 @@ extern "C" int moei_cache_retrieve(moei_cache* c, int32_t layer, const int32_t* 
                 MOEI_HIP(hipStreamWaitEvent(c->copy_stream, c->ev_main, 0));
                 waited = true;
             }
+            int rc = settle_pending(c, slot, c->copy_stream);  // a prefetch into this slot goes first
+            if (rc) return rc;
             MOEI_HIP(hipMemcpyAsync(c->d_pool + (size_t)slot * c->slot_bytes,
                                     c->h_experts + (size_t)(fid % c->n_host) * c->slot_bytes, c->slot_bytes,
                                     hipMemcpyHostToDevice, c->copy_stream));
         }
+        c->stamp[slot] = ++c->clock;
         h_slots[j] = slot;
         if (h_victims) h_victims[j] = victim;
     }
@@ -374,6 +450,111 @@ extern "C" int moei_cache_retrieve(moei_cache* c, int32_t layer, const int32_t* 
         MOEI_LAUNCH_CHECK();
     }
     if (h_n_miss) *h_n_miss = n_miss;
+    return MOEI_OK;
+}
+
+extern "C" int moei_cache_set_policy(moei_cache* c, int32_t policy) {
+    MOEI_REQUIRE(c, "moei_cache_set_policy: null pointer");
+    MOEI_REQUIRE(policy >= kPolicyEam && policy <= kPolicyCount, "moei_cache_set_policy: unknown policy %d", policy);
+    c->policy = policy;
+    return MOEI_OK;
+}
+
+extern "C" int moei_cache_set_prefetch(moei_cache* c, int32_t depth) {
+    MOEI_REQUIRE(c, "moei_cache_set_prefetch: null pointer");
+    MOEI_REQUIRE(depth >= 0 && depth <= kMaxPrefetch, "moei_cache_set_prefetch: depth = %d outside [0, %d]", depth,
+                 kMaxPrefetch);
+    if (depth > 0 && !c->h_experts)
+        MOEI_FAIL(MOEI_ESTATE, "moei_cache_set_prefetch: the cache has no host copy to prefetch from");
+    c->pf_depth = depth;
+    return MOEI_OK;
+}
+
+extern "C" int moei_cache_prefetch(moei_cache* c, const int32_t* h_pf_order, int32_t n_pf, const int32_t* h_ev_order,
+                                   int32_t n_ev, const float* h_V, int32_t depth, const int32_t* h_protect,
+                                   int32_t n_protect, int32_t* h_fids, int32_t* h_victims, int32_t* h_slots,
+                                   int32_t* h_n_issued, void* stream) {
+    MOEI_REQUIRE(c && h_V, "moei_cache_prefetch: null pointer");
+    MOEI_REQUIRE(n_pf >= 0 && (n_pf == 0 || h_pf_order), "moei_cache_prefetch: bad prefetch order");
+    MOEI_REQUIRE(n_ev >= 0 && (n_ev == 0 || h_ev_order), "moei_cache_prefetch: bad eviction order");
+    MOEI_REQUIRE(n_protect >= 0 && (n_protect == 0 || h_protect), "moei_cache_prefetch: bad protect list");
+    MOEI_REQUIRE(depth >= 0 && depth <= kMaxPrefetch, "moei_cache_prefetch: depth = %d outside [0, %d]", depth,
+                 kMaxPrefetch);
+    if (!c->h_experts) MOEI_FAIL(MOEI_ESTATE, "moei_cache_prefetch: the cache has no host copy to prefetch from");
+    const int LE = c->d.L * c->d.E;
+    const int n_cand = n_pf < depth ? n_pf : depth;
+    for (int i = 0; i < n_cand; ++i)
+        MOEI_REQUIRE(h_pf_order[i] >= 0 && h_pf_order[i] < LE, "moei_cache_prefetch: expert id %d outside [0, %d)",
+                     h_pf_order[i], LE);
+    hipStream_t s = as_stream(stream);
+    auto is_protected = [&](int fid) {
+        for (int i = 0; i < n_protect; ++i)
+            if (h_protect[i] == fid) return true;
+        return false;
+    };
+    SlotUpdates upd{};
+    int pos = 0, issued = 0;
+    bool gated = false;
+    for (int i = 0; i < n_cand; ++i) {
+        const int fid = h_pf_order[i];
+        if (c->slot_of[fid] >= 0) continue;
+        int slot = -1, victim = -1;
+        for (int t = 0; t < c->S; ++t)
+            if (c->owner[t] < 0) {
+                slot = t;
+                break;
+            }
+        if (slot < 0) {
+            // the cheapest victim that is still there; it is displaced only by a candidate that Alg. 1's
+            // own score values more (fp32, the precision the scores are handed over in)
+            while (pos < n_ev) {
+                const int v = h_ev_order[pos];
+                if (v >= 0 && v < LE && c->slot_of[v] >= 0 && !is_protected(v)) break;
+                ++pos;
+            }
+            if (pos >= n_ev) break;
+            const int v = h_ev_order[pos];
+            if (!(h_V[fid] > h_V[v])) continue;
+            victim = v;
+            ++pos;
+            slot = c->slot_of[victim];
+            c->slot_of[victim] = -1;
+            upd.fid[upd.n] = victim;
+            upd.slot[upd.n++] = -1;
+        }
+        c->slot_of[fid] = slot;
+        c->owner[slot] = fid;
+        c->stamp[slot] = ++c->clock;
+        upd.fid[upd.n] = fid;
+        upd.slot[upd.n++] = slot;
+        if (!gated) {  // work already queued on `stream` may still read the slots that are given up
+            MOEI_HIP(hipEventRecord(c->ev_main, s));
+            MOEI_HIP(hipStreamWaitEvent(c->pf_stream, c->ev_main, 0));
+            gated = true;
+        }
+        if (c->slot_pending[slot]) {  // an unfinished prefetch into this slot: same stream, runs first
+            c->slot_pending[slot] = 0;
+            --c->n_pending;
+        }
+        MOEI_HIP(hipMemcpyAsync(c->d_pool + (size_t)slot * c->slot_bytes,
+                                c->h_experts + (size_t)(fid % c->n_host) * c->slot_bytes, c->slot_bytes,
+                                hipMemcpyHostToDevice, c->pf_stream));
+        if (!c->slot_ev[slot]) MOEI_HIP(hipEventCreateWithFlags(&c->slot_ev[slot], hipEventDisableTiming));
+        MOEI_HIP(hipEventRecord(c->slot_ev[slot], c->pf_stream));
+        c->slot_pending[slot] = 1;
+        ++c->n_pending;
+        ++c->n_prefetched;
+        if (h_fids) h_fids[issued] = fid;
+        if (h_victims) h_victims[issued] = victim;
+        if (h_slots) h_slots[issued] = slot;
+        ++issued;
+    }
+    if (issued > 0) {
+        // the device table names the new owners at once; whoever reads such a slot waits for its copy
+        launch(K_ROUTE_TOPK, apply_slot_updates_kernel, dim3(1), dim3(2 * kMaxAct), 0, s, c->d_slot_of, upd);
+        MOEI_LAUNCH_CHECK();
+    }
+    if (h_n_issued) *h_n_issued = issued;
     return MOEI_OK;
 }
 
@@ -493,10 +674,19 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
     if (rc) return rc;
     rc = launch_priority_rank(eamc, c->d_n_pf, c->d_n_ev, c->d_pf_order, c->d_ev_order, side);
     if (rc) return rc;
+    const bool do_prefetch = sync_mode && c->pf_depth > 0 && c->policy == kPolicyEam;
+    const int LE = d.L * E;
+    const int n_ev_copy = do_prefetch ? (k + c->pf_depth < LE ? k + c->pf_depth : LE) : k;
+    const int n_pf_copy = c->pf_depth < LE ? c->pf_depth : LE;
     if (sync_mode) {
         MOEI_HIP(hipMemcpyAsync(&c->pin->best, c->d_best, 4, hipMemcpyDeviceToHost, side));
         MOEI_HIP(hipMemcpyAsync(&c->pin->n_ev, c->d_n_ev, 4, hipMemcpyDeviceToHost, side));
-        MOEI_HIP(hipMemcpyAsync(c->pin->ev_head, c->d_ev_order, (size_t)k * 4, hipMemcpyDeviceToHost, side));
+        MOEI_HIP(hipMemcpyAsync(c->pin->ev_head, c->d_ev_order, (size_t)n_ev_copy * 4, hipMemcpyDeviceToHost, side));
+        if (do_prefetch) {
+            MOEI_HIP(hipMemcpyAsync(&c->pin->n_pf, c->d_n_pf, 4, hipMemcpyDeviceToHost, side));
+            MOEI_HIP(hipMemcpyAsync(c->pin->pf_head, c->d_pf_order, (size_t)n_pf_copy * 4, hipMemcpyDeviceToHost, side));
+            MOEI_HIP(hipMemcpyAsync(c->pin_V, c->d_V, (size_t)LE * 4, hipMemcpyDeviceToHost, side));
+        }
     }
     // one event per step at the end of the side chain (an event record between two kernels
     // costs a few microseconds on its stream): it releases this step's buffer set and is what
@@ -510,21 +700,38 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
     {
         MOEI_HIP(hipEventSynchronize(c->ev_routed));
         int n_miss = 0;
+        int32_t protect[kMaxAct];
         for (int j = 0; j < k; ++j) {
             int e = c->pin->idx[j];
             if (e < 0 || e >= E) MOEI_FAIL(MOEI_ESTATE, "moe_decode_layer: router produced expert %d", e);
             if (c->slot_of[layer * E + e] < 0) ++n_miss;
+            protect[j] = layer * E + e;
         }
         bool side_done = false;
-        if (n_miss > 0) {
+        // the eviction order is needed only when a pick misses under the paper's policy
+        int n_ev = 0;
+        if (n_miss > 0 && c->policy == kPolicyEam) {
             MOEI_HIP(hipEventSynchronize(c->ev_side));
             side_done = true;
-            int n_ev = c->pin->n_ev < k ? c->pin->n_ev : k;
-            int32_t slots[kMaxAct];
-            rc = moei_cache_retrieve(c, layer, c->pin->idx, k, c->pin->ev_head, n_ev, slots, nullptr, nullptr, s);
-            if (rc) return rc;
+            n_ev = c->pin->n_ev < k ? c->pin->n_ev : k;
+        }
+        int32_t slots[kMaxAct];
+        rc = moei_cache_retrieve(c, layer, c->pin->idx, k, c->pin->ev_head, n_ev, slots, nullptr, nullptr, s);
+        if (rc) return rc;
+        if (n_miss > 0) {
             rc = launch_gather_slots(c->d_idx, k, c->d_slot_of + (size_t)layer * E, c->d_slot_ids, c->d_flags, s);
             if (rc) return rc;
+        }
+        if (do_prefetch) {
+            if (!side_done) MOEI_HIP(hipEventSynchronize(c->ev_side));
+            side_done = true;
+            const int n_pf = c->pin->n_pf < n_pf_copy ? c->pin->n_pf : n_pf_copy;
+            const int n_ev_all = c->pin->n_ev < n_ev_copy ? c->pin->n_ev : n_ev_copy;
+            rc = moei_cache_prefetch(c, c->pin->pf_head, n_pf, c->pin->ev_head, n_ev_all, c->pin_V, c->pf_depth, protect,
+                                     k, c->last_pf_fid, c->last_pf_victim, nullptr, &c->last_n_pf, s);
+            if (rc) return rc;
+        } else {
+            c->last_n_pf = 0;
         }
         if (h_topk_idx) memcpy(h_topk_idx, c->pin->idx, (size_t)k * 4);
         if (h_n_miss) *h_n_miss = n_miss;
@@ -535,6 +742,15 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
     }
     return launch_expert_ffn(d, c->d_pool, c->slot_elems, c->n_total, c->ffn, c->d_slot_ids, c->d_gate,
                              k + d.n_shared, d_x, d_y, c->d_flags, s);
+}
+
+extern "C" int moei_cache_last_prefetch(moei_cache* c, int32_t* h_fids, int32_t* h_victims, int32_t cap, int32_t* h_n) {
+    MOEI_REQUIRE(c && h_n, "moei_cache_last_prefetch: null pointer");
+    MOEI_REQUIRE(cap >= c->last_n_pf, "moei_cache_last_prefetch: room for %d entries, %d needed", cap, c->last_n_pf);
+    if (h_fids) memcpy(h_fids, c->last_pf_fid, (size_t)c->last_n_pf * 4);
+    if (h_victims) memcpy(h_victims, c->last_pf_victim, (size_t)c->last_n_pf * 4);
+    *h_n = c->last_n_pf;
+    return MOEI_OK;
 }
 
 extern "C" int moei_cache_set_match_count(moei_cache* c, int32_t m) {
@@ -559,6 +775,12 @@ extern "C" int moei_cache_last_matches(moei_cache* c, int32_t* h_top, float* h_t
 extern "C" int moei_cache_join(moei_cache* c, void* stream) {
     MOEI_REQUIRE(c, "moei_cache_join: null pointer");
     if (c->side_pending) MOEI_HIP(hipStreamWaitEvent(as_stream(stream), c->ev_side, 0));
+    if (c->n_pending > 0) {  // prefetch copies that no stream has waited for yet
+        for (int t = 0; t < c->S; ++t) {
+            int rc = settle_pending(c, t, as_stream(stream));
+            if (rc) return rc;
+        }
+    }
     return MOEI_OK;
 }
 
@@ -566,6 +788,9 @@ extern "C" int moei_cache_sync(moei_cache* c) {
     MOEI_REQUIRE(c, "moei_cache_sync: null pointer");
     MOEI_HIP(hipStreamSynchronize(c->side_stream));
     MOEI_HIP(hipStreamSynchronize(c->copy_stream));
+    MOEI_HIP(hipStreamSynchronize(c->pf_stream));
+    std::fill(c->slot_pending.begin(), c->slot_pending.end(), 0);
+    c->n_pending = 0;
     c->side_pending = false;
     for (int r = 0; r < kRing; ++r) c->match_pending[r] = false;
     return MOEI_OK;
