@@ -48,6 +48,10 @@ def parse():
     ap.add_argument("--cpu-steps", type=int, default=None, help="oracle layer steps timed (default: sized to ~15 s)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-offload", action="store_true")
+    ap.add_argument("--policy-sweep", action="store_true",
+                    help="offload replay under each eviction rule and with prefetching (extra.policy_sweep)")
+    ap.add_argument("--policy-tokens", type=int, default=16, help="decode tokens per request in the policy sweep")
+    ap.add_argument("--policy-requests", type=int, default=6)
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--batch-sweep", action="store_true",
                     help="also time the batched match and grouped FFN for B = 1..16 (EAMC of 10,000 traces)")
@@ -349,30 +353,60 @@ def main():
         for s in range(L * cfg.n_shared):
             t = oc.slot_tensor(cfg.S + s)
             t.copy_(d_shared[s % len(d_shared)].view(t.dtype))
-        oc.reset(cfg.S)
-        d_eam.copy_(prefill)
-        n_off = args.offload_tokens * L
-        per = []
-        for i in range(n_off):
-            torch.cuda.synchronize()
-            a = time.perf_counter()
-            idx, best, n_miss = layer_step(i, sync=True, c=oc)
-            torch.cuda.synchronize()
-            per.append((time.perf_counter() - a, n_miss))
-        hit_steps = [t for t, nm in per if nm == 0]
-        miss_steps = [(t, nm) for t, nm in per if nm > 0]
-        tot_miss = sum(nm for _, nm in per)
-        extra["offload"] = {
-            "slots": cfg.S, "layer_steps": n_off, "hit_rate": 1.0 - tot_miss / (n_off * k),
-            "us_per_step_blended": sum(t for t, _ in per) / n_off * 1e6,
-            "us_per_step_all_hit": (sum(hit_steps) / len(hit_steps) * 1e6) if hit_steps else None,
-            "all_hit_steps": len(hit_steps),
-            "us_per_step_with_miss": (sum(t for t, _ in miss_steps) / len(miss_steps) * 1e6) if miss_steps else None,
-            "host_link_GBps": (tot_miss * cfg.expert_bytes / sum(t for t, _ in miss_steps) / 1e9) if miss_steps else None,
-            "note": "synchronous steps, each timed from the host; misses copied from pinned host memory",
-        }
+
+        def offload_run(policy, depth, tokens, n_req=1):
+            # n_req > 1: requests of different activation groups served back to back; the cache and
+            # the policy's own history carry over, the request's EAM starts from its own prefill
+            oc.reset(cfg.S)
+            oc.set_policy(policy)
+            oc.set_prefetch(depth)
+            per, n_pf = [], 0
+            for r in range(n_req):
+                if r == 0:
+                    rq_eam, rq_bias, rq_x = prefill, d_bias, d_x
+                else:
+                    rq = mi.make_request(cfg, r, decode=tokens)
+                    rq_eam, rq_bias, rq_x = dev(rq.prefill_eam.astype(np.int32)), dev(rq.bias), dev(rq.x)
+                d_eam.copy_(rq_eam)
+                for i in range(tokens * L):
+                    t, l = i // L, i % L
+                    torch.cuda.synchronize()
+                    a = time.perf_counter()
+                    idx, best, n_miss = m.moe_decode_layer(oc, eamc, d_eam, l, routers[l], rq_bias[l], rq_x[t, l], y,
+                                                           sync=True, stream=stream)
+                    torch.cuda.synchronize()
+                    per.append((time.perf_counter() - a, n_miss))
+                    if depth:
+                        n_pf += len(oc.last_prefetch())
+            oc.sync()
+            n_off = len(per)
+            hit_steps = [t for t, nm in per if nm == 0]
+            miss_steps = [(t, nm) for t, nm in per if nm > 0]
+            tot_miss = sum(nm for _, nm in per)
+            return {
+                "policy": policy, "prefetch_depth": depth, "requests": n_req,
+                "slots": cfg.S, "layer_steps": n_off, "hit_rate": 1.0 - tot_miss / (n_off * k),
+                "prefetched_experts": n_pf,
+                "us_per_step_blended": sum(t for t, _ in per) / n_off * 1e6,
+                "us_per_step_all_hit": (sum(hit_steps) / len(hit_steps) * 1e6) if hit_steps else None,
+                "all_hit_steps": len(hit_steps),
+                "us_per_step_with_miss": (sum(t for t, _ in miss_steps) / len(miss_steps) * 1e6) if miss_steps else None,
+                "host_link_GBps": (tot_miss * cfg.expert_bytes / sum(t for t, _ in miss_steps) / 1e9) if miss_steps else None,
+            }
+
+        extra["offload"] = offload_run("eam", 0, args.offload_tokens)
+        extra["offload"]["note"] = "synchronous steps, each timed from the host; misses copied from pinned host memory"
         log(f"[bench] offload: hit rate {extra['offload']['hit_rate']:.3f}, "
             f"{extra['offload']['us_per_step_blended']:.0f} us/step blended")
+        if args.policy_sweep:
+            # the same request under the comparison eviction rules and with prefetching switched on
+            rows = []
+            for policy, depth in (("eam", 0), ("eam", 2), ("lru", 0), ("count", 0)):
+                r = offload_run(policy, depth, args.policy_tokens, args.policy_requests)
+                rows.append(r)
+                log(f"[bench] policy {policy} prefetch {depth}: hit rate {r['hit_rate']:.3f}, "
+                    f"{r['us_per_step_blended']:.0f} us/step, {r['prefetched_experts']} prefetched")
+            extra["policy_sweep"] = rows
         oc.close()
 
     # ------------------------------------------------ leg 5: CPU oracle on a bounded sample
