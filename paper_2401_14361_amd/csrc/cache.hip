@@ -719,7 +719,7 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
         rc = moei_cache_retrieve(c, layer, c->pin->idx, k, c->pin->ev_head, n_ev, slots, nullptr, nullptr, s);
         if (rc) return rc;
         if (n_miss > 0) {
-            rc = launch_gather_slots(c->d_idx, k, c->d_slot_of + (size_t)layer * E, c->d_slot_ids, c->d_flags, s);
+            rc = launch_gather_slots(c->d_idx, k, c->d_slot_of + (size_t)layer * E, c->d_slot_ids + d.n_shared, c->d_flags, s);
             if (rc) return rc;
         }
         if (do_prefetch) {

@@ -707,7 +707,11 @@ __global__ void __launch_bounds__(256) ffn_grouped_reduce_kernel(const float* __
 
 int ffn_scratch_alloc(const moei_model_desc& d, int n_act_max, FfnScratch* out) {
     out->n_act_max = n_act_max;
-    out->n_part = compute_units();
+    // the streaming kernels take one workgroup per compute unit; a few units are left to the
+    // side stream's match and priority kernels so that these never hold up a streaming workgroup
+    int reserve = env_int("MOEI_RESERVE_CUS", 8);
+    if (reserve < 0 || reserve > compute_units() / 2) reserve = 0;
+    out->n_part = compute_units() - reserve;
     hipError_t e = hipMalloc((void**)&out->d_part, (size_t)out->n_part * d.H * sizeof(float));
     if (e != hipSuccess) {
         out->d_part = nullptr;

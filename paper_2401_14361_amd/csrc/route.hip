@@ -5,6 +5,7 @@
 // (Sec. 4.3).  One wavefront serves one token: the E logits sit in LDS, each of
 // the k rounds is a 64-lane butterfly arg-max.
 #include "kernels.hpp"
+#include "topk.hpp"
 #include "wtypes.hpp"
 
 namespace moei {
@@ -12,115 +13,6 @@ namespace moei {
 namespace {
 
 constexpr int kMaxE = 4096;
-
-struct Cand {
-    float v;
-    int e;  // -1: none
-};
-
-__device__ __forceinline__ Cand better(Cand a, Cand b) {
-    // larger logit first; equal logits go to the lower expert index
-    if (b.e < 0) return a;
-    if (a.e < 0) return b;
-    if (a.v > b.v) return a;
-    if (b.v > a.v) return b;
-    return (a.e < b.e) ? a : b;
-}
-
-// Softmax + top-k of z[0..E) (in LDS) by one wavefront, k <= 64.  Every expert's rank is
-// the number of experts that come before it (larger logit, or equal logit and lower
-// index), counted against broadcast LDS reads; rank r < k is pick r.  The picks land in
-// s_idx[k] / s_w[k] (LDS); the caller reads them after a __syncthreads().
-constexpr int kRankMaxE = 1024;
-__device__ __forceinline__ void wave_topk_rank(const float* z, int E, int k, int renorm, int lane, int* s_idx,
-                                               float* s_w) {
-    const int per = (E + kWave - 1) / kWave;
-    float m = -INFINITY;
-    for (int r = 0; r < per; ++r) {
-        int e = lane + r * kWave;
-        if (e < E) m = fmaxf(m, z[e]);
-    }
-    m = wave_max_dpp(m);
-    float s = 0.f;
-    for (int r = 0; r < per; ++r) {
-        int e = lane + r * kWave;
-        if (e < E) s += expf(z[e] - m);
-    }
-    s = wave_sum_dpp(s);
-    float sel = 0.f;
-    for (int r = 0; r < per; ++r) {
-        const int e = lane + r * kWave;
-        if (e < E) {
-            const float v = z[e];
-            int rank = 0;
-            for (int j = 0; j < E; ++j) {
-                const float u = z[j];
-                rank += (u > v || (u == v && j < e)) ? 1 : 0;
-            }
-            if (rank < k) {
-                const float p = expf(v - m) / s;
-                s_idx[rank] = e;
-                s_w[rank] = p;
-                sel += p;
-            }
-        }
-    }
-    if (renorm) {
-        sel = wave_sum_dpp(sel);
-        __syncthreads();  // single-wavefront workgroup: orders the LDS writes above with the reads below
-        if (lane < k) s_w[lane] = s_w[lane] / sel;
-    }
-}
-
-// The same by k rounds of a 64-lane butterfly arg-max (any E up to 4096).
-// Lane j < k returns pick j in (idx, w); other lanes return idx = -1.
-__device__ __forceinline__ void wave_topk(const float* z, int E, int k, int renorm, int lane, int& idx_out,
-                                          float& w_out) {
-    const int per = (E + kWave - 1) / kWave;  // <= 64, so one 64-bit mask per lane marks taken entries
-    float m = -INFINITY;
-    for (int r = 0; r < per; ++r) {
-        int e = lane + r * kWave;
-        if (e < E) m = fmaxf(m, z[e]);
-    }
-    m = wave_max(m);
-    float s = 0.f;
-    for (int r = 0; r < per; ++r) {
-        int e = lane + r * kWave;
-        if (e < E) s += expf(z[e] - m);
-    }
-    s = wave_sum(s);
-
-    unsigned long long taken = 0ull;
-    idx_out = -1;
-    w_out = 0.f;
-    float sel_sum = 0.f;
-    for (int j = 0; j < k; ++j) {
-        Cand c{0.f, -1};
-        for (int r = 0; r < per; ++r) {
-            int e = lane + r * kWave;
-            if (e < E && !((taken >> r) & 1ull)) {
-                float v = z[e];
-                if (c.e < 0 || v > c.v) c = Cand{v, e};
-            }
-        }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            Cand o;
-            o.v = __shfl_xor(c.v, off, 64);
-            o.e = __shfl_xor(c.e, off, 64);
-            c = better(c, o);
-        }
-        // c is now identical in all lanes; k <= E guarantees c.e >= 0
-        if ((c.e & (kWave - 1)) == lane) taken |= 1ull << (c.e / kWave);
-        float p = expf(c.v - m) / s;
-        sel_sum += p;
-        if (lane == j) {
-            idx_out = c.e;
-            w_out = p;
-        }
-    }
-    if (renorm) w_out = w_out / sel_sum;
-}
 
 __global__ void __launch_bounds__(kWave) route_topk_kernel(const float* __restrict__ logits, int E, int k,
                                                            int renorm, int32_t* __restrict__ idx,
@@ -266,6 +158,8 @@ __global__ void __launch_bounds__(kWave) route_fused_kernel(RouteFusedArgs a) {
     __threadfence();
     for (int j = lane; j < a.E; j += kWave)
         z[j] = __hip_atomic_load(&a.logits[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_pick[lane] = 0;  // NaN logits leave ranks unassigned: such picks then name expert 0
+    s_pw[lane] = 0.f;
     __syncthreads();
     int my_idx;
     float my_w;
@@ -283,13 +177,14 @@ __global__ void __launch_bounds__(kWave) route_fused_kernel(RouteFusedArgs a) {
         const int cnt = s_eam[my_idx] + 1;  // one writer per cell
         eam_row[my_idx] = cnt;
         a.snap[(size_t)a.layer * a.E + my_idx] = cnt;
+        // activated experts of the step: the always-on shared experts first, then the picks
         int slot = s_slot[my_idx];
-        a.slot_ids[lane] = slot;
-        a.gate[lane] = my_w;
+        a.slot_ids[a.n_shared + lane] = slot;
+        a.gate[a.n_shared + lane] = my_w;
         if (slot < 0 && a.flags) atomicOr(a.flags, 2);
     } else if (lane < a.k + a.n_shared) {
-        a.slot_ids[lane] = a.shared_base + (lane - a.k);
-        a.gate[lane] = 1.0f;
+        a.slot_ids[lane - a.k] = a.shared_base + (lane - a.k);
+        a.gate[lane - a.k] = 1.0f;
     }
     if (lane == 0) *a.ticket = 0;  // ready for the next launch on this stream
 }
