@@ -26,7 +26,7 @@ import numpy as np
 __all__ = [
     "to_f64", "router_logits", "softmax", "route_topk", "eam_update", "eamc_match",
     "eamc_match_topm", "aggregate_matches", "expert_priority", "swiglu_expert", "expert_ffn",
-    "ExpertCache", "decode_layer",
+    "ExpertCache", "decode_layer", "prefill_layer",
 ]
 
 
@@ -429,3 +429,31 @@ def decode_layer(traces, eam, cache: ExpertCache, layer: int, W_r, bias, x, expe
     y = expert_ffn(x, experts, gates)
     return dict(logits=z, idx=idx, w=w, best=best, sim=sim, matched=list(matched), P=P, V=V, pf_order=pf,
                 ev_order=ev, events=events, prefetched=prefetched, y=y)
+
+
+# ------------------------------------------------------------- prefill iteration
+def prefill_layer(eam, layer: int, W_r, bias, X, expert_of, shared_of, k: int, renorm: bool):
+    """One MoE layer of the prefill iteration: all n prompt tokens pass the layer together
+    (Sec. 4.3: an iteration routes n tokens, every token adds its k picks to row l of the EAM).
+
+    Token by token: routing decision, EAM update, the picked experts' FFNs weighted by
+    the gate weights plus the shared experts with weight 1.  Every expert is taken to be
+    available (the cache is not consulted: the prompt pass decides nothing about
+    eviction here).  Returns (idx [n][k], w [n][k], Y [n][H] fp64); ``eam`` is updated in place.
+    """
+    X = to_f64(X)
+    n = X.shape[0]
+    L, E = eam.shape
+    idx = np.zeros((n, k), dtype=np.int64)
+    w = np.zeros((n, k), dtype=np.float64)
+    Y = np.zeros((n, X.shape[1]), dtype=np.float64)
+    shared = list(shared_of(layer))
+    for t in range(n):
+        z = router_logits(W_r, X[t], bias)
+        i_t, w_t = route_topk(z, k, renorm)
+        idx[t], w[t] = i_t[0], w_t[0]
+        eam_update(eam, layer, idx[t])
+        experts = [expert_of(layer * E + int(j)) for j in idx[t]] + shared
+        gates = [float(v) for v in w[t]] + [1.0] * len(shared)
+        Y[t] = expert_ffn(X[t], experts, gates)
+    return idx, w, Y

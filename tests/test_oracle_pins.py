@@ -594,3 +594,59 @@ def test_decode_layer_composes_its_parts():
     y = O.expert_ffn(req.x[0, 0], [expert_of(int(j)) for j in idx[0]], w[0])
     np.testing.assert_array_equal(y, out["y"])
     assert out["best"] == O.eamc_match(T, eam)[0]
+
+
+# ================================================================ prefill iteration
+def test_prefill_layer_against_dense_all_expert_formulation():
+    # every expert applied to every token with dense library matmuls, then masked by the routing:
+    # a different formulation of the same sum (torch, fp64)
+    rng = np.random.default_rng(41)
+    L, E, k, H, I, n = 3, 6, 2, 16, 12, 23
+    Wr = rng.standard_normal((E, H))
+    bias = rng.standard_normal(E)
+    X = rng.standard_normal((n, H))
+    Wg, Wu = rng.standard_normal((E, I, H)) * 0.3, rng.standard_normal((E, I, H)) * 0.3
+    Wd = rng.standard_normal((E, H, I)) * 0.3
+    Sg, Su, Sd = rng.standard_normal((I, H)) * 0.3, rng.standard_normal((I, H)) * 0.3, rng.standard_normal((H, I)) * 0.3
+    layer = 1
+    for renorm in (False, True):
+        eam = rng.integers(0, 5, size=(L, E)).astype(np.int64)
+        before = eam.copy()
+        idx, w, Y = O.prefill_layer(eam, layer, Wr, bias, X, lambda f: (Wg[f % E], Wu[f % E], Wd[f % E]),
+                                    lambda l: [(Sg, Su, Sd)], k, renorm)
+        tX = torch.from_numpy(X)
+        logits = tX @ torch.from_numpy(Wr).T + torch.from_numpy(bias)
+        prob = torch.softmax(logits, dim=1)
+        top = torch.topk(logits, k, dim=1)
+        assert (top.indices.numpy() == idx).all()
+        gate = torch.zeros((n, E), dtype=torch.float64)
+        sel = prob.gather(1, top.indices)
+        if renorm:
+            sel = sel / sel.sum(dim=1, keepdim=True)
+        gate.scatter_(1, top.indices, sel)
+        np.testing.assert_allclose(w, sel.numpy(), rtol=1e-12)
+        dense = torch.zeros((n, H), dtype=torch.float64)
+        for e in range(E):
+            g = tX @ torch.from_numpy(Wg[e]).T
+            u = tX @ torch.from_numpy(Wu[e]).T
+            dense += gate[:, e:e + 1] * ((torch.nn.functional.silu(g) * u) @ torch.from_numpy(Wd[e]).T)
+        g = tX @ torch.from_numpy(Sg).T
+        dense += (torch.nn.functional.silu(g) * (tX @ torch.from_numpy(Su).T)) @ torch.from_numpy(Sd).T
+        np.testing.assert_allclose(Y, dense.numpy(), rtol=1e-10, atol=1e-12)
+        # Sec. 4.3: the n tokens add n*k to row l, nothing elsewhere; the row is the histogram of the picks
+        delta = eam - before
+        assert delta[layer].sum() == n * k and (np.delete(delta, layer, axis=0) == 0).all()
+        assert (delta[layer] == np.bincount(idx.reshape(-1), minlength=E)).all()
+
+
+def test_prefill_layer_token_order_does_not_matter():
+    rng = np.random.default_rng(42)
+    L, E, k, H, I, n = 2, 5, 2, 8, 6, 11
+    Wr, X = rng.standard_normal((E, H)), rng.standard_normal((n, H))
+    ex = [(rng.standard_normal((I, H)), rng.standard_normal((I, H)), rng.standard_normal((H, I))) for _ in range(E)]
+    e1, e2 = np.zeros((L, E), dtype=np.int64), np.zeros((L, E), dtype=np.int64)
+    perm = rng.permutation(n)
+    i1, w1, Y1 = O.prefill_layer(e1, 0, Wr, None, X, lambda f: ex[f % E], lambda l: [], k, True)
+    i2, w2, Y2 = O.prefill_layer(e2, 0, Wr, None, X[perm], lambda f: ex[f % E], lambda l: [], k, True)
+    assert (e1 == e2).all() and (i1[perm] == i2).all()
+    np.testing.assert_array_equal(Y1[perm], Y2)
