@@ -258,6 +258,22 @@ int moei_cache_set_match_count(moei_cache* c, int32_t m);
  * drained: h_top[cap] / h_top_sim[cap] (either may be NULL), *h_m = how many. */
 int moei_cache_last_matches(moei_cache* c, int32_t* h_top, float* h_top_sim, int32_t cap,
                             int32_t* h_m, void* stream);
+/* The prefill iteration of one MoE layer (Sec. 4.3: an iteration routes n tokens; each adds its
+ * k picks to row `layer` of the EAM): for the n prompt tokens d_X[n][H] (bf16), routing as in
+ * moe_decode_layer, d_eam[layer][e] += number of tokens that picked e, and
+ * d_Y[n][H] (fp32) = sum over the token's picks of gate weight x expert FFN, plus the layer's
+ * shared experts with weight 1.  Tokens are grouped per expert and the groups run on the
+ * matrix cores (activations rounded to bf16 between the two projections: the stated 2e-2 bar
+ * applies, not the tighter fp32 one of the decode path).  Every picked expert must be
+ * resident (the cache is not consulted or changed; a non-resident pick raises error flag
+ * bit 1 and contributes zero).  Optional outputs d_idx_out[n][k], d_w_out[n][k] (device).
+ * bf16 weights, H a multiple of 128 and <= 4096, E <= 2048, n <= 8192; scratch for the
+ * longest prompt so far is kept in the cache (allocated on a first or longer call, which
+ * drains the device).  All work is queued on `stream`. */
+int moe_prefill_layer(moei_cache* c, int32_t* d_eam, int32_t layer,
+                      const void* d_router_w, const float* d_router_bias,
+                      const void* d_X, int32_t n, float* d_Y,
+                      int32_t* d_idx_out, float* d_w_out, void* stream);
 /* Makes `stream` wait for the match/priority work that the last moe_decode_layer put on
  * the cache's side stream (the next moe_decode_layer does this by itself) and for every
  * prefetch copy that no stream has waited for yet.  Call it

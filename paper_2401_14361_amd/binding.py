@@ -16,7 +16,7 @@ import torch
 __all__ = [
     "MoeiError", "ModelDesc", "lib", "lib_path", "Eamc", "Cache",
     "moe_route_topk", "eam_update", "eamc_match", "eamc_match_topm", "expert_priority", "expert_ffn_gemv",
-    "moe_decode_layer", "expert_ffn_grouped", "WDTYPE_FP32", "WDTYPE_BF16", "EXPORTS", "expert_pack", "profile_enable", "profile_disable", "profile_read",
+    "moe_decode_layer", "moe_prefill_layer", "expert_ffn_grouped", "WDTYPE_FP32", "WDTYPE_BF16", "EXPORTS", "expert_pack", "profile_enable", "profile_disable", "profile_read",
 ]
 
 WDTYPE_FP32, WDTYPE_BF16 = 0, 1
@@ -30,7 +30,7 @@ EXPORTS = [
     "moei_cache_get_slots", "moei_cache_retrieve", "expert_ffn_gemv", "expert_ffn_grouped", "moei_cache_error_flags",
     "moe_decode_layer", "moei_cache_last_step", "moei_cache_join", "moei_cache_sync",
     "moei_cache_set_match_count", "moei_cache_last_matches",
-    "moei_cache_set_policy", "moei_cache_prefetch", "moei_cache_set_prefetch", "moei_cache_last_prefetch",
+    "moe_prefill_layer", "moei_cache_set_policy", "moei_cache_prefetch", "moei_cache_set_prefetch", "moei_cache_last_prefetch",
     "moei_profile_enable", "moei_profile_disable", "moei_profile_kernels", "moei_profile_kernel_name",
     "moei_profile_read",
 ]
@@ -416,6 +416,22 @@ def moe_decode_layer(cache: Cache, eamc: Eamc, eam: torch.Tensor, layer: int, ro
 
 
 # -------------------------------------------------------------------- kernel timing
+def moe_prefill_layer(cache: Cache, eam: torch.Tensor, layer: int, router_w: torch.Tensor, router_bias,
+                      X: torch.Tensor, Y: torch.Tensor | None = None, want_picks: bool = False, stream=None):
+    """Prefill iteration of one layer: X [n][H] (bf16 bits) -> Y [n][H] fp32; eam [L][E] int32 updated in
+    place.  Returns Y, or (Y, idx [n][k], w [n][k]) with want_picks."""
+    _dev(eam, torch.int32)
+    n, H = X.shape
+    assert H == cache.desc.H and X.is_contiguous()
+    if Y is None:
+        Y = torch.empty((n, H), dtype=torch.float32, device=X.device)
+    idx = torch.empty((n, cache.desc.k), dtype=torch.int32, device=X.device) if want_picks else None
+    w = torch.empty((n, cache.desc.k), dtype=torch.float32, device=X.device) if want_picks else None
+    _check(lib().moe_prefill_layer(cache.h, _p(eam), layer, _p(router_w), _p(router_bias), _p(X), n, _p(Y),
+                                   _p(idx), _p(w), _stream(stream)))
+    return (Y, idx, w) if want_picks else Y
+
+
 def profile_enable(max_samples: int) -> None:
     _check(lib().moei_profile_enable(max_samples))
 

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoei.so")
-SOURCES = ["cache.hip", "route.hip", "match.hip", "priority.hip", "ffn.hip", "profile.hip"]
+SOURCES = ["cache.hip", "route.hip", "match.hip", "priority.hip", "ffn.hip", "prefill.hip", "profile.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

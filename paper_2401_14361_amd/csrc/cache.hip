@@ -120,9 +120,24 @@ struct moei_cache {
     std::vector<char> slot_pending;
     int n_pending = 0;
     long n_prefetched = 0;
+    PrefillScratch prefill;  // allocated at the first prefill call, grown when a longer prompt comes
     int32_t last_pf_fid[kMaxPrefetch] = {}, last_pf_victim[kMaxPrefetch] = {};
     int32_t last_n_pf = 0;  // prefetches issued by the last layer step
 };
+
+namespace {
+void prefill_scratch_free(PrefillScratch* p) {
+    (void)hipFree(p->d_idx);
+    (void)hipFree(p->d_w);
+    (void)hipFree(p->d_perm);
+    (void)hipFree(p->d_pgate);
+    (void)hipFree(p->d_where);
+    (void)hipFree(p->d_items);
+    (void)hipFree(p->d_meta);
+    (void)hipFree(p->d_part);
+    *p = PrefillScratch{};
+}
+}  // namespace
 
 extern "C" const char* moei_last_error(void) { return g_err; }
 extern "C" const char* moei_version(void) { return "moei 0.1 (gfx950)"; }
@@ -156,6 +171,7 @@ extern "C" int moei_cache_destroy(moei_cache* c) {
     (void)hipFree(c->d_ev_order);
     (void)hipFree(c->d_n_pf);
     (void)hipFree(c->d_n_ev);
+    prefill_scratch_free(&c->prefill);
     if (c->pin) (void)hipHostFree(c->pin);
     if (c->pin_V) (void)hipHostFree(c->pin_V);
     if (c->pf_stream) {
@@ -588,6 +604,48 @@ extern "C" int expert_ffn_grouped(moei_cache* c, int32_t layer, const int32_t* d
     return launch_expert_ffn_grouped(c->d, c->d_pool, c->slot_elems, c->d_items, c->d_n_items, c->d_gpart,
                                      c->d_slot_of + (size_t)layer * c->d.E, c->S + layer * c->d.n_shared, d_idx, d_w, B,
                                      d_x, d_y, c->d_flags, as_stream(stream));
+}
+
+extern "C" int moe_prefill_layer(moei_cache* c, int32_t* d_eam, int32_t layer, const void* d_router_w,
+                                 const float* d_router_bias, const void* d_X, int32_t n, float* d_Y, int32_t* d_idx_out,
+                                 float* d_w_out, void* stream) {
+    MOEI_REQUIRE(c && d_eam && d_router_w, "moe_prefill_layer: null pointer");
+    const moei_model_desc& d = c->d;
+    MOEI_REQUIRE(layer >= 0 && layer < d.L, "moe_prefill_layer: layer %d outside [0, %d)", layer, d.L);
+    MOEI_REQUIRE(n >= 0 && n <= 8192, "moe_prefill_layer: n = %d outside [0, 8192]", n);
+    int rc = prefill_check(d);
+    if (rc) return rc;
+    if (n == 0) return MOEI_OK;
+    MOEI_REQUIRE(d_X && d_Y, "moe_prefill_layer: null pointer");
+    hipStream_t s = as_stream(stream);
+    PrefillScratch& p = c->prefill;
+    if (n > p.n_max) {  // scratch for the longest prompt so far (not a stream operation: drains the device)
+        MOEI_HIP(hipDeviceSynchronize());
+        prefill_scratch_free(&p);
+        const int n_max = n < 512 ? 512 : n;
+        const size_t nk = (size_t)n_max * d.k;
+        hipError_t e = hipMalloc((void**)&p.d_idx, nk * 4);
+        if (e == hipSuccess) e = hipMalloc((void**)&p.d_w, nk * 4);
+        if (e == hipSuccess) e = hipMalloc((void**)&p.d_perm, nk * 4);
+        if (e == hipSuccess) e = hipMalloc((void**)&p.d_pgate, nk * 4);
+        if (e == hipSuccess) e = hipMalloc((void**)&p.d_where, nk * 8);
+        if (e == hipSuccess) e = hipMalloc(&p.d_items, (size_t)prefill_max_items(d, n_max) * prefill_item_bytes());
+        if (e == hipSuccess) e = hipMalloc((void**)&p.d_meta, 8);
+        if (e == hipSuccess) e = hipMalloc((void**)&p.d_part, prefill_part_floats(d, n_max) * sizeof(float));
+        if (e != hipSuccess) {
+            prefill_scratch_free(&p);
+            MOEI_FAIL(MOEI_ENOMEM, "moe_prefill_layer: scratch allocation failed: %s", hipGetErrorString(e));
+        }
+        p.n_max = n_max;
+        p.seg_max = prefill_seg_max(d, n_max);
+    }
+    rc = launch_prefill(d, p, c->d_pool, c->slot_elems, c->n_total, c->d_slot_of + (size_t)layer * d.E,
+                        c->S + layer * d.n_shared, d_eam + (size_t)layer * d.E, d_router_w, d_router_bias, d_X, n, d_Y,
+                        c->d_flags, s);
+    if (rc) return rc;
+    if (d_idx_out) MOEI_HIP(hipMemcpyAsync(d_idx_out, p.d_idx, (size_t)n * d.k * 4, hipMemcpyDeviceToDevice, s));
+    if (d_w_out) MOEI_HIP(hipMemcpyAsync(d_w_out, p.d_w, (size_t)n * d.k * 4, hipMemcpyDeviceToDevice, s));
+    return MOEI_OK;
 }
 
 extern "C" int moei_cache_error_flags(moei_cache* c, int32_t* h_flags, void* stream) {

@@ -52,6 +52,30 @@ int launch_expert_ffn_grouped(const moei_model_desc& d, const void* d_pool, size
                               const int32_t* d_idx, const float* d_w, int B, const void* d_x, float* d_y,
                               int32_t* d_flags, hipStream_t s);
 
+// ---------------------------------------------------------------- prefill.hip
+struct PrefillScratch {
+    int n_max = 0;     // tokens the buffers are sized for
+    int seg_max = 0;
+    int32_t* d_idx = nullptr;   // [n_max][k] picks
+    float* d_w = nullptr;       // [n_max][k] gate weights
+    int32_t* d_perm = nullptr;  // [n_max*k]
+    float* d_pgate = nullptr;   // [n_max*k]
+    int32_t* d_where = nullptr;  // [n_max*k][2]
+    void* d_items = nullptr;
+    int32_t* d_meta = nullptr;  // [2]
+    float* d_part = nullptr;
+};
+int prefill_check(const moei_model_desc& d);
+int prefill_token_tile(const moei_model_desc& d);
+size_t prefill_item_bytes();
+int prefill_max_items(const moei_model_desc& d, int n_max);
+int prefill_seg_max(const moei_model_desc& d, int n_max);
+size_t prefill_part_floats(const moei_model_desc& d, int n_max);
+int launch_prefill(const moei_model_desc& d, const PrefillScratch& ps, const void* d_pool, size_t slot_elems,
+                   int n_slots_total, const int32_t* d_slot_of_row, int shared_base, int32_t* d_eam_row,
+                   const void* d_router_w, const float* d_router_bias, const void* d_X, int n, float* d_Y,
+                   int32_t* d_flags, hipStream_t s);
+
 }  // namespace moei
 
 // The EAM collection (Sec. 4.5): traces layer-major on the device.
