@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--cpu-steps", type=int, default=None, help="oracle layer steps timed (default: sized to ~15 s)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-offload", action="store_true")
+    ap.add_argument("--prefill", action="store_true", help="time the prefill iteration of one layer (extra.prefill)")
+    ap.add_argument("--prefill-max", type=int, default=2048)
     ap.add_argument("--policy-sweep", action="store_true",
                     help="offload replay under each eviction rule and with prefetching (extra.policy_sweep)")
     ap.add_argument("--policy-tokens", type=int, default=16, help="decode tokens per request in the policy sweep")
@@ -345,6 +347,36 @@ def main():
                 f"= {distinct * cfg.expert_bytes / t_ffn / 1e3:.0f} GB/s")
         extra["batch_sweep"] = sweep
         e10k.close()
+
+    # ------------------------------------------------ optional: the prefill iteration on this shape
+    if args.prefill and cfg.wdtype == "bf16" and H <= 4096:
+        rows = []
+        for n_tok in (64, 128, 256, 512, 1024, 2048):
+            if n_tok > args.prefill_max:
+                break
+            rng = np.random.default_rng(n_tok)
+            Xp = dev(mi.to_store(cfg, rng.standard_normal((n_tok, H)).astype(np.float32)))
+            Yp = torch.empty((n_tok, H), dtype=torch.float32, device="cuda")
+            eam_p = prefill.clone()
+            for _ in range(2):
+                _, pidx, _ = m.moe_prefill_layer(cache, eam_p, 0, routers[0], d_bias[0], Xp, Y=Yp, want_picks=True)
+            torch.cuda.synchronize()
+            reps = 10
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record()
+            for i in range(reps):
+                m.moe_prefill_layer(cache, eam_p, i % L, routers[i % L], d_bias[i % L], Xp, Y=Yp)
+            ev1.record()
+            torch.cuda.synchronize()
+            us = ev0.elapsed_time(ev1) / reps * 1e3
+            distinct = len(np.unique(pidx.cpu().numpy())) + cfg.n_shared
+            flops = 6.0 * H * cfg.I * n_tok * (k + cfg.n_shared)
+            rows.append({"tokens": n_tok, "us_per_layer": us, "distinct_experts": distinct,
+                         "weight_GBps": distinct * cfg.expert_bytes / us / 1e3, "TFLOPs": flops / us / 1e6,
+                         "tokens_per_s": n_tok / us * 1e6})
+            log(f"[bench] prefill {n_tok} tokens: {us:.0f} us per layer, {distinct} experts -> "
+                f"{rows[-1]['weight_GBps']:.0f} GB/s of distinct weights, {rows[-1]['TFLOPs']:.1f} TFLOP/s")
+        extra["prefill"] = rows
 
     # ------------------------------------------------ leg 4: offload replay (capped cache, PCIe misses)
     if not args.no_offload and cfg.S < L * E:

@@ -134,6 +134,7 @@ void prefill_scratch_free(PrefillScratch* p) {
     (void)hipFree(p->d_where);
     (void)hipFree(p->d_items);
     (void)hipFree(p->d_meta);
+    (void)hipFree(p->d_cntw);
     (void)hipFree(p->d_part);
     *p = PrefillScratch{};
 }
@@ -631,6 +632,7 @@ extern "C" int moe_prefill_layer(moei_cache* c, int32_t* d_eam, int32_t layer, c
         if (e == hipSuccess) e = hipMalloc((void**)&p.d_where, nk * 8);
         if (e == hipSuccess) e = hipMalloc(&p.d_items, (size_t)prefill_max_items(d, n_max) * prefill_item_bytes());
         if (e == hipSuccess) e = hipMalloc((void**)&p.d_meta, 8);
+        if (e == hipSuccess) e = hipMalloc((void**)&p.d_cntw, (size_t)d.E * 4 * 4);
         if (e == hipSuccess) e = hipMalloc((void**)&p.d_part, prefill_part_floats(d, n_max) * sizeof(float));
         if (e != hipSuccess) {
             prefill_scratch_free(&p);

@@ -63,6 +63,7 @@ struct PrefillScratch {
     int32_t* d_where = nullptr;  // [n_max*k][2]
     void* d_items = nullptr;
     int32_t* d_meta = nullptr;  // [2]
+    int32_t* d_cntw = nullptr;  // [E][4]
     float* d_part = nullptr;
 };
 int prefill_check(const moei_model_desc& d);

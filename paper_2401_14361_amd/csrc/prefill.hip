@@ -4,8 +4,9 @@
 // row l of the request's EAM.  Four launches:
 //   1. prefill_route_kernel   router logits + softmax/top-k, one wavefront per token (the
 //                             same summation order as the decode routing, so the same bits)
-//   2. prefill_group_kernel   histogram of the picks -> EAM row; tokens grouped per expert
-//                             in ascending token order, cut into items of <= TM tokens
+//   2. prefill_count_kernel / prefill_place_kernel
+//                             histogram of the picks -> EAM row; tokens grouped per expert in
+//                             ascending token order, cut into items of <= TM tokens
 //   3. prefill_ffn_kernel     grouped SwiGLU expert FFN on the matrix cores: an item's tokens
 //                             sit in LDS, the expert's weights stream past once per item
 //   4. prefill_reduce_kernel  y[t] = sum of the token's partial rows, in pick order
@@ -125,71 +126,100 @@ struct GroupArgsP {
     int32_t* where;    // [n*k][2] (item, row) of every routed (token, pick)
     PItem* items;
     int32_t* meta;  // [0] = items in all, [1] = routed items
+    int32_t* cntw;  // [E][4] tokens that pick the expert, per wavefront range of the grouping kernels
     int32_t* flags;
 };
 
-__global__ void __launch_bounds__(1024) prefill_group_kernel(GroupArgsP g) {
-    __shared__ int s_cnt[kPfMaxE];
-    __shared__ int s_off[kPfMaxE];
-    __shared__ int s_ioff[kPfMaxE];
-    __shared__ int s_nrouted;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    constexpr int NW = 1024 / kWave;
-    // does token t pick expert e, and as which pick?
-    auto pick_of = [&](int t, int e) -> int {
-        int j_hit = -1;
-        if (t < g.n)
-            for (int j = 0; j < g.k; ++j)
-                if (g.idx[(size_t)t * g.k + j] == e) j_hit = j;
-        return j_hit;
-    };
-    for (int e = wv; e < g.E; e += NW) {
+constexpr int kGrpThreads = 256;
+constexpr int kGrpWaves = kGrpThreads / kWave;
+
+// does token t pick expert e, and as which pick?  (-1: no)
+__device__ __forceinline__ int pick_of(const GroupArgsP& g, int t, int e) {
+    int j_hit = -1;
+    if (t < g.n)
+        for (int j = 0; j < g.k; ++j)
+            if (g.idx[(size_t)t * g.k + j] == e) j_hit = j;
+    return j_hit;
+}
+
+// tokens [w*span, (w+1)*span) belong to wavefront w of an expert's workgroup
+__device__ __forceinline__ int group_span(int n) { return ((n + kGrpWaves - 1) / kGrpWaves + kWave - 1) / kWave * kWave; }
+
+// 2a. grid E: how many tokens pick expert e, per wavefront range -> cntw[e][kGrpWaves]
+__global__ void __launch_bounds__(kGrpThreads) prefill_count_kernel(GroupArgsP g) {
+    const int e = blockIdx.x, lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+    const int span = group_span(g.n);
+    int c = 0;
+    for (int t0 = wv * span; t0 < min(g.n, (wv + 1) * span); t0 += kWave)
+        c += __popcll(__ballot(pick_of(g, t0 + lane, e) >= 0));
+    if (lane == 0) g.cntw[e * kGrpWaves + wv] = c;
+}
+
+// 2b. grid E: offsets by a prefix over the counts, EAM row update, placement in ascending
+// token order, the expert's items; workgroup 0 also lists the shared experts' items.
+__global__ void __launch_bounds__(kGrpThreads) prefill_place_kernel(GroupArgsP g) {
+    __shared__ int s_red[3][kGrpWaves];
+    const int e = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    // tokens and items of the experts before this one, items of all experts
+    int toks = 0, its = 0, its_all = 0;
+    for (int f = tid; f < g.E; f += kGrpThreads) {
         int c = 0;
-        for (int t0 = 0; t0 < g.n; t0 += kWave) c += __popcll(__ballot(pick_of(t0 + lane, e) >= 0));
-        if (lane == 0) s_cnt[e] = c;
+        for (int w = 0; w < kGrpWaves; ++w) c += g.cntw[f * kGrpWaves + w];
+        const int ni = (c + g.TM - 1) / g.TM;
+        if (f < e) {
+            toks += c;
+            its += ni;
+        }
+        its_all += ni;
+    }
+    toks = (int)wave_sum_u32_dpp((unsigned)toks);
+    its = (int)wave_sum_u32_dpp((unsigned)its);
+    its_all = (int)wave_sum_u32_dpp((unsigned)its_all);
+    if (lane == 0) {
+        s_red[0][wv] = toks;
+        s_red[1][wv] = its;
+        s_red[2][wv] = its_all;
     }
     __syncthreads();
-    if (tid == 0) {
-        int o = 0, io = 0;
-        for (int e = 0; e < g.E; ++e) {
-            s_off[e] = o;
-            s_ioff[e] = io;
-            o += s_cnt[e];
-            io += (s_cnt[e] + g.TM - 1) / g.TM;
+    int off = 0, ioff = 0, n_routed = 0, cnt = 0, before = 0;
+    for (int w = 0; w < kGrpWaves; ++w) {
+        off += s_red[0][w];
+        ioff += s_red[1][w];
+        n_routed += s_red[2][w];
+        const int cw = g.cntw[e * kGrpWaves + w];
+        if (w < wv) before += cw;
+        cnt += cw;
+    }
+    if (tid == 0) g.eam_row[e] += cnt;  // Sec. 4.3: the n tokens add n*k to row l
+    const int span = group_span(g.n);
+    int pos = before;
+    for (int t0 = wv * span; t0 < min(g.n, (wv + 1) * span); t0 += kWave) {
+        const int t = t0 + lane;
+        const int j = pick_of(g, t, e);
+        const unsigned long long mask = __ballot(j >= 0);
+        if (j >= 0) {
+            const int r = pos + __popcll(mask & ((1ull << lane) - 1ull));
+            g.perm[off + r] = t;
+            g.pgate[off + r] = g.w[(size_t)t * g.k + j];
+            g.where[((size_t)t * g.k + j) * 2] = ioff + r / g.TM;
+            g.where[((size_t)t * g.k + j) * 2 + 1] = r % g.TM;
         }
-        s_nrouted = io;
+        pos += __popcll(mask);
     }
-    for (int e = tid; e < g.E; e += 1024) g.eam_row[e] += s_cnt[e];  // Sec. 4.3: n tokens add n*k to row l
-    __syncthreads();
-    for (int e = wv; e < g.E; e += NW) {
-        const int off = s_off[e], ioff = s_ioff[e], cnt = s_cnt[e];
-        int pos = 0;
-        for (int t0 = 0; t0 < g.n; t0 += kWave) {
-            const int t = t0 + lane;
-            const int j = pick_of(t, e);
-            const unsigned long long mask = __ballot(j >= 0);
-            if (j >= 0) {
-                const int r = pos + __popcll(mask & ((1ull << lane) - 1ull));
-                g.perm[off + r] = t;
-                g.pgate[off + r] = g.w[(size_t)t * g.k + j];
-                g.where[((size_t)t * g.k + j) * 2] = ioff + r / g.TM;
-                g.where[((size_t)t * g.k + j) * 2 + 1] = r % g.TM;
-            }
-            pos += __popcll(mask);
+    const int slot = g.slot_of_row[e];
+    if (cnt > 0 && slot < 0 && tid == 0) atomicOr(g.flags, 2);
+    for (int it = tid; it * g.TM < cnt; it += kGrpThreads)
+        g.items[ioff + it] = PItem{slot, min(g.TM, cnt - it * g.TM), off + it * g.TM, -1};
+    if (e == 0) {
+        const int tiles = (g.n + g.TM - 1) / g.TM;
+        for (int q = tid; q < g.n_shared * tiles; q += kGrpThreads) {
+            const int s = q / tiles, tile = q - s * tiles;
+            g.items[n_routed + q] = PItem{g.shared_base + s, min(g.TM, g.n - tile * g.TM), 0, tile * g.TM};
         }
-        const int slot = g.slot_of_row[e];
-        if (cnt > 0 && slot < 0 && lane == 0) atomicOr(g.flags, 2);
-        for (int it = lane; it * g.TM < cnt; it += kWave)
-            g.items[ioff + it] = PItem{slot, min(g.TM, cnt - it * g.TM), off + it * g.TM, -1};
-    }
-    const int tiles = (g.n + g.TM - 1) / g.TM;
-    for (int q = tid; q < g.n_shared * tiles; q += 1024) {
-        const int s = q / tiles, tile = q - s * tiles;
-        g.items[s_nrouted + q] = PItem{g.shared_base + s, min(g.TM, g.n - tile * g.TM), 0, tile * g.TM};
-    }
-    if (tid == 0) {
-        g.meta[0] = s_nrouted + g.n_shared * tiles;
-        g.meta[1] = s_nrouted;
+        if (tid == 0) {
+            g.meta[0] = n_routed + g.n_shared * tiles;
+            g.meta[1] = n_routed;
+        }
     }
 }
 
@@ -524,8 +554,10 @@ int launch_prefill(const moei_model_desc& d, const PrefillScratch& ps, const voi
            d_router_bias, d_X, n, d.H, d.E, d.k, (int)(d.renorm_topk != 0), vec_ok, ps.d_idx, ps.d_w);
     MOEI_LAUNCH_CHECK();
     GroupArgsP g{ps.d_idx, ps.d_w, n, d.k, d.E, d.n_shared, TM, d_slot_of_row, shared_base, d_eam_row, ps.d_perm,
-                 ps.d_pgate, ps.d_where, reinterpret_cast<PItem*>(ps.d_items), ps.d_meta, d_flags};
-    launch(K_FFN_GROUP, prefill_group_kernel, dim3(1), dim3(1024), 0, s, g);
+                 ps.d_pgate, ps.d_where, reinterpret_cast<PItem*>(ps.d_items), ps.d_meta, ps.d_cntw, d_flags};
+    launch(K_FFN_GROUP, prefill_count_kernel, dim3(d.E), dim3(kGrpThreads), 0, s, g);
+    MOEI_LAUNCH_CHECK();
+    launch(K_FFN_GROUP, prefill_place_kernel, dim3(d.E), dim3(kGrpThreads), 0, s, g);
     MOEI_LAUNCH_CHECK();
     const int G = pf_compute_units();
     PfArgs a{reinterpret_cast<const uint16_t*>(d_pool), slot_elems, n_slots_total,
