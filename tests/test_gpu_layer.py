@@ -199,6 +199,69 @@ def test_async_layer_step_matches_sync_and_flags_a_miss(m):
     eamc.close()
 
 
+def test_layer_steps_in_a_hip_graph_replay_like_eager_steps(m):
+    # one token's L asynchronous layer steps captured once, replayed for several tokens with eager
+    # work and synchronisations between the replays; every replay must equal the eager steps bit for bit
+    cfg = mi.get_config("C2").scaled(L=4, H=256, I=192, N=60, prompt=32)
+    L, E = cfg.L, cfg.E
+    T, _, _ = mi.eamc_traces(cfg, threads=2)
+    req = mi.make_request(cfg, 4, decode=6)
+    bank = pack_bank(m, cfg, mi.expert_bank(cfg, L * E, threads=2))
+    shared = pack_bank(m, cfg, mi.expert_bank(cfg.scaled(cid=78), L * cfg.n_shared, threads=2))
+    desc = m.ModelDesc.from_config(cfg)
+    eamc = m.Eamc(desc, cfg.N)
+    eamc.load(T)
+    routers = [dev(mi.router_weights(cfg, l)) for l in range(L)]
+    d_bias, d_x = dev(req.bias), dev(req.x)
+    n_tok = 5
+
+    def fresh():
+        c = m.Cache(desc, L * E, pinned(bank), pinned(shared))
+        c.reset(L * E)
+        return c, dev(req.prefill_eam.astype(np.int32))
+
+    cache, d_eam = fresh()
+    want_y, want_eam, want_orders = [], [], []
+    for t in range(n_tok):
+        ys = torch.empty((L, cfg.H), dtype=torch.float32, device="cuda")
+        for l in range(L):
+            m.moe_decode_layer(cache, eamc, d_eam, l, routers[l], d_bias[l], d_x[t, l], ys[l], sync=False)
+        torch.cuda.synchronize()
+        want_y.append(ys.cpu().numpy())
+        want_eam.append(d_eam.cpu().numpy())
+        last = cache.last_step()
+        want_orders.append((last["ev_order"].tolist(), last["pf_order"].tolist()))
+    cache.close()
+
+    cache, d_eam = fresh()
+    x_stage = torch.empty_like(d_x[0])
+    y_all = torch.empty((L, cfg.H), dtype=torch.float32, device="cuda")
+    cache.sync()
+    cap = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=cap):
+        for l in range(L):
+            m.moe_decode_layer(cache, eamc, d_eam, l, routers[l], d_bias[l], x_stage[l], y_all[l], sync=False)
+        cache.join()
+    cache.sync()
+    d_eam.copy_(dev(req.prefill_eam.astype(np.int32)))      # the capture itself did not run anything
+    for t in range(n_tok):
+        x_stage.copy_(d_x[t])
+        graph.replay()
+        torch.cuda.synchronize()
+        assert (y_all.cpu().numpy() == want_y[t]).all(), t
+        assert (d_eam.cpu().numpy() == want_eam[t]).all(), t
+        last = cache.last_step()
+        assert (last["ev_order"].tolist(), last["pf_order"].tolist()) == want_orders[t], t
+        # the program's own eager work between replays
+        m.eamc_match(eamc, d_eam)
+        y_all.zero_()
+        torch.cuda.synchronize()
+    assert cache.error_flags() == 0
+    cache.close()
+    eamc.close()
+
+
 # ------------------------------------------------------------------ full benchmark shapes
 def test_full_size_deepseek_v2_lite_token_with_capped_cache(m):
     # configuration 2 at full size (26 x 64 experts of 2048 x 1408 bf16, 1,000 traces, 416 slots):
