@@ -137,12 +137,25 @@ __global__ void __launch_bounds__(kWave) route_fused_kernel(RouteFusedArgs a) {
     const WT* x = reinterpret_cast<const WT*>(a.x);
     float acc = 0.f;
     if (a.vec_ok) {
-        for (int c = lane * V::N; c < a.H; c += kWave * V::N) {
-            typename V::raw wv = V::load(row + c);
-            typename V::raw xv = V::load(x + c);
-            float xf[V::N];
-            V::unpack(xv, xf);
-            acc = V::dot(wv, xf, acc);
+        // four chunks' loads go out together (one round trip for rows up to 4 x 64 vectors); the
+        // sum still runs over the chunks in ascending order
+        constexpr int CW = kWave * V::N;
+        for (int c0 = lane * V::N; c0 < a.H; c0 += 4 * CW) {
+            typename V::raw wv[4], xv[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = c0 + q * CW < a.H ? c0 + q * CW : c0;
+                wv[q] = V::load(row + c);
+                xv[q] = V::load(x + c);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (c0 + q * CW < a.H) {
+                    float xf[V::N];
+                    V::unpack(xv[q], xf);
+                    acc = V::dot(wv[q], xf, acc);
+                }
+            }
         }
     } else {
         for (int c = lane; c < a.H; c += kWave) acc = __builtin_fmaf(V::one(row + c), V::one(x + c), acc);
