@@ -224,23 +224,39 @@ __device__ __forceinline__ Best pick(Best a, Best b) {
     return r;
 }
 
-__device__ __forceinline__ u64 shfl_xor_u64(u64 v, int off) {
-    unsigned lo = __shfl_xor((unsigned)(v & 0xffffffffull), off, 64);
-    unsigned hi = __shfl_xor((unsigned)(v >> 32), off, 64);
-    return ((u64)hi << 32) | lo;
+// A candidate moved across lanes by a DPP pattern / read from one lane through scalar registers.
+template <int CTRL>
+__device__ __forceinline__ Best best_dpp(Best me) {
+    auto mv = [](unsigned v) { return MOEI_DPP_U32(v, CTRL); };
+    auto mv64 = [&](u64 v) { return ((u64)mv((unsigned)(v >> 32)) << 32) | mv((unsigned)v); };
+    Best o;
+    o.dot = mv64(me.dot);
+    o.nt = mv64(me.nt);
+    o.key = __longlong_as_double((long long)mv64((u64)__double_as_longlong(me.key)));
+    o.idx = (int)mv((unsigned)me.idx);
+    return o;
+}
+__device__ __forceinline__ Best best_lane(Best me, int lane) {
+    auto rd = [&](unsigned v) { return (unsigned)__builtin_amdgcn_readlane((int)v, lane); };
+    auto rd64 = [&](u64 v) { return ((u64)rd((unsigned)(v >> 32)) << 32) | rd((unsigned)v); };
+    Best o;
+    o.dot = rd64(me.dot);
+    o.nt = rd64(me.nt);
+    o.key = __longlong_as_double((long long)rd64((u64)__double_as_longlong(me.key)));
+    o.idx = (int)rd((unsigned)me.idx);
+    return o;
 }
 
+// The wavefront's best candidate, in every lane: DPP inside each row of 16 lanes (the order is
+// total, so both partners of an exchange keep the same winner), then the four row winners
+// through scalar registers.
 __device__ __forceinline__ Best wave_pick(Best me) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        Best o;
-        o.dot = shfl_xor_u64(me.dot, off);
-        o.nt = shfl_xor_u64(me.nt, off);
-        o.key = __longlong_as_double((long long)shfl_xor_u64((u64)__double_as_longlong(me.key), off));
-        o.idx = __shfl_xor(me.idx, off, 64);
-        me = pick(me, o);
-    }
-    return me;
+    me = pick(me, best_dpp<0xB1>(me));   // quad_perm [1,0,3,2]
+    me = pick(me, best_dpp<0x4E>(me));   // quad_perm [2,3,0,1]
+    me = pick(me, best_dpp<0x141>(me));  // row_half_mirror
+    me = pick(me, best_dpp<0x140>(me));  // row_mirror
+    const Best r0 = best_lane(me, 0), r1 = best_lane(me, 16), r2 = best_lane(me, 32), r3 = best_lane(me, 48);
+    return pick(pick(r0, r1), pick(r2, r3));
 }
 
 __device__ __forceinline__ double cosine(u64 dot, u64 nq, u64 nt) {
