@@ -305,6 +305,9 @@ int moei_profile_disable(void);
 int moei_profile_kernels(void);
 const char* moei_profile_kernel_name(int32_t id);
 int moei_profile_read(int32_t id, double* total_ms, int32_t* count);
+/* The recorded launches of one kernel one by one, in launch order: h_ms[min(cap, *count)]
+ * milliseconds each; *count = launches recorded (may exceed cap). */
+int moei_profile_samples(int32_t id, float* h_ms, int32_t cap, int32_t* count);
 
 #ifdef __cplusplus
 }

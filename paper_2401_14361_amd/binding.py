@@ -16,7 +16,7 @@ import torch
 __all__ = [
     "MoeiError", "ModelDesc", "lib", "lib_path", "Eamc", "Cache",
     "moe_route_topk", "eam_update", "eamc_match", "eamc_match_topm", "expert_priority", "expert_ffn_gemv",
-    "moe_decode_layer", "moe_prefill_layer", "expert_ffn_grouped", "WDTYPE_FP32", "WDTYPE_BF16", "EXPORTS", "expert_pack", "profile_enable", "profile_disable", "profile_read",
+    "moe_decode_layer", "moe_prefill_layer", "expert_ffn_grouped", "WDTYPE_FP32", "WDTYPE_BF16", "EXPORTS", "expert_pack", "profile_enable", "profile_disable", "profile_read", "profile_samples",
 ]
 
 WDTYPE_FP32, WDTYPE_BF16 = 0, 1
@@ -32,7 +32,7 @@ EXPORTS = [
     "moei_cache_set_match_count", "moei_cache_last_matches",
     "moe_prefill_layer", "moei_cache_set_policy", "moei_cache_prefetch", "moei_cache_set_prefetch", "moei_cache_last_prefetch",
     "moei_profile_enable", "moei_profile_disable", "moei_profile_kernels", "moei_profile_kernel_name",
-    "moei_profile_read",
+    "moei_profile_read", "moei_profile_samples",
 ]
 
 
@@ -438,6 +438,18 @@ def profile_enable(max_samples: int) -> None:
 
 def profile_disable() -> None:
     _check(lib().moei_profile_disable())
+
+
+def profile_samples(name: str) -> np.ndarray:
+    """Durations (microseconds) of the recorded launches of one kernel, in launch order."""
+    for i in range(lib().moei_profile_kernels()):
+        if lib().moei_profile_kernel_name(i).decode() == name:
+            n = C.c_int32(0)
+            _check(lib().moei_profile_samples(i, None, 0, C.byref(n)))
+            out = np.empty(max(n.value, 1), dtype=np.float32)
+            _check(lib().moei_profile_samples(i, _p(out), n.value, C.byref(n)))
+            return out[:n.value].astype(np.float64) * 1e3
+    raise KeyError(name)
 
 
 def profile_read() -> dict:

@@ -94,3 +94,18 @@ extern "C" int moei_profile_read(int32_t id, double* total_ms, int32_t* count) {
     *count = n;
     return MOEI_OK;
 }
+
+extern "C" int moei_profile_samples(int32_t id, float* h_ms, int32_t cap, int32_t* count) {
+    MOEI_REQUIRE(count, "moei_profile_samples: null pointer");
+    MOEI_REQUIRE(id >= 0 && id < K_COUNT, "moei_profile_samples: kernel id %d outside [0, %d)", id, (int)K_COUNT);
+    MOEI_REQUIRE(cap >= 0 && (cap == 0 || h_ms), "moei_profile_samples: bad buffer");
+    MOEI_HIP(hipDeviceSynchronize());
+    int n = 0;
+    for (size_t i = 0; i < g_used; ++i) {
+        if (g_pool[i].id != id) continue;
+        if (n < cap) MOEI_HIP(hipEventElapsedTime(&h_ms[n], g_pool[i].b, g_pool[i].e));
+        ++n;
+    }
+    *count = n;
+    return MOEI_OK;
+}
