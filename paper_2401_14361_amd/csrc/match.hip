@@ -247,16 +247,78 @@ __device__ __forceinline__ Best best_lane(Best me, int lane) {
     return o;
 }
 
-// The wavefront's best candidate, in every lane: DPP inside each row of 16 lanes (the order is
-// total, so both partners of an exchange keep the same winner), then the four row winners
-// through scalar registers.
-__device__ __forceinline__ Best wave_pick(Best me) {
+// The same search on (key, index) alone: three registers per exchange instead of seven.  It is
+// final only if no comparison on the way was a near tie (keys within 2^-48 of each other and
+// not both zero); `tie` reports that, and the caller then repeats the search with the exact
+// comparison.  Two zero keys are two zero similarities: the lower index wins, exactly.
+struct KeyIdx {
+    double key;
+    int idx;
+};
+__device__ __forceinline__ KeyIdx pick_key(KeyIdx a, KeyIdx b, bool& tie) {
+    if (b.idx < 0) return a;
+    if (a.idx < 0) return b;
+    const double d = a.key - b.key;
+    const double tol = fmax(a.key, b.key) * 0x1p-48;
+    bool take_b;
+    if (d > tol) {
+        take_b = false;
+    } else if (d < -tol) {
+        take_b = true;
+    } else if (a.key == 0.0 && b.key == 0.0) {
+        take_b = b.idx < a.idx;
+    } else {
+        tie = true;
+        take_b = false;
+    }
+    KeyIdx r;
+    r.key = take_b ? b.key : a.key;
+    r.idx = take_b ? b.idx : a.idx;
+    return r;
+}
+template <int CTRL>
+__device__ __forceinline__ KeyIdx keyidx_dpp(KeyIdx me) {
+    const u64 k = (u64)__double_as_longlong(me.key);
+    KeyIdx o;
+    o.key = __longlong_as_double((long long)(((u64)MOEI_DPP_U32((unsigned)(k >> 32), CTRL) << 32) | MOEI_DPP_U32((unsigned)k, CTRL)));
+    o.idx = (int)MOEI_DPP_U32((unsigned)me.idx, CTRL);
+    return o;
+}
+__device__ __forceinline__ KeyIdx keyidx_lane(KeyIdx me, int lane) {
+    const u64 k = (u64)__double_as_longlong(me.key);
+    KeyIdx o;
+    o.key = __longlong_as_double((long long)(((u64)(unsigned)__builtin_amdgcn_readlane((int)(k >> 32), lane) << 32) |
+                                             (unsigned)__builtin_amdgcn_readlane((int)k, lane)));
+    o.idx = __builtin_amdgcn_readlane(me.idx, lane);
+    return o;
+}
+
+__device__ __forceinline__ Best wave_pick_exact(Best me) {
     me = pick(me, best_dpp<0xB1>(me));   // quad_perm [1,0,3,2]
     me = pick(me, best_dpp<0x4E>(me));   // quad_perm [2,3,0,1]
     me = pick(me, best_dpp<0x141>(me));  // row_half_mirror
     me = pick(me, best_dpp<0x140>(me));  // row_mirror
     const Best r0 = best_lane(me, 0), r1 = best_lane(me, 16), r2 = best_lane(me, 32), r3 = best_lane(me, 48);
     return pick(pick(r0, r1), pick(r2, r3));
+}
+
+// The wavefront's best candidate, in every lane: DPP inside each row of 16 lanes (the order is
+// total, so both partners of an exchange keep the same winner), then the four row winners
+// through scalar registers.  All 64 lanes must be active.
+__device__ __forceinline__ Best wave_pick(Best me) {
+    bool tie = false;
+    KeyIdx k{me.key, me.idx};
+    k = pick_key(k, keyidx_dpp<0xB1>(k), tie);
+    k = pick_key(k, keyidx_dpp<0x4E>(k), tie);
+    k = pick_key(k, keyidx_dpp<0x141>(k), tie);
+    k = pick_key(k, keyidx_dpp<0x140>(k), tie);
+    const KeyIdx r0 = keyidx_lane(k, 0), r1 = keyidx_lane(k, 16), r2 = keyidx_lane(k, 32), r3 = keyidx_lane(k, 48);
+    const KeyIdx w = pick_key(pick_key(r0, r1, tie), pick_key(r2, r3, tie), tie);
+    if (__ballot(tie) != 0ull) return wave_pick_exact(me);  // uniform
+    if (w.idx < 0) return make_best(0, 1, -1);
+    // the winner's dot product and norm come from the lane that holds it
+    const int owner = __builtin_amdgcn_readfirstlane(__ffsll((long long)__ballot(me.idx == w.idx)) - 1);
+    return best_lane(me, owner);
 }
 
 __device__ __forceinline__ double cosine(u64 dot, u64 nq, u64 nt) {
@@ -409,6 +471,44 @@ struct TopmArgs {
     ScoreArgs sc;
 };
 
+// m rounds of "best of the workgroup, then retire it".  Every wavefront keeps its own winner in
+// LDS; after a round only the wavefront that held the overall winner searches again, the others'
+// winners stand.  `local_best()` is the calling thread's best remaining candidate, `retire(idx)`
+// removes a candidate from the calling thread, `emit(r, w)` is called by thread 0 with winner r.
+template <typename LocalBest, typename Retire, typename Emit>
+__device__ __forceinline__ void extract_top(int m, u64* s_dot, u64* s_nt, int* s_idx, int* s_win, LocalBest local_best,
+                                            Retire retire, Emit emit) {
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+    bool stale = true;  // uniform over the wavefront: its LDS entry must be recomputed
+    for (int r = 0; r < m; ++r) {
+        if (stale) {
+            const Best wb = wave_pick(local_best());
+            if (lane == 0) {
+                s_dot[wv] = wb.dot;
+                s_nt[wv] = wb.nt;
+                s_idx[wv] = wb.idx;
+            }
+            stale = false;
+        }
+        __syncthreads();
+        if (wv == 0) {
+            Best w = make_best(0, 1, -1);
+            if (lane < kPickWaves && s_idx[lane] >= 0) w = make_best(s_dot[lane], s_nt[lane], s_idx[lane]);
+            w = wave_pick(w);
+            if (lane == 0) {
+                *s_win = w.idx;
+                emit(r, w);
+            }
+        }
+        __syncthreads();
+        const int win = *s_win;
+        if (win >= 0) {
+            retire(win);
+            stale = s_idx[wv] == win;  // LDS read, the same in every lane
+        }
+    }
+}
+
 // grid (workgroups over traces): each workgroup extracts the m best of its 1024 traces by m
 // rounds of the exact pick; the last workgroup to arrive extracts the m best of all winners.
 __global__ void __launch_bounds__(kPickThreads) eamc_topm_kernel(TopmArgs a) {
@@ -450,10 +550,12 @@ __global__ void __launch_bounds__(kPickThreads) eamc_topm_kernel(TopmArgs a) {
         if (a.sims) a.sims[n] = (float)cosine(dot, nq, nt);
         me = make_best(dot, nt, n);
     }
-    for (int r = 0; r < a.m; ++r) {
-        const Best w = block_pick(me, s_dot, s_nt, s_idx);
-        if (tid == 0) {
-            s_win = w.idx;
+    extract_top(
+        a.m, s_dot, s_nt, s_idx, &s_win, [&]() { return me; },
+        [&](int win) {
+            if (me.idx == win) me = make_best(0, 1, -1);
+        },
+        [&](int r, const Best& w) {
             if (single) {
                 a.top[r] = w.idx;
                 if (a.top_sim) a.top_sim[r] = w.idx >= 0 ? (float)cosine(w.dot, nq, w.nt) : 0.f;
@@ -464,10 +566,7 @@ __global__ void __launch_bounds__(kPickThreads) eamc_topm_kernel(TopmArgs a) {
                 a.cand[ci * 2 + 1] = w.nt;
                 a.cand_idx[ci] = w.idx;
             }
-        }
-        __syncthreads();
-        if (s_win >= 0 && me.idx == s_win) me = make_best(0, 1, -1);  // taken: out of the next rounds
-    }
+        });
     if (!single) {
         if (tid == 0) {
             __threadfence();
@@ -491,22 +590,25 @@ __global__ void __launch_bounds__(kPickThreads) eamc_topm_kernel(TopmArgs a) {
                 }
             }
         }
-        for (int r = 0; r < a.m; ++r) {
-            Best loc = mine[0];
+        __syncthreads();  // the first phase is done with the LDS winners
+        extract_top(
+            a.m, s_dot, s_nt, s_idx, &s_win,
+            [&]() {
+                Best loc = mine[0];
 #pragma unroll
-            for (int u = 1; u < kTopmPerThread; ++u) loc = pick(loc, mine[u]);
-            const Best w = block_pick(loc, s_dot, s_nt, s_idx);
-            if (tid == 0) {
-                s_win = w.idx;
+                for (int u = 1; u < kTopmPerThread; ++u) loc = pick(loc, mine[u]);
+                return loc;
+            },
+            [&](int win) {
+#pragma unroll
+                for (int u = 0; u < kTopmPerThread; ++u)
+                    if (mine[u].idx == win) mine[u] = make_best(0, 1, -1);
+            },
+            [&](int r, const Best& w) {
                 a.top[r] = w.idx;
                 if (a.top_sim) a.top_sim[r] = w.idx >= 0 ? (float)cosine(w.dot, nq, w.nt) : 0.f;
                 s_best[r] = w.idx;
-            }
-            __syncthreads();
-#pragma unroll
-            for (int u = 0; u < kTopmPerThread; ++u)
-                if (s_win >= 0 && mine[u].idx == s_win) mine[u] = make_best(0, 1, -1);
-        }
+            });
         if (tid == 0) *a.ticket = 0;  // ready for the next launch on this stream
     }
     if (a.do_score) score_cells(a.sc, s_sn, s_best, true);
