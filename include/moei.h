@@ -234,9 +234,9 @@ int moei_cache_set_policy(moei_cache* c, int32_t policy);
  * expert_priority); otherwise it is skipped and the victim is offered to the next one.
  * Copies run on the cache's prefetch stream after everything already queued on `stream`;
  * they are NOT waited for here: moei_cache_retrieve and the synchronous moe_decode_layer
- * make the reading stream wait when a prefetched expert is picked or replaced,
- * moei_cache_join does so for all of them (needed before expert_ffn_gemv / asynchronous
- * layer steps that may touch such a slot).  The slot tables name the new owners at once.
+ * make the reading stream wait when a prefetched expert is picked or replaced, an
+ * asynchronous moe_decode_layer waits for all of them, and so does moei_cache_join (needed
+ * before expert_ffn_gemv / expert_ffn_grouped / moe_prefill_layer touch such a slot).  The slot tables name the new owners at once.
  * Outputs (each may be NULL): h_fids / h_victims (-1 = free slot) / h_slots [depth],
  * *h_n_issued.  All arrays are host memory.  MOEI_ESTATE without a host copy. */
 int moei_cache_prefetch(moei_cache* c, const int32_t* h_pf_order, int32_t n_pf,

@@ -682,6 +682,14 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
     // reads (a wait that has long been satisfied unless the side stream falls far behind).
     c->parity = (c->parity + 1) % kRing;
     if (c->match_pending[c->parity]) MOEI_HIP(hipStreamWaitEvent(s, c->ev_match[c->parity], 0));
+    // The asynchronous step picks its slots on the device, so the host cannot tell which
+    // prefetch copies it depends on: the stream waits for all that are still unsettled (none in
+    // a run that never prefetches; the synchronous step waits slot by slot instead).
+    if (!sync_mode && c->n_pending > 0)
+        for (int t = 0; t < c->S; ++t) {
+            rc = settle_pending(c, t, s);
+            if (rc) return rc;
+        }
     c->d_idx = c->d_idx2[c->parity];
     int32_t* d_snap = c->d_snap[c->parity];
 
