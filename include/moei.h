@@ -75,6 +75,13 @@ int moei_eamc_insert(moei_eamc* c, const int32_t* h_eam, int32_t victim);
 /* Failure recovery (Sec. B.2): trace-major dump of the collection to host memory,
  * h_traces[N][L][E]; pass the result to moei_eamc_load to restore.  Synchronous. */
 int moei_eamc_export(const moei_eamc* c, int32_t* h_traces, int32_t max_traces);
+/* The same through a file (the EAMC is checkpointed with the model, Sec. B.2): a 32-byte
+ * header (magic "MOEIEAMC", version, L, E, N) and the traces as int32 [N][L][E].  Restoring
+ * replaces the contents; a file of another shape, with more traces than the capacity, with
+ * a cell the collection cannot hold, truncated or not a checkpoint is refused and leaves
+ * the collection as it was (MOEI_EINVAL; MOEI_ESTATE if the file cannot be opened).  Synchronous. */
+int moei_eamc_save(const moei_eamc* c, const char* path);
+int moei_eamc_restore(moei_eamc* c, const char* path);
 int moei_eamc_size(const moei_eamc* c);            /* N, or MOEI_EINVAL */
 int moei_eamc_destroy(moei_eamc* c);
 

@@ -24,7 +24,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 EXPORTS = [
     "moei_last_error", "moei_version",
-    "moei_eamc_create", "moei_eamc_load", "moei_eamc_insert", "moei_eamc_export", "moei_eamc_size", "moei_eamc_destroy",
+    "moei_eamc_create", "moei_eamc_load", "moei_eamc_insert", "moei_eamc_export", "moei_eamc_save", "moei_eamc_restore", "moei_eamc_size", "moei_eamc_destroy",
     "moe_route_topk", "eam_update", "eamc_match", "eamc_match_topm", "expert_priority",
     "moei_cache_create", "moei_cache_destroy", "moei_expert_pack", "moei_cache_reset", "moei_cache_slot_ptr", "moei_cache_slot_table",
     "moei_cache_get_slots", "moei_cache_retrieve", "expert_ffn_gemv", "expert_ffn_grouped", "moei_cache_error_flags",
@@ -131,6 +131,13 @@ class Eamc:
         out = np.zeros((self.size, self.desc.L, self.desc.E), dtype=np.int32)
         _check(lib().moei_eamc_export(self.h, _p(out), out.shape[0]))
         return out
+
+    def save(self, path: str) -> None:
+        """Checkpoint file of the collection (failure recovery)."""
+        _check(lib().moei_eamc_save(self.h, os.fsencode(path)))
+
+    def restore(self, path: str) -> None:
+        _check(lib().moei_eamc_restore(self.h, os.fsencode(path)))
 
     @property
     def size(self) -> int:

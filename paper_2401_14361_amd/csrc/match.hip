@@ -14,6 +14,8 @@
 #include <new>
 #include <vector>
 
+#include <stdio.h>
+
 #include "kernels.hpp"
 #include "score.hpp"
 
@@ -760,12 +762,14 @@ extern "C" int moei_eamc_load(moei_eamc* c, const int32_t* h_traces, int32_t N) 
     MOEI_REQUIRE(N >= 0, "moei_eamc_load: N = %d is negative", N);
     if (N > c->n_cap) MOEI_FAIL(MOEI_ECAPACITY, "moei_eamc_load: N = %d exceeds the capacity %d", N, c->n_cap);
     MOEI_REQUIRE(N == 0 || h_traces, "moei_eamc_load: null traces");
-    c->N = 0;
-    if (N == 0) return MOEI_OK;
     const int L = c->d.L, E = c->d.E;
     const size_t LE = (size_t)L * E;
-    int rc = check_cells(h_traces, (size_t)N * LE, c->cell_bytes);
-    if (rc) return rc;
+    if (N > 0) {  // refused input leaves the collection as it was
+        int rc = check_cells(h_traces, (size_t)N * LE, c->cell_bytes);
+        if (rc) return rc;
+    }
+    c->N = 0;
+    if (N == 0) return MOEI_OK;
     // trace-major -> layer-major staging, one layer at a time
     std::vector<unsigned long long> norm((size_t)N);
     for (int n = 0; n < N; ++n) norm[n] = norm2_of(h_traces + (size_t)n * LE, LE);
@@ -844,6 +848,70 @@ extern "C" int moei_eamc_export(const moei_eamc* c, int32_t* h_traces, int32_t m
         }
     }
     return MOEI_OK;
+}
+
+// Checkpoint file (failure recovery, App. B.2): a 32-byte header - magic "MOEIEAMC", version 1,
+// L, E, N, 4 reserved bytes as zero - then the traces as int32 [N][L][E], little endian.
+namespace {
+struct EamcFileHeader {
+    char magic[8];
+    int32_t version, L, E, N;
+    int32_t reserved[2];
+};
+static_assert(sizeof(EamcFileHeader) == 32, "header layout");
+const char kEamcMagic[8] = {'M', 'O', 'E', 'I', 'E', 'A', 'M', 'C'};
+}  // namespace
+
+extern "C" int moei_eamc_save(const moei_eamc* c, const char* path) {
+    MOEI_REQUIRE(c && path, "moei_eamc_save: null pointer");
+    std::vector<int32_t> host;
+    try {
+        host.resize((size_t)c->N * c->d.L * c->d.E);
+    } catch (...) {
+        MOEI_FAIL(MOEI_ENOMEM, "moei_eamc_save: out of host memory");
+    }
+    int rc = moei_eamc_export(c, host.data(), c->N);
+    if (rc) return rc;
+    FILE* f = fopen(path, "wb");
+    if (!f) MOEI_FAIL(MOEI_ESTATE, "moei_eamc_save: cannot open %s for writing", path);
+    EamcFileHeader h{};
+    memcpy(h.magic, kEamcMagic, 8);
+    h.version = 1;
+    h.L = c->d.L;
+    h.E = c->d.E;
+    h.N = c->N;
+    bool ok = fwrite(&h, sizeof(h), 1, f) == 1;
+    if (ok && !host.empty()) ok = fwrite(host.data(), sizeof(int32_t), host.size(), f) == host.size();
+    ok = (fclose(f) == 0) && ok;
+    if (!ok) MOEI_FAIL(MOEI_ESTATE, "moei_eamc_save: writing %s failed", path);
+    return MOEI_OK;
+}
+
+extern "C" int moei_eamc_restore(moei_eamc* c, const char* path) {
+    MOEI_REQUIRE(c && path, "moei_eamc_restore: null pointer");
+    FILE* f = fopen(path, "rb");
+    if (!f) MOEI_FAIL(MOEI_ESTATE, "moei_eamc_restore: cannot open %s", path);
+    EamcFileHeader h{};
+    if (fread(&h, sizeof(h), 1, f) != 1 || memcmp(h.magic, kEamcMagic, 8) != 0 || h.version != 1) {
+        fclose(f);
+        MOEI_FAIL(MOEI_EINVAL, "moei_eamc_restore: %s is not an EAMC checkpoint", path);
+    }
+    if (h.L != c->d.L || h.E != c->d.E || h.N < 0 || h.N > c->n_cap) {
+        fclose(f);
+        MOEI_FAIL(MOEI_EINVAL, "moei_eamc_restore: checkpoint holds %d traces of %dx%d, the collection takes %d of %dx%d",
+                  h.N, h.L, h.E, c->n_cap, c->d.L, c->d.E);
+    }
+    std::vector<int32_t> host;
+    try {
+        host.resize((size_t)h.N * h.L * h.E);
+    } catch (...) {
+        fclose(f);
+        MOEI_FAIL(MOEI_ENOMEM, "moei_eamc_restore: out of host memory");
+    }
+    const bool ok = host.empty() || fread(host.data(), sizeof(int32_t), host.size(), f) == host.size();
+    fclose(f);
+    if (!ok) MOEI_FAIL(MOEI_EINVAL, "moei_eamc_restore: %s is truncated", path);
+    return moei_eamc_load(c, host.data(), h.N);
 }
 
 namespace moei {

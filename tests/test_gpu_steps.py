@@ -137,6 +137,50 @@ def test_eamc_match_large_counts_and_empty_collection(m):
     assert eamc.size == 0
 
 
+def test_eamc_checkpoint_file_round_trip(m, tmp_path):
+    # failure recovery (App. B.2): the collection is written to a file and read back into a fresh one
+    rng = np.random.default_rng(9)
+    L, E, N = 5, 12, 37
+    T = (rng.integers(0, 500, size=(N, L, E)) * (rng.random((N, L, E)) < 0.5)).astype(np.int32)
+    desc = m.ModelDesc(L, E, 1, 0, 8, 8, m.WDTYPE_BF16, 0, EPS)
+    q = dev(T[11] + 1)
+    for cb in (4, 2):
+        a = m.Eamc(desc, 50, cb)
+        a.load(T)
+        path = str(tmp_path / f"eamc{cb}.bin")
+        a.save(path)
+        want = [t.cpu().numpy() for t in m.eamc_match(a, q, want_sims=True)]
+        a.close()
+        b = m.Eamc(desc, 40, 6 - cb)                       # another capacity and cell width
+        b.restore(path)
+        assert b.size == N and (b.export() == T).all()
+        got = [t.cpu().numpy() for t in m.eamc_match(b, q, want_sims=True)]
+        assert (got[0] == want[0]).all() and (got[1] == want[1]).all() and (got[2] == want[2]).all()
+        # refused files leave the collection untouched
+        raw = open(path, "rb").read()
+        for bad in (raw[:100], b"XXXX" + raw[4:], raw[:12] + (99).to_bytes(4, "little") + raw[16:]):
+            open(path, "wb").write(bad)
+            with pytest.raises(m.MoeiError):
+                b.restore(path)
+            assert b.size == N and (b.export() == T).all()
+        small = m.Eamc(desc, N - 1, 4)
+        open(path, "wb").write(raw)
+        with pytest.raises(m.MoeiError):
+            small.restore(path)
+        with pytest.raises(m.MoeiError):
+            small.restore(str(tmp_path / "missing.bin"))
+        small.close()
+        b.close()
+    # an empty collection round-trips too
+    e = m.Eamc(desc, 4, 4)
+    p0 = str(tmp_path / "empty.bin")
+    e.save(p0)
+    e.load(T[:3])
+    e.restore(p0)
+    assert e.size == 0
+    e.close()
+
+
 def test_eamc_insert_replace_and_export(m):
     # App. B.1: at capacity the incoming EAM replaces the stored one it is most similar to
     rng = np.random.default_rng(5)
