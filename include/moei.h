@@ -274,7 +274,7 @@ int moei_cache_last_matches(moei_cache* c, int32_t* h_top, float* h_top_sim, int
  * applies, not the tighter fp32 one of the decode path).  Every picked expert must be
  * resident (the cache is not consulted or changed; a non-resident pick raises error flag
  * bit 1 and contributes zero).  Optional outputs d_idx_out[n][k], d_w_out[n][k] (device).
- * bf16 weights, H a multiple of 128 and <= 4096, E <= 2048, n <= 8192; scratch for the
+ * bf16 weights, H a multiple of 128 and <= 4096, I a multiple of 8, E <= 2048, n <= 8192; scratch for the
  * longest prompt so far is kept in the cache (allocated on a first or longer call, which
  * drains the device).  All work is queued on `stream`. */
 int moe_prefill_layer(moei_cache* c, int32_t* d_eam, int32_t layer,

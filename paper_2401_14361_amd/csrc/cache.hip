@@ -135,7 +135,8 @@ void prefill_scratch_free(PrefillScratch* p) {
     (void)hipFree(p->d_items);
     (void)hipFree(p->d_meta);
     (void)hipFree(p->d_cntw);
-    (void)hipFree(p->d_part);
+    (void)hipFree(p->d_act);
+    (void)hipFree(p->d_yc);
     *p = PrefillScratch{};
 }
 }  // namespace
@@ -629,17 +630,17 @@ extern "C" int moe_prefill_layer(moei_cache* c, int32_t* d_eam, int32_t layer, c
         if (e == hipSuccess) e = hipMalloc((void**)&p.d_w, nk * 4);
         if (e == hipSuccess) e = hipMalloc((void**)&p.d_perm, nk * 4);
         if (e == hipSuccess) e = hipMalloc((void**)&p.d_pgate, nk * 4);
-        if (e == hipSuccess) e = hipMalloc((void**)&p.d_where, nk * 8);
+        if (e == hipSuccess) e = hipMalloc((void**)&p.d_where, nk * 4);
         if (e == hipSuccess) e = hipMalloc(&p.d_items, (size_t)prefill_max_items(d, n_max) * prefill_item_bytes());
         if (e == hipSuccess) e = hipMalloc((void**)&p.d_meta, 8);
         if (e == hipSuccess) e = hipMalloc((void**)&p.d_cntw, (size_t)d.E * 4 * 4);
-        if (e == hipSuccess) e = hipMalloc((void**)&p.d_part, prefill_part_floats(d, n_max) * sizeof(float));
+        if (e == hipSuccess) e = hipMalloc((void**)&p.d_act, prefill_rows(d, n_max) * d.I * 2);
+        if (e == hipSuccess) e = hipMalloc((void**)&p.d_yc, prefill_rows(d, n_max) * d.H * sizeof(float));
         if (e != hipSuccess) {
             prefill_scratch_free(&p);
             MOEI_FAIL(MOEI_ENOMEM, "moe_prefill_layer: scratch allocation failed: %s", hipGetErrorString(e));
         }
         p.n_max = n_max;
-        p.seg_max = prefill_seg_max(d, n_max);
     }
     rc = launch_prefill(d, p, c->d_pool, c->slot_elems, c->n_total, c->d_slot_of + (size_t)layer * d.E,
                         c->S + layer * d.n_shared, d_eam + (size_t)layer * d.E, d_router_w, d_router_bias, d_X, n, d_Y,

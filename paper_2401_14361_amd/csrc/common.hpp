@@ -54,6 +54,10 @@ enum KernelId {
     K_FFN_FUSED,
     K_FFN_REDUCE,
     K_FFN_GROUP,
+    K_PF_ROUTE,
+    K_PF_GATEUP,
+    K_PF_DOWN,
+    K_PF_REDUCE,
     K_COUNT
 };
 extern bool g_prof_on;

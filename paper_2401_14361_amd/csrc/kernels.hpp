@@ -54,24 +54,22 @@ int launch_expert_ffn_grouped(const moei_model_desc& d, const void* d_pool, size
 
 // ---------------------------------------------------------------- prefill.hip
 struct PrefillScratch {
-    int n_max = 0;     // tokens the buffers are sized for
-    int seg_max = 0;
+    int n_max = 0;              // tokens the buffers are sized for
     int32_t* d_idx = nullptr;   // [n_max][k] picks
     float* d_w = nullptr;       // [n_max][k] gate weights
-    int32_t* d_perm = nullptr;  // [n_max*k]
-    float* d_pgate = nullptr;   // [n_max*k]
-    int32_t* d_where = nullptr;  // [n_max*k][2]
+    int32_t* d_perm = nullptr;  // [n_max*k] tokens grouped per expert
+    float* d_pgate = nullptr;   // [n_max*k] their gate weights
+    int32_t* d_where = nullptr;  // [n_max*k] row of every (token, pick)
     void* d_items = nullptr;
     int32_t* d_meta = nullptr;  // [2]
     int32_t* d_cntw = nullptr;  // [E][4]
-    float* d_part = nullptr;
+    uint16_t* d_act = nullptr;  // [n_max*(k+n_shared)][I] activations, bf16
+    float* d_yc = nullptr;      // [n_max*(k+n_shared)][H] contributions
 };
 int prefill_check(const moei_model_desc& d);
-int prefill_token_tile(const moei_model_desc& d);
 size_t prefill_item_bytes();
 int prefill_max_items(const moei_model_desc& d, int n_max);
-int prefill_seg_max(const moei_model_desc& d, int n_max);
-size_t prefill_part_floats(const moei_model_desc& d, int n_max);
+size_t prefill_rows(const moei_model_desc& d, int n_max);
 int launch_prefill(const moei_model_desc& d, const PrefillScratch& ps, const void* d_pool, size_t slot_elems,
                    int n_slots_total, const int32_t* d_slot_of_row, int shared_base, int32_t* d_eam_row,
                    const void* d_router_w, const float* d_router_bias, const void* d_X, int n, float* d_Y,

@@ -6,15 +6,17 @@
 //                             same summation order as the decode routing, so the same bits)
 //   2. prefill_count_kernel / prefill_place_kernel
 //                             histogram of the picks -> EAM row; tokens grouped per expert in
-//                             ascending token order, cut into items of <= TM tokens
-//   3. prefill_ffn_kernel     grouped SwiGLU expert FFN on the matrix cores: an item's tokens
-//                             sit in LDS, the expert's weights stream past once per item
-//   4. prefill_reduce_kernel  y[t] = sum of the token's partial rows, in pick order
-// With tens of tokens per expert the layer is still bound by streaming the weights (one
-// weight byte meets ~TM flops); the matrix cores only keep the arithmetic off the critical
-// path.  v_mfma_f32_16x16x32_bf16: A is 16 x 32 (lane l holds row l%16, k = 8*(l/16)..+8),
-// B is 32 x 16 (lane l holds column l%16, same k), D is 16 x 16 (lane l holds column l%16,
-// rows 4*(l/16)..+4).
+//                             ascending token order, cut into items of <= 64 tokens
+//   3. prefill_gateup_kernel, prefill_down_kernel
+//                             grouped SwiGLU expert FFN on the matrix cores as two tiled products
+//                             per item; an expert's weights pass once per item
+//   4. prefill_reduce_kernel  y[t] = sum of the token's rows, in pick order
+// With tens of tokens per expert the layer is still bound by streaming the weights (one weight
+// byte meets about as many flops as the item has tokens); the matrix cores keep the arithmetic
+// off the critical path.  v_mfma_f32_16x16x32_bf16: A is 16 x 32 (lane l holds row l%16,
+// k = 8*(l/16)..+8), B is 32 x 16 (lane l holds column l%16, same k), D is 16 x 16 (lane l holds
+// column l%16, rows 4*(l/16)..+4).
+#include <stdlib.h>
 #include <string.h>
 
 #include "kernels.hpp"
@@ -28,10 +30,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kPfWaves = 8;
-constexpr int kPfThreads = kPfWaves * kWave;
-constexpr int kPfChunk = 16 * kPfWaves;  // intermediate units per chunk: 16 per wavefront
-constexpr int kPfPad = 8;                // bf16 elements of padding per LDS row (bank spread)
+constexpr int kPfPad = 8;  // bf16 elements of padding per LDS row (bank spread)
 constexpr int kPfMaxE = 2048;
 
 struct PItem {
@@ -39,9 +38,14 @@ struct PItem {
     int32_t ntok;       // tokens of the item, <= TM
     int32_t list_off;   // routed: position of the item's first token in perm / pgate
     int32_t first_tok;  // shared expert: tokens first_tok .. first_tok + ntok - 1 with weight 1; else -1
+    int32_t row0;       // the item's first row of the activation / contribution buffers
 };
 
 // ------------------------------------------------------------------ 1. routing of n tokens
+// grid n: one workgroup of four wavefronts per token.  The token sits in LDS as fp32; logit
+// rows are dealt to the wavefronts, eight rows' loads in flight per round trip; every row's sum
+// runs over the chunks in ascending order, as in the decode routing.  Wavefront 0 then takes
+// the top-k.
 template <typename WT>
 __global__ void __launch_bounds__(4 * kWave) prefill_route_kernel(const void* __restrict__ Wv,
                                                                   const float* __restrict__ bias,
@@ -50,24 +54,22 @@ __global__ void __launch_bounds__(4 * kWave) prefill_route_kernel(const void* __
                                                                   float* __restrict__ w) {
     using V = WVec<WT>;
     extern __shared__ __align__(16) float smem[];
-    __shared__ int s_idx[4][kWave];
-    __shared__ float s_w[4][kWave];
-    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
-    float* xs = smem + (size_t)wv * H;           // this wavefront's token, fp32
-    float* z = smem + (size_t)4 * H + (size_t)wv * E;  // its logits
-    const int t = blockIdx.x * 4 + wv;
-    if (t >= n) return;  // uniform over the wavefront; no workgroup barrier below
+    __shared__ int s_idx[kWave];
+    __shared__ float s_w[kWave];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    float* xs = smem;      // [H] the token, fp32
+    float* z = smem + H;   // [E] its logits
+    const int t = blockIdx.x;
     const WT* W = reinterpret_cast<const WT*>(Wv);
     const WT* x = reinterpret_cast<const WT*>(Xv) + (size_t)t * H;
-    for (int c = lane; c < H; c += kWave) xs[c] = V::one(x + c);
-    s_idx[wv][lane] = 0;  // NaN logits leave ranks unassigned: such picks then name expert 0
-    s_w[wv][lane] = 0.f;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    // eight rows at a time, so that eight loads are in flight per round trip; every row's sum
-    // runs over the chunks in ascending order, as in the decode routing
+    for (int c = tid; c < H; c += 4 * kWave) xs[c] = V::one(x + c);
+    if (tid < kWave) {  // NaN logits leave ranks unassigned: such picks then name expert 0
+        s_idx[tid] = 0;
+        s_w[tid] = 0.f;
+    }
+    __syncthreads();
     constexpr int RB = 8;
-    for (int e0 = 0; e0 < E; e0 += RB) {
+    for (int e0 = wv * RB; e0 < E; e0 += 4 * RB) {
         float acc[RB];
 #pragma unroll
         for (int q = 0; q < RB; ++q) acc[q] = 0.f;
@@ -94,16 +96,16 @@ __global__ void __launch_bounds__(4 * kWave) prefill_route_kernel(const void* __
             if (lane == 0 && e0 + q < E) z[e0 + q] = zq + (bias ? bias[e0 + q] : 0.f);
         }
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    __syncthreads();
+    if (wv != 0) return;
     int my_idx;
     float my_w;
     if (E <= kRankMaxE) {
-        const float sel = wave_topk_rank(z, E, k, renorm, lane, s_idx[wv], s_w[wv], false);
+        const float sel = wave_topk_rank(z, E, k, renorm, lane, s_idx, s_w, false);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        my_idx = lane < k ? s_idx[wv][lane] : -1;
-        my_w = lane < k ? (renorm ? s_w[wv][lane] / sel : s_w[wv][lane]) : 0.f;
+        my_idx = lane < k ? s_idx[lane] : -1;
+        my_w = lane < k ? (renorm ? s_w[lane] / sel : s_w[lane]) : 0.f;
     } else {
         wave_topk(z, E, k, renorm, lane, my_idx, my_w);
     }
@@ -123,7 +125,7 @@ struct GroupArgsP {
     int32_t* eam_row;  // [E] row `layer` of the EAM
     int32_t* perm;     // [n*k] tokens grouped per expert, ascending token order inside an expert
     float* pgate;      // [n*k] their gate weights
-    int32_t* where;    // [n*k][2] (item, row) of every routed (token, pick)
+    int32_t* where;    // [n*k] row (= position in perm) of every routed (token, pick)
     PItem* items;
     int32_t* meta;  // [0] = items in all, [1] = routed items
     int32_t* cntw;  // [E][4] tokens that pick the expert, per wavefront range of the grouping kernels
@@ -201,20 +203,20 @@ __global__ void __launch_bounds__(kGrpThreads) prefill_place_kernel(GroupArgsP g
             const int r = pos + __popcll(mask & ((1ull << lane) - 1ull));
             g.perm[off + r] = t;
             g.pgate[off + r] = g.w[(size_t)t * g.k + j];
-            g.where[((size_t)t * g.k + j) * 2] = ioff + r / g.TM;
-            g.where[((size_t)t * g.k + j) * 2 + 1] = r % g.TM;
+            g.where[(size_t)t * g.k + j] = off + r;
         }
         pos += __popcll(mask);
     }
     const int slot = g.slot_of_row[e];
     if (cnt > 0 && slot < 0 && tid == 0) atomicOr(g.flags, 2);
     for (int it = tid; it * g.TM < cnt; it += kGrpThreads)
-        g.items[ioff + it] = PItem{slot, min(g.TM, cnt - it * g.TM), off + it * g.TM, -1};
+        g.items[ioff + it] = PItem{slot, min(g.TM, cnt - it * g.TM), off + it * g.TM, -1, off + it * g.TM};
     if (e == 0) {
         const int tiles = (g.n + g.TM - 1) / g.TM;
         for (int q = tid; q < g.n_shared * tiles; q += kGrpThreads) {
             const int s = q / tiles, tile = q - s * tiles;
-            g.items[n_routed + q] = PItem{g.shared_base + s, min(g.TM, g.n - tile * g.TM), 0, tile * g.TM};
+            g.items[n_routed + q] =
+                PItem{g.shared_base + s, min(g.TM, g.n - tile * g.TM), 0, tile * g.TM, g.n * g.k + s * g.n + tile * g.TM};
         }
         if (tid == 0) {
             g.meta[0] = n_routed + g.n_shared * tiles;
@@ -224,7 +226,20 @@ __global__ void __launch_bounds__(kGrpThreads) prefill_place_kernel(GroupArgsP g
 }
 
 // ------------------------------------------------------------------ 3. grouped expert FFN on the matrix cores
-struct PfArgs {
+// Two tiled matrix products per item (an expert and up to 64 of its tokens):
+//   3a. act[row][u] = silu(<W_gate[u], x_row>) * <W_up[u], x_row> * gate_row      (K = H)
+//   3b. yc[row][h]  = sum_u act[row][u] * W_down[h][u]                             (K = I)
+// `row` numbers the (token, pick) pairs in grouped order, then the (shared expert, token)
+// pairs.  The weights of an expert pass once per item; the small operand (inputs / activations)
+// goes through LDS in k-slices, double-buffered.
+constexpr int kTileTok = 64;   // tokens per item: four 16-token blocks
+constexpr int kMmThreads = 256;
+constexpr int kGuUnits = 64;   // 3a: intermediate units per workgroup, 16 per wavefront
+constexpr int kGuKS = 128;     // 3a: k-slice of inputs and weight rows in LDS
+constexpr int kDnCols = 512;   // 3b: output columns per workgroup, 128 per wavefront
+constexpr int kDnKS = 128;     // 3b: k-slice of the activations in LDS
+
+struct MmArgs {
     const uint16_t* pool;
     size_t slot_elems;
     int n_slots_total;
@@ -233,8 +248,9 @@ struct PfArgs {
     const uint16_t* X;  // [n][H] bf16
     const int32_t* perm;
     const float* pgate;
-    float* part;  // [workgroups][seg_max][TM][H]
-    int H, I, seg_max;
+    uint16_t* act;  // [rows][I] bf16
+    float* yc;      // [rows][H]
+    int H, I;
     int32_t* flags;
 };
 
@@ -248,231 +264,254 @@ __device__ __forceinline__ uint32_t bf16_bits(float f) {
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
-// The intermediate units of all items form one row space of n_items * I rows, split evenly
-// into contiguous ranges, one per workgroup; a range is cut at item boundaries into
-// segments.  Per segment: the item's tokens go to LDS (bf16, TM x H); per chunk of 128
-// units, phase 1 forms gate and up pre-activations for 16 units per wavefront (K = H),
-// the activations go to LDS as bf16 (TM x 128), phase 2 adds them times the down columns
-// into the wavefront's share of y (128-column groups), which stays in registers until the
-// segment ends.  TB = token blocks of 16 (TM = 16 TB), CGW = column groups per wavefront.
-template <int TB, int CGW>
-__global__ void __launch_bounds__(kPfThreads) prefill_ffn_kernel(PfArgs a) {
-    constexpr int TM = 16 * TB;
-    constexpr int PW = 4;  // k-steps of phase 1 in flight (2 loads each)
+// 3a.  grid (ceil(I / 64), items).  D = A B with A = 16 weight rows (units) x 32 k, B = 32 k x 16
+// tokens, both from LDS; a wavefront owns 16 units x 64 tokens (gate and up).  The weight rows
+// are fetched in 256-byte runs (a k-slice of a row), the next slice into registers while the
+// current one is multiplied.
+__global__ void __launch_bounds__(kMmThreads) prefill_gateup_kernel(MmArgs a) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
+    constexpr int ls = kGuKS + kPfPad;  // LDS row stride, elements
+    uint16_t* Xs = reinterpret_cast<uint16_t*>(smem_raw);  // [kTileTok][ls] inputs
+    uint16_t* Ws = Xs + (size_t)kTileTok * ls;             // [2 * kGuUnits][ls] gate rows, then up rows
+    __shared__ float s_gate[kTileTok];
+    const int item = blockIdx.y;
+    if (item >= a.meta[0]) return;
+    const PItem it = a.items[item];
+    if (it.slot < 0 || it.slot >= a.n_slots_total) return;  // the down kernel writes the zeros and raises the flag
     const int H = a.H, I = a.I;
-    const int xs_stride = H + kPfPad;
-    constexpr int act_stride = kPfChunk + kPfPad;
-    uint16_t* Xs = reinterpret_cast<uint16_t*>(smem_raw);  // [TM][H + pad]
-    uint16_t* Act = Xs + (size_t)TM * xs_stride;           // [TM][128 + pad]
-    float* s_gate = reinterpret_cast<float*>(Act + (size_t)TM * act_stride);  // [TM]
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int lrow = lane & 15, lgrp = lane >> 4;
-    const int n_items = a.meta[0];
-    const long total = (long)n_items * I;
-    const long R0 = total * blockIdx.x / gridDim.x, R1 = total * (blockIdx.x + 1) / gridDim.x;
-    const int n_cg = H / 128;
+    const uint16_t* wslot = a.pool + (size_t)it.slot * a.slot_elems;
+    const int u_wg = blockIdx.x * kGuUnits;
 
-    int seg = 0;
-    for (long row = R0; row < R1 && seg < a.seg_max; ++seg) {
-        const int item = (int)(row / I);
-        const int r0 = (int)(row - (long)item * I);
-        const int r1 = (int)min((long)I, r0 + (R1 - row));
-        row += r1 - r0;
-        const PItem it = a.items[item];
-        const bool slot_ok = it.slot >= 0 && it.slot < a.n_slots_total;
-        if (!slot_ok && tid == 0) atomicOr(a.flags, 1);
-        const uint16_t* wslot = a.pool + (size_t)(slot_ok ? it.slot : 0) * a.slot_elems;
-        __syncthreads();  // the previous segment is done with the LDS
-        // the item's tokens: gate weights and inputs (rows beyond ntok are zero)
-        if (tid < TM) {
-            float gw = 0.f;
-            if (tid < it.ntok && slot_ok) gw = it.first_tok >= 0 ? 1.0f : a.pgate[it.list_off + tid];
-            s_gate[tid] = gw;
+    if (tid < kTileTok) s_gate[tid] = tid < it.ntok ? (it.first_tok >= 0 ? 1.0f : a.pgate[it.list_off + tid]) : 0.f;
+    constexpr int VPR = kGuKS / 8;                                // 16-byte vectors per row and slice
+    constexpr int NX = kTileTok * VPR / kMmThreads;               // input vectors per thread and slice
+    constexpr int NW = 2 * kGuUnits * VPR / kMmThreads;           // weight vectors per thread and slice
+    const uint16_t* xsrc[NX];
+#pragma unroll
+    for (int j = 0; j < NX; ++j) {
+        const int v = tid + kMmThreads * j, r = v / VPR;
+        int tok = -1;
+        if (r < it.ntok) tok = it.first_tok >= 0 ? it.first_tok + r : a.perm[it.list_off + r];
+        xsrc[j] = tok >= 0 ? a.X + (size_t)tok * H + (v % VPR) * 8 : nullptr;
+    }
+    const uint16_t* wsrc[NW];
+#pragma unroll
+    for (int j = 0; j < NW; ++j) {
+        const int v = tid + kMmThreads * j, rho = v / VPR;  // rho: 0..63 gate rows, 64..127 up rows
+        const int u = min(u_wg + (rho & (kGuUnits - 1)), I - 1);  // rows past I are masked at the end
+        wsrc[j] = wslot + (size_t)u * 3 * H + (rho >= kGuUnits ? H : 0) + (v % VPR) * 8;
+    }
+    const int n_slices = (H + kGuKS - 1) / kGuKS;
+    uint4 xst[NX], wst[NW];
+    auto fetch = [&](int s) {
+#pragma unroll
+        for (int j = 0; j < NW; ++j) {
+            const int kk = s * kGuKS + ((tid + kMmThreads * j) % VPR) * 8;
+            wst[j] = kk < H ? *reinterpret_cast<const uint4*>(wsrc[j] + s * kGuKS) : make_uint4(0, 0, 0, 0);
         }
-        for (int v = tid; v < TM * (H / 8); v += kPfThreads) {
-            const int r = v / (H / 8), c = v - r * (H / 8);
-            uint4 val = make_uint4(0, 0, 0, 0);
-            if (r < it.ntok) {
-                const int tok = it.first_tok >= 0 ? it.first_tok + r : a.perm[it.list_off + r];
-                val = *reinterpret_cast<const uint4*>(a.X + (size_t)tok * H + c * 8);
-            }
-            *reinterpret_cast<uint4*>(Xs + (size_t)r * xs_stride + c * 8) = val;
+#pragma unroll
+        for (int j = 0; j < NX; ++j) {
+            const int kk = s * kGuKS + ((tid + kMmThreads * j) % VPR) * 8;
+            xst[j] = (xsrc[j] && kk < H) ? *reinterpret_cast<const uint4*>(xsrc[j] + s * kGuKS) : make_uint4(0, 0, 0, 0);
         }
-        f32x4 Y[CGW][TB][8];
+    };
+    auto put = [&]() {
 #pragma unroll
-        for (int q = 0; q < CGW; ++q)
+        for (int j = 0; j < NW; ++j) {
+            const int v = tid + kMmThreads * j;
+            *reinterpret_cast<uint4*>(Ws + (size_t)(v / VPR) * ls + (v % VPR) * 8) = wst[j];
+        }
 #pragma unroll
-            for (int tb = 0; tb < TB; ++tb)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) Y[q][tb][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < NX; ++j) {
+            const int v = tid + kMmThreads * j;
+            *reinterpret_cast<uint4*>(Xs + (size_t)(v / VPR) * ls + (v % VPR) * 8) = xst[j];
+        }
+    };
 
-        for (int c0 = r0; c0 < r1; c0 += kPfChunk) {
-            __syncthreads();  // inputs staged / the previous chunk's activations consumed
-            // ---- phase 1: units c0 + 16 wv + (0..15), K = H in steps of 32
-            {
-                const int u = min(c0 + 16 * wv + lrow, r1 - 1);  // rows past the segment are masked below
-                const uint16_t* wg = wslot + (size_t)u * 3 * H + lgrp * 8;
-                const uint16_t* wu = wg + H;
-                const uint16_t* xb = Xs + (size_t)lrow * xs_stride + lgrp * 8;
-                f32x4 G[TB], U[TB];
+    f32x4 G[4], U[4];
 #pragma unroll
-                for (int tb = 0; tb < TB; ++tb) G[tb] = U[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
-                const int steps = H / 32;
-                bf16x8 ag[PW], au[PW];
+    for (int tb = 0; tb < 4; ++tb) G[tb] = U[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const uint16_t* ag = Ws + (size_t)(16 * wv + lrow) * ls + lgrp * 8;
+    const uint16_t* au = ag + (size_t)kGuUnits * ls;
+    const uint16_t* xb = Xs + (size_t)lrow * ls + lgrp * 8;
+
+    fetch(0);
+    for (int s = 0; s < n_slices; ++s) {
+        __syncthreads();  // the previous slice has been multiplied
+        put();
+        __syncthreads();
+        if (s + 1 < n_slices) fetch(s + 1);  // on its way while this slice is multiplied
+        const int steps = min(kGuKS, H - s * kGuKS) / 32;
+        for (int ks = 0; ks < steps; ++ks) {
+            const bf16x8 cg = ld_bf16x8(ag + ks * 32), cu = ld_bf16x8(au + ks * 32);
 #pragma unroll
-                for (int q = 0; q < PW; ++q) {
-                    const int s = q < steps ? q : 0;
-                    ag[q] = ld_bf16x8(wg + s * 32);
-                    au[q] = ld_bf16x8(wu + s * 32);
-                }
-                for (int s0 = 0; s0 < steps; s0 += PW) {
-#pragma unroll
-                    for (int q = 0; q < PW; ++q) {
-                        const int s = s0 + q;
-                        const bf16x8 cg_ = ag[q], cu_ = au[q];
-                        const int sn = s + PW < steps ? s + PW : 0;  // past the end: an in-bounds dummy
-                        ag[q] = ld_bf16x8(wg + sn * 32);
-                        au[q] = ld_bf16x8(wu + sn * 32);
-                        if (s < steps) {
-#pragma unroll
-                            for (int tb = 0; tb < TB; ++tb) {
-                                const bf16x8 b = ld_bf16x8(xb + (size_t)tb * 16 * xs_stride + s * 32);
-                                G[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cg_, b, G[tb], 0, 0, 0);
-                                U[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cu_, b, U[tb], 0, 0, 0);
-                            }
-                        }
-                    }
-                }
-                // D[unit 4*lgrp + v][token lrow] -> activation, bf16, to Act[token][unit]
-#pragma unroll
-                for (int tb = 0; tb < TB; ++tb) {
-                    const float gw = s_gate[tb * 16 + lrow];
-                    uint32_t h[4];
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int unit = c0 + 16 * wv + lgrp * 4 + v;
-                        const float act = unit < r1 ? silu_f(G[tb][v]) * U[tb][v] * gw : 0.f;
-                        h[v] = bf16_bits(act);
-                    }
-                    uint2 packed = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
-                    *reinterpret_cast<uint2*>(Act + (size_t)(tb * 16 + lrow) * act_stride + 16 * wv + lgrp * 4) = packed;
-                }
-            }
-            __syncthreads();
-            // ---- phase 2: y[token][column group] += Act[token][unit] * W_down[unit][column]
-#pragma unroll
-            for (int q = 0; q < CGW; ++q) {
-                const int cg = wv + kPfWaves * q;
-                if (cg < n_cg) {  // uniform over the wavefront
-                    const uint16_t* wd = wslot + 2 * H + cg * 128 + lrow * 8;
-#pragma unroll 1
-                    for (int ks = 0; ks < kPfChunk / 32; ++ks) {
-                        // eight units for eight columns per lane, transposed in registers to eight
-                        // columns of eight units each (the column a lane serves in matrix i is
-                        // cg*128 + 8*lrow + i)
-                        uint4 ld[8];
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) {
-                            const int unit = min(c0 + ks * 32 + lgrp * 8 + j, r1 - 1);
-                            ld[j] = *reinterpret_cast<const uint4*>(wd + (size_t)unit * 3 * H);
-                        }
-                        bf16x8 av[TB];
-#pragma unroll
-                        for (int tb = 0; tb < TB; ++tb)
-                            av[tb] = ld_bf16x8(Act + (size_t)(tb * 16 + lrow) * act_stride + ks * 32 + lgrp * 8);
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) {
-                            uint32_t dw[4];
-#pragma unroll
-                            for (int p = 0; p < 4; ++p) {
-                                const uint32_t lo = reinterpret_cast<const uint32_t*>(&ld[2 * p])[i >> 1];
-                                const uint32_t hi = reinterpret_cast<const uint32_t*>(&ld[2 * p + 1])[i >> 1];
-                                dw[p] = (i & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u)
-                                                : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-                            }
-                            bf16x8 wt;
-                            memcpy(&wt, dw, 16);
-#pragma unroll
-                            for (int tb = 0; tb < TB; ++tb)
-                                Y[q][tb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[tb], wt, Y[q][tb][i], 0, 0, 0);
-                        }
-                    }
-                }
+            for (int tb = 0; tb < 4; ++tb) {
+                const bf16x8 b = ld_bf16x8(xb + (size_t)tb * 16 * ls + ks * 32);
+                G[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cg, b, G[tb], 0, 0, 0);
+                U[tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cu, b, U[tb], 0, 0, 0);
             }
         }
-        // ---- the segment's partial rows: D[token 4*lgrp + v][column lrow] of matrix i is column cg*128 + 8*lrow + i
-        float* out = a.part + ((size_t)blockIdx.x * a.seg_max + seg) * TM * H;
+    }
+    // D[unit 4*lgrp + v][token lrow] -> activation, bf16, act[row][unit]
+    const bool packed = (I & 3) == 0;
+    const int u0 = u_wg + 16 * wv + lgrp * 4;
 #pragma unroll
-        for (int q = 0; q < CGW; ++q) {
-            const int cg = wv + kPfWaves * q;
-            if (cg < n_cg) {
+    for (int tb = 0; tb < 4; ++tb) {
+        const int tok = tb * 16 + lrow;
+        if (tok >= it.ntok) continue;
+        const float gw = s_gate[tok];
+        uint16_t* dst_row = a.act + (size_t)(it.row0 + tok) * I;
+        uint32_t h[4];
 #pragma unroll
-                for (int tb = 0; tb < TB; ++tb)
+        for (int v = 0; v < 4; ++v) h[v] = bf16_bits(silu_f(G[tb][v]) * U[tb][v] * gw);
+        if (packed && u0 + 3 < I) {
+            *reinterpret_cast<uint2*>(dst_row + u0) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+        } else {
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        float* dst = out + (size_t)(tb * 16 + lgrp * 4 + v) * H + cg * 128 + lrow * 8;
-                        *reinterpret_cast<float4*>(dst) =
-                            make_float4(Y[q][tb][0][v], Y[q][tb][1][v], Y[q][tb][2][v], Y[q][tb][3][v]);
-                        *reinterpret_cast<float4*>(dst + 4) =
-                            make_float4(Y[q][tb][4][v], Y[q][tb][5][v], Y[q][tb][6][v], Y[q][tb][7][v]);
-                    }
-            }
+            for (int v = 0; v < 4; ++v)
+                if (u0 + v < I) dst_row[u0 + v] = (uint16_t)h[v];
         }
     }
 }
 
-// ------------------------------------------------------------------ 4. y[t] = sum of the token's partial rows
-// One workgroup per token.  The partial rows of contribution j (the k picks in pick order, then
-// the shared experts) are those of the segments that cover its item; they are listed in LDS
-// first and then added in list order.
-constexpr int kPfListMax = 1024;
-__global__ void __launch_bounds__(256) prefill_reduce_kernel(const float* __restrict__ part,
-                                                             const int32_t* __restrict__ where,
-                                                             const int32_t* __restrict__ meta, int n, int k, int n_shared,
-                                                             int TM, int I, int H, int n_blocks, int seg_max,
-                                                             float* __restrict__ y, int32_t* __restrict__ flags) {
-    __shared__ int s_list[kPfListMax];
-    __shared__ int s_n;
-    const int t = blockIdx.x;
-    const int n_items = meta[0], n_routed = meta[1];
-    const long total = (long)n_items * I;
-    if (threadIdx.x == 0) {
-        int cnt = 0;
-        const int tiles = (n + TM - 1) / TM;
-        for (int j = 0; j < k + n_shared; ++j) {
-            int item, row;
-            if (j < k) {
-                item = where[((size_t)t * k + j) * 2];
-                row = where[((size_t)t * k + j) * 2 + 1];
-            } else {
-                item = n_routed + (j - k) * tiles + t / TM;
-                row = t % TM;
-            }
-            const long lo = (long)item * I, hi = lo + I;
-            int g = (int)(lo * n_blocks / total);
-            while (g + 1 < n_blocks && total * (g + 1) / n_blocks <= lo) ++g;
-            while (g > 0 && total * g / n_blocks > lo) --g;
-            for (; g < n_blocks && total * g / n_blocks < hi; ++g) {
-                const long b0 = total * g / n_blocks, b1 = total * (g + 1) / n_blocks;
-                if (b1 <= lo || b1 == b0) continue;  // ends before the item, or an empty range
-                const int seg = item - (int)(b0 / I);
-                if (seg >= seg_max || cnt >= kPfListMax) {
-                    atomicOr(flags, 4);
-                    continue;
+// 3b.  grid (ceil(H / 512), items).  D = A B with A = 16 tokens x 32 units from LDS, B = 32 units x
+// 16 columns of W_down.  The slot stores W_down unit-major, so a lane loads eight units x eight
+// columns and transposes them in registers into eight operands of eight units each; the column
+// a lane serves in matrix i is then col0 + 8*lrow + i (which 16 columns a matrix covers is only
+// a labelling).  A wavefront owns 64 tokens x 128 columns.
+__global__ void __launch_bounds__(kMmThreads) prefill_down_kernel(MmArgs a) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    constexpr int as_stride = kDnKS + kPfPad;
+    uint16_t* As = reinterpret_cast<uint16_t*>(smem_raw);  // [2][kTileTok][as_stride]
+    const int item = blockIdx.y;
+    if (item >= a.meta[0]) return;
+    const PItem it = a.items[item];
+    const int H = a.H, I = a.I;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int lrow = lane & 15, lgrp = lane >> 4;
+    const int col0 = blockIdx.x * kDnCols + 128 * wv;
+    const bool active = col0 < H;  // uniform over the wavefront
+    if (it.slot < 0 || it.slot >= a.n_slots_total) {  // not resident: the rows are zero, the flag says so
+        if (tid == 0) atomicOr(a.flags, 1);
+        const int c_end = min(H, (int)(blockIdx.x + 1) * kDnCols);
+        for (int r = 0; r < it.ntok; ++r)
+            for (int c = blockIdx.x * kDnCols + tid; c < c_end; c += kMmThreads) a.yc[(size_t)(it.row0 + r) * H + c] = 0.f;
+        return;
+    }
+    const uint16_t* wd = a.pool + (size_t)it.slot * a.slot_elems + 2 * H + (active ? col0 : 0) + lrow * 8;
+
+    constexpr int VPR = kDnKS / 8;                   // 16
+    constexpr int NV = kTileTok * VPR / kMmThreads;  // 4
+    const uint16_t* arow[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int v = tid + kMmThreads * j;
+        const int r = v / VPR;
+        arow[j] = r < it.ntok ? a.act + (size_t)(it.row0 + r) * I + (v % VPR) * 8 : nullptr;
+    }
+    const int n_slices = (I + kDnKS - 1) / kDnKS;
+    uint4 stage[NV];
+    auto fetch = [&](int s) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int kk = s * kDnKS + ((tid + kMmThreads * j) % VPR) * 8;
+            stage[j] = (arow[j] && kk < I) ? *reinterpret_cast<const uint4*>(arow[j] + s * kDnKS) : make_uint4(0, 0, 0, 0);
+        }
+    };
+    auto put = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int v = tid + kMmThreads * j;
+            *reinterpret_cast<uint4*>(As + ((size_t)buf * kTileTok + v / VPR) * as_stride + (v % VPR) * 8) = stage[j];
+        }
+    };
+    auto load_w = [&](int k0, uint4* dst) {  // units k0 + 8*lgrp + j (clamped: their activations are zero)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            dst[j] = *reinterpret_cast<const uint4*>(wd + (size_t)min(k0 + lgrp * 8 + j, I - 1) * 3 * H);
+    };
+
+    f32x4 Y[4][8];
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) Y[tb][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    fetch(0);
+    put(0);
+    __syncthreads();
+    uint4 cur[8], nxt[8];
+    load_w(0, cur);
+    for (int s = 0; s < n_slices; ++s) {
+        if (s + 1 < n_slices) fetch(s + 1);
+        const uint16_t* ab = As + ((size_t)(s & 1) * kTileTok + lrow) * as_stride + lgrp * 8;
+        const int k0 = s * kDnKS;
+        const int steps = (min(kDnKS, I - k0) + 31) / 32;
+#pragma unroll 1
+        for (int ks = 0; ks < steps; ++ks) {
+            // the next step's weights (the next slice's first step after the last one; past the
+            // end an in-bounds dummy)
+            int kn = k0 + (ks + 1) * 32;
+            if (kn >= I) kn = 0;
+            load_w(kn, nxt);
+            bf16x8 av[4];
+#pragma unroll
+            for (int tb = 0; tb < 4; ++tb) av[tb] = ld_bf16x8(ab + (size_t)tb * 16 * as_stride + ks * 32);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                uint32_t dw[4];
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const uint32_t lo = reinterpret_cast<const uint32_t*>(&cur[2 * p])[i >> 1];
+                    const uint32_t hi = reinterpret_cast<const uint32_t*>(&cur[2 * p + 1])[i >> 1];
+                    dw[p] = (i & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
                 }
-                s_list[cnt++] = ((g * seg_max + seg) * TM + row);
+                bf16x8 wt;
+                memcpy(&wt, dw, 16);
+#pragma unroll
+                for (int tb = 0; tb < 4; ++tb)
+                    Y[tb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[tb], wt, Y[tb][i], 0, 0, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) cur[j] = nxt[j];
+        }
+        if (s + 1 < n_slices) put((s + 1) & 1);
+        __syncthreads();
+    }
+    if (!active) return;
+    // D[token 4*lgrp + v][column lrow] of matrix i is column col0 + 8*lrow + i
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int tok = tb * 16 + lgrp * 4 + v;
+            if (tok < it.ntok) {
+                float* dst = a.yc + (size_t)(it.row0 + tok) * H + col0 + lrow * 8;
+                *reinterpret_cast<float4*>(dst) = make_float4(Y[tb][0][v], Y[tb][1][v], Y[tb][2][v], Y[tb][3][v]);
+                *reinterpret_cast<float4*>(dst + 4) = make_float4(Y[tb][4][v], Y[tb][5][v], Y[tb][6][v], Y[tb][7][v]);
             }
         }
-        s_n = cnt;
-    }
+}
+
+// ------------------------------------------------------------------ 4. y[t] = sum of the token's rows, in pick order
+// grid n, one workgroup per token: the k picks' rows, then the shared experts' rows.
+__global__ void __launch_bounds__(256) prefill_reduce_kernel(const float* __restrict__ yc,
+                                                             const int32_t* __restrict__ where, int n, int k,
+                                                             int n_shared, int H, float* __restrict__ y) {
+    __shared__ int s_rows[kWave + kWave];
+    const int t = blockIdx.x;
+    const int nc = k + n_shared;
+    if ((int)threadIdx.x < nc)
+        s_rows[threadIdx.x] = (int)threadIdx.x < k ? where[(size_t)t * k + threadIdx.x] : n * k + ((int)threadIdx.x - k) * n + t;
     __syncthreads();
-    const int cnt = s_n;
     for (int c = threadIdx.x; c < H / 4; c += 256) {
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int e = 0; e < cnt; ++e) {
-            const float4 v = *reinterpret_cast<const float4*>(part + (size_t)s_list[e] * H + c * 4);
+        for (int j = 0; j < nc; ++j) {
+            const float4 v = *reinterpret_cast<const float4*>(yc + (size_t)s_rows[j] * H + c * 4);
             acc.x += v.x;
             acc.y += v.y;
             acc.z += v.z;
@@ -480,18 +519,6 @@ __global__ void __launch_bounds__(256) prefill_reduce_kernel(const float* __rest
         }
         *reinterpret_cast<float4*>(y + (size_t)t * H + c * 4) = acc;
     }
-}
-
-int g_pf_cus = 0;
-int pf_compute_units() {
-    if (g_pf_cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            n = 256;
-        g_pf_cus = n;
-    }
-    return g_pf_cus;
 }
 
 template <typename K>
@@ -513,28 +540,20 @@ int pf_allow_lds(K kernel, size_t bytes) {
 
 }  // namespace
 
-int prefill_token_tile(const moei_model_desc& d) { return d.H <= 2048 ? 32 : 16; }
-
 int prefill_check(const moei_model_desc& d) {
     if (d.wdtype != MOEI_WDTYPE_BF16) MOEI_FAIL(MOEI_EINVAL, "moe_prefill_layer: bf16 weights only");
     if (d.H % 128 != 0 || d.H > 4096)
         MOEI_FAIL(MOEI_ECAPACITY, "moe_prefill_layer: H = %d must be a multiple of 128 and at most 4096", d.H);
+    if (d.I % 8 != 0) MOEI_FAIL(MOEI_ECAPACITY, "moe_prefill_layer: I = %d must be a multiple of 8", d.I);
     if (d.E > kPfMaxE) MOEI_FAIL(MOEI_ECAPACITY, "moe_prefill_layer: E = %d exceeds %d", d.E, kPfMaxE);
     return MOEI_OK;
 }
 
 size_t prefill_item_bytes() { return sizeof(PItem); }
 int prefill_max_items(const moei_model_desc& d, int n_max) {
-    const int TM = prefill_token_tile(d);
-    return (n_max * d.k + TM - 1) / TM + d.E + d.n_shared * ((n_max + TM - 1) / TM);
+    return (n_max * d.k + kTileTok - 1) / kTileTok + d.E + d.n_shared * ((n_max + kTileTok - 1) / kTileTok);
 }
-int prefill_seg_max(const moei_model_desc& d, int n_max) {
-    const int G = pf_compute_units();
-    return (prefill_max_items(d, n_max) + G - 1) / G + 1;
-}
-size_t prefill_part_floats(const moei_model_desc& d, int n_max) {
-    return (size_t)pf_compute_units() * prefill_seg_max(d, n_max) * prefill_token_tile(d) * d.H;
-}
+size_t prefill_rows(const moei_model_desc& d, int n_max) { return (size_t)n_max * (d.k + d.n_shared); }
 
 int launch_prefill(const moei_model_desc& d, const PrefillScratch& ps, const void* d_pool, size_t slot_elems,
                    int n_slots_total, const int32_t* d_slot_of_row, int shared_base, int32_t* d_eam_row,
@@ -545,38 +564,34 @@ int launch_prefill(const moei_model_desc& d, const PrefillScratch& ps, const voi
     if (n > ps.n_max) MOEI_FAIL(MOEI_ECAPACITY, "moe_prefill_layer: n = %d exceeds the scratch for %d tokens", n, ps.n_max);
     if ((uintptr_t)d_X % 16 != 0 || (uintptr_t)d_pool % 16 != 0 || (slot_elems * 2) % 16 != 0 || (uintptr_t)d_Y % 16 != 0)
         MOEI_FAIL(MOEI_EINVAL, "moe_prefill_layer: buffers must be 16-byte aligned");
-    const int TM = prefill_token_tile(d);
     const int vec_ok = (d.H % 8 == 0) && ((uintptr_t)d_router_w % 16 == 0);
-    const size_t route_smem = ((size_t)4 * d.H + (size_t)4 * d.E) * sizeof(float);
+    const size_t route_smem = ((size_t)d.H + (size_t)d.E) * sizeof(float);
     rc = pf_allow_lds(prefill_route_kernel<uint16_t>, route_smem);
     if (rc) return rc;
-    launch(K_ROUTE_TOPK, prefill_route_kernel<uint16_t>, dim3((n + 3) / 4), dim3(4 * kWave), route_smem, s, d_router_w,
+    launch(K_PF_ROUTE, prefill_route_kernel<uint16_t>, dim3(n), dim3(4 * kWave), route_smem, s, d_router_w,
            d_router_bias, d_X, n, d.H, d.E, d.k, (int)(d.renorm_topk != 0), vec_ok, ps.d_idx, ps.d_w);
     MOEI_LAUNCH_CHECK();
-    GroupArgsP g{ps.d_idx, ps.d_w, n, d.k, d.E, d.n_shared, TM, d_slot_of_row, shared_base, d_eam_row, ps.d_perm,
+    GroupArgsP g{ps.d_idx, ps.d_w, n, d.k, d.E, d.n_shared, kTileTok, d_slot_of_row, shared_base, d_eam_row, ps.d_perm,
                  ps.d_pgate, ps.d_where, reinterpret_cast<PItem*>(ps.d_items), ps.d_meta, ps.d_cntw, d_flags};
     launch(K_FFN_GROUP, prefill_count_kernel, dim3(d.E), dim3(kGrpThreads), 0, s, g);
     MOEI_LAUNCH_CHECK();
     launch(K_FFN_GROUP, prefill_place_kernel, dim3(d.E), dim3(kGrpThreads), 0, s, g);
     MOEI_LAUNCH_CHECK();
-    const int G = pf_compute_units();
-    PfArgs a{reinterpret_cast<const uint16_t*>(d_pool), slot_elems, n_slots_total,
+    // the number of items is known on the device only: the grids cover the largest possible count
+    const int max_items = prefill_max_items(d, n);
+    MmArgs a{reinterpret_cast<const uint16_t*>(d_pool), slot_elems, n_slots_total,
              reinterpret_cast<const PItem*>(ps.d_items), ps.d_meta, reinterpret_cast<const uint16_t*>(d_X), ps.d_perm,
-             ps.d_pgate, ps.d_part, d.H, d.I, ps.seg_max, d_flags};
-    const size_t smem = ((size_t)TM * (d.H + kPfPad) + (size_t)TM * (kPfChunk + kPfPad)) * 2 + (size_t)TM * 4;
-    if (TM == 32) {
-        rc = pf_allow_lds(prefill_ffn_kernel<2, 2>, smem);
-        if (rc) return rc;
-        launch(K_FFN_FUSED, prefill_ffn_kernel<2, 2>, dim3(G), dim3(kPfThreads), smem, s, a);
-    } else {
-        rc = pf_allow_lds(prefill_ffn_kernel<1, 4>, smem);
-        if (rc) return rc;
-        launch(K_FFN_FUSED, prefill_ffn_kernel<1, 4>, dim3(G), dim3(kPfThreads), smem, s, a);
-    }
+             ps.d_pgate, ps.d_act, ps.d_yc, d.H, d.I, d_flags};
+    const size_t gu_smem = (size_t)(kTileTok + 2 * kGuUnits) * (kGuKS + kPfPad) * 2;
+    launch(K_PF_GATEUP, prefill_gateup_kernel, dim3((d.I + kGuUnits - 1) / kGuUnits, max_items), dim3(kMmThreads), gu_smem,
+           s, a);
     MOEI_LAUNCH_CHECK();
-    launch(K_FFN_REDUCE, prefill_reduce_kernel, dim3(n), dim3(256), 0, s, (const float*)ps.d_part,
-           (const int32_t*)ps.d_where, (const int32_t*)ps.d_meta, n, d.k, d.n_shared, TM, d.I, d.H, G, ps.seg_max, d_Y,
-           d_flags);
+    const size_t dn_smem = (size_t)2 * kTileTok * (kDnKS + kPfPad) * 2;
+    launch(K_PF_DOWN, prefill_down_kernel, dim3((d.H + kDnCols - 1) / kDnCols, max_items), dim3(kMmThreads), dn_smem, s,
+           a);
+    MOEI_LAUNCH_CHECK();
+    launch(K_PF_REDUCE, prefill_reduce_kernel, dim3(n), dim3(256), 0, s, (const float*)ps.d_yc,
+           (const int32_t*)ps.d_where, n, d.k, d.n_shared, d.H, d_Y);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
 }
