@@ -41,7 +41,7 @@ def to_f64(a) -> np.ndarray:
 
 # ---------------------------------------------------------- step 1: router, top-k
 def router_logits(W_r, x, bias=None) -> np.ndarray:
-    """logit_j = sum_h W_r[j][h] x[h] (+ b_j).  Sec. 2: "the router assigns each token"."""
+    """logit_j = sum_h W_r[j][h] x[h] (+ b_j): the router scores of one token (Sec. 2)."""
     z = to_f64(W_r) @ to_f64(x)
     if bias is not None:
         z = z + to_f64(bias)
@@ -352,7 +352,7 @@ class ExpertCache:
         return out
 
     def prefetch(self, pf_order, ev_order, V, depth: int, protect=()):
-        """Prefetching into the cache (Sec. 4.6, "enhancing the cache with prefetching").
+        """Prefetching into the cache (Sec. 4.6: the cache is extended by prefetching).
 
         reading (the paper leaves the mechanism out): after a layer's retrieval the
         first ``depth`` entries of ``pf_order`` (most likely future experts first)
