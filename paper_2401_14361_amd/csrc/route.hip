@@ -1,9 +1,8 @@
 // Step 1 and 2 of the layer step: router GEMV, softmax + top-k, EAM update.
 //
-// The router assigns each token to k of the E experts of a layer (Sec. 2 of the
-// paper); every assignment increments the request's Expert Activation Matrix
-// (Sec. 4.3).  One wavefront serves one token: the E logits sit in LDS, each of
-// the k rounds is a 64-lane butterfly arg-max.
+// Every token goes to k of a layer's E experts (Sec. 2 of the paper); each such pick
+// adds one to the request's Expert Activation Matrix (Sec. 4.3).  One wavefront serves
+// one token: the E logits sit in LDS and every expert's rank is counted against them.
 #include "kernels.hpp"
 #include "topk.hpp"
 #include "wtypes.hpp"

@@ -1,5 +1,5 @@
 // Softmax + top-k of one token's router logits by a single wavefront (Sec. 2 of the paper:
-// the router assigns each token to k of the E experts of a layer).  Shared by the routing
+// every token goes to k of a layer's E experts).  Shared by the routing
 // kernels and by the fused layer kernel.
 #pragma once
 
