@@ -431,11 +431,12 @@ __global__ void __launch_bounds__(kPickThreads) eamc_pick_kernel(PickArgs a) {
         a.cand[(cbase + blockIdx.x) * 2 + 1] = r.nt;
         a.cand_idx[cbase + blockIdx.x] = r.idx;
         __threadfence();
-        s_ticket = __hip_atomic_fetch_add(&a.ticket[b], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        s_ticket = __hip_atomic_fetch_add(&a.ticket[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (s_ticket != gridDim.x - 1) return;
-    __threadfence();
+    if (tid == 0) __threadfence();  // one acquire for the workgroup (the winners are read past the caches anyway)
+    __syncthreads();
     Best fin = make_best(0, 1, -1);
     for (int i = tid; i < (int)gridDim.x; i += kPickThreads) {
         const int idx = __hip_atomic_load(&a.cand_idx[cbase + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -572,11 +573,12 @@ __global__ void __launch_bounds__(kPickThreads) eamc_topm_kernel(TopmArgs a) {
     if (!single) {
         if (tid == 0) {
             __threadfence();
-            s_ticket = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            s_ticket = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __syncthreads();
         if (s_ticket != gridDim.x - 1) return;
-        __threadfence();
+        if (tid == 0) __threadfence();
+        __syncthreads();
         const int total = (int)gridDim.x * a.m;  // the host keeps this within kTopmPerThread per thread
         Best mine[kTopmPerThread];
 #pragma unroll

@@ -162,8 +162,11 @@ __global__ void __launch_bounds__(kWave) route_fused_kernel(RouteFusedArgs a) {
     acc = wave_sum_dpp(acc);
     if (lane == 0) {
         a.logits[e] = acc + (a.bias ? a.bias[e] : 0.f);
+        // release by the fence, then a relaxed arrival count (an acquire-release read-modify-write
+        // would repeat the cache write-back and add an invalidate in every wavefront); only the
+        // last to arrive needs the acquire, which is the fence below
         __threadfence();
-        s_ticket = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        s_ticket = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (s_ticket != gridDim.x - 1) return;
