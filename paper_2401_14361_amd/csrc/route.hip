@@ -105,84 +105,95 @@ __global__ void eam_update_kernel(int32_t* __restrict__ eam, int B, int L, int E
 }
 
 // Routing of the fused layer step for one token in ONE launch: a wavefront per expert
-// forms logit = <W_r[e], x> + b_e; the last wavefront to finish (arrival counter) then takes
+// forms logit = <W_r[e], x> + b_e; the last workgroup to finish (arrival counter) then takes
 // the top-k, updates the EAM row and writes the slot ids / gate weights the FFN reads.
+constexpr int kRouteWaves = 4;  // expert rows per workgroup: fewer workgroups, fewer device-scope fences
 template <typename WT>
-__global__ void __launch_bounds__(kWave) route_fused_kernel(RouteFusedArgs a) {
+__global__ void __launch_bounds__(kRouteWaves * kWave) route_fused_kernel(RouteFusedArgs a) {
     using V = WVec<WT>;
     extern __shared__ float z[];  // E logits, then E slot ids, then the E counts of this layer's EAM row
     __shared__ unsigned s_ticket;
     __shared__ int s_pick[kWave];
     __shared__ float s_pw[kWave];
+    __shared__ float s_sel;
     int* s_slot = reinterpret_cast<int*>(z + a.E);
     int* s_eam = s_slot + a.E;
-    const int e = blockIdx.x;
-    const int lane = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    constexpr int NT = kRouteWaves * kWave;
+    const int e = blockIdx.x * kRouteWaves + wv;
     int32_t* eam_row = a.eam + (size_t)a.layer * a.E;
-    // any wavefront may turn out to be the last: each fetches the layer's slot row and EAM row
+    // any workgroup may turn out to be the last: each fetches the layer's slot row and EAM row
     // now, so that nothing but the logits is left to load after the arrival counter
-    for (int j = lane; j < a.E; j += kWave) {
+    for (int j = tid; j < a.E; j += NT) {
         s_slot[j] = a.slot_of_row[j];
         s_eam[j] = eam_row[j];
     }
-    // every wavefront copies its share of the EAM into the snapshot the match will read
-    // (this step's k increments are added to the snapshot by the last wavefront)
+    // every workgroup copies its share of the EAM into the snapshot the match will read
+    // (this step's k increments are added to the snapshot by the last workgroup)
     {
         const int seg = (a.LE + (int)gridDim.x - 1) / (int)gridDim.x;
-        const int i1 = min(a.LE, (e + 1) * seg);
-        for (int i = e * seg + lane; i < i1; i += kWave) a.snap[i] = a.eam[i];
+        const int i1 = min(a.LE, ((int)blockIdx.x + 1) * seg);
+        for (int i = blockIdx.x * seg + tid; i < i1; i += NT) a.snap[i] = a.eam[i];
     }
-    const WT* row = reinterpret_cast<const WT*>(a.W) + (size_t)e * a.H;
-    const WT* x = reinterpret_cast<const WT*>(a.x);
-    float acc = 0.f;
-    if (a.vec_ok) {
-        // four chunks' loads go out together (one round trip for rows up to 4 x 64 vectors); the
-        // sum still runs over the chunks in ascending order
-        constexpr int CW = kWave * V::N;
-        for (int c0 = lane * V::N; c0 < a.H; c0 += 4 * CW) {
-            typename V::raw wv[4], xv[4];
+    if (e < a.E) {  // uniform over the wavefront
+        const WT* row = reinterpret_cast<const WT*>(a.W) + (size_t)e * a.H;
+        const WT* x = reinterpret_cast<const WT*>(a.x);
+        float acc = 0.f;
+        if (a.vec_ok) {
+            // four chunks' loads go out together (one round trip for rows up to 4 x 64 vectors); the
+            // sum still runs over the chunks in ascending order
+            constexpr int CW = kWave * V::N;
+            for (int c0 = lane * V::N; c0 < a.H; c0 += 4 * CW) {
+                typename V::raw wr[4], xv[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int c = c0 + q * CW < a.H ? c0 + q * CW : c0;
-                wv[q] = V::load(row + c);
-                xv[q] = V::load(x + c);
-            }
+                for (int q = 0; q < 4; ++q) {
+                    const int c = c0 + q * CW < a.H ? c0 + q * CW : c0;
+                    wr[q] = V::load(row + c);
+                    xv[q] = V::load(x + c);
+                }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (c0 + q * CW < a.H) {
-                    float xf[V::N];
-                    V::unpack(xv[q], xf);
-                    acc = V::dot(wv[q], xf, acc);
+                for (int q = 0; q < 4; ++q) {
+                    if (c0 + q * CW < a.H) {
+                        float xf[V::N];
+                        V::unpack(xv[q], xf);
+                        acc = V::dot(wr[q], xf, acc);
+                    }
                 }
             }
+        } else {
+            for (int c = lane; c < a.H; c += kWave) acc = __builtin_fmaf(V::one(row + c), V::one(x + c), acc);
         }
-    } else {
-        for (int c = lane; c < a.H; c += kWave) acc = __builtin_fmaf(V::one(row + c), V::one(x + c), acc);
+        acc = wave_sum_dpp(acc);
+        if (lane == 0) a.logits[e] = acc + (a.bias ? a.bias[e] : 0.f);
     }
-    acc = wave_sum_dpp(acc);
-    if (lane == 0) {
-        a.logits[e] = acc + (a.bias ? a.bias[e] : 0.f);
+    __syncthreads();
+    if (tid == 0) {
         // release by the fence, then a relaxed arrival count (an acquire-release read-modify-write
-        // would repeat the cache write-back and add an invalidate in every wavefront); only the
-        // last to arrive needs the acquire, which is the fence below
+        // would repeat the cache write-back and add an invalidate); only the last workgroup to
+        // arrive needs the acquire, which is the fence below
         __threadfence();
         s_ticket = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (s_ticket != gridDim.x - 1) return;
-    __threadfence();
-    for (int j = lane; j < a.E; j += kWave)
-        z[j] = __hip_atomic_load(&a.logits[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    s_pick[lane] = 0;  // NaN logits leave ranks unassigned: such picks then name expert 0
-    s_pw[lane] = 0.f;
+    if (tid == 0) __threadfence();
     __syncthreads();
+    for (int j = tid; j < a.E; j += NT)
+        z[j] = __hip_atomic_load(&a.logits[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid < kWave) {  // NaN logits leave ranks unassigned: such picks then name expert 0
+        s_pick[tid] = 0;
+        s_pw[tid] = 0.f;
+    }
+    __syncthreads();
+    if (wv != 0) return;
     int my_idx;
     float my_w;
     if (a.E <= kRankMaxE) {
-        wave_topk_rank(z, a.E, a.k, a.renorm, lane, s_pick, s_pw);
-        __syncthreads();
+        const float sel = wave_topk_rank(z, a.E, a.k, a.renorm, lane, s_pick, s_pw, false);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
         my_idx = lane < a.k ? s_pick[lane] : -1;
-        my_w = lane < a.k ? s_pw[lane] : 0.f;
+        my_w = lane < a.k ? (a.renorm ? s_pw[lane] / sel : s_pw[lane]) : 0.f;
     } else {
         wave_topk(z, a.E, a.k, a.renorm, lane, my_idx, my_w);
     }
@@ -223,9 +234,11 @@ int launch_route_fused(RouteFusedArgs a, int wdtype, hipStream_t s) {
     const int n = wdtype == MOEI_WDTYPE_BF16 ? 8 : 4;
     a.vec_ok = (a.H % n == 0) && ((uintptr_t)a.W % 16 == 0) && ((uintptr_t)a.x % 16 == 0);
     if (wdtype == MOEI_WDTYPE_BF16)
-        launch(K_ROUTE_TOPK, route_fused_kernel<uint16_t>, dim3(a.E), dim3(kWave), 3 * a.E * sizeof(float), s, a);
+        launch(K_ROUTE_TOPK, route_fused_kernel<uint16_t>, dim3((a.E + kRouteWaves - 1) / kRouteWaves), dim3(kRouteWaves * kWave),
+               3 * a.E * sizeof(float), s, a);
     else
-        launch(K_ROUTE_TOPK, route_fused_kernel<float>, dim3(a.E), dim3(kWave), 3 * a.E * sizeof(float), s, a);
+        launch(K_ROUTE_TOPK, route_fused_kernel<float>, dim3((a.E + kRouteWaves - 1) / kRouteWaves), dim3(kRouteWaves * kWave),
+               3 * a.E * sizeof(float), s, a);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
 }
