@@ -226,14 +226,16 @@ __global__ void __launch_bounds__(kGrpThreads) prefill_place_kernel(GroupArgsP g
 }
 
 // ------------------------------------------------------------------ 3. grouped expert FFN on the matrix cores
-// Two tiled matrix products per item (an expert and up to 64 of its tokens):
+// Two tiled matrix products per item (an expert and up to TM = 64 or 128 of its tokens):
 //   3a. act[row][u] = silu(<W_gate[u], x_row>) * <W_up[u], x_row> * gate_row      (K = H)
 //   3b. yc[row][h]  = sum_u act[row][u] * W_down[h][u]                             (K = I)
 // `row` numbers the (token, pick) pairs in grouped order, then the (shared expert, token)
-// pairs.  The weights of an expert pass once per item; the small operand (inputs / activations)
-// goes through LDS in k-slices, double-buffered.
-constexpr int kTileTok = 64;   // tokens per item: four 16-token blocks
-constexpr int kMmThreads = 256;
+// pairs.  The weights of an expert pass once per item, so long prompts take the larger items;
+// the small operand (inputs / activations) goes through LDS in k-slices, double-buffered.  A
+// workgroup has four wavefronts per 64 tokens of the item: wavefront w serves output group
+// w % 4 (16 units / 128 columns) for tokens 64 * (w / 4) .. + 64.
+constexpr int kTileTok = 64;      // tokens per item for short prompts: four 16-token blocks
+constexpr int kTileTokBig = 128;  // for long prompts
 constexpr int kGuUnits = 64;   // 3a: intermediate units per workgroup, 16 per wavefront
 constexpr int kGuKS = 128;     // 3a: k-slice of inputs and weight rows in LDS
 constexpr int kDnCols = 512;   // 3b: output columns per workgroup, 128 per wavefront
@@ -268,12 +270,14 @@ __device__ __forceinline__ uint32_t bf16_bits(float f) {
 // tokens, both from LDS; a wavefront owns 16 units x 64 tokens (gate and up).  The weight rows
 // are fetched in 256-byte runs (a k-slice of a row), the next slice into registers while the
 // current one is multiplied.
-__global__ void __launch_bounds__(kMmThreads) prefill_gateup_kernel(MmArgs a) {
+template <int TM>
+__global__ void __launch_bounds__(TM * 4) prefill_gateup_kernel(MmArgs a) {
+    constexpr int kMmThreads = TM * 4;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     constexpr int ls = kGuKS + kPfPad;  // LDS row stride, elements
-    uint16_t* Xs = reinterpret_cast<uint16_t*>(smem_raw);  // [kTileTok][ls] inputs
-    uint16_t* Ws = Xs + (size_t)kTileTok * ls;             // [2 * kGuUnits][ls] gate rows, then up rows
-    __shared__ float s_gate[kTileTok];
+    uint16_t* Xs = reinterpret_cast<uint16_t*>(smem_raw);  // [TM][ls] inputs
+    uint16_t* Ws = Xs + (size_t)TM * ls;                   // [2 * kGuUnits][ls] gate rows, then up rows
+    __shared__ float s_gate[TM];
     const int item = blockIdx.y;
     if (item >= a.meta[0]) return;
     const PItem it = a.items[item];
@@ -282,12 +286,14 @@ __global__ void __launch_bounds__(kMmThreads) prefill_gateup_kernel(MmArgs a) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int lrow = lane & 15, lgrp = lane >> 4;
+    const int ug = wv & 3, tq = wv >> 2;  // unit group, token quarter
+    const bool live = tq * 64 < it.ntok;  // a quarter past the item's tokens only helps staging
     const uint16_t* wslot = a.pool + (size_t)it.slot * a.slot_elems;
     const int u_wg = blockIdx.x * kGuUnits;
 
-    if (tid < kTileTok) s_gate[tid] = tid < it.ntok ? (it.first_tok >= 0 ? 1.0f : a.pgate[it.list_off + tid]) : 0.f;
+    if (tid < TM) s_gate[tid] = tid < it.ntok ? (it.first_tok >= 0 ? 1.0f : a.pgate[it.list_off + tid]) : 0.f;
     constexpr int VPR = kGuKS / 8;                                // 16-byte vectors per row and slice
-    constexpr int NX = kTileTok * VPR / kMmThreads;               // input vectors per thread and slice
+    constexpr int NX = TM * VPR / kMmThreads;                     // input vectors per thread and slice
     constexpr int NW = 2 * kGuUnits * VPR / kMmThreads;           // weight vectors per thread and slice
     const uint16_t* xsrc[NX];
 #pragma unroll
@@ -334,9 +340,9 @@ __global__ void __launch_bounds__(kMmThreads) prefill_gateup_kernel(MmArgs a) {
     f32x4 G[4], U[4];
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb) G[tb] = U[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const uint16_t* ag = Ws + (size_t)(16 * wv + lrow) * ls + lgrp * 8;
+    const uint16_t* ag = Ws + (size_t)(16 * ug + lrow) * ls + lgrp * 8;
     const uint16_t* au = ag + (size_t)kGuUnits * ls;
-    const uint16_t* xb = Xs + (size_t)lrow * ls + lgrp * 8;
+    const uint16_t* xb = Xs + (size_t)(64 * tq + lrow) * ls + lgrp * 8;
 
     fetch(0);
     for (int s = 0; s < n_slices; ++s) {
@@ -344,7 +350,7 @@ __global__ void __launch_bounds__(kMmThreads) prefill_gateup_kernel(MmArgs a) {
         put();
         __syncthreads();
         if (s + 1 < n_slices) fetch(s + 1);  // on its way while this slice is multiplied
-        const int steps = min(kGuKS, H - s * kGuKS) / 32;
+        const int steps = live ? min(kGuKS, H - s * kGuKS) / 32 : 0;
         for (int ks = 0; ks < steps; ++ks) {
             const bf16x8 cg = ld_bf16x8(ag + ks * 32), cu = ld_bf16x8(au + ks * 32);
 #pragma unroll
@@ -357,10 +363,10 @@ __global__ void __launch_bounds__(kMmThreads) prefill_gateup_kernel(MmArgs a) {
     }
     // D[unit 4*lgrp + v][token lrow] -> activation, bf16, act[row][unit]
     const bool packed = (I & 3) == 0;
-    const int u0 = u_wg + 16 * wv + lgrp * 4;
+    const int u0 = u_wg + 16 * ug + lgrp * 4;
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb) {
-        const int tok = tb * 16 + lrow;
+        const int tok = tq * 64 + tb * 16 + lrow;
         if (tok >= it.ntok) continue;
         const float gw = s_gate[tok];
         uint16_t* dst_row = a.act + (size_t)(it.row0 + tok) * I;
@@ -382,10 +388,12 @@ __global__ void __launch_bounds__(kMmThreads) prefill_gateup_kernel(MmArgs a) {
 // columns and transposes them in registers into eight operands of eight units each; the column
 // a lane serves in matrix i is then col0 + 8*lrow + i (which 16 columns a matrix covers is only
 // a labelling).  A wavefront owns 64 tokens x 128 columns.
-__global__ void __launch_bounds__(kMmThreads) prefill_down_kernel(MmArgs a) {
+template <int TM>
+__global__ void __launch_bounds__(TM * 4) prefill_down_kernel(MmArgs a) {
+    constexpr int kMmThreads = TM * 4;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     constexpr int as_stride = kDnKS + kPfPad;
-    uint16_t* As = reinterpret_cast<uint16_t*>(smem_raw);  // [2][kTileTok][as_stride]
+    uint16_t* As = reinterpret_cast<uint16_t*>(smem_raw);  // [2][TM][as_stride]
     const int item = blockIdx.y;
     if (item >= a.meta[0]) return;
     const PItem it = a.items[item];
@@ -393,8 +401,10 @@ __global__ void __launch_bounds__(kMmThreads) prefill_down_kernel(MmArgs a) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int lrow = lane & 15, lgrp = lane >> 4;
-    const int col0 = blockIdx.x * kDnCols + 128 * wv;
-    const bool active = col0 < H;  // uniform over the wavefront
+    const int cg = wv & 3, tq = wv >> 2;  // column group, token quarter
+    const int col0 = blockIdx.x * kDnCols + 128 * cg;
+    // uniform over the wavefront: its columns exist and its quarter holds tokens of the item
+    const bool active = col0 < H && tq * 64 < it.ntok;
     if (it.slot < 0 || it.slot >= a.n_slots_total) {  // not resident: the rows are zero, the flag says so
         if (tid == 0) atomicOr(a.flags, 1);
         const int c_end = min(H, (int)(blockIdx.x + 1) * kDnCols);
@@ -402,10 +412,10 @@ __global__ void __launch_bounds__(kMmThreads) prefill_down_kernel(MmArgs a) {
             for (int c = blockIdx.x * kDnCols + tid; c < c_end; c += kMmThreads) a.yc[(size_t)(it.row0 + r) * H + c] = 0.f;
         return;
     }
-    const uint16_t* wd = a.pool + (size_t)it.slot * a.slot_elems + 2 * H + (active ? col0 : 0) + lrow * 8;
+    const uint16_t* wd = a.pool + (size_t)it.slot * a.slot_elems + 2 * H + (col0 < H ? col0 : 0) + lrow * 8;
 
-    constexpr int VPR = kDnKS / 8;                   // 16
-    constexpr int NV = kTileTok * VPR / kMmThreads;  // 4
+    constexpr int VPR = kDnKS / 8;             // 16
+    constexpr int NV = TM * VPR / kMmThreads;  // 4
     const uint16_t* arow[NV];
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
@@ -426,7 +436,7 @@ __global__ void __launch_bounds__(kMmThreads) prefill_down_kernel(MmArgs a) {
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
             const int v = tid + kMmThreads * j;
-            *reinterpret_cast<uint4*>(As + ((size_t)buf * kTileTok + v / VPR) * as_stride + (v % VPR) * 8) = stage[j];
+            *reinterpret_cast<uint4*>(As + ((size_t)buf * TM + v / VPR) * as_stride + (v % VPR) * 8) = stage[j];
         }
     };
     auto load_w = [&](int k0, uint4* dst) {  // units k0 + 8*lgrp + j (clamped: their activations are zero)
@@ -445,12 +455,12 @@ __global__ void __launch_bounds__(kMmThreads) prefill_down_kernel(MmArgs a) {
     put(0);
     __syncthreads();
     uint4 cur[8], nxt[8];
-    load_w(0, cur);
+    if (active) load_w(0, cur);
     for (int s = 0; s < n_slices; ++s) {
         if (s + 1 < n_slices) fetch(s + 1);
-        const uint16_t* ab = As + ((size_t)(s & 1) * kTileTok + lrow) * as_stride + lgrp * 8;
+        const uint16_t* ab = As + ((size_t)(s & 1) * TM + 64 * tq + lrow) * as_stride + lgrp * 8;
         const int k0 = s * kDnKS;
-        const int steps = (min(kDnKS, I - k0) + 31) / 32;
+        const int steps = active ? (min(kDnKS, I - k0) + 31) / 32 : 0;
 #pragma unroll 1
         for (int ks = 0; ks < steps; ++ks) {
             // the next step's weights (the next slice's first step after the last one; past the
@@ -488,7 +498,7 @@ __global__ void __launch_bounds__(kMmThreads) prefill_down_kernel(MmArgs a) {
     for (int tb = 0; tb < 4; ++tb)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            const int tok = tb * 16 + lgrp * 4 + v;
+            const int tok = tq * 64 + tb * 16 + lgrp * 4 + v;
             if (tok < it.ntok) {
                 float* dst = a.yc + (size_t)(it.row0 + tok) * H + col0 + lrow * 8;
                 *reinterpret_cast<float4*>(dst) = make_float4(Y[tb][0][v], Y[tb][1][v], Y[tb][2][v], Y[tb][3][v]);
@@ -550,9 +560,37 @@ int prefill_check(const moei_model_desc& d) {
 }
 
 size_t prefill_item_bytes() { return sizeof(PItem); }
-int prefill_max_items(const moei_model_desc& d, int n_max) {
-    return (n_max * d.k + kTileTok - 1) / kTileTok + d.E + d.n_shared * ((n_max + kTileTok - 1) / kTileTok);
+namespace {
+int max_items_for(const moei_model_desc& d, int n, int tm) {
+    return (n * d.k + tm - 1) / tm + d.E + d.n_shared * ((n + tm - 1) / tm);
 }
+// tokens per item: the larger tile once the average expert holds more than one small tile
+int tile_tokens(const moei_model_desc& d, int n) {
+    const char* v = getenv("MOEI_PREFILL_TILE");
+    if (v && atoi(v) == kTileTok) return kTileTok;
+    if (v && atoi(v) == kTileTokBig) return kTileTokBig;
+    return (long)n * d.k > (long)kTileTok * d.E ? kTileTokBig : kTileTok;
+}
+
+template <int TM>
+int launch_mm(const moei_model_desc& d, const MmArgs& a, int max_items, hipStream_t s) {
+    const size_t gu_smem = (size_t)(TM + 2 * kGuUnits) * (kGuKS + kPfPad) * 2;
+    const size_t dn_smem = (size_t)2 * TM * (kDnKS + kPfPad) * 2;
+    int rc = pf_allow_lds(prefill_gateup_kernel<TM>, gu_smem);
+    if (rc) return rc;
+    rc = pf_allow_lds(prefill_down_kernel<TM>, dn_smem);
+    if (rc) return rc;
+    launch(K_PF_GATEUP, prefill_gateup_kernel<TM>, dim3((d.I + kGuUnits - 1) / kGuUnits, max_items), dim3(TM * 4), gu_smem,
+           s, a);
+    MOEI_LAUNCH_CHECK();
+    launch(K_PF_DOWN, prefill_down_kernel<TM>, dim3((d.H + kDnCols - 1) / kDnCols, max_items), dim3(TM * 4), dn_smem, s, a);
+    MOEI_LAUNCH_CHECK();
+    return MOEI_OK;
+}
+}  // namespace
+
+// the scratch is sized for the small tile, which yields the most items
+int prefill_max_items(const moei_model_desc& d, int n_max) { return max_items_for(d, n_max, kTileTok); }
 size_t prefill_rows(const moei_model_desc& d, int n_max) { return (size_t)n_max * (d.k + d.n_shared); }
 
 int launch_prefill(const moei_model_desc& d, const PrefillScratch& ps, const void* d_pool, size_t slot_elems,
@@ -571,25 +609,20 @@ int launch_prefill(const moei_model_desc& d, const PrefillScratch& ps, const voi
     launch(K_PF_ROUTE, prefill_route_kernel<uint16_t>, dim3(n), dim3(4 * kWave), route_smem, s, d_router_w,
            d_router_bias, d_X, n, d.H, d.E, d.k, (int)(d.renorm_topk != 0), vec_ok, ps.d_idx, ps.d_w);
     MOEI_LAUNCH_CHECK();
-    GroupArgsP g{ps.d_idx, ps.d_w, n, d.k, d.E, d.n_shared, kTileTok, d_slot_of_row, shared_base, d_eam_row, ps.d_perm,
+    const int tm = tile_tokens(d, n);
+    GroupArgsP g{ps.d_idx, ps.d_w, n, d.k, d.E, d.n_shared, tm, d_slot_of_row, shared_base, d_eam_row, ps.d_perm,
                  ps.d_pgate, ps.d_where, reinterpret_cast<PItem*>(ps.d_items), ps.d_meta, ps.d_cntw, d_flags};
     launch(K_FFN_GROUP, prefill_count_kernel, dim3(d.E), dim3(kGrpThreads), 0, s, g);
     MOEI_LAUNCH_CHECK();
     launch(K_FFN_GROUP, prefill_place_kernel, dim3(d.E), dim3(kGrpThreads), 0, s, g);
     MOEI_LAUNCH_CHECK();
     // the number of items is known on the device only: the grids cover the largest possible count
-    const int max_items = prefill_max_items(d, n);
+    const int max_items = max_items_for(d, n, tm);
     MmArgs a{reinterpret_cast<const uint16_t*>(d_pool), slot_elems, n_slots_total,
              reinterpret_cast<const PItem*>(ps.d_items), ps.d_meta, reinterpret_cast<const uint16_t*>(d_X), ps.d_perm,
              ps.d_pgate, ps.d_act, ps.d_yc, d.H, d.I, d_flags};
-    const size_t gu_smem = (size_t)(kTileTok + 2 * kGuUnits) * (kGuKS + kPfPad) * 2;
-    launch(K_PF_GATEUP, prefill_gateup_kernel, dim3((d.I + kGuUnits - 1) / kGuUnits, max_items), dim3(kMmThreads), gu_smem,
-           s, a);
-    MOEI_LAUNCH_CHECK();
-    const size_t dn_smem = (size_t)2 * kTileTok * (kDnKS + kPfPad) * 2;
-    launch(K_PF_DOWN, prefill_down_kernel, dim3((d.H + kDnCols - 1) / kDnCols, max_items), dim3(kMmThreads), dn_smem, s,
-           a);
-    MOEI_LAUNCH_CHECK();
+    rc = tm == kTileTokBig ? launch_mm<kTileTokBig>(d, a, max_items, s) : launch_mm<kTileTok>(d, a, max_items, s);
+    if (rc) return rc;
     launch(K_PF_REDUCE, prefill_reduce_kernel, dim3(n), dim3(256), 0, s, (const float*)ps.d_yc,
            (const int32_t*)ps.d_where, n, d.k, d.n_shared, d.H, d_Y);
     MOEI_LAUNCH_CHECK();

@@ -85,9 +85,10 @@ def _check(o):
         assert rel_max_err(o["Y"][t], o["rY"][t]) <= FFN_TOL, t
 
 
-@pytest.mark.parametrize("n", [1, 7, 64, 65, 130, 200])
+@pytest.mark.parametrize("n", [1, 7, 64, 65, 130, 200, 700])
 def test_prefill_reduced_deepseek_shape(m, n):
-    # DeepSeek-V2-Lite structure (top-6 of 64 + 2 shared, bf16), narrow matrices; token counts around the 64-token tile
+    # DeepSeek-V2-Lite structure (top-6 of 64 + 2 shared, bf16), narrow matrices; token counts around the 64-token
+    # tile, and one prompt long enough (n k > 64 E) that the items hold up to 128 tokens
     cfg = mi.get_config("C2").scaled(L=3, H=256, I=192, N=8, prompt=16)
     _check(_prefill_case(m, cfg, n, layer=1))
 
@@ -98,6 +99,8 @@ def test_prefill_ragged_rows_and_small_expert_counts(m):
     _check(_prefill_case(m, cfg, 90, layer=0))
     cfg = mi.get_config("C3").scaled(L=2, H=512, I=72, N=8, prompt=16)      # Mixtral structure: renormalised top-2 of 8, no shared experts
     _check(_prefill_case(m, cfg, 50, layer=1))
+    # the same structure with a prompt that takes 128-token items, the last item of most experts ragged
+    _check(_prefill_case(m, cfg, 300, layer=0))
 
 
 def test_prefill_wide_rows(m):
