@@ -42,6 +42,8 @@ def test_cache_retrieve_sequence_and_slot_contents(m):
                 need = {layer * E + int(p) for p in picks}
                 resident = [f for f in range(L * E) if ref.slot_of[f] >= 0 and f not in need]
                 ev = rng.permutation(resident)[: (1 if it % 5 == 0 else len(resident))]
+                if it % 3 == 1:  # an order with stale entries and experts needed now: both are passed over
+                    ev = rng.permutation(L * E)
                 want = ref.retrieve(layer, picks, ev)
                 slots, victims, n_miss = cache.retrieve(layer, picks, ev)
                 assert slots.tolist() == [w[3] for w in want]

@@ -56,6 +56,29 @@ def test_comparison_policies_follow_the_oracle(m, policy):
     cache.close()
 
 
+def test_a_prefetched_expert_is_the_most_recent_use_under_lru(m):
+    # the hand-worked case of the oracle's pin, through the library
+    cfg = mi.get_config("C1").scaled(H=64, I=32, L=1, E=4, k=1)
+    packed = pack_bank(m, cfg, mi.expert_bank(cfg, 4, threads=2))
+    cache = m.Cache(m.ModelDesc.from_config(cfg), 2, pinned(packed))
+    cache.reset(0)
+    cache.set_policy("lru")
+    ref = O.ExpertCache(1, 4, 2, warm=False, policy="lru")
+    V = np.array([0.0, 0.0, 1.0, 0.0], dtype=np.float32)
+    for step in (("r", 0), ("p", 1), ("r", 0), ("r", 2), ("r", 1), ("p", 3), ("r", 0)):
+        if step[0] == "r":
+            want = ref.retrieve(0, [step[1]])
+            slots, victims, n_miss = cache.retrieve(0, [step[1]], [])
+            assert (slots.tolist(), victims.tolist()) == ([w[3] for w in want], [w[2] for w in want]), step
+        else:
+            ev = [int(f) for f in np.nonzero(ref.slot_of >= 0)[0]]
+            want = ref.prefetch([step[1]], ev, np.where(np.arange(4) == step[1], 1.0, 0.0), depth=1)
+            got = cache.prefetch([step[1]], ev, np.where(np.arange(4) == step[1], 1.0, 0.0).astype(np.float32), depth=1)
+            assert [tuple(g) for g in got] == want, step
+        assert (cache.get_slots() == ref.slot_of).all(), step
+    cache.close()
+
+
 def test_prefetch_step_follows_the_oracle_and_fills_the_slots(m):
     cfg = mi.get_config("C1").scaled(H=64, I=32, L=5)
     L, E, k, S = cfg.L, cfg.E, cfg.k, 9

@@ -571,6 +571,36 @@ def test_cache_cold_start_fills_lowest_free_slots():
     assert ev == [(5, True, -1, 2), (6, False, 0, 1)]
 
 
+def test_retrieval_passes_over_needed_and_departed_eviction_candidates():
+    # Alg. 1 by hand on 2 layers x 3 experts; 3 slots, holding experts 0, 1, 2 (flat ids) at the start
+    c = O.ExpertCache(2, 3, 3, warm=True)
+    assert c.retrieve(0, [1], [1, 2, 0]) == [(1, True, -1, 1)]
+    # layer 1 needs flat ids 3 and 4, both misses; the order's head (3) is not resident: passed over
+    assert c.retrieve(1, [0, 1], [3, 2, 0, 1]) == [(3, False, 2, 2), (4, False, 0, 0)]
+    # slots now hold 4, 1, 3; the order's head (4) is needed by this very call and stays
+    assert c.retrieve(1, [1, 2], [4, 3, 1]) == [(4, True, -1, 0), (5, False, 3, 2)]
+    # slots hold 4, 1, 5; expert 2 left long ago and nobody needs it: a stale entry, passed over
+    assert c.retrieve(0, [0], [2, 1]) == [(0, False, 1, 1)]
+    assert sorted(np.nonzero(c.slot_of >= 0)[0].tolist()) == [0, 4, 5]
+    for f in (0, 4, 5):
+        assert c.owner[c.slot_of[f]] == f
+
+
+def test_a_prefetched_expert_is_the_most_recent_use_under_lru():
+    c = O.ExpertCache(1, 4, 2, warm=False, policy="lru")
+    c.retrieve(0, [0], [])                                      # slot 0, stamp 1
+    assert c.prefetch([1], [], np.zeros(4), depth=1) == [(1, -1, 1)]   # slot 1, stamp 2
+    c.retrieve(0, [0], [])                                      # expert 0 used again: stamp 3
+    # the least recently used is now the prefetched expert 1, not expert 0
+    assert c.retrieve(0, [2], []) == [(2, False, 1, 1)]
+    c2 = O.ExpertCache(1, 4, 2, warm=False, policy="lru")
+    c2.retrieve(0, [0], [])
+    c2.retrieve(0, [1], [])
+    assert c2.prefetch([2], [0], np.array([0.0, 0.0, 1.0, 0.0]), depth=1) == [(2, 0, 0)]   # takes expert 0's slot
+    # expert 2 was brought in after expert 1 was used: expert 1 is the older one
+    assert c2.retrieve(0, [3], []) == [(3, False, 1, 1)]
+
+
 # ============================================================ composite (via parts)
 def test_decode_layer_composes_its_parts():
     from moei_inputs import get_config, eamc_traces, make_request, router_weights, expert_weights
