@@ -12,9 +12,9 @@ garbled are marked "reading:".
 
 Pin status (tests marked "not gpu" under tests/): every function below is pinned
 to something other than itself -- brute force with exact fractions, library
-routines, closed forms, invariants, or the worked example of Sec. 4.7 -- except
-the composite ``decode_layer``, which the paper prints no value for: it is
-pinned only through its parts.
+routines, closed forms, invariants, or the worked example of Sec. 4.7.  The
+composite ``decode_layer``, which the paper prints no value for, is pinned through
+its parts and through one layer step worked by hand.
 """
 from __future__ import annotations
 
@@ -407,7 +407,7 @@ def decode_layer(traces, eam, cache: ExpertCache, layer: int, W_r, bias, x, expe
     that already holds this layer's routing (Alg. 1 calls PredictEAM with the
     current EAM).  With m > 1 the m most similar traces are aggregated; with
     prefetch_depth > 0 the layer's retrieval is followed by ``ExpertCache.prefetch``.
-    Composite: pinned only through its parts.
+    Composite: pinned through its parts and through a step worked by hand (tests).
     """
     L, E = eam.shape
     z = router_logits(W_r, x, bias)

@@ -626,6 +626,64 @@ def test_decode_layer_composes_its_parts():
     assert out["best"] == O.eamc_match(T, eam)[0]
 
 
+def _hand_step(m):
+    """A layer step small enough to follow by hand: 3 layers x 4 experts, top-2 without
+    renormalisation, an identity router, one-unit experts that only touch y[0]."""
+    L, E = 3, 4
+    T = np.array([[[4, 4, 0, 0], [0, 8, 0, 0], [0, 0, 0, 8]],
+                  [[0, 0, 4, 4], [8, 0, 0, 0], [0, 0, 8, 0]]])
+    cache = O.ExpertCache(L, E, 3, warm=False)
+    cache.retrieve(0, [0, 2])                                   # slots 0, 1 hold flat ids 0 and 2
+    cache.retrieve(1, [1])                                      # slot 2 holds flat id 5
+    par = {0: (0.5, 1.0), 1: (-0.25, 2.0)}                      # expert -> (g, d); o = d silu(g x0) x1 e_0
+
+    def mk(g, d):
+        return (np.array([[g, 0.0, 0.0, 0.0]]), np.array([[0.0, 1.0, 0.0, 0.0]]), np.array([[d], [0.0], [0.0], [0.0]]))
+
+    eam = np.zeros((L, E), dtype=np.int64)
+    out = O.decode_layer(T, eam, cache, 0, np.eye(4), None, np.array([4.0, 3.0, 0.0, 0.0]),
+                         lambda f: mk(*par.get(f, (9.0, 9.0))), lambda l: [mk(1.0, -1.0)], 2, False, 2.0 ** -20, m=m)
+    return out, eam, cache
+
+
+def test_decode_layer_hand_worked_step():
+    out, eam, cache = _hand_step(1)
+    silu = lambda t: t / (1.0 + math.exp(-t))
+    z = np.array([4.0, 3.0, 0.0, 0.0])
+    p = np.exp(z) / np.exp(z).sum()
+    assert out["idx"].tolist() == [0, 1]
+    np.testing.assert_allclose(out["w"], p[:2], rtol=1e-15)
+    assert eam.tolist() == [[1, 1, 0, 0], [0, 0, 0, 0], [0, 0, 0, 0]]
+    # the query (1, 1, 0, ...) meets trace 0 in <q, T> = 8, trace 1 in 0; |q|^2 = 2, |T_0|^2 = 160
+    assert out["best"] == 0 and out["matched"] == [0]
+    assert out["sim"] == pytest.approx(1.0 / math.sqrt(5.0), rel=1e-15)
+    # prefetch scores from trace 0 at layer 0: (row-normalised cell) x (1 - (i - 0)/3)
+    P = np.zeros((3, 4)); P[1, 1] = 2.0 / 3.0; P[2, 3] = 1.0 / 3.0
+    np.testing.assert_allclose(out["P"], P, rtol=1e-15)
+    assert out["pf_order"] == [11]                              # (1, 1) is resident already
+    # eviction: residents 0, 2, 5 without the experts running now (0 and 1): V[2] ~ eps/8 < V[5] ~ 2/3
+    assert out["ev_order"] == [2, 5]
+    assert out["V"][0, 0] == pytest.approx((4 + 2.0 ** -20) / 8.0, rel=1e-15)
+    assert out["V"][1, 1] == pytest.approx((8 + 2.0 ** -20) * (2.0 / 3.0) / 8.0, rel=1e-15)
+    # Alg. 1: expert 0 hits slot 0; expert 1 misses, the cache is full, the order's head (2) gives up slot 1
+    assert out["events"] == [(0, True, -1, 0), (1, False, 2, 1)]
+    assert sorted(np.nonzero(cache.slot_of >= 0)[0].tolist()) == [0, 1, 5]
+    # y[0] = p_0 silu(0.5 * 4) 3 + p_1 2 silu(-0.25 * 4) 3 - silu(4) 3 (the shared expert enters with weight 1)
+    want = p[0] * silu(2.0) * 3.0 + p[1] * 2.0 * silu(-1.0) * 3.0 - silu(4.0) * 3.0
+    np.testing.assert_allclose(out["y"], [want, 0.0, 0.0, 0.0], rtol=1e-14, atol=0)
+
+
+def test_decode_layer_hand_worked_step_with_two_matches():
+    out, _, _ = _hand_step(2)
+    # both traces are returned (similarities 1/sqrt(5) and 0) and their cells are summed:
+    # rows (4,4,4,4), (8,8,0,0), (0,0,8,8)
+    assert out["matched"] == [0, 1] and out["best"] == 0
+    P = np.zeros((3, 4)); P[1, 0] = P[1, 1] = 0.5 * 2.0 / 3.0; P[2, 2] = P[2, 3] = 0.5 / 3.0
+    np.testing.assert_allclose(out["P"], P, rtol=1e-15)
+    assert out["pf_order"] == [4, 10, 11]                       # 5 is resident; equal scores by ascending id
+    assert out["ev_order"] == [2, 5]                            # V[2] = (4 + eps)/16 < V[5] = (8 + eps)(2/3)/16
+
+
 # ================================================================ prefill iteration
 def test_prefill_layer_against_dense_all_expert_formulation():
     # every expert applied to every token with dense library matmuls, then masked by the routing:
