@@ -115,14 +115,17 @@ __global__ void __launch_bounds__((StreamShape<NCH>::kMaxWaves * kWave)) ffn_fus
     auto step_off = [&](int s) -> int {
         return s < 2 * NCH ? ((s & 1) ? H : 0) + (s >> 1) * CW : 2 * H + (s - 2 * NCH) * CW;
     };
-    auto ld = [&](size_t unit, int off) -> Raw { return V::load(pool + unit + off + lane_off); };
+    auto ld = [&](size_t unit, int off) -> Raw { return V::load_once(pool + unit + off + lane_off); };
 
     float acc[NCH * N];
 #pragma unroll
     for (int k = 0; k < NCH * N; ++k) acc[k] = 0.f;
     Raw win[PF];
 
-    int t = blockIdx.x * a.waves + wv;
+    // unit t -> wavefront t mod W, numbered wavefront-major (w = wv * workgroups + workgroup): when
+    // the units do not fill the last round, every compute unit keeps most of its wavefronts busy
+    // instead of whole workgroups running out of work
+    int t = wv * gridDim.x + blockIdx.x;
     float gate = 0.f, gate_n = 0.f;
     bool ok = false, ok_n = false;
     size_t p = 0;
@@ -177,14 +180,15 @@ __global__ void __launch_bounds__((StreamShape<NCH>::kMaxWaves * kWave)) ffn_fus
                     acc[(s - 2 * NCH) * N + k] = __builtin_fmaf(ai, d[k], acc[(s - 2 * NCH) * N + k]);
             }
             // The consumed slot is free again: refill it with the load PF steps ahead.  After
-            // the last unit the refills re-read one already cached chunk, so that every step
-            // issues exactly one load and the loop body has no branch.  The scheduling barriers
-            // keep the compiler from hoisting refills and growing the window.
+            // the last unit the refills read the pool's first chunk (the same kilobyte for every
+            // wavefront, so it comes from the cache), so that every step issues exactly one load
+            // and the loop body has no branch.  The scheduling barriers keep the compiler from
+            // hoisting refills and growing the window.
             __builtin_amdgcn_sched_barrier(0);
             if (s + PF < STEPS)
                 win[s % PF] = ld(p, step_off(s + PF));
             else
-                win[s % PF] = ld(pn, more ? step_off(s + PF - STEPS) : 0);
+                win[s % PF] = ld(more ? pn : 0, more ? step_off(s + PF - STEPS) : 0);
             __builtin_amdgcn_sched_barrier(0);
         }
         t = tn;
@@ -540,7 +544,7 @@ __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(Gr
     auto step_off = [&](int s) -> int {
         return s < 2 * NCH ? ((s & 1) ? H : 0) + (s >> 1) * CW : 2 * H + (s - 2 * NCH) * CW;
     };
-    auto ld = [&](size_t unit, int off) -> Raw { return V::load(pool + unit + off + lane_off); };
+    auto ld = [&](size_t unit, int off) -> Raw { return V::load_once(pool + unit + off + lane_off); };
 
     int seg = 0;
     for (long row = R0; row < R1 && seg < a.seg_max; ++seg) {  // uniform over the workgroup
@@ -610,7 +614,7 @@ __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(Gr
                 if (s + PF < STEPS)
                     win[s % PF] = ld(p, step_off(s + PF));
                 else
-                    win[s % PF] = ld(pn, more ? step_off(s + PF - STEPS) : 0);
+                    win[s % PF] = ld(more ? pn : 0, more ? step_off(s + PF - STEPS) : 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
             p = pn;

@@ -18,6 +18,7 @@
 
 #include "kernels.hpp"
 #include "score.hpp"
+#include "wtypes.hpp"
 
 namespace moei {
 
@@ -37,6 +38,7 @@ struct DotArgs {
     int n_lsplit;
     int TN;               // traces per tile
     int rowV;             // vectors per trace row
+    int once;             // the scan exceeds the last-level cache: load with the non-temporal hint
 };
 
 template <typename CT, int VEC>
@@ -46,6 +48,10 @@ template <>
 struct CellVec<int32_t, 4> {
     using raw = int4;
     static __device__ __forceinline__ raw load(const int32_t* p) { return *reinterpret_cast<const int4*>(p); }
+    static __device__ __forceinline__ raw load_once(const int32_t* p) {
+        const uint4 v = load_once_16(p);
+        return make_int4((int)v.x, (int)v.y, (int)v.z, (int)v.w);
+    }
     static __device__ __forceinline__ u64 dot(raw v, const int32_t* q, u64 acc) {
         int4 qq = *reinterpret_cast<const int4*>(q);
         acc += (u64)(uint32_t)v.x * (uint32_t)qq.x;
@@ -60,6 +66,7 @@ template <>
 struct CellVec<int32_t, 1> {
     using raw = int32_t;
     static __device__ __forceinline__ raw load(const int32_t* p) { return *p; }
+    static __device__ __forceinline__ raw load_once(const int32_t* p) { return *p; }
     static __device__ __forceinline__ u64 dot(raw v, const int32_t* q, u64 acc) {
         return acc + (u64)(uint32_t)v * (uint32_t)q[0];
     }
@@ -69,6 +76,7 @@ template <>
 struct CellVec<uint16_t, 8> {
     using raw = uint4;
     static __device__ __forceinline__ raw load(const uint16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+    static __device__ __forceinline__ raw load_once(const uint16_t* p) { return load_once_16(p); }
     static __device__ __forceinline__ u64 dot(raw v, const int32_t* q, u64 acc) {
         int4 q0 = *reinterpret_cast<const int4*>(q);
         int4 q1 = *reinterpret_cast<const int4*>(q + 4);
@@ -88,6 +96,7 @@ template <>
 struct CellVec<uint16_t, 1> {
     using raw = uint16_t;
     static __device__ __forceinline__ raw load(const uint16_t* p) { return *p; }
+    static __device__ __forceinline__ raw load_once(const uint16_t* p) { return *p; }
     static __device__ __forceinline__ u64 dot(raw v, const int32_t* q, u64 acc) {
         return acc + (u64)v * (uint32_t)q[0];
     }
@@ -146,7 +155,9 @@ __global__ void __launch_bounds__(kDotThreads) eamc_dot_kernel(DotArgs a) {
         typename CV::raw v[J];
 #pragma unroll
         for (int j = 0; j < J; ++j)
-            if (valid[j]) v[j] = CV::load(base + (size_t)j * kDotThreads * VEC);
+            if (valid[j])
+                v[j] = a.once ? CV::load_once(base + (size_t)j * kDotThreads * VEC)
+                              : CV::load(base + (size_t)j * kDotThreads * VEC);
 #pragma unroll
         for (int j = 0; j < J; ++j)
             if (valid[j]) {
@@ -928,7 +939,11 @@ int launch_dots(const moei_eamc* c, const int32_t* d_eam, int B, int layer_hi, i
     *n_lsplit = p.n_lsplit;
     if (p.n_lsplit > c->lsplit_max || p.smem > 64 * 1024)
         MOEI_FAIL(MOEI_ECAPACITY, "eamc_match: L*E = %d is too large for the match kernel's LDS staging", L * E);
-    DotArgs a{c->d_traces, d_eam, c->d_part, c->n_cap, c->N, L, E, B, layer_hi + 1, p.lper, p.n_lsplit, p.TN, p.rowV};
+    // a collection that fits the 256 MB last-level cache stays there between layer steps; a longer
+    // scan is read once per match and should not displace other data
+    const size_t scan_bytes = (size_t)c->N * (layer_hi + 1) * E * c->cell_bytes;
+    DotArgs a{c->d_traces, d_eam, c->d_part, c->n_cap, c->N, L, E, B, layer_hi + 1, p.lper, p.n_lsplit, p.TN, p.rowV,
+              scan_bytes > ((size_t)192 << 20)};
     dim3 grid(p.n_tiles, p.n_lsplit, (B + p.NB - 1) / p.NB);
     if (c->cell_bytes == 4)
         return p.VEC == 4 ? launch_dot_j<int32_t, 4>(p, a, grid, s) : launch_dot_j<int32_t, 1>(p, a, grid, s);
