@@ -426,11 +426,14 @@ struct GroupArgs {
     int32_t* flags;
 };
 
-// One workgroup.  Thread e collects the tokens routed to expert e (in token order) and cuts
-// them into items of at most tb tokens; item positions follow expert order, shared experts last.
-__global__ void __launch_bounds__(256) ffn_group_kernel(GroupArgs a) {
-    __shared__ int s_cnt[256];
-    __shared__ int s_base;
+// The item list of a call, built by every workgroup for itself (the picks of a batch are a few
+// hundred bytes, the list a few kilobytes of LDS; a launch of its own would cost more than all
+// workgroups repeating it).  Thread e < 256 collects the tokens routed to expert e (in token
+// order) and cuts them into items of at most tb tokens; item positions follow expert order, the
+// shared experts last.  All threads of the workgroup call; with `publish` the list also goes to
+// global memory for the reduction kernel and a pick that is not resident raises its flag.
+// Returns the item count (in every thread).
+__device__ __forceinline__ int build_items(const GroupArgs& a, GroupItem* s_items, int* s_cnt, int* s_base, bool publish) {
     const int tid = threadIdx.x;
     const int n_pick = a.B * a.k;
     int base = 0;
@@ -439,7 +442,7 @@ __global__ void __launch_bounds__(256) ffn_group_kernel(GroupArgs a) {
         int ntok = 0;
         int toks[kMaxBatch];
         float ws[kMaxBatch];
-        if (e < a.E)
+        if (tid < 256 && e < a.E)
             for (int p = 0; p < n_pick; ++p)
                 if (a.idx[p] == e && ntok < kMaxBatch) {
                     toks[ntok] = p / a.k;
@@ -450,53 +453,60 @@ __global__ void __launch_bounds__(256) ffn_group_kernel(GroupArgs a) {
         if (ntok > 0) {
             slot = a.slot_of_row[e];
             if (slot < 0) {  // not resident: contributes nothing, flagged
-                atomicOr(a.flags, 2);
+                if (publish) atomicOr(a.flags, 2);
                 ntok = 0;
             }
         }
         const int my_items = (ntok + a.tb - 1) / a.tb;
-        s_cnt[tid] = my_items;
+        if (tid < 256) s_cnt[tid] = my_items;
         __syncthreads();
-        int before = 0;
-        for (int i = 0; i < tid; ++i) before += s_cnt[i];
-        if (tid == 255) s_base = before + my_items;
-        for (int g = 0; g < my_items; ++g) {
-            GroupItem it;
-            it.slot = slot;
-            it.ntok = min(a.tb, ntok - g * a.tb);
-            for (int j = 0; j < kMaxGroup; ++j) {
-                const bool on = j < it.ntok;
-                it.tok[j] = on ? toks[g * a.tb + j] : 0;
-                it.w[j] = on ? ws[g * a.tb + j] : 0.f;
+        if (tid < 256) {
+            int before = 0;
+            for (int i = 0; i < tid; ++i) before += s_cnt[i];
+            if (tid == 255) *s_base = before + my_items;
+            for (int g = 0; g < my_items; ++g) {
+                GroupItem it;
+                it.slot = slot;
+                it.ntok = min(a.tb, ntok - g * a.tb);
+                for (int j = 0; j < kMaxGroup; ++j) {
+                    const bool on = j < it.ntok;
+                    it.tok[j] = on ? toks[g * a.tb + j] : 0;
+                    it.w[j] = on ? ws[g * a.tb + j] : 0.f;
+                }
+                s_items[base + before + g] = it;
             }
-            a.items[base + before + g] = it;
         }
         __syncthreads();
-        base += s_base;
+        base += *s_base;
         __syncthreads();
     }
-    if (tid == 0) {
-        int n = base;
-        for (int s = 0; s < a.n_shared; ++s)
-            for (int t0 = 0; t0 < a.B; t0 += a.tb) {
-                GroupItem it;
-                it.slot = a.shared_base + s;
-                it.ntok = min(a.tb, a.B - t0);
-                for (int j = 0; j < kMaxGroup; ++j) {
-                    it.tok[j] = j < it.ntok ? t0 + j : 0;
-                    it.w[j] = j < it.ntok ? 1.0f : 0.f;
-                }
-                a.items[n++] = it;
-            }
-        *a.n_items = n;
+    int n = base;
+    const int tiles = (a.B + a.tb - 1) / a.tb;
+    for (int q = tid; q < a.n_shared * tiles; q += blockDim.x) {
+        const int sh = q / tiles, t0 = (q - sh * tiles) * a.tb;
+        GroupItem it;
+        it.slot = a.shared_base + sh;
+        it.ntok = min(a.tb, a.B - t0);
+        for (int j = 0; j < kMaxGroup; ++j) {
+            it.tok[j] = j < it.ntok ? t0 + j : 0;
+            it.w[j] = j < it.ntok ? 1.0f : 0.f;
+        }
+        s_items[n + q] = it;
     }
+    n += a.n_shared * tiles;
+    __syncthreads();
+    if (publish) {
+        for (int q = tid; q < n; q += blockDim.x) a.items[q] = s_items[q];
+        if (tid == 0) *a.n_items = n;
+    }
+    return n;
 }
 
 struct GroupedFfnArgs {
     const void* pool;
     size_t slot_elems;
-    const GroupItem* items;
-    const int32_t* n_items;
+    GroupArgs grp;   // picks, gate weights, slot row; the item list goes to grp.items / grp.n_items
+    int max_items;   // room in the LDS item list
     const void* x;  // [B][H]
     float* part;    // [workgroups][seg_max][TB][H]
     int H, I;
@@ -526,14 +536,18 @@ __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(Gr
     constexpr int STEPS = StreamShape<NCH>::kSteps;
     constexpr int PF = StreamShape<NCH>::kWindow;
     extern __shared__ __align__(16) float smem[];
+    __shared__ int s_cnt[256];
+    __shared__ int s_base;
     float* xs = smem;              // [TB][H] inputs of the item's tokens, fp32
     float* yp = smem + TB * a.H;   // [kGroupedWaves][H] y rows of one token, one per wavefront
+    GroupItem* s_items = reinterpret_cast<GroupItem*>(yp + (size_t)kGroupedWaves * a.H);  // [max_items]
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int H = a.H, I = a.I;
     const WT* pool = reinterpret_cast<const WT*>(a.pool);
     const unsigned lane_off = (unsigned)lane * N;
-    const long total = (long)*a.n_items * I;
+    const int n_items = build_items(a.grp, s_items, s_cnt, &s_base, blockIdx.x == 0);
+    const long total = (long)n_items * I;
     const long R0 = grouped_range_begin(total, blockIdx.x, gridDim.x);
     const long R1 = grouped_range_begin(total, blockIdx.x + 1, gridDim.x);
     auto scalar = [](size_t v) -> size_t {
@@ -552,7 +566,7 @@ __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(Gr
         const int r0 = (int)(row - (long)item * I);
         const int r1 = (int)min((long)I, r0 + (R1 - row));
         row += r1 - r0;
-        const GroupItem it = a.items[item];
+        const GroupItem it = s_items[item];
         // this wavefront's rows of the segment: r0 + wv, r0 + wv + 8, ...
         const int nr = (r1 - r0 - wv + kGroupedWaves - 1) / kGroupedWaves;  // may be <= 0
         const size_t row_stride = (size_t)kGroupedWaves * 3 * H;
@@ -768,8 +782,7 @@ size_t grouped_part_floats(const moei_model_desc& d) {
 
 namespace {
 template <typename WT>
-int launch_grouped_typed(const moei_model_desc& d, GroupedFfnArgs ga, GroupArgs gr, int B, float* d_y,
-                         hipStream_t s) {
+int launch_grouped_typed(const moei_model_desc& d, GroupedFfnArgs ga, int B, float* d_y, hipStream_t s) {
     using V = WVec<WT>;
     const int nch = d.H / (kWave * V::N);
     const int grid = compute_units();
@@ -777,10 +790,9 @@ int launch_grouped_typed(const moei_model_desc& d, GroupedFfnArgs ga, GroupArgs 
     int rc;
 #define MOEI_GROUPED_CASE(N_)                                                                           \
     case N_: {                                                                                          \
-        gr.tb = GroupedShape<N_>::kTB;                                                                  \
-        launch(K_FFN_GROUP, ffn_group_kernel, dim3(1), dim3(256), 0, s, gr);                            \
-        MOEI_LAUNCH_CHECK();                                                                            \
-        const size_t smem = (size_t)(GroupedShape<N_>::kTB + kGroupedWaves) * d.H * sizeof(float);      \
+        ga.grp.tb = GroupedShape<N_>::kTB;                                                              \
+        const size_t smem = (size_t)(GroupedShape<N_>::kTB + kGroupedWaves) * d.H * sizeof(float) +     \
+                            (size_t)ga.max_items * sizeof(GroupItem);                                   \
         if (smem > kLdsBudget) MOEI_FAIL(MOEI_ECAPACITY, "expert_ffn_grouped: H = %d does not fit the LDS staging", d.H); \
         rc = allow_big_lds(ffn_grouped_kernel<WT, N_>, smem);                                           \
         if (rc) return rc;                                                                              \
@@ -800,8 +812,8 @@ int launch_grouped_typed(const moei_model_desc& d, GroupedFfnArgs ga, GroupArgs 
     }
 #undef MOEI_GROUPED_CASE
     launch(K_FFN_REDUCE, ffn_grouped_reduce_kernel, dim3(d.H / 64, B), dim3(256),
-           (size_t)grid * ga.seg_max * sizeof(int32_t), s, (const float*)ga.part, ga.items, ga.n_items, gr.tb, d.I, d.H,
-           grid, ga.seg_max, d_y);
+           (size_t)grid * ga.seg_max * sizeof(int32_t), s, (const float*)ga.part, (const GroupItem*)ga.grp.items,
+           (const int32_t*)ga.grp.n_items, ga.grp.tb, d.I, d.H, grid, ga.seg_max, d_y);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
 }
@@ -818,9 +830,9 @@ int launch_expert_ffn_grouped(const moei_model_desc& d, const void* d_pool, size
         MOEI_FAIL(MOEI_EINVAL, "expert_ffn_grouped: H = %d must be a multiple of %d", d.H, kWave * n);
     GroupArgs gr{d_idx, d_w, d_slot_of_row, B, d.k, d.E, d.n_shared, shared_base, 0,
                  reinterpret_cast<GroupItem*>(d_items), d_n_items, d_flags};
-    GroupedFfnArgs ga{d_pool, slot_elems, reinterpret_cast<const GroupItem*>(d_items), d_n_items, d_x, d_part, d.H, d.I, 0};
-    if (d.wdtype == MOEI_WDTYPE_BF16) return launch_grouped_typed<uint16_t>(d, ga, gr, B, d_y, s);
-    return launch_grouped_typed<float>(d, ga, gr, B, d_y, s);
+    GroupedFfnArgs ga{d_pool, slot_elems, gr, grouped_max_items(d), d_x, d_part, d.H, d.I, 0};
+    if (d.wdtype == MOEI_WDTYPE_BF16) return launch_grouped_typed<uint16_t>(d, ga, B, d_y, s);
+    return launch_grouped_typed<float>(d, ga, B, d_y, s);
 }
 
 }  // namespace moei

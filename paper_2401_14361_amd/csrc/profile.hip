@@ -18,7 +18,7 @@ size_t g_used = 0;
 
 const char* const kNames[K_COUNT] = {
     "route_topk_kernel", "eamc_dot_kernel",   "eamc_pick_kernel", "priority_score_kernel",
-    "priority_rank_kernel", "ffn_fused_kernel", "ffn_reduce_kernel", "ffn_group_kernel",
+    "priority_rank_kernel", "ffn_fused_kernel", "ffn_reduce_kernel", "prefill_group_kernels",
     "prefill_route_kernel", "prefill_gateup_kernel", "prefill_down_kernel", "prefill_reduce_kernel",
 };
 
