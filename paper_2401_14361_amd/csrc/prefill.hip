@@ -255,7 +255,23 @@ struct MmArgs {
     int H, I;
     int32_t* flags;
     int once;  // every expert's weights pass once (short prompt): load them with the non-temporal hint
+    int n_ub;  // gate/up: blocks of 64 units;  down: blocks of 512 columns
+    int n_cb;
 };
+
+// Workgroups are handed to the chip's 8 XCDs in turn, and every XCD has an L2 of its own.  The
+// grids are one-dimensional and numbered so that one XCD always serves the same output blocks
+// (unit blocks / column blocks, i.e. the same weight rows) for item after item: the items of
+// one expert follow each other in the list, so the second and later ones find the expert's
+// weights in that XCD's L2 instead of fetching them again.
+constexpr int kXcds = 8;
+__device__ __forceinline__ bool xcd_work(int n_blocks, int* item, int* block) {
+    const int per = (n_blocks + kXcds - 1) / kXcds;  // output blocks per XCD
+    const int v = blockIdx.x, xcd = v % kXcds, w = v / kXcds;
+    *item = w / per;
+    *block = xcd + kXcds * (w % per);
+    return *block < n_blocks;
+}
 
 __device__ __forceinline__ bf16x8 ld_bf16x8(const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
 
@@ -279,7 +295,8 @@ __global__ void __launch_bounds__(TM * 4) prefill_gateup_kernel(MmArgs a) {
     uint16_t* Xs = reinterpret_cast<uint16_t*>(smem_raw);  // [TM][ls] inputs
     uint16_t* Ws = Xs + (size_t)TM * ls;                   // [2 * kGuUnits][ls] gate rows, then up rows
     __shared__ float s_gate[TM];
-    const int item = blockIdx.y;
+    int item, ub;
+    if (!xcd_work(a.n_ub, &item, &ub)) return;
     if (item >= a.meta[0]) return;
     const PItem it = a.items[item];
     if (it.slot < 0 || it.slot >= a.n_slots_total) return;  // the down kernel writes the zeros and raises the flag
@@ -290,7 +307,7 @@ __global__ void __launch_bounds__(TM * 4) prefill_gateup_kernel(MmArgs a) {
     const int ug = wv & 3, tq = wv >> 2;  // unit group, token quarter
     const bool live = tq * 64 < it.ntok;  // a quarter past the item's tokens only helps staging
     const uint16_t* wslot = a.pool + (size_t)it.slot * a.slot_elems;
-    const int u_wg = blockIdx.x * kGuUnits;
+    const int u_wg = ub * kGuUnits;
 
     if (tid < TM) s_gate[tid] = tid < it.ntok ? (it.first_tok >= 0 ? 1.0f : a.pgate[it.list_off + tid]) : 0.f;
     constexpr int VPR = kGuKS / 8;                                // 16-byte vectors per row and slice
@@ -589,8 +606,8 @@ int launch_mm(const moei_model_desc& d, const MmArgs& a, int max_items, hipStrea
     if (rc) return rc;
     rc = pf_allow_lds(prefill_down_kernel<TM>, dn_smem);
     if (rc) return rc;
-    launch(K_PF_GATEUP, prefill_gateup_kernel<TM>, dim3((d.I + kGuUnits - 1) / kGuUnits, max_items), dim3(TM * 4), gu_smem,
-           s, a);
+    const int gu_per = (a.n_ub + kXcds - 1) / kXcds;
+    launch(K_PF_GATEUP, prefill_gateup_kernel<TM>, dim3(kXcds * gu_per * max_items), dim3(TM * 4), gu_smem, s, a);
     MOEI_LAUNCH_CHECK();
     launch(K_PF_DOWN, prefill_down_kernel<TM>, dim3((d.H + kDnCols - 1) / kDnCols, max_items), dim3(TM * 4), dn_smem, s, a);
     MOEI_LAUNCH_CHECK();
@@ -629,7 +646,8 @@ int launch_prefill(const moei_model_desc& d, const PrefillScratch& ps, const voi
     const int max_items = max_items_for(d, n, tm);
     MmArgs a{reinterpret_cast<const uint16_t*>(d_pool), slot_elems, n_slots_total,
              reinterpret_cast<const PItem*>(ps.d_items), ps.d_meta, reinterpret_cast<const uint16_t*>(d_X), ps.d_perm,
-             ps.d_pgate, ps.d_act, ps.d_yc, d.H, d.I, d_flags, weights_pass_once(d, n)};
+             ps.d_pgate, ps.d_act, ps.d_yc, d.H, d.I, d_flags, weights_pass_once(d, n), (d.I + kGuUnits - 1) / kGuUnits,
+             (d.H + kDnCols - 1) / kDnCols};
     rc = tm == kTileTokBig ? launch_mm<kTileTokBig>(d, a, max_items, s) : launch_mm<kTileTok>(d, a, max_items, s);
     if (rc) return rc;
     launch(K_PF_REDUCE, prefill_reduce_kernel, dim3(n), dim3(256), 0, s, (const float*)ps.d_yc,
