@@ -70,8 +70,9 @@ __device__ __forceinline__ void block_sum_rows(float* yp, int H, int waves, int 
 template <int NCH>
 struct StreamShape {
     static constexpr int kSteps = 3 * NCH;
-    // window depth: the largest divisor-quotient of the step count that is <= 16
-    static constexpr int kWindow = kSteps <= 16 ? kSteps : (kSteps / 2 <= 16 && kSteps % 2 == 0 ? kSteps / 2 : kSteps / 3);
+    // window depth: all steps of a unit if they are at most 16, else half of them if that is at most 12
+    // (15 loads in flight for rows of 10 chunks left no registers: 3 spills), else a third
+    static constexpr int kWindow = kSteps <= 16 ? kSteps : (kSteps / 2 <= 12 && kSteps % 2 == 0 ? kSteps / 2 : kSteps / 3);
     // register budget: window + y accumulators decide how many wavefronts fit a SIMD
     static constexpr int kMaxWaves = NCH <= 4 ? 16 : (NCH <= 10 ? 12 : 8);
 };
