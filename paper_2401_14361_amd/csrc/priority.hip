@@ -59,12 +59,19 @@ __global__ void __launch_bounds__(kRankThreads)
         const u64 mine = keys[f];
         if (mine == kNone) continue;  // uniform over the wavefront
         int rank = 0;
-#pragma unroll 4
-        for (int g0 = 0; g0 < LE; g0 += kWave) {
-            const int g = g0 + lane;
-            const u64 kg = g < LE ? keys[g] : kNone;
-            const bool before = kg < mine || (kg == mine && g < f);
-            rank += __popcll(__ballot(before));
+        for (int g0 = 0; g0 < LE; g0 += 4 * kWave) {  // four LDS reads in flight, then four ballots
+            u64 kg[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int g = g0 + u * kWave + lane;
+                kg[u] = g < LE ? keys[g] : kNone;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int g = g0 + u * kWave + lane;
+                const bool before = kg[u] < mine || (kg[u] == mine && g < f);  // a padding key is never before
+                rank += __popcll(__ballot(before));
+            }
         }
         if (lane == 0) order[rank] = f;
     }

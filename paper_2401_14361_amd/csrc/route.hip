@@ -115,7 +115,6 @@ __global__ void __launch_bounds__(kRouteWaves * kWave) route_fused_kernel(RouteF
     __shared__ unsigned s_ticket;
     __shared__ int s_pick[kWave];
     __shared__ float s_pw[kWave];
-    __shared__ float s_sel;
     int* s_slot = reinterpret_cast<int*>(z + a.E);
     int* s_eam = s_slot + a.E;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
