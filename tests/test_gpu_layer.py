@@ -129,6 +129,56 @@ def _replay(m, cfg, S, n_tokens, n_unique, cell_bytes, rid=0, match_m=1):
     return n_miss_total
 
 
+def test_requests_in_sequence_starting_from_an_empty_collection(m):
+    # the online loop (App. B.1): the first request meets an empty EAMC (no match: best = -1, all
+    # prefetch scores zero, eviction by layer decay alone); its request-level EAM is inserted when
+    # it ends; later requests match what their predecessors left
+    cfg = mi.get_config("C1").scaled(H=64, I=32)
+    L, E, k, S = cfg.L, cfg.E, cfg.k, 10
+    bank = mi.expert_bank(cfg, L * E, threads=2)
+    routers = [mi.router_weights(cfg, l) for l in range(L)]
+    desc = m.ModelDesc.from_config(cfg)
+    eamc = m.Eamc(desc, 8, 4)
+    cache = m.Cache(desc, S, pinned(pack_bank(m, cfg, bank)))
+    cache.reset(S)
+    ref_cache = O.ExpertCache(L, E, S)
+    d_routers = [dev(w) for w in routers]
+    y = torch.empty(cfg.H, dtype=torch.float32, device="cuda")
+    T = np.zeros((0, L, E), dtype=np.int32)
+    bests = []
+    for rid in range(3):
+        req = mi.make_request(cfg, 40 + rid, decode=12)
+        tokens = pick_clear_tokens(cfg, req, 4)
+        d_eam = dev(req.prefill_eam.astype(np.int32))
+        ref_eam = req.prefill_eam.astype(np.int64).copy()
+        d_bias, d_x = dev(req.bias), dev(req.x)
+        for t in tokens:
+            for l in range(L):
+                idx, best, n_miss = m.moe_decode_layer(cache, eamc, d_eam, l, d_routers[l], d_bias[l], d_x[t, l], y)
+                last = cache.last_step()
+                ref = O.decode_layer(T, ref_eam, ref_cache, l, routers[l], req.bias[l], req.x[t, l],
+                                     lambda f: split_expert(cfg, bank[f]), lambda layer: [], k, bool(cfg.renorm), EPS)
+                where = f"request {rid} token {t} layer {l}"
+                assert idx.tolist() == ref["idx"].tolist(), where
+                assert best == ref["best"], where
+                assert last["ev_order"].tolist() == ref["ev_order"], where
+                assert last["pf_order"].tolist() == ref["pf_order"], where
+                np.testing.assert_allclose(last["V"], ref["V"], rtol=1e-6, err_msg=where)
+                np.testing.assert_allclose(last["P"], ref["P"], rtol=1e-6, atol=0, err_msg=where)
+                assert (cache.get_slots() == ref_cache.slot_of).all(), where
+                assert rel_max_err(y.cpu().numpy(), ref["y"]) <= FFN_TOL_FP32ACC, where
+                bests.append(best)
+        assert (d_eam.cpu().numpy() == ref_eam).all()
+        eamc.insert(ref_eam.astype(np.int32))
+        T = np.concatenate([T, ref_eam.astype(np.int32)[None]], axis=0)
+        assert eamc.size == rid + 1 and (eamc.export() == T).all()
+    n_first = 4 * L
+    assert all(b == -1 for b in bests[:n_first]) and all(b >= 0 for b in bests[n_first:])
+    assert cache.error_flags() == 0
+    eamc.close()
+    cache.close()
+
+
 def test_decode_request_tiny_config(m):
     # configuration 1 as specified: 4 layers x 8 experts, top-2, fp32, 12 of 32 slots, 16 decode tokens
     cfg = mi.get_config("C1")
