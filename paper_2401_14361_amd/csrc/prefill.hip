@@ -47,6 +47,7 @@ struct PItem {
     int32_t list_off;   // routed: position of the item's first token in perm / pgate
     int32_t first_tok;  // shared expert: tokens first_tok .. first_tok + ntok - 1 with weight 1; else -1
     int32_t row0;       // the item's first row of the activation / contribution buffers
+    int32_t once;       // the expert has no other item: its weights are read once (non-temporal loads)
 };
 
 // ------------------------------------------------------------------ 1. routing of n tokens
@@ -218,13 +219,14 @@ __global__ void __launch_bounds__(kGrpThreads) prefill_place_kernel(GroupArgsP g
     const int slot = g.slot_of_row[e];
     if (cnt > 0 && slot < 0 && tid == 0) atomicOr(g.flags, 2);
     for (int it = tid; it * g.TM < cnt; it += kGrpThreads)
-        g.items[ioff + it] = PItem{slot, min(g.TM, cnt - it * g.TM), off + it * g.TM, -1, off + it * g.TM};
+        g.items[ioff + it] = PItem{slot, min(g.TM, cnt - it * g.TM), off + it * g.TM, -1, off + it * g.TM, cnt <= g.TM};
     if (e == 0) {
         const int tiles = (g.n + g.TM - 1) / g.TM;
         for (int q = tid; q < g.n_shared * tiles; q += kGrpThreads) {
             const int s = q / tiles, tile = q - s * tiles;
             g.items[n_routed + q] =
-                PItem{g.shared_base + s, min(g.TM, g.n - tile * g.TM), 0, tile * g.TM, g.n * g.k + s * g.n + tile * g.TM};
+                PItem{g.shared_base + s, min(g.TM, g.n - tile * g.TM), 0, tile * g.TM, g.n * g.k + s * g.n + tile * g.TM,
+                      tiles == 1};
         }
         if (tid == 0) {
             g.meta[0] = n_routed + g.n_shared * tiles;
@@ -262,7 +264,6 @@ struct MmArgs {
     float* yc;      // [rows][H]
     int H, I;
     int32_t* flags;
-    int once;  // every expert's weights pass once (short prompt): load them with the non-temporal hint
     int n_ub;  // gate/up: blocks of 64 units;  down: blocks of 512 columns
     int n_cb;
 };
@@ -342,7 +343,7 @@ __global__ void __launch_bounds__(TM * 4) prefill_gateup_kernel(MmArgs a) {
 #pragma unroll
         for (int j = 0; j < NW; ++j) {
             const int kk = s * kGuKS + ((tid + kMmThreads * j) % VPR) * 8;
-            wst[j] = kk < H ? (a.once ? load_once_16(wsrc[j] + s * kGuKS) : *reinterpret_cast<const uint4*>(wsrc[j] + s * kGuKS))
+            wst[j] = kk < H ? (it.once ? load_once_16(wsrc[j] + s * kGuKS) : *reinterpret_cast<const uint4*>(wsrc[j] + s * kGuKS))
                             : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
@@ -467,7 +468,7 @@ __global__ void __launch_bounds__(TM * 4, 2) prefill_down_kernel(MmArgs a) {  //
     auto load_w = [&](int k0, uint4* dst) {  // units k0 + 8*lgrp + j (clamped: their activations are zero)
 #pragma unroll
         for (int j = 0; j < 8; ++j)
-            dst[j] = a.once ? load_once_16(wd + (size_t)min(k0 + lgrp * 8 + j, I - 1) * 3 * H)
+            dst[j] = it.once ? load_once_16(wd + (size_t)min(k0 + lgrp * 8 + j, I - 1) * 3 * H)
                             : *reinterpret_cast<const uint4*>(wd + (size_t)min(k0 + lgrp * 8 + j, I - 1) * 3 * H);
     };
 
@@ -599,12 +600,6 @@ int tile_tokens(const moei_model_desc& d, int n) {
     return (long)n * d.k > (long)kTileTok * d.E ? kTileTokBig : kTileTok;
 }
 
-// Short prompts: nearly every expert holds one item, so its weights are read once and are loaded
-// with the non-temporal hint (measured: 263 -> 243 us per layer at 64 tokens, 298 -> 294 us at 256);
-// from about half a small tile per expert on, items of one expert re-read its weights through the
-// caches and the hint costs time (351 -> 368 us at 512 tokens).
-int weights_pass_once(const moei_model_desc& d, int n) { return (long)n * d.k <= 32L * d.E && n <= 4 * kTileTok; }
-
 template <int TM>
 int launch_mm(const moei_model_desc& d, const MmArgs& a, int max_items, hipStream_t s) {
     const size_t gu_smem = (size_t)(TM + 2 * kGuUnits) * kTileK * 2;
@@ -653,7 +648,7 @@ int launch_prefill(const moei_model_desc& d, const PrefillScratch& ps, const voi
     const int max_items = max_items_for(d, n, tm);
     MmArgs a{reinterpret_cast<const uint16_t*>(d_pool), slot_elems, n_slots_total,
              reinterpret_cast<const PItem*>(ps.d_items), ps.d_meta, reinterpret_cast<const uint16_t*>(d_X), ps.d_perm,
-             ps.d_pgate, ps.d_act, ps.d_yc, d.H, d.I, d_flags, weights_pass_once(d, n), (d.I + kGuUnits - 1) / kGuUnits,
+             ps.d_pgate, ps.d_act, ps.d_yc, d.H, d.I, d_flags, (d.I + kGuUnits - 1) / kGuUnits,
              (d.H + kDnCols - 1) / kDnCols};
     rc = tm == kTileTokBig ? launch_mm<kTileTokBig>(d, a, max_items, s) : launch_mm<kTileTok>(d, a, max_items, s);
     if (rc) return rc;
