@@ -648,9 +648,9 @@ Plan make_plan(const moei_eamc* c, int L_scan, int B) {
     if (p.TN < 1) p.TN = 1;
     p.J = (p.TN * p.rowV + kDotThreads - 1) / kDotThreads;
     p.n_tiles = (c->N + p.TN - 1) / p.TN;
-    // aim at enough workgroups to fill the chip (two rounds of them when the scan is long);
-    // the query groups multiply the grid as well
-    const int target = kTargetBlocks > 0 ? kTargetBlocks : (jt > 1 ? 512 : 256);
+    // aim at two rounds of workgroups over the chip (short scans too: 4.2 instead of 4.5 us for
+    // 1,000 traces beside the streaming FFN); the query groups multiply the grid as well
+    const int target = kTargetBlocks > 0 ? kTargetBlocks : 512;
     const int per_split = p.n_tiles * ((B + p.NB - 1) / p.NB);
     int want = (target + per_split - 1) / per_split;
     int lmax = L_scan < c->lsplit_max ? L_scan : c->lsplit_max;
