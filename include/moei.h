@@ -16,6 +16,12 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls are asynchronous on it unless they fill h_* outputs, in which case
  *     they synchronise as documented per function.
+ *   - A moei_eamc and a moei_cache each hold device scratch (partial sums, arrival
+ *     counters, sort keys, partial rows) that their calls reuse: calls that name
+ *     the same object must be ordered by the caller (one stream, or events
+ *     between streams); calls on different objects are independent.  A cache's
+ *     layer step uses the EAMC it is handed on the cache's own side stream:
+ *     moei_cache_join / moei_cache_sync order that work before other uses of it.
  *   - Matrices are row-major and dense.  Layer indices are 0-based.
  *   - Notation (Sec. 4.3 of the paper): L MoE layers, E routed experts per
  *     layer, k experts per token, EAM = L x E matrix of token counts; H hidden
