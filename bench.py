@@ -487,8 +487,17 @@ def main():
                            shared_of, k, bool(cfg.renorm), EPS)
             spent += time.perf_counter() - a
             n_cpu += 1
+        model = ""
+        try:
+            for line in open("/proc/cpuinfo"):
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+        except OSError:
+            pass
         cpu = {"value": spent / n_cpu * 1e6, "unit": "us per MoE-layer decode step", "cores": threads, "kind": "oracle",
-               "sample": f"first {n_cpu} layer steps of the same request (all experts resident), {spent:.1f} s of CPU time"}
+               "sample": f"first {n_cpu} layer steps of the same request (all experts resident), {spent:.1f} s of CPU time",
+               "host_cpus": os.cpu_count(), "cpu_model": model}
         log(f"[bench] oracle: {cpu['value'] / 1e3:.0f} ms per layer step on {threads} thread(s)")
 
     out = {
