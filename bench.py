@@ -352,8 +352,8 @@ def main():
             torch.cuda.synchronize()
             t_match = ev0.elapsed_time(ev1) / 50 * 1e3
             ev0.record(stream)
-            for _ in range(50):
-                m.expert_ffn_grouped(cache, 0, idx_b, w_b, xb, stream=stream)
+            for i in range(50):  # another layer's slots every call: the weights come from HBM, not from a cache
+                m.expert_ffn_grouped(cache, i % L, idx_b, w_b, xb, stream=stream)
             ev1.record(stream)
             torch.cuda.synchronize()
             t_ffn = ev0.elapsed_time(ev1) / 50 * 1e3
