@@ -434,9 +434,18 @@ struct GroupArgs {
 // shared experts last.  All threads of the workgroup call; with `publish` the list also goes to
 // global memory for the reduction kernel and a pick that is not resident raises its flag.
 // Returns the item count (in every thread).
-__device__ __forceinline__ int build_items(const GroupArgs& a, GroupItem* s_items, int* s_cnt, int* s_base, bool publish) {
+__device__ __forceinline__ int build_items(const GroupArgs& a, GroupItem* s_items, int* s_pick, int* s_cnt, int* s_base,
+                                           bool publish) {
+    // s_pick[B*k] and, behind it, the gate weights: the call's picks are loaded once, then every
+    // expert's scan runs over LDS
     const int tid = threadIdx.x;
     const int n_pick = a.B * a.k;
+    float* s_pickw = reinterpret_cast<float*>(s_pick + n_pick);
+    for (int p = tid; p < n_pick; p += blockDim.x) {
+        s_pick[p] = a.idx[p];
+        s_pickw[p] = a.w[p];
+    }
+    __syncthreads();
     int base = 0;
     for (int e0 = 0; e0 < a.E; e0 += 256) {
         const int e = e0 + tid;
@@ -445,9 +454,9 @@ __device__ __forceinline__ int build_items(const GroupArgs& a, GroupItem* s_item
         float ws[kMaxBatch];
         if (tid < 256 && e < a.E)
             for (int p = 0; p < n_pick; ++p)
-                if (a.idx[p] == e && ntok < kMaxBatch) {
+                if (s_pick[p] == e && ntok < kMaxBatch) {
                     toks[ntok] = p / a.k;
-                    ws[ntok] = a.w[p];
+                    ws[ntok] = s_pickw[p];
                     ++ntok;
                 }
         int slot = -1;
@@ -547,7 +556,8 @@ __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(Gr
     const int H = a.H, I = a.I;
     const WT* pool = reinterpret_cast<const WT*>(a.pool);
     const unsigned lane_off = (unsigned)lane * N;
-    const int n_items = build_items(a.grp, s_items, s_cnt, &s_base, blockIdx.x == 0);
+    int* s_pick = reinterpret_cast<int*>(s_items + a.max_items);  // [2][B*k]
+    const int n_items = build_items(a.grp, s_items, s_pick, s_cnt, &s_base, blockIdx.x == 0);
     const long total = (long)n_items * I;
     const long R0 = grouped_range_begin(total, blockIdx.x, gridDim.x);
     const long R1 = grouped_range_begin(total, blockIdx.x + 1, gridDim.x);
@@ -660,19 +670,25 @@ __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(Gr
     }
 }
 
-// y[b][h] = sum of the partial rows of the segments whose item holds token b: 16 slices take
-// the segments in turn (workgroup-major order) and are then added in slice order.
-// grid (H / 64, B), 256 threads = 16 slices x 16 float4 columns; dynamic LDS: n_blocks * seg_max ints.
+// y[b][h] = sum of the partial rows of the segments whose item holds token b.  The workgroup
+// first lists those rows in segment order (workgroup-major) in LDS; 32 slices of the list are
+// then added by a thread each, all of a slice's loads in flight together, and the slice sums are
+// added in slice order.  grid (H / 32, B), 256 threads = 32 slices x 8 float4 columns;
+// dynamic LDS: 2 * n_blocks * seg_max ints.
 __global__ void __launch_bounds__(256) ffn_grouped_reduce_kernel(const float* __restrict__ part,
                                                                  const GroupItem* __restrict__ items,
                                                                  const int32_t* __restrict__ n_items, int tb, int I,
                                                                  int H, int n_blocks, int seg_max,
                                                                  float* __restrict__ y) {
     extern __shared__ __align__(16) int32_t s_rows[];  // partial row of each segment for this token, or -1
-    __shared__ float4 s_red[16][16];
-    const int b = blockIdx.y;
+    __shared__ float s_sum[32][32];
+    __shared__ int s_wbase[4];
+    __shared__ int s_nv;
+    const int n = n_blocks * seg_max;
+    int32_t* s_list = s_rows + n;  // the rows that exist, in segment order
+    const int b = blockIdx.y, tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const long total = (long)*n_items * I;
-    for (int g = threadIdx.x; g < n_blocks; g += 256) {
+    for (int g = tid; g < n_blocks; g += 256) {
         long row = grouped_range_begin(total, g, n_blocks);
         const long R1 = grouped_range_begin(total, g + 1, n_blocks);
         for (int seg = 0; seg < seg_max; ++seg) {
@@ -688,37 +704,52 @@ __global__ void __launch_bounds__(256) ffn_grouped_reduce_kernel(const float* __
         }
     }
     __syncthreads();
-    const int slice = threadIdx.x >> 4, col = threadIdx.x & 15;
-    const int h = blockIdx.x * 64 + col * 4;
-    const int n = n_blocks * seg_max;
+    // compaction in list order: ballots inside a wavefront, running offsets across wavefronts and rounds
+    int base = 0;
+    for (int e0 = 0; e0 < n; e0 += 256) {
+        const int e = e0 + tid;
+        const int r = e < n ? s_rows[e] : -1;
+        const unsigned long long mask = __ballot(r >= 0);
+        if (lane == 0) s_wbase[wv] = __popcll(mask);
+        __syncthreads();
+        int before = base;
+        for (int w = 0; w < wv; ++w) before += s_wbase[w];
+        if (r >= 0) s_list[before + __popcll(mask & ((1ull << lane) - 1ull))] = r;
+        base += s_wbase[0] + s_wbase[1] + s_wbase[2] + s_wbase[3];
+        __syncthreads();
+    }
+    if (tid == 0) s_nv = base;
+    __syncthreads();
+    const int nv = s_nv;
+    const int cq = tid & 7, sl = tid >> 3;
+    const int h = blockIdx.x * 32 + cq * 4;
+    const int per = (nv + 31) / 32;
+    const int p0 = sl * per, p1 = min(nv, p0 + per);
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int e0 = slice; e0 < n; e0 += 64) {
-        float4 v[4];
+    for (int p = p0; p < p1; p += 8) {
+        float4 v[8];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int e = e0 + 16 * u;
-            const int r = e < n ? s_rows[e] : -1;
-            v[u] = r >= 0 ? *reinterpret_cast<const float4*>(part + (size_t)r * H + h) : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
+        for (int u = 0; u < 8; ++u)
+            v[u] = p + u < p1 ? *reinterpret_cast<const float4*>(part + (size_t)s_list[p + u] * H + h)
+                              : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < 8; ++u) {
             acc.x += v[u].x;
             acc.y += v[u].y;
             acc.z += v[u].z;
             acc.w += v[u].w;
         }
     }
-    s_red[slice][col] = acc;
+    s_sum[sl][cq * 4 + 0] = acc.x;
+    s_sum[sl][cq * 4 + 1] = acc.y;
+    s_sum[sl][cq * 4 + 2] = acc.z;
+    s_sum[sl][cq * 4 + 3] = acc.w;
     __syncthreads();
-    if (slice == 0) {
-        float4 t = s_red[0][col];
-        for (int k = 1; k < 16; ++k) {
-            t.x += s_red[k][col].x;
-            t.y += s_red[k][col].y;
-            t.z += s_red[k][col].z;
-            t.w += s_red[k][col].w;
-        }
-        *reinterpret_cast<float4*>(y + (size_t)b * H + h) = t;
+    if (tid < 32) {
+        float t = 0.f;
+#pragma unroll
+        for (int k2 = 0; k2 < 32; ++k2) t += s_sum[k2][tid];
+        y[(size_t)b * H + blockIdx.x * 32 + tid] = t;
     }
 }
 
@@ -795,7 +826,7 @@ int launch_grouped_typed(const moei_model_desc& d, GroupedFfnArgs ga, int B, flo
     case N_: {                                                                                          \
         ga.grp.tb = GroupedShape<N_>::kTB;                                                              \
         const size_t smem = (size_t)(GroupedShape<N_>::kTB + kGroupedWaves) * d.H * sizeof(float) +     \
-                            (size_t)ga.max_items * sizeof(GroupItem);                                   \
+                            (size_t)ga.max_items * sizeof(GroupItem) + (size_t)B * d.k * 8;             \
         if (smem > kLdsBudget) MOEI_FAIL(MOEI_ECAPACITY, "expert_ffn_grouped: H = %d does not fit the LDS staging", d.H); \
         rc = allow_big_lds(ffn_grouped_kernel<WT, N_>, smem);                                           \
         if (rc) return rc;                                                                              \
@@ -814,8 +845,8 @@ int launch_grouped_typed(const moei_model_desc& d, GroupedFfnArgs ga, int B, flo
                       kWave * V::N);
     }
 #undef MOEI_GROUPED_CASE
-    launch(K_FFN_REDUCE, ffn_grouped_reduce_kernel, dim3(d.H / 64, B), dim3(256),
-           (size_t)grid * ga.seg_max * sizeof(int32_t), s, (const float*)ga.part, (const GroupItem*)ga.grp.items,
+    launch(K_FFN_REDUCE, ffn_grouped_reduce_kernel, dim3(d.H / 32, B), dim3(256),
+           (size_t)2 * grid * ga.seg_max * sizeof(int32_t), s, (const float*)ga.part, (const GroupItem*)ga.grp.items,
            (const int32_t*)ga.grp.n_items, ga.grp.tb, d.I, d.H, grid, ga.seg_max, d_y);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
