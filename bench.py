@@ -84,7 +84,7 @@ def main():
 
     import moei_inputs as mi
     import paper_2401_14361_amd as m
-    from tests.helpers import EPS, dev, pack_bank, pinned, split_expert
+    from moei_inputs.plumbing import EPS, dev, pack_bank, pinned, split_expert
 
     if not os.path.exists(m.lib_path()):
         from paper_2401_14361_amd.build import build

@@ -314,8 +314,11 @@ constexpr size_t kLdsBudget = 150 * 1024;  // of the 160 KiB per compute unit
 // Wavefronts per workgroup: the count in [4, max_waves] that wastes the fewest unit slots when
 // n_units are dealt out to blocks * waves wavefronts (ties go to more wavefronts).
 int plan_waves(int n_units, int blocks, int max_waves) {
-    int forced = env_int("MOEI_FFN_WAVES", 0);
+    static const int forced = env_int("MOEI_FFN_WAVES", 0);  // the environment is read once per process
     if (forced >= 1 && forced <= max_waves) return forced;
+    // a layer step repeats the same shape call after call: the last plan is kept
+    static int memo_key[3] = {-1, -1, -1}, memo_val = 0;
+    if (memo_key[0] == n_units && memo_key[1] == blocks && memo_key[2] == max_waves) return memo_val;
     int best = max_waves;
     double best_eff = -1.0;
     for (int m = max_waves; m >= (max_waves < 4 ? 1 : 4); --m) {
@@ -326,6 +329,10 @@ int plan_waves(int n_units, int blocks, int max_waves) {
             best = m;
         }
     }
+    memo_key[0] = n_units;
+    memo_key[1] = blocks;
+    memo_key[2] = max_waves;
+    memo_val = best;
     return best;
 }
 
@@ -800,8 +807,9 @@ int launch_expert_ffn(const moei_model_desc& d, const void* d_pool, size_t slot_
     a.flags = d_flags;
     const int wb = d.wdtype == MOEI_WDTYPE_BF16 ? 2 : 4;
     const int n = 16 / wb;
+    static const bool force_generic = env_int("MOEI_FFN_GENERIC", 0) != 0;
     const bool fast = (d.H % (kWave * n) == 0) && ((uintptr_t)d_pool % 16 == 0) && ((slot_elems * wb) % 16 == 0) &&
-                      env_int("MOEI_FFN_GENERIC", 0) == 0;
+                      !force_generic;
     if (d.wdtype == MOEI_WDTYPE_BF16) return launch_ffn_typed<uint16_t>(a, fast, scr.n_part, d_y, s);
     return launch_ffn_typed<float>(a, fast, scr.n_part, d_y, s);
 }
