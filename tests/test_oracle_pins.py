@@ -684,6 +684,70 @@ def test_decode_layer_hand_worked_step_with_two_matches():
     assert out["ev_order"] == [2, 5]                            # V[2] = (4 + eps)/16 < V[5] = (8 + eps)(2/3)/16
 
 
+def test_decode_layer_hand_worked_step_with_prefetch():
+    """Layer 1 of a 4-layer x 4-expert model, top-2, identity router, prefetch depth 2.  The numbers are
+    chosen so that the prefetch order (by P) and the admission measure (V, Alg. 1's score) disagree:
+    the first candidate has the larger P but the smaller V and is turned down, the second is admitted.
+    Everything below is worked out by hand in fractions (eps = 2^-20 only breaks exact zeros)."""
+    L, E = 4, 4
+    T = np.array([[[2, 2, 0, 0], [3, 2, 3, 0], [0, 0, 6, 4], [0, 5, 0, 0]],      # row sums 4, 8, 10, 5
+                  [[0, 0, 5, 5], [0, 0, 0, 7], [7, 0, 0, 0], [0, 0, 0, 3]]])     # orthogonal to the query
+    cache = O.ExpertCache(L, E, 4, warm=False)
+    cache.retrieve(0, [0, 2])                                   # slots 0, 1: flat ids 0 and 2
+    cache.retrieve(1, [1, 2])                                   # slots 2, 3: flat ids 5 and 6
+    par = {5: (0.5, 1.0), 4: (-0.25, 2.0)}                      # expert -> (g, d); o = d silu(g x0) x1 e_0
+
+    def mk(g, d):
+        return (np.array([[g, 0.0, 0.0, 0.0]]), np.array([[0.0, 1.0, 0.0, 0.0]]), np.array([[d], [0.0], [0.0], [0.0]]))
+
+    def run(depth):
+        c = O.ExpertCache(L, E, 4, warm=False)
+        c.retrieve(0, [0, 2])
+        c.retrieve(1, [1, 2])
+        eam = np.zeros((L, E), dtype=np.int64)
+        eam[0, :2] = 1                                          # this iteration's layer 0 picked experts 0 and 1
+        out = O.decode_layer(T, eam, c, 1, np.eye(4), None, np.array([3.0, 4.0, 0.0, 0.0]),
+                             lambda f: mk(*par.get(f, (9.0, 9.0))), lambda l: [mk(1.0, -1.0)], 2, False, 2.0 ** -20,
+                             prefetch_depth=depth)
+        return out, eam, c
+
+    out, eam, c = run(2)
+    assert out["idx"].tolist() == [1, 0]                        # logits (3, 4, 0, 0)
+    assert eam.tolist() == [[1, 1, 0, 0], [1, 1, 0, 0], [0, 0, 0, 0], [0, 0, 0, 0]]
+    # <q, T_0> = 2 + 2 + 3 + 2 = 9, |q|^2 = 4, |T_0|^2 = 107; <q, T_1> = 0
+    assert out["best"] == 0 and out["sim"] == pytest.approx(9.0 / (2.0 * math.sqrt(107.0)), rel=1e-15)
+    # prefetch scores at l = 1: cell / row sum x (L - i + l) / L for i > 1
+    P = np.zeros((L, E)); P[2, 2] = 0.6 * 0.75; P[2, 3] = 0.4 * 0.75; P[3, 1] = 1.0 * 0.5
+    np.testing.assert_allclose(out["P"], P, rtol=1e-15)
+    assert out["pf_order"] == [13, 10, 11]                      # 0.5 > 0.45 > 0.3, none of them resident
+    # eviction scores (cell + eps)(L - i) / (row sum x L): V[6] = 9/32, V[10] = 3/10, V[13] = 1/4
+    e = 2.0 ** -20
+    assert out["V"][1, 2] == pytest.approx((3 + e) * 3 / 32, rel=1e-15)
+    assert out["V"][2, 2] == pytest.approx((6 + e) * 2 / 40, rel=1e-15)
+    assert out["V"][3, 1] == pytest.approx((5 + e) * 1 / 20, rel=1e-15)
+    # residents 0, 2, 5, 6 without the experts that run now (5 and 4): V[2] ~ eps/4 < V[6] = 9/32 < V[0] = 1/2
+    assert out["ev_order"] == [2, 6, 0]
+    # Alg. 1: pick 1 (flat 5) hits slot 2; pick 0 (flat 4) misses, the cache is full, flat 2 gives up slot 1
+    assert out["events"] == [(5, True, -1, 2), (4, False, 2, 1)]
+    # prefetch: candidate 13 (P = 1/2) meets the cheapest remaining victim 6 (2 has left): V[13] = 1/4 is not
+    # above V[6] = 9/32 -> turned down; candidate 10 (P = 0.45): V[10] = 3/10 > 9/32 -> takes slot 3 from 6
+    assert out["prefetched"] == [(10, 6, 3)]
+    assert c.owner.tolist() == [0, 4, 5, 10]
+    assert sorted(np.nonzero(c.slot_of >= 0)[0].tolist()) == [0, 4, 5, 10]
+    silu = lambda t: t / (1.0 + math.exp(-t))
+    p = np.exp([3.0, 4.0, 0.0, 0.0]) / np.exp([3.0, 4.0, 0.0, 0.0]).sum()
+    want = p[1] * silu(1.5) * 4.0 + p[0] * 2.0 * silu(-0.75) * 4.0 - silu(3.0) * 4.0
+    np.testing.assert_allclose(out["y"], [want, 0.0, 0.0, 0.0], rtol=1e-14, atol=0)
+    # depth 1 considers only candidate 13 and prefetches nothing; depth 3 adds candidate 11, whose
+    # V = 1/5 is not above the next victim's (flat 0, V = 1/2); depth 0 never prefetches
+    out1, _, c1 = run(1)
+    assert out1["prefetched"] == [] and c1.owner.tolist() == [0, 4, 5, 6]
+    out3, _, c3 = run(3)
+    assert out3["prefetched"] == [(10, 6, 3)] and c3.owner.tolist() == [0, 4, 5, 10]
+    out0, _, c0 = run(0)
+    assert out0["prefetched"] == [] and c0.owner.tolist() == [0, 4, 5, 6]
+
+
 # ================================================================ prefill iteration
 def test_prefill_layer_against_dense_all_expert_formulation():
     # every expert applied to every token with dense library matmuls, then masked by the routing:
