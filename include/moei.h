@@ -196,6 +196,17 @@ int moei_cache_retrieve(moei_cache* c, int32_t layer, const int32_t* h_idx, int3
  * n_act <= k + n_shared. */
 int expert_ffn_gemv(moei_cache* c, const int32_t* d_slot_ids, const float* d_gate_w,
                     int32_t n_act, const void* d_x, float* d_y, void* stream);
+/* expert_ffn_gemv for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels
+ * and bit-identical results, but the workgroup partial rows live in a static device array of
+ * 256 x 5120 floats (5 MiB per GPU the library runs on, held until the process ends) instead of
+ * the cache's own scratch, and the call itself allocates nothing.  MOEI_ECAPACITY when
+ * (compute units - 24) x H exceeds that array (H <= 5649 on a 256-unit part).  Every call on a
+ * GPU shares that GPU's array: calls that overlap on one GPU - other streams, other caches,
+ * other threads - race; order them on one stream or with events.  Nothing in the array has
+ * to be cleared between calls (every row that is read is written first by the same call). */
+int expert_ffn_gemv_static(moei_cache* c, const int32_t* d_slot_ids, const float* d_gate_w,
+                           int32_t n_act, const void* d_x, float* d_y, void* stream);
 /* Step 5 for a decode batch of B independent requests (B <= 16): for every token b,
  *   y[b] = sum_j d_w[b][j] * expert(layer, d_idx[b][j])(x[b]) + sum over the layer's shared experts,
  * with the picks' slots looked up in the device slot table.  Tokens are grouped per activated

@@ -16,6 +16,7 @@ import torch
 __all__ = [
     "MoeiError", "ModelDesc", "lib", "lib_path", "Eamc", "Cache",
     "moe_route_topk", "eam_update", "eamc_match", "eamc_match_topm", "expert_priority", "expert_ffn_gemv",
+    "expert_ffn_gemv_static",
     "moe_decode_layer", "moe_prefill_layer", "expert_ffn_grouped", "WDTYPE_FP32", "WDTYPE_BF16", "EXPORTS", "expert_pack", "profile_enable", "profile_disable", "profile_read", "profile_samples",
 ]
 
@@ -27,7 +28,7 @@ EXPORTS = [
     "moei_eamc_create", "moei_eamc_load", "moei_eamc_insert", "moei_eamc_export", "moei_eamc_save", "moei_eamc_restore", "moei_eamc_size", "moei_eamc_destroy",
     "moe_route_topk", "eam_update", "eamc_match", "eamc_match_topm", "expert_priority",
     "moei_cache_create", "moei_cache_destroy", "moei_expert_pack", "moei_cache_reset", "moei_cache_slot_ptr", "moei_cache_slot_table",
-    "moei_cache_get_slots", "moei_cache_retrieve", "expert_ffn_gemv", "expert_ffn_grouped", "moei_cache_error_flags",
+    "moei_cache_get_slots", "moei_cache_retrieve", "expert_ffn_gemv", "expert_ffn_gemv_static", "expert_ffn_grouped", "moei_cache_error_flags",
     "moe_decode_layer", "moei_cache_last_step", "moei_cache_join", "moei_cache_sync",
     "moei_cache_set_match_count", "moei_cache_last_matches",
     "moe_prefill_layer", "moei_cache_set_policy", "moei_cache_prefetch", "moei_cache_set_prefetch", "moei_cache_last_prefetch",
@@ -391,6 +392,19 @@ def expert_ffn_gemv(cache: Cache, slot_ids: torch.Tensor, gate_w: torch.Tensor, 
     y = out if out is not None else torch.empty(cache.desc.H, dtype=torch.float32, device=x.device)
     _check(lib().expert_ffn_gemv(cache.h, _p(slot_ids), _p(gate_w), slot_ids.numel(), _p(x), _p(y), _stream(stream)))
     return y
+
+
+def expert_ffn_gemv_static(cache: Cache, slot_ids: torch.Tensor, gate_w: torch.Tensor, x: torch.Tensor, out: torch.Tensor,
+                           stream=None) -> torch.Tensor:
+    """expert_ffn_gemv with its scratch in the library's static device array: allocates nothing,
+    so the output tensor is the caller's."""
+    _dev(slot_ids, torch.int32)
+    _dev(gate_w, torch.float32)
+    _dev(out, torch.float32)
+    assert x.is_cuda and x.is_contiguous() and x.numel() == cache.desc.H and out.numel() == cache.desc.H
+    _check(lib().expert_ffn_gemv_static(cache.h, _p(slot_ids), _p(gate_w), slot_ids.numel(), _p(x), _p(out),
+                                        _stream(stream)))
+    return out
 
 
 def expert_ffn_grouped(cache: Cache, layer: int, idx: torch.Tensor, w: torch.Tensor, x: torch.Tensor,

@@ -586,6 +586,16 @@ extern "C" int expert_ffn_gemv(moei_cache* c, const int32_t* d_slot_ids, const f
                              c->d_flags, as_stream(stream));
 }
 
+extern "C" int expert_ffn_gemv_static(moei_cache* c, const int32_t* d_slot_ids, const float* d_gate_w, int32_t n_act,
+                                      const void* d_x, float* d_y, void* stream) {
+    MOEI_REQUIRE(c && d_x && d_y, "expert_ffn_gemv_static: null pointer");
+    MOEI_REQUIRE(n_act >= 0 && n_act <= c->ffn.n_act_max,
+                 "expert_ffn_gemv_static: n_act = %d outside [0, k + n_shared = %d]", n_act, c->ffn.n_act_max);
+    MOEI_REQUIRE(n_act == 0 || (d_slot_ids && d_gate_w), "expert_ffn_gemv_static: null slot ids or gate weights");
+    return launch_expert_ffn_static(c->d, c->d_pool, c->slot_elems, c->n_total, c->ffn.n_part, d_slot_ids, d_gate_w,
+                                    n_act, d_x, d_y, c->d_flags, as_stream(stream));
+}
+
 extern "C" int expert_ffn_grouped(moei_cache* c, int32_t layer, const int32_t* d_idx, const float* d_w, int32_t B,
                                   const void* d_x, float* d_y, void* stream) {
     MOEI_REQUIRE(c && d_idx && d_w && d_x && d_y, "expert_ffn_grouped: null pointer");

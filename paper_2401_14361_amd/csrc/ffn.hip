@@ -771,6 +771,9 @@ int ffn_scratch_alloc(const moei_model_desc& d, int n_act_max, FfnScratch* out) 
     int reserve = env_int("MOEI_RESERVE_CUS", 24);
     if (reserve < 0 || reserve > compute_units() / 2) reserve = 0;
     out->n_part = compute_units() - reserve;
+    float* unused = nullptr;  // the static scratch of expert_ffn_gemv_static: address looked up at set-up
+    int rc = static_part_ptr(&unused);
+    if (rc) return rc;
     hipError_t e = hipMalloc((void**)&out->d_part, (size_t)out->n_part * d.H * sizeof(float));
     if (e != hipSuccess) {
         out->d_part = nullptr;
@@ -782,6 +785,52 @@ int ffn_scratch_alloc(const moei_model_desc& d, int n_act_max, FfnScratch* out) 
 void ffn_scratch_free(FfnScratch* s) {
     (void)hipFree(s->d_part);
     s->d_part = nullptr;
+}
+
+// ------------------------------------------------------------------ scratch that is never allocated
+// The workgroup partial rows of expert_ffn_gemv_static live in this array: one copy per GPU that
+// the library runs on, held until the process ends.  Host code never uses the array's name as an
+// address: its device address is looked up once per device and kept in g_static_part.
+}  // namespace moei
+
+static __device__ __align__(256) float scratch[moei::kStaticPartFloats];
+
+namespace moei {
+
+namespace {
+constexpr int kMaxDevices = 64;
+float* g_static_part[kMaxDevices] = {};
+}  // namespace
+
+// Device address of the static partial-row array on the current device (looked up at the
+// first call on that device: cache creation, else the entry point itself).
+int static_part_ptr(float** out) {
+    int dev = -1;
+    MOEI_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) MOEI_FAIL(MOEI_EINVAL, "device ordinal %d outside [0, %d)", dev, kMaxDevices);
+    if (!g_static_part[dev]) {
+        float* ptr = nullptr;
+        MOEI_HIP(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) MOEI_FAIL(MOEI_EHIP, "the static scratch array has no device address");
+        g_static_part[dev] = ptr;
+    }
+    *out = g_static_part[dev];
+    return MOEI_OK;
+}
+
+int launch_expert_ffn_static(const moei_model_desc& d, const void* d_pool, size_t slot_elems, int n_slots_total,
+                             int n_part, const int32_t* d_slot_ids, const float* d_gate_w, int n_act, const void* d_x,
+                             float* d_y, int32_t* d_flags, hipStream_t s) {
+    if ((size_t)n_part * (size_t)d.H > kStaticPartFloats)
+        MOEI_FAIL(MOEI_ECAPACITY,
+                  "expert_ffn_gemv_static: %d partial rows of H = %d floats exceed the static scratch of %zu floats "
+                  "(H <= %zu on this device)",
+                  n_part, d.H, kStaticPartFloats, kStaticPartFloats / (size_t)n_part);
+    FfnScratch scr;
+    int rc = static_part_ptr(&scr.d_part);
+    if (rc) return rc;
+    scr.n_part = n_part;
+    return launch_expert_ffn(d, d_pool, slot_elems, n_slots_total, scr, d_slot_ids, d_gate_w, n_act, d_x, d_y, d_flags, s);
 }
 
 int launch_expert_ffn(const moei_model_desc& d, const void* d_pool, size_t slot_elems, int n_slots_total,

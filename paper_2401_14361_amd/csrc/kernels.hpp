@@ -43,6 +43,13 @@ int launch_expert_ffn(const moei_model_desc& d, const void* d_pool, size_t slot_
                       const FfnScratch& scr, const int32_t* d_slot_ids, const float* d_gate_w, int n_act,
                       const void* d_x, float* d_y, int32_t* d_flags, hipStream_t s);
 
+// the same with the partial rows in a static device array (no allocation anywhere on the path)
+constexpr size_t kStaticPartFloats = (size_t)256 * 5120;  // 5 MiB: 256 workgroups x H = 5120
+int static_part_ptr(float** out);
+int launch_expert_ffn_static(const moei_model_desc& d, const void* d_pool, size_t slot_elems, int n_slots_total,
+                             int n_part, const int32_t* d_slot_ids, const float* d_gate_w, int n_act, const void* d_x,
+                             float* d_y, int32_t* d_flags, hipStream_t s);
+
 // decode batch B > 1: tokens grouped per activated expert
 int grouped_max_items(const moei_model_desc& d);
 size_t grouped_item_bytes();
