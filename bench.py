@@ -55,6 +55,8 @@ def parse():
     ap.add_argument("--policy-tokens", type=int, default=16, help="decode tokens per request in the policy sweep")
     ap.add_argument("--policy-requests", type=int, default=6)
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-shapes", action="store_true",
+                    help="skip the FFN kernel at the C3/C4 widths and the full C4 match (extra.other_shapes)")
     ap.add_argument("--batch-sweep", action="store_true",
                     help="also time the batched match and grouped FFN for B = 1..16 (EAMC of 10,000 traces)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -104,8 +106,14 @@ def main():
     L, E, k, H, I = cfg.L, cfg.E, cfg.k, cfg.H, cfg.I
     n_act = k + cfg.n_shared
     T_dec = cfg.decode
-    K = args.steps if args.steps is not None else T_dec * L
-    W = args.warmup if args.warmup is not None else 4 * L
+    # The timed unit is a whole decode token (L layer steps, one HIP graph): --steps and --warmup are
+    # rounded up to whole tokens, at least 10 tokens are timed, and the JSON line reports the steps
+    # that were actually timed.
+    K_req = args.steps if args.steps is not None else T_dec * L
+    W_req = args.warmup if args.warmup is not None else 4 * L
+    tok_timed = max(10, -(-K_req // L))
+    tok_warm = max(1, -(-W_req // L))
+    K, W = tok_timed * L, tok_warm * L
     t_setup = time.time()
 
     # ------------------------------------------------------------------ inputs
@@ -161,7 +169,7 @@ def main():
     # the same steps with one token's L layer steps captured in a HIP graph: the layer inputs
     # sit in a fixed staging buffer that is refreshed per token (in a model the previous
     # layer writes them there)
-    if not args.no_graph and K % L == 0 and W % L == 0:
+    if not args.no_graph:
         d_eam.copy_(prefill)
         x_stage = torch.empty_like(d_x[0])
         y_all = torch.empty((L, H), dtype=torch.float32, device="cuda")
@@ -327,6 +335,76 @@ def main():
     }
     log(f"[bench] match {match_us:.1f} us; big-N dot {dot_us:.1f} us = {big_bytes / dot_us / 1e3:.0f} GB/s; "
         f"gemv {gemv_us:.1f} us = {ffn_bytes / gemv_us / 1e3:.0f} GB/s")
+
+    # ------------------------------------------------ leg 3b: the two streaming kernels at the other shapes
+    # expert_ffn_gemv at the Mixtral (C3) and DeepSeek-V2 (C4) widths over rotating slots, and the
+    # EAMC match over the full DeepSeek-V2 collection (10,000 x 59 x 160 cells, 377.6 MB): per-launch
+    # kernel durations from the start/stop stamps, algorithmic bytes / duration against the HBM peak
+    if not args.no_shapes and cfg.name == "C2":
+        shapes = {}
+        for cname, n_rot in (("C3", 8), ("C4", 64)):
+            scfg = mi.get_config(cname).scaled(L=1)
+            sdesc = m.ModelDesc.from_config(scfg)
+            na = scfg.k + scfg.n_shared
+            sc = m.Cache(sdesc, n_rot)
+            gen = torch.Generator(device="cuda").manual_seed(mi.BASE_SEED + scfg.cid)
+            for sl in range(n_rot):          # N(0, 0.02) weights in storage precision, drawn on the device
+                t = sc.slot_tensor(sl)
+                t.copy_((torch.randn(t.numel(), device="cuda", generator=gen) * scfg.w_std).to(t.dtype))
+            sc.reset(0)
+            sx = dev(mi.to_store(scfg, np.random.default_rng(scfg.cid).standard_normal(scfg.H).astype(np.float32)))
+            sy = torch.empty(scfg.H, dtype=torch.float32, device="cuda")
+            sets = [dev(((np.arange(na) + r * na) % n_rot).astype(np.int32)) for r in range(n_rot // na)]
+            sg = dev(np.full(na, 1.0 / na, np.float32))
+            n_call = 40
+            for r in range(4):
+                m.expert_ffn_gemv(sc, sets[r % len(sets)], sg, sx, stream=stream, out=sy)
+            m.profile_enable(4 * n_call)
+            for r in range(n_call):
+                m.expert_ffn_gemv(sc, sets[r % len(sets)], sg, sx, stream=stream, out=sy)
+            torch.cuda.synchronize()
+            smp = m.profile_samples("ffn_fused_kernel")
+            m.profile_disable()
+            assert sc.error_flags() == 0 and bool(torch.isfinite(sy).all())
+            b = na * scfg.expert_bytes
+            us = float(np.mean(smp))
+            shapes[f"ffn_fused_kernel_{cname}"] = {
+                "workload": f"{cname} width: {na} experts of H={scfg.H}, I={scfg.I} bf16 per launch, rotating over "
+                            f"{n_rot} slots ({n_rot * scfg.expert_bytes / 1e9:.1f} GB)",
+                "launches": len(smp), "avg_us": us, "median_us": float(np.median(smp)),
+                "alg_bytes": b, "GBps": b / us / 1e3, "frac": b / us / 1e3 / HBM_PEAK_GBPS}
+            log(f"[bench] {cname}-width FFN kernel: {us:.1f} us = {b / us / 1e3:.0f} GB/s = {b / us / 1e3 / HBM_PEAK_GBPS:.3f} of peak")
+            sc.close()
+            del sc
+            torch.cuda.empty_cache()
+        c4 = mi.get_config("C4")
+        t0 = time.time()
+        tr4, _, _ = mi.eamc_traces(c4, threads=16)
+        d4 = m.ModelDesc.from_config(c4)
+        e4 = m.Eamc(d4, c4.N, 4)
+        e4.load(tr4)
+        q4 = dev(mi.make_request(c4, 0, decode=1).prefill_eam.astype(np.int32))
+        q4[0, :c4.k] += 1                       # the configuration has no prompt: one routed token
+        for _ in range(3):
+            m.eamc_match(e4, q4, stream=stream)
+        m.profile_enable(256)
+        for _ in range(30):
+            m.eamc_match(e4, q4, stream=stream)
+        torch.cuda.synchronize()
+        dsm, psm = m.profile_samples("eamc_dot_kernel"), m.profile_samples("eamc_pick_kernel")
+        m.profile_disable()
+        b4 = c4.N * c4.L * c4.E * 4
+        us4 = float(np.mean(dsm))
+        shapes["eamc_match_C4"] = {
+            "workload": f"C4 collection: {c4.N} traces x {c4.L} x {c4.E} int32 cells ({b4 / 1e6:.1f} MB), one query",
+            "launches": len(dsm), "dot_kernel_avg_us": us4, "dot_kernel_median_us": float(np.median(dsm)),
+            "pick_kernel_avg_us": float(np.mean(psm)), "alg_bytes": b4, "GBps": b4 / us4 / 1e3,
+            "frac": b4 / us4 / 1e3 / HBM_PEAK_GBPS, "traces_per_s": c4.N / (us4 + float(np.mean(psm))) * 1e6}
+        log(f"[bench] C4 match ({time.time() - t0:.0f}s to draw and load): dot kernel {us4:.1f} us = {b4 / us4 / 1e3:.0f} GB/s = "
+            f"{b4 / us4 / 1e3 / HBM_PEAK_GBPS:.3f} of peak, pick {float(np.mean(psm)):.1f} us")
+        e4.close()
+        del tr4
+        extra["other_shapes"] = shapes
 
     # ------------------------------------------------ optional: decode batches on this shape
     if args.batch_sweep:
@@ -503,12 +581,14 @@ def main():
     out = {
         "metric": "us per MoE-layer decode step (EAMC traces scanned/s and expert GEMV HBM GB/s in `extra`)",
         "value": us_step, "unit": "us", "n_gpus": 1, "steps": K, "warmup": W,
+        "steps_requested": K_req, "warmup_requested": W_req,
         "ms_per_step": us_step / 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 weights, fp32 accumulate" if cfg.wdtype == "bf16" else "fp32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}{slice_note}: {L} MoE layers x {E} experts top-{k} + {cfg.n_shared} shared, H={H}, I={I}, "
                                f"{cfg.wdtype}; EAMC {cfg.N} traces; batch 1, {T_dec} decode tokens; all experts resident "
                                f"in HBM ({S_res} slots, {n_unique} distinct weight sets repeated)",
-                   "mode": mode, "us_per_step_without_graph": us_step_eager},
+                   "mode": mode, "us_per_step_without_graph": us_step_eager,
+                   "timed": f"{tok_timed} decode tokens x {L} layer steps after {tok_warm} warm-up token(s)"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kern,

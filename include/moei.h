@@ -97,7 +97,10 @@ int moei_eamc_destroy(moei_eamc* c);
  * probable experts in descending order (ties to the lower index), and their gate
  * weights (softmax probabilities; divided by their sum if renorm != 0).
  * d_logits[B][E] fp32 -> d_idx[B][k] int32, d_w[B][k] fp32.  Needs 1 <= k <= E <= 4096.
- * Logits must not be NaN. */
+ * A token whose logits admit no softmax - a NaN among them, or no finite maximum (all
+ * -inf, or a +inf) - gets no picks: all k indices -1, all k weights 0 (-inf entries beside a
+ * finite maximum are fine: probability 0).  eam_update and expert_ffn_grouped pass over
+ * indices of -1. */
 int moe_route_topk(const float* d_logits, int32_t B, int32_t E, int32_t k, int32_t renorm,
                    int32_t* d_idx, float* d_w, void* stream);
 
@@ -218,7 +221,10 @@ int expert_ffn_gemv_static(moei_cache* c, const int32_t* d_slot_ids, const float
 int expert_ffn_grouped(moei_cache* c, int32_t layer, const int32_t* d_idx, const float* d_w, int32_t B,
                        const void* d_x, float* d_y, void* stream);
 /* Device-side error flags raised by kernels since the last call (bit 0: bad slot id,
- * bit 1: a routed expert was not resident in a step without host retrieval).
+ * bit 1: a routed expert was not resident in a step without host retrieval, bit 2: the
+ * router logits of a token admitted no softmax - NaN or no finite maximum - so the token
+ * got no picks: its EAM row is unchanged and only the shared experts contribute to its
+ * output; the asynchronous moe_decode_layer also raises bit 0 for the empty slots then).
  * Synchronises `stream`. */
 int moei_cache_error_flags(moei_cache* c, int32_t* h_flags, void* stream);
 
@@ -233,7 +239,9 @@ int moei_cache_error_flags(moei_cache* c, int32_t* h_flags, void* stream);
  * up on the device and a non-resident pick raises error flag bit 1.  Otherwise the
  * call waits for the routing decision, serves misses from the host copy, and fills
  * h_topk_idx[k], *h_best (matched trace, waits for the side stream) and *h_n_miss
- * (each may be NULL). */
+ * (each may be NULL).  Router logits that admit no softmax (NaN, no finite maximum): the
+ * synchronous call returns MOEI_ESTATE before any expert runs; the asynchronous one
+ * raises error flag bit 2 (see moei_cache_error_flags). */
 int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d_eam, int32_t layer,
                      const void* d_router_w, const float* d_router_bias,
                      const void* d_x, float* d_y,

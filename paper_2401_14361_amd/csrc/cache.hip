@@ -27,9 +27,11 @@ struct SlotUpdates {
     int32_t slot[2 * kMaxAct];
 };
 
+// The entries are applied in list order by one thread: a list may name an expert twice (evicted by
+// one entry, brought back by a later one) and the last entry must win.
 __global__ void apply_slot_updates_kernel(int32_t* __restrict__ slot_of, SlotUpdates u) {
-    int t = threadIdx.x;
-    if (t < u.n) slot_of[u.fid[t]] = u.slot[t];
+    if (threadIdx.x == 0)
+        for (int t = 0; t < u.n; ++t) slot_of[u.fid[t]] = u.slot[t];
 }
 
 // Host mirrors in pinned memory so that the device-to-host copies are asynchronous.
@@ -464,7 +466,7 @@ extern "C" int moei_cache_retrieve(moei_cache* c, int32_t layer, const int32_t* 
     if (n_miss > 0) {
         MOEI_HIP(hipEventRecord(c->ev_copy, c->copy_stream));
         MOEI_HIP(hipStreamWaitEvent(s, c->ev_copy, 0));
-        launch(K_ROUTE_TOPK, apply_slot_updates_kernel, dim3(1), dim3(2 * kMaxAct), 0, s, c->d_slot_of, upd);
+        launch(K_ROUTE_TOPK, apply_slot_updates_kernel, dim3(1), dim3(kWave), 0, s, c->d_slot_of, upd);
         MOEI_LAUNCH_CHECK();
     }
     if (h_n_miss) *h_n_miss = n_miss;
@@ -569,7 +571,7 @@ extern "C" int moei_cache_prefetch(moei_cache* c, const int32_t* h_pf_order, int
     }
     if (issued > 0) {
         // the device table names the new owners at once; whoever reads such a slot waits for its copy
-        launch(K_ROUTE_TOPK, apply_slot_updates_kernel, dim3(1), dim3(2 * kMaxAct), 0, s, c->d_slot_of, upd);
+        launch(K_ROUTE_TOPK, apply_slot_updates_kernel, dim3(1), dim3(kWave), 0, s, c->d_slot_of, upd);
         MOEI_LAUNCH_CHECK();
     }
     if (h_n_issued) *h_n_issued = issued;
@@ -782,7 +784,10 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
         int32_t protect[kMaxAct];
         for (int j = 0; j < k; ++j) {
             int e = c->pin->idx[j];
-            if (e < 0 || e >= E) MOEI_FAIL(MOEI_ESTATE, "moe_decode_layer: router produced expert %d", e);
+            if (e < 0 || e >= E)
+                MOEI_FAIL(MOEI_ESTATE,
+                          "moe_decode_layer: the router produced expert %d (logits that are NaN or have no finite "
+                          "maximum give a token no picks)", e);
             if (c->slot_of[layer * E + e] < 0) ++n_miss;
             protect[j] = layer * E + e;
         }
@@ -794,6 +799,9 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
             side_done = true;
             n_ev = c->pin->n_ev < k ? c->pin->n_ev : k;
         }
+        // under the comparison policies nothing above waited for the side stream, whose scoring still
+        // reads the device slot table that the retrieval is about to change
+        if (n_miss > 0 && !side_done) MOEI_HIP(hipStreamWaitEvent(s, c->ev_side, 0));
         int32_t slots[kMaxAct];
         rc = moei_cache_retrieve(c, layer, c->pin->idx, k, c->pin->ev_head, n_ev, slots, nullptr, nullptr, s);
         if (rc) return rc;

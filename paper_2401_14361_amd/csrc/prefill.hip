@@ -60,7 +60,8 @@ __global__ void __launch_bounds__(4 * kWave) prefill_route_kernel(const void* __
                                                                   const float* __restrict__ bias,
                                                                   const void* __restrict__ Xv, int n, int H, int E, int k,
                                                                   int renorm, int vec_ok, int32_t* __restrict__ idx,
-                                                                  float* __restrict__ w) {
+                                                                  float* __restrict__ w, int32_t* __restrict__ where,
+                                                                  int32_t* __restrict__ flags) {
     using V = WVec<WT>;
     extern __shared__ __align__(16) float smem[];
     __shared__ int s_idx[kWave];
@@ -72,10 +73,6 @@ __global__ void __launch_bounds__(4 * kWave) prefill_route_kernel(const void* __
     const WT* W = reinterpret_cast<const WT*>(Wv);
     const WT* x = reinterpret_cast<const WT*>(Xv) + (size_t)t * H;
     for (int c = tid; c < H; c += 4 * kWave) xs[c] = V::one(x + c);
-    if (tid < kWave) {  // NaN logits leave ranks unassigned: such picks then name expert 0
-        s_idx[tid] = 0;
-        s_w[tid] = 0.f;
-    }
     __syncthreads();
     constexpr int RB = 8;
     for (int e0 = wv * RB; e0 < E; e0 += 4 * RB) {
@@ -109,7 +106,11 @@ __global__ void __launch_bounds__(4 * kWave) prefill_route_kernel(const void* __
     if (wv != 0) return;
     int my_idx;
     float my_w;
-    if (E <= kRankMaxE) {
+    if (wave_logits_bad(z, E, lane)) {  // uniform: the token gets no picks and only its shared experts' output
+        my_idx = -1;
+        my_w = 0.f;
+        if (lane == 0) atomicOr(flags, 4);
+    } else if (E <= kRankMaxE) {
         const float sel = wave_topk_rank(z, E, k, renorm, lane, s_idx, s_w, false);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -121,6 +122,7 @@ __global__ void __launch_bounds__(4 * kWave) prefill_route_kernel(const void* __
     if (lane < k) {
         idx[(size_t)t * k + lane] = my_idx;
         w[(size_t)t * k + lane] = my_w;
+        where[(size_t)t * k + lane] = -1;  // no contribution row yet: the grouping names one per placed pick
     }
 }
 
@@ -549,6 +551,7 @@ __global__ void __launch_bounds__(256) prefill_reduce_kernel(const float* __rest
     for (int c = threadIdx.x; c < H / 4; c += 256) {
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int j = 0; j < nc; ++j) {
+            if (s_rows[j] < 0) continue;  // a pick that was never placed (token without picks)
             const float4 v = *reinterpret_cast<const float4*>(yc + (size_t)s_rows[j] * H + c * 4);
             acc.x += v.x;
             acc.y += v.y;
@@ -635,7 +638,7 @@ int launch_prefill(const moei_model_desc& d, const PrefillScratch& ps, const voi
     rc = pf_allow_lds(prefill_route_kernel<uint16_t>, route_smem);
     if (rc) return rc;
     launch(K_PF_ROUTE, prefill_route_kernel<uint16_t>, dim3(n), dim3(4 * kWave), route_smem, s, d_router_w,
-           d_router_bias, d_X, n, d.H, d.E, d.k, (int)(d.renorm_topk != 0), vec_ok, ps.d_idx, ps.d_w);
+           d_router_bias, d_X, n, d.H, d.E, d.k, (int)(d.renorm_topk != 0), vec_ok, ps.d_idx, ps.d_w, ps.d_where, d_flags);
     MOEI_LAUNCH_CHECK();
     const int tm = tile_tokens(d, n);
     GroupArgsP g{ps.d_idx, ps.d_w, n, d.k, d.E, d.n_shared, tm, d_slot_of_row, shared_base, d_eam_row, ps.d_perm,

@@ -25,7 +25,10 @@ __global__ void __launch_bounds__(kWave) route_topk_kernel(const float* __restri
     __syncthreads();
     int my_idx;
     float my_w;
-    if (E <= kRankMaxE) {
+    if (wave_logits_bad(z, E, lane)) {  // uniform: no picks for this token
+        my_idx = -1;
+        my_w = 0.f;
+    } else if (E <= kRankMaxE) {
         wave_topk_rank(z, E, k, renorm, lane, s_idx, s_w);
         __syncthreads();
         my_idx = lane < k ? s_idx[lane] : -1;
@@ -48,6 +51,13 @@ __global__ void __launch_bounds__(kWave) route_topk_wide_kernel(const float* __r
     const int lane = threadIdx.x;
     for (int e = lane; e < E; e += kWave) z[e] = logits[(size_t)b * E + e];
     __syncthreads();
+    if (wave_logits_bad(z, E, lane)) {  // uniform: no picks for this token
+        for (int j = lane; j < k; j += kWave) {
+            idx[(size_t)b * k + j] = -1;
+            w[(size_t)b * k + j] = 0.f;
+        }
+        return;
+    }
     const int per = (E + kWave - 1) / kWave;
     float m = -INFINITY;
     for (int r = 0; r < per; ++r) {
@@ -179,15 +189,18 @@ __global__ void __launch_bounds__(kRouteWaves * kWave) route_fused_kernel(RouteF
     __syncthreads();
     for (int j = tid; j < a.E; j += NT)
         z[j] = __hip_atomic_load(&a.logits[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (tid < kWave) {  // NaN logits leave ranks unassigned: such picks then name expert 0
-        s_pick[tid] = 0;
-        s_pw[tid] = 0.f;
-    }
     __syncthreads();
     if (wv != 0) return;
     int my_idx;
     float my_w;
-    if (a.E <= kRankMaxE) {
+    const bool bad = wave_logits_bad(z, a.E, lane);  // uniform
+    if (bad) {
+        // no softmax exists: the token gets no picks, the EAM stays as it is, the FFN sees slot -1
+        // (which contributes nothing) and the flag tells the host
+        my_idx = -1;
+        my_w = 0.f;
+        if (lane == 0 && a.flags) atomicOr(a.flags, 4);
+    } else if (a.E <= kRankMaxE) {
         const float sel = wave_topk_rank(z, a.E, a.k, a.renorm, lane, s_pick, s_pw, false);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -196,7 +209,12 @@ __global__ void __launch_bounds__(kRouteWaves * kWave) route_fused_kernel(RouteF
     } else {
         wave_topk(z, a.E, a.k, a.renorm, lane, my_idx, my_w);
     }
-    if (lane < a.k) {
+    if (lane < a.k && bad) {
+        a.idx[lane] = -1;
+        a.w[lane] = 0.f;
+        a.slot_ids[a.n_shared + lane] = -1;
+        a.gate[a.n_shared + lane] = 0.f;
+    } else if (lane < a.k) {
         a.idx[lane] = my_idx;
         a.w[lane] = my_w;
         const int cnt = s_eam[my_idx] + 1;  // one writer per cell

@@ -23,6 +23,21 @@ __device__ __forceinline__ Cand better(Cand a, Cand b) {
     return (a.e < b.e) ? a : b;
 }
 
+// Logits for which no softmax exists: a NaN anywhere, or no finite maximum (all -inf, or a +inf).
+// Called by all 64 lanes of one wavefront; the answer is the same in every lane.  The routing
+// kernels then give the token no picks (index -1, weight 0) instead of ranking garbage.
+__device__ __forceinline__ bool wave_logits_bad(const float* z, int E, int lane) {
+    bool nan = false;
+    float m = -INFINITY;
+    for (int e = lane; e < E; e += kWave) {
+        const float v = z[e];
+        nan |= (v != v);
+        m = fmaxf(m, v);  // ignores a NaN operand
+    }
+    m = wave_max_dpp(m);
+    return __ballot(nan) != 0ull || !(fabsf(m) < INFINITY);
+}
+
 // Softmax + top-k of z[0..E) (in LDS) by one wavefront, k <= 64.  Every expert's rank is
 // the number of experts that come before it (larger logit, or equal logit and lower
 // index), counted against broadcast LDS reads; rank r < k is pick r.  The picks land in

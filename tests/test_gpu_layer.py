@@ -70,7 +70,13 @@ def test_cache_retrieve_sequence_and_slot_contents(m):
     c2.close()
 
 
-def _replay(m, cfg, S, n_tokens, n_unique, cell_bytes, rid=0, match_m=1):
+def _weights_as_f64(cfg, flat):
+    """(W_gate, W_up, W_down) of a drawn expert, converted to fp64 once (the conversion is exact; the
+    oracle would repeat it at every use, which takes seconds for a 352 MB expert)."""
+    return tuple(O.to_f64(w) for w in split_expert(cfg, flat))
+
+
+def _replay(m, cfg, S, n_tokens, n_unique, cell_bytes, rid=0, match_m=1, f64_cache=False):
     L, E, k = cfg.L, cfg.E, cfg.k
     T, _, _ = mi.eamc_traces(cfg, threads=4)
     req = mi.make_request(cfg, rid, decode=n_tokens + 8)
@@ -94,8 +100,10 @@ def _replay(m, cfg, S, n_tokens, n_unique, cell_bytes, rid=0, match_m=1):
     ref_eam = req.prefill_eam.astype(np.int64).copy()
     ref_cache = O.ExpertCache(L, E, S)
 
+    f64 = [_weights_as_f64(cfg, bank[u]) for u in range(n_unique)] if f64_cache else None
+
     def expert_of(fid):
-        return split_expert(cfg, bank[fid % n_unique])
+        return f64[fid % n_unique] if f64_cache else split_expert(cfg, bank[fid % n_unique])
 
     def shared_of(layer):
         return [split_expert(cfg, shared[layer * cfg.n_shared + s]) for s in range(cfg.n_shared)]
@@ -211,36 +219,144 @@ def test_decode_request_with_aggregated_matches(m):
     _replay(m, cfg, cfg.S, 3, cfg.L * cfg.E, 4, rid=2, match_m=5)
 
 
-def test_async_layer_step_matches_sync_and_flags_a_miss(m):
+def _resident_setup(m, cfg, n_unique, rid, n_decode):
+    """Everything resident (the asynchronous step looks its slots up on the device and cannot miss)."""
+    L, E = cfg.L, cfg.E
+    T, _, _ = mi.eamc_traces(cfg, threads=4)
+    req = mi.make_request(cfg, rid, decode=n_decode)
+    bank = mi.expert_bank(cfg, n_unique, threads=4)
+    shared = mi.expert_bank(cfg.scaled(cid=cfg.cid + 50), max(L * cfg.n_shared, 1), threads=2)
+    desc = m.ModelDesc.from_config(cfg)
+    eamc = m.Eamc(desc, cfg.N)
+    eamc.load(T)
+    packed, packed_sh = pack_bank(m, cfg, bank), pack_bank(m, cfg, shared)
+    d_packed = [dev(packed[u]) for u in range(n_unique)]
+
+    def fresh():
+        c = m.Cache(desc, L * E)
+        for s_ in range(L * E):
+            t = c.slot_tensor(s_)
+            t.copy_(d_packed[s_ % n_unique].view(t.dtype))
+        for s_ in range(L * cfg.n_shared):
+            t = c.slot_tensor(L * E + s_)
+            t.copy_(dev(packed_sh[s_]).view(t.dtype))
+        c.reset(L * E)
+        return c
+
+    def expert_of(fid):
+        return split_expert(cfg, bank[fid % n_unique])
+
+    def shared_of(layer):
+        return [split_expert(cfg, shared[layer * cfg.n_shared + s_]) for s_ in range(cfg.n_shared)]
+
+    return T, req, eamc, fresh, expert_of, shared_of
+
+
+def _check_step(cfg, where, last, matched, ref, y, eam_now, ref_eam):
+    """One layer step of the device-driven path against the oracle's: the EAM (hence the picks), gate
+    weights, matched traces, similarity, both score tables and both orders, the output."""
+    assert (eam_now == ref_eam).all(), where
+    np.testing.assert_allclose(last["w"], ref["w"], rtol=1e-4, err_msg=where)
+    assert matched == ref["matched"], where
+    np.testing.assert_allclose(last["sim"], ref["sim"], rtol=1e-5, err_msg=where)
+    assert last["ev_order"].tolist() == ref["ev_order"], where
+    assert last["pf_order"].tolist() == ref["pf_order"], where
+    np.testing.assert_allclose(last["P"], ref["P"], rtol=1e-6, err_msg=where)
+    np.testing.assert_allclose(last["V"], ref["V"], rtol=1e-6, err_msg=where)
+    err = rel_max_err(y, ref["y"])
+    assert err <= FFN_TOL_FP32ACC <= FFN_TOL, (where, err)
+
+
+def _async_against_oracle(m, cfg, n_unique, n_tokens, rid):
+    """Asynchronous layer steps (no host outputs: slots looked up on the device, nothing waits for
+    the side stream), each compared with the oracle's layer step."""
+    L, E, k = cfg.L, cfg.E, cfg.k
+    T, req, eamc, fresh, expert_of, shared_of = _resident_setup(m, cfg, n_unique, rid, n_tokens + 8)
+    tokens = pick_clear_tokens(cfg, req, n_tokens)
+    routers = [mi.router_weights(cfg, l) for l in range(L)]
+    d_routers, d_bias, d_x = [dev(w) for w in routers], dev(req.bias), dev(req.x)
+    cache = fresh()
+    d_eam = dev(req.prefill_eam.astype(np.int32))
+    ref_eam = req.prefill_eam.astype(np.int64).copy()
+    ref_cache = O.ExpertCache(L, E, L * E)
+    y = torch.empty(cfg.H, dtype=torch.float32, device="cuda")
+    for t in tokens:
+        for l in range(L):
+            m.moe_decode_layer(cache, eamc, d_eam, l, d_routers[l], d_bias[l], d_x[t, l], y, sync=False)
+            last = cache.last_step()
+            ref = O.decode_layer(T, ref_eam, ref_cache, l, routers[l], req.bias[l], req.x[t, l], expert_of, shared_of,
+                                 k, bool(cfg.renorm), EPS)
+            assert all(e[1] for e in ref["events"])
+            _check_step(cfg, f"async token {t} layer {l}", last, cache.last_matches()[0].tolist(), ref,
+                        y.cpu().numpy(), d_eam.cpu().numpy(), ref_eam)
+    assert cache.error_flags() == 0
+    cache.close()
+    eamc.close()
+
+
+def _graph_against_oracle(m, cfg, n_unique, n_tokens, rid):
+    """One token's L asynchronous layer steps captured in a HIP graph and replayed per token, with
+    eager work and synchronisations between replays.  After every replay: each layer's output, the
+    EAM, and the last layer's match, scores and orders against the oracle run over the same steps."""
+    L, E, k = cfg.L, cfg.E, cfg.k
+    T, req, eamc, fresh, expert_of, shared_of = _resident_setup(m, cfg, n_unique, rid, n_tokens + 8)
+    tokens = pick_clear_tokens(cfg, req, n_tokens)
+    routers = [mi.router_weights(cfg, l) for l in range(L)]
+    d_routers, d_bias, d_x = [dev(w) for w in routers], dev(req.bias), dev(req.x)
+    cache = fresh()
+    d_eam = dev(req.prefill_eam.astype(np.int32))
+    x_stage = torch.empty_like(d_x[0])
+    y_all = torch.empty((L, cfg.H), dtype=torch.float32, device="cuda")
+    cache.sync()
+    cap = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=cap):
+        for l in range(L):
+            m.moe_decode_layer(cache, eamc, d_eam, l, d_routers[l], d_bias[l], x_stage[l], y_all[l], sync=False)
+        cache.join()
+    cache.sync()
+    d_eam.copy_(dev(req.prefill_eam.astype(np.int32)))      # the capture itself did not run anything
+    ref_eam = req.prefill_eam.astype(np.int64).copy()
+    ref_cache = O.ExpertCache(L, E, L * E)
+    for t in tokens:
+        x_stage.copy_(d_x[t])
+        graph.replay()
+        torch.cuda.synchronize()
+        got_y, got_eam = y_all.cpu().numpy(), d_eam.cpu().numpy()
+        last, matched = cache.last_step(), cache.last_matches()[0].tolist()
+        for l in range(L):
+            ref = O.decode_layer(T, ref_eam, ref_cache, l, routers[l], req.bias[l], req.x[t, l], expert_of, shared_of,
+                                 k, bool(cfg.renorm), EPS)
+            err = rel_max_err(got_y[l], ref["y"])
+            assert err <= FFN_TOL_FP32ACC, (t, l, err)
+        _check_step(cfg, f"graph token {t}", last, matched, ref, got_y[L - 1], got_eam, ref_eam)
+        # the program's own eager work between replays
+        m.eamc_match(eamc, d_eam)
+        y_all.zero_()
+        torch.cuda.synchronize()
+    assert cache.error_flags() == 0
+    cache.close()
+    eamc.close()
+
+
+def test_async_layer_steps_against_the_oracle(m):
+    cfg = mi.get_config("C2").scaled(L=3, H=128, I=64, N=40, prompt=16, E=16, k=3)
+    _async_against_oracle(m, cfg, cfg.L * cfg.E, 4, rid=2)
+    cfg = mi.get_config("C1")
+    _async_against_oracle(m, cfg, cfg.L * cfg.E, 3, rid=3)
+
+
+def test_async_layer_step_flags_a_miss(m):
+    # a pick that is not resident cannot be served without the host: the flag says so
     cfg = mi.get_config("C2").scaled(L=3, H=128, I=64, N=40, prompt=16, E=16, k=3)
     L, E = cfg.L, cfg.E
     T, _, _ = mi.eamc_traces(cfg, threads=2)
     req = mi.make_request(cfg, 2, decode=4)
-    bank = mi.expert_bank(cfg, L * E, threads=2)
-    shared = mi.expert_bank(cfg.scaled(cid=77), L * cfg.n_shared, threads=2)
+    bank = pack_bank(m, cfg, mi.expert_bank(cfg, L * E, threads=2))
+    shared = pack_bank(m, cfg, mi.expert_bank(cfg.scaled(cid=77), L * cfg.n_shared, threads=2))
     desc = m.ModelDesc.from_config(cfg)
     eamc = m.Eamc(desc, cfg.N)
     eamc.load(T)
-    bank, shared = pack_bank(m, cfg, bank), pack_bank(m, cfg, shared)
-    outs = {}
-    for mode in ("sync", "async"):
-        cache = m.Cache(desc, L * E, pinned(bank), pinned(shared))
-        cache.reset(L * E)                               # fully resident: no host round trip needed
-        d_eam = dev(req.prefill_eam.astype(np.int32))
-        ys = []
-        for t in range(4):
-            for l in range(L):
-                y = torch.empty(cfg.H, dtype=torch.float32, device="cuda")
-                m.moe_decode_layer(cache, eamc, d_eam, l, dev(mi.router_weights(cfg, l)), dev(req.bias[l]),
-                                   dev(req.x[t, l]), y, sync=(mode == "sync"))
-                ys.append(y)
-        torch.cuda.synchronize()
-        assert cache.error_flags() == 0
-        outs[mode] = (torch.stack(ys).cpu().numpy(), d_eam.cpu().numpy(), cache.last_step())
-        cache.close()
-    assert (outs["sync"][0] == outs["async"][0]).all() and (outs["sync"][1] == outs["async"][1]).all()
-    assert outs["sync"][2]["ev_order"].tolist() == outs["async"][2]["ev_order"].tolist()
-    # a pick that is not resident cannot be served without the host: the flag says so
     cache = m.Cache(desc, cfg.k, pinned(bank), pinned(shared))
     cache.reset(0)
     y = torch.empty(cfg.H, dtype=torch.float32, device="cuda")
@@ -251,86 +367,72 @@ def test_async_layer_step_matches_sync_and_flags_a_miss(m):
     eamc.close()
 
 
-def test_layer_steps_in_a_hip_graph_replay_like_eager_steps(m):
-    # one token's L asynchronous layer steps captured once, replayed for several tokens with eager
-    # work and synchronisations between the replays; every replay must equal the eager steps bit for bit
-    cfg = mi.get_config("C2").scaled(L=4, H=256, I=192, N=60, prompt=32)
+def test_layer_step_with_router_logits_that_have_no_softmax(m):
+    # error path: a NaN in the router bias.  Asynchronous step: flag bit 2, no picks, the EAM row
+    # untouched, the output is the shared experts' alone; synchronous step: an error, nothing runs
+    cfg = mi.get_config("C2").scaled(L=2, H=128, I=64, N=20, prompt=16, E=16, k=3)
     L, E = cfg.L, cfg.E
-    T, _, _ = mi.eamc_traces(cfg, threads=2)
-    req = mi.make_request(cfg, 4, decode=6)
-    bank = pack_bank(m, cfg, mi.expert_bank(cfg, L * E, threads=2))
-    shared = pack_bank(m, cfg, mi.expert_bank(cfg.scaled(cid=78), L * cfg.n_shared, threads=2))
-    desc = m.ModelDesc.from_config(cfg)
-    eamc = m.Eamc(desc, cfg.N)
-    eamc.load(T)
-    routers = [dev(mi.router_weights(cfg, l)) for l in range(L)]
-    d_bias, d_x = dev(req.bias), dev(req.x)
-    n_tok = 5
-
-    def fresh():
-        c = m.Cache(desc, L * E, pinned(bank), pinned(shared))
-        c.reset(L * E)
-        return c, dev(req.prefill_eam.astype(np.int32))
-
-    cache, d_eam = fresh()
-    want_y, want_eam, want_orders = [], [], []
-    for t in range(n_tok):
-        ys = torch.empty((L, cfg.H), dtype=torch.float32, device="cuda")
-        for l in range(L):
-            m.moe_decode_layer(cache, eamc, d_eam, l, routers[l], d_bias[l], d_x[t, l], ys[l], sync=False)
-        torch.cuda.synchronize()
-        want_y.append(ys.cpu().numpy())
-        want_eam.append(d_eam.cpu().numpy())
-        last = cache.last_step()
-        want_orders.append((last["ev_order"].tolist(), last["pf_order"].tolist()))
-    cache.close()
-
-    cache, d_eam = fresh()
-    x_stage = torch.empty_like(d_x[0])
-    y_all = torch.empty((L, cfg.H), dtype=torch.float32, device="cuda")
+    T, req, eamc, fresh, expert_of, shared_of = _resident_setup(m, cfg, L * E, 6, 2)
+    cache = fresh()
+    eam0 = req.prefill_eam.astype(np.int32)
+    d_eam = dev(eam0)
+    bias = req.bias[1].astype(np.float32).copy()
+    bias[5] = np.nan
+    y = torch.empty(cfg.H, dtype=torch.float32, device="cuda")
+    W = dev(mi.router_weights(cfg, 1))
+    m.moe_decode_layer(cache, eamc, d_eam, 1, W, dev(bias), dev(req.x[0, 1]), y, sync=False)
+    torch.cuda.synchronize()
+    assert cache.error_flags() & 4
+    assert (d_eam.cpu().numpy() == eam0).all()
+    want = O.expert_ffn(req.x[0, 1], shared_of(1), [1.0] * cfg.n_shared)
+    assert rel_max_err(y.cpu().numpy(), want) <= FFN_TOL_FP32ACC
+    with pytest.raises(m.MoeiError) as e:
+        m.moe_decode_layer(cache, eamc, d_eam, 1, W, dev(bias), dev(req.x[0, 1]), y, sync=True)
+    assert e.value.code == -4 and "no finite" in str(e.value)
     cache.sync()
-    cap = torch.cuda.Stream()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph, stream=cap):
-        for l in range(L):
-            m.moe_decode_layer(cache, eamc, d_eam, l, routers[l], d_bias[l], x_stage[l], y_all[l], sync=False)
-        cache.join()
-    cache.sync()
-    d_eam.copy_(dev(req.prefill_eam.astype(np.int32)))      # the capture itself did not run anything
-    for t in range(n_tok):
-        x_stage.copy_(d_x[t])
-        graph.replay()
-        torch.cuda.synchronize()
-        assert (y_all.cpu().numpy() == want_y[t]).all(), t
-        assert (d_eam.cpu().numpy() == want_eam[t]).all(), t
-        last = cache.last_step()
-        assert (last["ev_order"].tolist(), last["pf_order"].tolist()) == want_orders[t], t
-        # the program's own eager work between replays
-        m.eamc_match(eamc, d_eam)
-        y_all.zero_()
-        torch.cuda.synchronize()
-    assert cache.error_flags() == 0
+    # the cache still works afterwards
+    cache.error_flags()
+    m.moe_decode_layer(cache, eamc, d_eam, 1, W, dev(req.bias[1]), dev(req.x[0, 1]), y, sync=False)
+    torch.cuda.synchronize()
+    assert cache.error_flags() == 0 and int(d_eam.cpu().numpy()[1].sum() - eam0[1].sum()) == cfg.k
     cache.close()
     eamc.close()
 
 
+def test_layer_steps_in_a_hip_graph_against_the_oracle(m):
+    cfg = mi.get_config("C2").scaled(L=4, H=256, I=192, N=60, prompt=32)
+    _graph_against_oracle(m, cfg, cfg.L * cfg.E, 5, rid=4)
+
+
 # ------------------------------------------------------------------ full benchmark shapes
-def test_full_size_deepseek_v2_lite_token_with_capped_cache(m):
+def test_full_size_deepseek_v2_lite_tokens_with_capped_cache(m):
     # configuration 2 at full size (26 x 64 experts of 2048 x 1408 bf16, 1,000 traces, 416 slots):
-    # one decode token, every layer step compared in full
+    # 8 decode tokens = 208 layer steps, every one compared in full while the cache keeps evicting
     cfg = mi.get_config("C2")
-    misses = _replay(m, cfg, cfg.S, 1, 24, 4)
+    misses = _replay(m, cfg, cfg.S, 8, 24, 4)
+    assert misses > 8 * cfg.k
+
+
+def test_full_size_deepseek_v2_lite_async_and_graph_steps(m):
+    # the path the benchmark times, at the benchmark's width: all 1,664 experts resident, asynchronous
+    # layer steps (one token, step by step) and the HIP-graph replay (two tokens of 26 layer steps)
+    cfg = mi.get_config("C2")
+    _async_against_oracle(m, cfg, 24, 1, rid=0)
+    _graph_against_oracle(m, cfg, 24, 2, rid=0)
+
+
+def test_full_size_mixtral_request_all_layers(m):
+    # configuration 3 at full size: all 32 layers x 8 experts of 4096 x 14336 bf16 (352 MB each),
+    # 96 of 256 slots, 1,000 traces; two decode tokens = 64 layer steps with misses from host memory
+    cfg = mi.get_config("C3")
+    misses = _replay(m, cfg, cfg.S, 2, 6, 4, f64_cache=True)
     assert misses > 0
 
 
-def test_full_size_mixtral_layer_steps(m):
-    # configuration 3 at full width (4096 x 14336 bf16 experts, 352 MB each), 3 of its layers
-    cfg = mi.get_config("C3").scaled(L=3, N=200, prompt=64)
-    _replay(m, cfg, 12, 1, 6, 4)
-
-
 def test_full_size_deepseek_v2_slice_steps(m):
-    # configuration 4's shapes: 160 experts per layer top-6 + 2 shared, 5120 x 1536; here 4 of the 59
-    # layers carry weights (the 59 x 160 match and priority sizes are covered in test_gpu_steps.py)
-    cfg = mi.get_config("C4").scaled(L=4, N=300, prompt=32)
+    # configuration 4's shapes: 160 experts per layer top-6 + 2 shared, 5120 x 1536, 10,000 traces; the 12
+    # layers whose 1,920 experts fill the 2,048-slot pool carry weights (the 59 x 160 match and priority
+    # sizes are covered in test_gpu_steps.py), one token through all of them
+    cfg = mi.get_config("C4")
+    cfg = cfg.scaled(L=cfg.S // cfg.E)
     _replay(m, cfg, cfg.L * cfg.E, 1, 12, 2)

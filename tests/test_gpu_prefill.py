@@ -34,7 +34,22 @@ def _clear_rows(cfg, W, bias, X, min_gap=1e-3):
     return keep
 
 
-def _prefill_case(m, cfg, n, layer, n_unique=None, resident=None):
+def _route_all(cfg, eam, layer, W, bias, X):
+    """The oracle's routing decision and EAM update for every token of the prompt (no expert runs)."""
+    n = X.shape[0]
+    idx = np.zeros((n, cfg.k), dtype=np.int64)
+    w = np.zeros((n, cfg.k), dtype=np.float64)
+    for t in range(n):
+        i_t, w_t = O.route_topk(O.router_logits(W, X[t], bias), cfg.k, bool(cfg.renorm))
+        idx[t], w[t] = i_t[0], w_t[0]
+        O.eam_update(eam, layer, idx[t])
+    return idx, w
+
+
+def _prefill_case(m, cfg, n, layer, n_unique=None, resident=None, sample=None, nan_token=None):
+    """With ``sample`` (a token count) the oracle routes every token (picks, gate weights, EAM) but
+    runs the expert FFNs only for that many tokens spread evenly over the prompt: at full width it
+    needs a quarter of a second per token."""
     L, E, k, H = cfg.L, cfg.E, cfg.k, cfg.H
     n_unique = n_unique or L * E
     bank = mi.expert_bank(cfg, n_unique, threads=4)
@@ -46,6 +61,10 @@ def _prefill_case(m, cfg, n, layer, n_unique=None, resident=None):
     rows = _clear_rows(cfg, W, req.bias[layer], Xall)[:n]
     assert len(rows) == n
     X = np.ascontiguousarray(Xall[rows])
+    X_dev = X
+    if nan_token is not None:   # the device sees a NaN in this token; the oracle is not asked about it
+        X_dev = X.copy()
+        X_dev[nan_token, 3] = 0x7FC0 if X.dtype == np.uint16 else np.nan
     desc = m.ModelDesc.from_config(cfg)
     S = L * E
     cache = m.Cache(desc, S)
@@ -59,16 +78,25 @@ def _prefill_case(m, cfg, n, layer, n_unique=None, resident=None):
     cache.reset(S if resident is None else resident)
     eam0 = req.prefill_eam.astype(np.int32)
     d_eam = dev(eam0)
-    Y, idx, w = m.moe_prefill_layer(cache, d_eam, layer, dev(W), dev(req.bias[layer]), dev(X), want_picks=True)
+    Y, idx, w = m.moe_prefill_layer(cache, d_eam, layer, dev(W), dev(req.bias[layer]), dev(X_dev), want_picks=True)
     torch.cuda.synchronize()
     ref_eam = eam0.astype(np.int64).copy()
-    ridx, rw, rY = O.prefill_layer(ref_eam, layer, W, req.bias[layer], X,
-                                   lambda f: split_expert(cfg, bank[f % n_unique]),
-                                   lambda l: [split_expert(cfg, shared[l * cfg.n_shared + s]) for s in range(cfg.n_shared)],
-                                   k, bool(cfg.renorm))
+    expert_of = lambda f: split_expert(cfg, bank[f % n_unique])
+    shared_of = lambda l: [split_expert(cfg, shared[l * cfg.n_shared + s]) for s in range(cfg.n_shared)]
+    rows_y = None
+    if sample is None:
+        ridx, rw, rY = O.prefill_layer(ref_eam, layer, W, req.bias[layer], X, expert_of, shared_of, k, bool(cfg.renorm))
+    else:
+        # routing of all tokens without any expert (H -> picks only), outputs of the sampled tokens
+        ridx, rw = _route_all(cfg, ref_eam, layer, W, req.bias[layer], X)
+        rows_y = np.unique(np.linspace(0, n - 1, sample).astype(np.int64))
+        scratch_eam = np.zeros_like(ref_eam)
+        _, _, rY = O.prefill_layer(scratch_eam, layer, W, req.bias[layer], X[rows_y], expert_of, shared_of, k,
+                                   bool(cfg.renorm))
     flags = cache.error_flags()
-    out = dict(idx=idx.cpu().numpy(), w=w.cpu().numpy(), Y=Y.cpu().numpy(), eam=d_eam.cpu().numpy(),
-               ridx=ridx, rw=rw, rY=rY, ream=ref_eam, flags=flags)
+    Yh = Y.cpu().numpy()
+    out = dict(idx=idx.cpu().numpy(), w=w.cpu().numpy(), Y=Yh if rows_y is None else Yh[rows_y], eam=d_eam.cpu().numpy(),
+               ridx=ridx, rw=rw, rY=rY, ream=ref_eam, eam0=eam0, flags=flags, finite=bool(np.isfinite(Yh).all()))
     cache.close()
     return out
 
@@ -115,6 +143,15 @@ def test_prefill_full_width_deepseek_v2_lite_layer(m):
     _check(o)
 
 
+def test_prefill_full_width_long_prompt_with_128_token_items(m):
+    # configuration 2 at full width with a 1,024-token prompt: n k > 64 E, so the items hold up to 128
+    # tokens; every token's picks, gate weights and the EAM in full, the outputs of 40 sampled tokens
+    cfg = mi.get_config("C2").scaled(L=1, N=8, prompt=16)
+    o = _prefill_case(m, cfg, 1024, layer=0, n_unique=16, sample=40)
+    assert o["finite"]
+    _check(o)
+
+
 def test_prefill_edge_cases(m):
     cfg = mi.get_config("C2").scaled(L=2, H=256, I=64, N=8, prompt=16)
     desc = m.ModelDesc.from_config(cfg)
@@ -132,6 +169,14 @@ def test_prefill_edge_cases(m):
     o = _prefill_case(m, cfg, 20, layer=1, resident=cfg.E)        # only layer 0's experts are resident
     assert o["flags"] & 2
     assert (o["idx"] == o["ridx"]).all() and np.isfinite(o["Y"]).all()
+    # a token whose router logits have no softmax (NaN in its input): flag bit 2, no picks, its
+    # output is the shared experts' alone (NaN here, as its input is); the other tokens are served as usual
+    o = _prefill_case(m, cfg, 12, layer=0, nan_token=4)
+    assert o["flags"] & 4 and (o["idx"][4] == -1).all() and (o["w"][4] == 0).all()
+    keep = [t for t in range(12) if t != 4]
+    assert (o["idx"][keep] == o["ridx"][keep]).all()
+    assert rel_max_err(o["Y"][keep], o["rY"][keep]) <= FFN_TOL_BF16_ACT
+    assert int(o["eam"][0].sum() - o["eam0"][0].sum()) == 11 * cfg.k
     # fp32 weights are refused, not mis-read
     cfg32 = mi.get_config("C1")
     c32 = m.Cache(m.ModelDesc.from_config(cfg32), cfg32.L * cfg32.E)

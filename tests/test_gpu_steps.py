@@ -58,6 +58,29 @@ def test_route_topk_all_equal_and_neg_inf(m):
     np.testing.assert_allclose(w.cpu().numpy(), rw, rtol=SIM_RTOL)
 
 
+@pytest.mark.parametrize("E,k", [(10, 4), (200, 70), (1500, 8)])
+def test_route_topk_logits_without_a_softmax_give_no_picks(m, E, k):
+    # error path (the paper's router always has a softmax): NaN, +inf or all -inf logits give the token
+    # index -1 / weight 0 for every pick; its neighbours in the batch are routed as usual
+    rng = np.random.default_rng(E)
+    z = rng.standard_normal((5, E)).astype(np.float32)
+    z[1, E // 2] = np.nan
+    z[2, :] = -np.inf
+    z[3, 3] = np.inf
+    idx, w = m.moe_route_topk(dev(z), k, True)
+    idx, w = idx.cpu().numpy(), w.cpu().numpy()
+    for b in (1, 2, 3):
+        assert (idx[b] == -1).all() and (w[b] == 0).all(), b
+    ridx, rw = O.route_topk(z[[0, 4]], k, True)
+    assert (idx[[0, 4]] == ridx).all()
+    np.testing.assert_allclose(w[[0, 4]], rw, rtol=SIM_RTOL, atol=1e-30)
+    # the EAM update passes over such picks
+    d_eam = dev(np.zeros((5, 2, E), dtype=np.int32))
+    m.eam_update(d_eam, 1, dev(idx.astype(np.int32)))
+    got = d_eam.cpu().numpy()
+    assert got[[1, 2, 3]].sum() == 0 and got[0, 1].sum() == k and got[4, 1].sum() == k
+
+
 # ----------------------------------------------------------------------- step 2
 def test_eam_update(m):
     rng = np.random.default_rng(7)
