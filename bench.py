@@ -578,6 +578,37 @@ def main():
                "host_cpus": os.cpu_count(), "cpu_model": model}
         log(f"[bench] oracle: {cpu['value'] / 1e3:.0f} ms per layer step on {threads} thread(s)")
 
+        # the same steps as plain C loops (oracle/cpu_step.c: scalar, fp64 accumulation, OpenMP over traces
+        # and over weight rows), on one core and on all of the cores this process may use
+        from oracle import cpu_step as CS
+        try:
+            usable = len(os.sched_getaffinity(0))
+        except AttributeError:
+            usable = os.cpu_count() or 1
+        n_all = max(1, min(usable, CS.threads_available()))
+        triples = [tuple(np.ascontiguousarray(a) for a in split_expert(cfg, bank[u])) for u in range(n_unique)]
+        sh_triples = [tuple(np.ascontiguousarray(a) for a in split_expert(cfg, shared[u])) for u in range(shared.shape[0])]
+        tabs = [CS.pointer_table([triples[(l * E + e) % n_unique] for e in range(E)]) for l in range(L)]
+        sh_tabs = [CS.pointer_table([sh_triples[(l * cfg.n_shared + s_) % len(sh_triples)] for s_ in range(cfg.n_shared)])
+                   if cfg.n_shared else None for l in range(L)]
+        all_resident = np.ones(L * E, dtype=np.uint8)
+        c_rows = {}
+        for nthr, budget_s in ((1, 8.0), (n_all, 5.0)):
+            c_eam = req.prefill_eam.astype(np.int64).copy()
+            n_c, spent_c = 0, 0.0
+            while spent_c < budget_s or n_c < 2:
+                l = n_c % L
+                a = time.perf_counter()
+                CS.decode_step(traces, c_eam, l, h_routers[l], req.bias[l], req.x[(n_c // L) % T_dec, l], tabs[l], sh_tabs[l],
+                               H, I, k, cfg.renorm, EPS, all_resident, threads=nthr)
+                spent_c += time.perf_counter() - a
+                n_c += 1
+            c_rows[nthr] = {"threads": nthr, "us_per_step": spent_c / n_c * 1e6, "layer_steps": n_c, "cpu_s": spent_c}
+            log(f"[bench] C loops, {nthr} thread(s): {spent_c / n_c * 1e3:.1f} ms per layer step ({n_c} steps)")
+        cpu["c_loops"] = {"kind": "plain C loops, fp64 accumulation, OpenMP over traces and weight rows (oracle/cpu_step.c)",
+                          "one_core": c_rows[1], "all_cores": c_rows[n_all], "usable_cpus": usable,
+                          "sample": "layer steps of the same request from its start, all experts resident"}
+
     out = {
         "metric": "us per MoE-layer decode step (EAMC traces scanned/s and expert GEMV HBM GB/s in `extra`)",
         "value": us_step, "unit": "us", "n_gpus": 1, "steps": K, "warmup": W,

@@ -276,12 +276,17 @@ int moei_cache_prefetch(moei_cache* c, const int32_t* h_pf_order, int32_t n_pf,
                         const int32_t* h_protect, int32_t n_protect,
                         int32_t* h_fids, int32_t* h_victims, int32_t* h_slots, int32_t* h_n_issued,
                         void* stream);
-/* Prefetch candidates the synchronous moe_decode_layer considers after each layer's
- * retrieval (0 = off, the default; needs MOEI_POLICY_EAM): moei_cache_prefetch with the
- * step's own orders and scores, protecting the layer's picks.  Asynchronous steps never
- * prefetch. */
+/* Prefetch candidates moe_decode_layer considers after each layer's retrieval (0 = off, the
+ * default; needs MOEI_POLICY_EAM): moei_cache_prefetch with the step's own orders and scores,
+ * protecting the layer's picks.  The synchronous step does this before it returns.  The
+ * asynchronous step computes the plan on the device (heads of both orders and the scores, into
+ * pinned memory) and the host carries it out at the next call that names this cache -
+ * moe_decode_layer of either kind, or moei_cache_join - after waiting for that step's match and
+ * scoring; nothing changes the cache in between, so the prefetches are the ones the synchronous
+ * step would have issued.  Such steps cannot be recorded in a stream capture (MOEI_ESTATE). */
 int moei_cache_set_prefetch(moei_cache* c, int32_t depth);
-/* What the last synchronous layer step prefetched: h_fids[cap] / h_victims[cap], *h_n. */
+/* What the last layer step prefetched (for an asynchronous step: once its plan has been carried
+ * out, see moei_cache_set_prefetch): h_fids[cap] / h_victims[cap], *h_n. */
 int moei_cache_last_prefetch(moei_cache* c, int32_t* h_fids, int32_t* h_victims, int32_t cap, int32_t* h_n);
 /* Number of most-similar traces the layer step's prediction aggregates (default 1; Sec. 4.5
  * step 2).  Takes effect from the next moe_decode_layer; *h_best stays the most similar. */
@@ -308,7 +313,8 @@ int moe_prefill_layer(moei_cache* c, int32_t* d_eam, int32_t layer,
                       int32_t* d_idx_out, float* d_w_out, void* stream);
 /* Makes `stream` wait for the match/priority work that the last moe_decode_layer put on
  * the cache's side stream (the next moe_decode_layer does this by itself) and for every
- * prefetch copy that no stream has waited for yet.  Call it
+ * prefetch copy that no stream has waited for yet; carries out the prefetch plan of an
+ * asynchronous step first (then it waits for that step's side stream on the host).  Call it
  * before ending a stream capture that contains asynchronous layer steps, so that the
  * side stream has joined `stream` again. */
 int moei_cache_join(moei_cache* c, void* stream);
@@ -319,11 +325,23 @@ int moei_cache_join(moei_cache* c, void* stream);
 int moei_cache_sync(moei_cache* c);
 /* Results of the most recent moe_decode_layer on this cache, copied to the host
  * (any pointer may be NULL): gate weights [k], best similarity, score matrices [L*E],
- * orders [L*E] and their lengths.  Synchronises both streams. */
+ * orders [L*E] and their lengths.  Synchronises both streams.
+ * A layer step itself selects only the heads of the two orders - Alg. 1 takes at most one victim
+ * per pick from the front of the eviction order, prefetching looks at `depth` candidates - and
+ * keeps the sort keys of every cell; the complete orders are ranked from those keys here, on
+ * demand (one more kernel per call that asks for an order). */
 int moei_cache_last_step(moei_cache* c, float* h_gate_w, float* h_best_sim,
                          float* h_prefetch, float* h_evict,
                          int32_t* h_pf_order, int32_t* h_n_pf, int32_t* h_ev_order, int32_t* h_n_ev,
                          void* stream);
+
+/* The heads of the two orders as the most recent moe_decode_layer selected them itself:
+ * h_ev_head[min(k + depth, n_ev)] (what Alg. 1's retrieval consumes) and h_pf_head[min(depth, n_pf)]
+ * (prefetch candidates; depth as set by moei_cache_set_prefetch), their lengths in *h_n_ev_head /
+ * *h_n_pf_head; cap_* = room in the arrays (MOEI_ECAPACITY if too small).  They are the leading
+ * entries of the complete orders.  Synchronises both streams. */
+int moei_cache_last_heads(moei_cache* c, int32_t* h_pf_head, int32_t cap_pf, int32_t* h_n_pf_head,
+                          int32_t* h_ev_head, int32_t cap_ev, int32_t* h_n_ev_head, void* stream);
 
 /* ------------------------------------------------------------------ kernel timing (diagnostic)
  * While enabled, every kernel launch of the library carries a start and a stop HIP event

@@ -29,7 +29,7 @@ EXPORTS = [
     "moe_route_topk", "eam_update", "eamc_match", "eamc_match_topm", "expert_priority",
     "moei_cache_create", "moei_cache_destroy", "moei_expert_pack", "moei_cache_reset", "moei_cache_slot_ptr", "moei_cache_slot_table",
     "moei_cache_get_slots", "moei_cache_retrieve", "expert_ffn_gemv", "expert_ffn_gemv_static", "expert_ffn_grouped", "moei_cache_error_flags",
-    "moe_decode_layer", "moei_cache_last_step", "moei_cache_join", "moei_cache_sync",
+    "moe_decode_layer", "moei_cache_last_step", "moei_cache_last_heads", "moei_cache_join", "moei_cache_sync",
     "moei_cache_set_match_count", "moei_cache_last_matches",
     "moe_prefill_layer", "moei_cache_set_policy", "moei_cache_prefetch", "moei_cache_set_prefetch", "moei_cache_last_prefetch",
     "moei_profile_enable", "moei_profile_disable", "moei_profile_kernels", "moei_profile_kernel_name",
@@ -220,6 +220,15 @@ class Cache:
 
     def sync(self) -> None:
         _check(lib().moei_cache_sync(self.h))
+
+    def last_heads(self, stream=None):
+        """(pf_head, ev_head): the leading entries of the two orders as the last layer step selected them."""
+        pf = np.empty(64, dtype=np.int32)
+        ev = np.empty(128, dtype=np.int32)
+        n_pf, n_ev = C.c_int32(0), C.c_int32(0)
+        _check(lib().moei_cache_last_heads(self.h, _p(pf), pf.size, C.byref(n_pf), _p(ev), ev.size, C.byref(n_ev),
+                                           _stream(stream)))
+        return pf[:n_pf.value].copy(), ev[:n_ev.value].copy()
 
     def last_step(self, stream=None) -> dict:
         LE, k = self.desc.L * self.desc.E, self.desc.k

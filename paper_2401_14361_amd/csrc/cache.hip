@@ -42,8 +42,7 @@ struct Pinned {
     int32_t pf_head[kMaxPrefetch];
     int32_t best;
     float best_sim;
-    int32_t n_ev;
-    int32_t n_pf;
+    int32_t n_list[2];  // n_pf, n_ev
     int32_t flags;
 };
 
@@ -106,9 +105,14 @@ struct moei_cache {
     int match_m = 1;            // traces aggregated by the layer step's prediction
     float* d_best_sim = nullptr;
     float *d_P = nullptr, *d_V = nullptr;
+    unsigned long long* d_keys = nullptr;  // [2][L*E] sort keys of the last step (prefetch, eviction)
+    int32_t *d_pf_head = nullptr, *d_ev_head = nullptr;  // leading entries of the orders, selected by the step itself
+    int last_h_pf = 0, last_h_ev = 0;      // heads the last step was asked to select
     int32_t *d_pf_order = nullptr, *d_ev_order = nullptr, *d_n_pf = nullptr, *d_n_ev = nullptr;
     Pinned* pin = nullptr;
     float* pin_V = nullptr;  // [L*E] eviction scores of the last step (pinned), for the prefetch admission
+    Pinned* pin_dev = nullptr;  // the same two blocks as the device addresses them
+    float* pin_V_dev = nullptr;
     // eviction policy and its host-side state
     int policy = kPolicyEam;
     std::vector<int64_t> stamp;  // per slot: clock value of its last use (0 = never)
@@ -125,6 +129,12 @@ struct moei_cache {
     PrefillScratch prefill;  // allocated at the first prefill call, grown when a longer prompt comes
     int32_t last_pf_fid[kMaxPrefetch] = {}, last_pf_victim[kMaxPrefetch] = {};
     int32_t last_n_pf = 0;  // prefetches issued by the last layer step
+    // an asynchronous step with prefetching leaves its plan (heads and scores in pinned memory) to be
+    // carried out by the host at the next call on this cache: nothing else touches the cache in between
+    bool plan_pending = false;
+    hipEvent_t plan_event = nullptr;  // end of the side chain that writes the plan
+    int plan_depth = 0, plan_k = 0;
+    bool pf_gate_recorded = false;  // ev_main already marks the point on the caller's stream that prefetch copies wait for
 };
 
 namespace {
@@ -171,6 +181,9 @@ extern "C" int moei_cache_destroy(moei_cache* c) {
     (void)hipFree(c->d_best_sim);
     (void)hipFree(c->d_P);
     (void)hipFree(c->d_V);
+    (void)hipFree(c->d_keys);
+    (void)hipFree(c->d_pf_head);
+    (void)hipFree(c->d_ev_head);
     (void)hipFree(c->d_pf_order);
     (void)hipFree(c->d_ev_order);
     (void)hipFree(c->d_n_pf);
@@ -228,6 +241,9 @@ int cache_alloc(moei_cache* c) {
     MOEI_DMALLOC(c->d_best_sim, kMaxMatchBatch * 4);
     MOEI_DMALLOC(c->d_P, LE * 4);
     MOEI_DMALLOC(c->d_V, LE * 4);
+    MOEI_DMALLOC(c->d_keys, 2 * LE * 8);
+    MOEI_DMALLOC(c->d_pf_head, (size_t)kMaxPrefetch * 4);
+    MOEI_DMALLOC(c->d_ev_head, (size_t)(kMaxAct + kMaxPrefetch) * 4);
     MOEI_DMALLOC(c->d_pf_order, LE * 4);
     MOEI_DMALLOC(c->d_ev_order, LE * 4);
     MOEI_DMALLOC(c->d_n_pf, 4);
@@ -240,9 +256,13 @@ int cache_alloc(moei_cache* c) {
     MOEI_HIP(hipMemset(c->d_best, 0xff, kMaxMatchBatch * 4));
     int rc = ffn_scratch_alloc(d, na, &c->ffn);
     if (rc) return rc;
-    MOEI_HIP(hipHostMalloc((void**)&c->pin, sizeof(Pinned), hipHostMallocDefault));
+    // mapped, coherent host memory: the routing and scoring kernels of a synchronous step store what the
+    // host reads next (picks, matched trace, heads, scores) straight into it
+    MOEI_HIP(hipHostMalloc((void**)&c->pin, sizeof(Pinned), hipHostMallocMapped | hipHostMallocCoherent));
     memset(c->pin, 0, sizeof(Pinned));
-    MOEI_HIP(hipHostMalloc((void**)&c->pin_V, LE * sizeof(float), hipHostMallocDefault));
+    MOEI_HIP(hipHostMalloc((void**)&c->pin_V, LE * sizeof(float), hipHostMallocMapped | hipHostMallocCoherent));
+    MOEI_HIP(hipHostGetDevicePointer((void**)&c->pin_dev, c->pin, 0));
+    MOEI_HIP(hipHostGetDevicePointer((void**)&c->pin_V_dev, c->pin_V, 0));
     MOEI_HIP(hipStreamCreateWithFlags(&c->pf_stream, hipStreamNonBlocking));
     MOEI_HIP(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
     MOEI_HIP(hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking));
@@ -314,6 +334,7 @@ extern "C" int moei_cache_reset(moei_cache* c, int32_t n_resident) {
                  "moei_cache_reset: n_resident = %d outside [0, min(S, L*E)]", n_resident);
     MOEI_HIP(hipDeviceSynchronize());
     c->side_pending = false;
+    c->plan_pending = false;
     for (int r = 0; r < kRing; ++r) c->match_pending[r] = false;
     std::fill(c->slot_of.begin(), c->slot_of.end(), -1);
     std::fill(c->owner.begin(), c->owner.end(), -1);
@@ -332,6 +353,7 @@ extern "C" int moei_cache_reset(moei_cache* c, int32_t n_resident) {
                                hipMemcpyHostToDevice));
     }
     MOEI_HIP(hipMemset(c->d_flags, 0, 4));
+    MOEI_HIP(hipMemset(c->d_ticket, 0, 4));
     return upload_slot_table(c);
 }
 
@@ -548,7 +570,7 @@ extern "C" int moei_cache_prefetch(moei_cache* c, const int32_t* h_pf_order, int
         upd.fid[upd.n] = fid;
         upd.slot[upd.n++] = slot;
         if (!gated) {  // work already queued on `stream` may still read the slots that are given up
-            MOEI_HIP(hipEventRecord(c->ev_main, s));
+            if (!c->pf_gate_recorded) MOEI_HIP(hipEventRecord(c->ev_main, s));
             MOEI_HIP(hipStreamWaitEvent(c->pf_stream, c->ev_main, 0));
             gated = true;
         }
@@ -676,6 +698,25 @@ extern "C" int moei_cache_error_flags(moei_cache* c, int32_t* h_flags, void* str
     return MOEI_OK;
 }
 
+namespace {
+// Carries out the prefetch plan an asynchronous layer step has left behind: waits for that step's
+// side chain, then runs the same admission as the synchronous step on the heads and scores it
+// wrote to pinned memory.  The cache is in the state that step left it in, so the result is the one
+// the synchronous step would have produced right away.
+int flush_prefetch_plan(moei_cache* c, hipStream_t s) {
+    if (!c->plan_pending) return MOEI_OK;
+    c->plan_pending = false;
+    MOEI_HIP(hipEventSynchronize(c->plan_event));
+    const int LE = c->d.L * c->d.E;
+    const int cap_pf = c->plan_depth < LE ? c->plan_depth : LE;
+    const int cap_ev = c->plan_k + c->plan_depth < LE ? c->plan_k + c->plan_depth : LE;
+    const int n_pf = c->pin->n_list[0] < cap_pf ? c->pin->n_list[0] : cap_pf;
+    const int n_ev = c->pin->n_list[1] < cap_ev ? c->pin->n_list[1] : cap_ev;
+    return moei_cache_prefetch(c, c->pin->pf_head, n_pf, c->pin->ev_head, n_ev, c->pin_V, c->plan_depth, nullptr, 0,
+                               c->last_pf_fid, c->last_pf_victim, nullptr, &c->last_n_pf, s);
+}
+}  // namespace
+
 extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d_eam, int32_t layer,
                                 const void* d_router_w, const float* d_router_bias, const void* d_x, float* d_y,
                                 int32_t* h_topk_idx, int32_t* h_best, int32_t* h_n_miss, void* stream) {
@@ -688,6 +729,18 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
     const bool sync_mode = h_topk_idx || h_best || h_n_miss;
     const int k = d.k, E = d.E;
     int rc;
+    // an asynchronous step plans its prefetches on the device and leaves them to the host; the host
+    // cannot be asked in the middle of a stream capture
+    const bool plan_prefetch = !sync_mode && c->pf_depth > 0 && c->policy == kPolicyEam && c->h_experts;
+    if (plan_prefetch || c->plan_pending) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        MOEI_HIP(hipStreamIsCapturing(s, &cap));
+        if (cap != hipStreamCaptureStatusNone)
+            MOEI_FAIL(MOEI_ESTATE, "moe_decode_layer: prefetching needs the host between layer steps and cannot be captured "
+                                   "(moei_cache_set_prefetch(c, 0) before the capture)");
+    }
+    rc = flush_prefetch_plan(c, s);
+    if (rc) return rc;
 
     // Routing hands the side stream a snapshot of the updated EAM and its picks in one of
     // kRing buffer sets used in turn, so the main stream never waits for the match and scoring
@@ -728,9 +781,9 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
     ra.slot_ids = c->d_slot_ids;
     ra.gate = c->d_gate;
     ra.flags = sync_mode ? nullptr : c->d_flags;
+    ra.host_idx = sync_mode ? c->pin_dev->idx : nullptr;
     rc = launch_route_fused(ra, d.wdtype, s);
     if (rc) return rc;
-    if (sync_mode) MOEI_HIP(hipMemcpyAsync(c->pin->idx, c->d_idx, (size_t)k * 4, hipMemcpyDeviceToHost, s));
     MOEI_HIP(hipEventRecord(c->ev_routed, s));
     // Asynchronous step: the expert FFNs go onto the main stream right behind the routing,
     // before any side-stream work is enqueued, so that neither the host-side enqueue time of
@@ -746,29 +799,34 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
     MOEI_HIP(hipStreamWaitEvent(side, c->ev_routed, 0));
     // match and scoring in one launch sequence (the workgroup that finishes the match scores
     // the matched trace), then the two orders
+    // Alg. 1 takes the victims from the head of the eviction order (one per miss at most) and prefetching
+    // looks at `depth` candidates: the step computes those heads; the complete orders are ranked from the
+    // step's keys when moei_cache_last_step asks for them
     ScoreArgs sc = make_score_args(eamc, c->d_best, c->match_m, layer, c->d_slot_of, d.eps, c->d_idx, k, c->d_P,
                                    c->d_V, c->d_n_pf, c->d_n_ev);
+    sc.keys = c->d_keys;
+    sc.pf_order = c->d_pf_head;
+    sc.ev_order = c->d_ev_head;
+    sc.h_pf = c->pf_depth;
+    sc.h_ev = k + c->pf_depth;
+    c->last_h_pf = sc.h_pf;
+    c->last_h_ev = sc.h_ev;
+    if (sync_mode || plan_prefetch) {  // what the host reads goes straight into pinned memory: no copies behind the kernels
+        sc.host_best = &c->pin_dev->best;
+        sc.host_n = c->pin_dev->n_list;
+        sc.host_pf_head = c->pin_dev->pf_head;
+        sc.host_ev_head = c->pin_dev->ev_head;
+        sc.host_V = (c->pf_depth > 0 && c->policy == kPolicyEam) ? c->pin_V_dev : nullptr;
+    }
     if (c->match_m == 1)
         rc = launch_match(eamc, d_snap, 1, d.L - 1, c->d_best, c->d_best_sim, nullptr, &sc, side);
     else
         rc = launch_match_topm(eamc, d_snap, d.L - 1, c->match_m, c->d_best, c->d_best_sim, nullptr, &sc, side);
     if (rc) return rc;
-    rc = launch_priority_rank(eamc, c->d_n_pf, c->d_n_ev, c->d_pf_order, c->d_ev_order, side);
-    if (rc) return rc;
     const bool do_prefetch = sync_mode && c->pf_depth > 0 && c->policy == kPolicyEam;
     const int LE = d.L * E;
     const int n_ev_copy = do_prefetch ? (k + c->pf_depth < LE ? k + c->pf_depth : LE) : k;
     const int n_pf_copy = c->pf_depth < LE ? c->pf_depth : LE;
-    if (sync_mode) {
-        MOEI_HIP(hipMemcpyAsync(&c->pin->best, c->d_best, 4, hipMemcpyDeviceToHost, side));
-        MOEI_HIP(hipMemcpyAsync(&c->pin->n_ev, c->d_n_ev, 4, hipMemcpyDeviceToHost, side));
-        MOEI_HIP(hipMemcpyAsync(c->pin->ev_head, c->d_ev_order, (size_t)n_ev_copy * 4, hipMemcpyDeviceToHost, side));
-        if (do_prefetch) {
-            MOEI_HIP(hipMemcpyAsync(&c->pin->n_pf, c->d_n_pf, 4, hipMemcpyDeviceToHost, side));
-            MOEI_HIP(hipMemcpyAsync(c->pin->pf_head, c->d_pf_order, (size_t)n_pf_copy * 4, hipMemcpyDeviceToHost, side));
-            MOEI_HIP(hipMemcpyAsync(c->pin_V, c->d_V, (size_t)LE * 4, hipMemcpyDeviceToHost, side));
-        }
-    }
     // one event per step at the end of the side chain (an event record between two kernels
     // costs a few microseconds on its stream): it releases this step's buffer set and is what
     // a join or a host-side wait refers to
@@ -777,6 +835,12 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
     c->ev_side = c->ev_match[c->parity];
     c->side_pending = true;
 
+    if (plan_prefetch) {
+        c->plan_pending = true;
+        c->plan_event = c->ev_match[c->parity];
+        c->plan_depth = c->pf_depth;
+        c->plan_k = k;
+    }
     if (!sync_mode) return MOEI_OK;
     {
         MOEI_HIP(hipEventSynchronize(c->ev_routed));
@@ -797,7 +861,7 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
         if (n_miss > 0 && c->policy == kPolicyEam) {
             MOEI_HIP(hipEventSynchronize(c->ev_side));
             side_done = true;
-            n_ev = c->pin->n_ev < k ? c->pin->n_ev : k;
+            n_ev = c->pin->n_list[1] < k ? c->pin->n_list[1] : k;
         }
         // under the comparison policies nothing above waited for the side stream, whose scoring still
         // reads the device slot table that the retrieval is about to change
@@ -809,13 +873,23 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
             rc = launch_gather_slots(c->d_idx, k, c->d_slot_of + (size_t)layer * E, c->d_slot_ids + d.n_shared, c->d_flags, s);
             if (rc) return rc;
         }
+        // the experts run as soon as their slots are settled: what is left below (prefetch planning,
+        // the matched trace for the caller) waits for the side stream while the FFN streams
+        // (prefetch copies wait for what is on the stream up to here - earlier steps may still read the
+        // slots they take - but not for this layer's experts, whose slots they never touch)
+        if (do_prefetch) MOEI_HIP(hipEventRecord(c->ev_main, s));
+        rc = launch_expert_ffn(d, c->d_pool, c->slot_elems, c->n_total, c->ffn, c->d_slot_ids, c->d_gate, k + d.n_shared,
+                               d_x, d_y, c->d_flags, s);
+        if (rc) return rc;
         if (do_prefetch) {
             if (!side_done) MOEI_HIP(hipEventSynchronize(c->ev_side));
             side_done = true;
-            const int n_pf = c->pin->n_pf < n_pf_copy ? c->pin->n_pf : n_pf_copy;
-            const int n_ev_all = c->pin->n_ev < n_ev_copy ? c->pin->n_ev : n_ev_copy;
+            const int n_pf = c->pin->n_list[0] < n_pf_copy ? c->pin->n_list[0] : n_pf_copy;
+            const int n_ev_all = c->pin->n_list[1] < n_ev_copy ? c->pin->n_list[1] : n_ev_copy;
+            c->pf_gate_recorded = true;
             rc = moei_cache_prefetch(c, c->pin->pf_head, n_pf, c->pin->ev_head, n_ev_all, c->pin_V, c->pf_depth, protect,
                                      k, c->last_pf_fid, c->last_pf_victim, nullptr, &c->last_n_pf, s);
+            c->pf_gate_recorded = false;
             if (rc) return rc;
         } else {
             c->last_n_pf = 0;
@@ -827,8 +901,27 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
             *h_best = c->pin->best;
         }
     }
-    return launch_expert_ffn(d, c->d_pool, c->slot_elems, c->n_total, c->ffn, c->d_slot_ids, c->d_gate,
-                             k + d.n_shared, d_x, d_y, c->d_flags, s);
+    return MOEI_OK;
+}
+
+extern "C" int moei_cache_last_heads(moei_cache* c, int32_t* h_pf_head, int32_t cap_pf, int32_t* h_n_pf_head,
+                                     int32_t* h_ev_head, int32_t cap_ev, int32_t* h_n_ev_head, void* stream) {
+    MOEI_REQUIRE(c && h_n_pf_head && h_n_ev_head, "moei_cache_last_heads: null pointer");
+    MOEI_HIP(hipStreamSynchronize(as_stream(stream)));
+    MOEI_HIP(hipStreamSynchronize(c->side_stream));
+    int32_t n_pf = 0, n_ev = 0;
+    MOEI_HIP(hipMemcpy(&n_pf, c->d_n_pf, 4, hipMemcpyDeviceToHost));
+    MOEI_HIP(hipMemcpy(&n_ev, c->d_n_ev, 4, hipMemcpyDeviceToHost));
+    const int h_pf = c->last_h_pf < n_pf ? c->last_h_pf : n_pf;
+    const int h_ev = c->last_h_ev < n_ev ? c->last_h_ev : n_ev;
+    if (h_pf > cap_pf || h_ev > cap_ev)
+        MOEI_FAIL(MOEI_ECAPACITY, "moei_cache_last_heads: room for %d / %d entries, %d / %d needed", cap_pf, cap_ev, h_pf, h_ev);
+    MOEI_REQUIRE((h_pf == 0 || h_pf_head) && (h_ev == 0 || h_ev_head), "moei_cache_last_heads: null pointer");
+    if (h_pf > 0) MOEI_HIP(hipMemcpy(h_pf_head, c->d_pf_head, (size_t)h_pf * 4, hipMemcpyDeviceToHost));
+    if (h_ev > 0) MOEI_HIP(hipMemcpy(h_ev_head, c->d_ev_head, (size_t)h_ev * 4, hipMemcpyDeviceToHost));
+    *h_n_pf_head = h_pf;
+    *h_n_ev_head = h_ev;
+    return MOEI_OK;
 }
 
 extern "C" int moei_cache_last_prefetch(moei_cache* c, int32_t* h_fids, int32_t* h_victims, int32_t cap, int32_t* h_n) {
@@ -861,6 +954,10 @@ extern "C" int moei_cache_last_matches(moei_cache* c, int32_t* h_top, float* h_t
 
 extern "C" int moei_cache_join(moei_cache* c, void* stream) {
     MOEI_REQUIRE(c, "moei_cache_join: null pointer");
+    if (c->plan_pending) {  // the prefetches the last asynchronous step planned are issued now
+        int rc = flush_prefetch_plan(c, as_stream(stream));
+        if (rc) return rc;
+    }
     if (c->side_pending) MOEI_HIP(hipStreamWaitEvent(as_stream(stream), c->ev_side, 0));
     if (c->n_pending > 0) {  // prefetch copies that no stream has waited for yet
         for (int t = 0; t < c->S; ++t) {
@@ -889,6 +986,11 @@ extern "C" int moei_cache_last_step(moei_cache* c, float* h_gate_w, float* h_bes
     MOEI_REQUIRE(c, "moei_cache_last_step: null pointer");
     MOEI_HIP(hipStreamSynchronize(as_stream(stream)));
     MOEI_HIP(hipStreamSynchronize(c->side_stream));
+    if (h_pf_order || h_ev_order) {  // the step selected the heads only: the complete orders are ranked from its keys now
+        int rc = launch_priority_rank(c->d, c->d_keys, c->d_n_pf, c->d_n_ev, c->d_pf_order, c->d_ev_order, c->side_stream);
+        if (rc) return rc;
+        MOEI_HIP(hipStreamSynchronize(c->side_stream));
+    }
     const size_t LE = (size_t)c->d.L * c->d.E;
     if (h_gate_w) MOEI_HIP(hipMemcpy(h_gate_w, c->d_w, (size_t)c->d.k * 4, hipMemcpyDeviceToHost));
     if (h_best_sim) MOEI_HIP(hipMemcpy(h_best_sim, c->d_best_sim, 4, hipMemcpyDeviceToHost));

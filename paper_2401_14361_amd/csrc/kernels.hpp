@@ -26,6 +26,7 @@ struct RouteFusedArgs {
     int32_t* slot_ids;           // [k + n_shared] out
     float* gate;                 // [k + n_shared] out
     int32_t* flags;              // error flags (bit 1: pick not resident)
+    int32_t* host_idx;           // [k] pinned host memory that receives the picks too (synchronous step), or null
 };
 int launch_route_fused(RouteFusedArgs a, int wdtype, hipStream_t s);
 int launch_gather_slots(const int32_t* d_idx, int k, const int32_t* d_slot_of_row, int32_t* d_slot_ids,

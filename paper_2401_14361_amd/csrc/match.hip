@@ -341,7 +341,7 @@ __device__ __forceinline__ double cosine(u64 dot, u64 nq, u64 nt) {
 
 constexpr int kPickThreads = 1024;
 static_assert(kPickThreads == kScoreThreads, "the finishing workgroup of the match also runs the scoring");
-constexpr int kPickChunk = 1024;  // traces per workgroup: one per thread
+constexpr int kPickChunk = kPickThreads;  // traces per workgroup: one per thread
 constexpr int kPickWaves = kPickThreads / kWave;
 
 struct PickArgs {
@@ -390,6 +390,23 @@ __global__ void __launch_bounds__(kPickThreads) eamc_pick_kernel(PickArgs a) {
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wv = tid / kWave;
 
+    // One trace per thread (kPickChunk == kPickThreads).  Its partial dot products and norm are
+    // requested first, so that they travel together with the query cells of the norm below: one trip
+    // to memory instead of two.
+    const int n = blockIdx.x * kPickChunk + tid;
+    const bool have = n < a.N;
+    u64 dot = 0, nt = 1;
+    if (have) {
+        const u64* pp = a.part + (size_t)b * a.n_lsplit * a.n_cap + n;
+        nt = a.norm2[n];
+        int s = 0;
+        for (; s + 4 <= a.n_lsplit; s += 4) {  // the split partials are independent loads: four at a time
+            const u64 v0 = pp[(size_t)s * a.n_cap], v1 = pp[(size_t)(s + 1) * a.n_cap];
+            const u64 v2 = pp[(size_t)(s + 2) * a.n_cap], v3 = pp[(size_t)(s + 3) * a.n_cap];
+            dot += (v0 + v1) + (v2 + v3);
+        }
+        for (; s < a.n_lsplit; ++s) dot += pp[(size_t)s * a.n_cap];
+    }
     u64 nq = 0;
     for (int i = tid; i < a.LE; i += kPickThreads) {
         u64 v = (uint32_t)a.q[(size_t)b * a.LE + i];
@@ -407,32 +424,22 @@ __global__ void __launch_bounds__(kPickThreads) eamc_pick_kernel(PickArgs a) {
     nq = s_nq;
 
     Best me = make_best(0, 1, -1);
-    const int n_end = min(a.N, (int)(blockIdx.x + 1) * kPickChunk);
-    for (int n = blockIdx.x * kPickChunk + tid; n < n_end; n += kPickThreads) {
-        // the split partials are independent loads: issue them four at a time
-        const u64* pp = a.part + (size_t)b * a.n_lsplit * a.n_cap + n;
-        const u64 nt = a.norm2[n];
-        u64 dot = 0;
-        int s = 0;
-        for (; s + 4 <= a.n_lsplit; s += 4) {
-            const u64 v0 = pp[(size_t)s * a.n_cap], v1 = pp[(size_t)(s + 1) * a.n_cap];
-            const u64 v2 = pp[(size_t)(s + 2) * a.n_cap], v3 = pp[(size_t)(s + 3) * a.n_cap];
-            dot += (v0 + v1) + (v2 + v3);
-        }
-        for (; s < a.n_lsplit; ++s) dot += pp[(size_t)s * a.n_cap];
+    if (have) {
         if (a.sims) a.sims[(size_t)b * a.N + n] = (float)cosine(dot, nq, nt);
-        me = pick(me, make_best(dot, nt, n));
+        me = make_best(dot, nt, n);
     }
     Best r = block_pick(me, s_dot, s_nt, s_idx);
     __shared__ int s_sn[2];
     __shared__ int s_best[kMaxMatchBatch];
+    __shared__ HeadLds s_heads;
+    __shared__ KeyLds s_keys;
     if (gridDim.x == 1) {
         if (tid == 0) {
             a.best[b] = r.idx;
             if (a.best_sim) a.best_sim[b] = r.idx >= 0 ? (float)cosine(r.dot, nq, a.norm2[r.idx]) : 0.f;
             s_best[0] = r.idx;
         }
-        if (a.do_score) score_cells(a.sc, s_sn, s_best, true);
+        if (a.do_score) score_and_heads(a.sc, s_heads, s_keys, s_sn, s_best, true);
         return;
     }
     // several workgroups: publish this one's winner, the last to arrive finishes
@@ -464,7 +471,7 @@ __global__ void __launch_bounds__(kPickThreads) eamc_pick_kernel(PickArgs a) {
         a.ticket[b] = 0;  // ready for the next launch on this stream
         s_best[0] = fin.idx;
     }
-    if (a.do_score) score_cells(a.sc, s_sn, s_best, true);
+    if (a.do_score) score_and_heads(a.sc, s_heads, s_keys, s_sn, s_best, true);
 }
 
 // ---- the m most similar traces of ONE query, most similar first (ties: lowest index)
@@ -534,6 +541,8 @@ __global__ void __launch_bounds__(kPickThreads) eamc_topm_kernel(TopmArgs a) {
     __shared__ int s_win;
     __shared__ int s_sn[2];
     __shared__ int s_best[kMaxMatchBatch];
+    __shared__ HeadLds s_heads;
+    __shared__ KeyLds s_keys;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wv = tid / kWave;
     const bool single = gridDim.x == 1;
@@ -626,7 +635,7 @@ __global__ void __launch_bounds__(kPickThreads) eamc_topm_kernel(TopmArgs a) {
             });
         if (tid == 0) *a.ticket = 0;  // ready for the next launch on this stream
     }
-    if (a.do_score) score_cells(a.sc, s_sn, s_best, true);
+    if (a.do_score) score_and_heads(a.sc, s_heads, s_keys, s_sn, s_best, true);
 }
 
 struct Plan {

@@ -20,7 +20,9 @@ constexpr int kRankThreads = 256;
 __global__ void __launch_bounds__(kScoreThreads) priority_score_kernel(ScoreArgs a) {
     __shared__ int s_n[2];
     __shared__ int s_best[kMaxMatchBatch];
-    score_cells(a, s_n, s_best, false);
+    __shared__ HeadLds s_heads;
+    __shared__ KeyLds s_keys;
+    score_and_heads(a, s_heads, s_keys, s_n, s_best, false);
 }
 
 // grid (workgroups, 2 lists).  The workgroup stages the list's L*E keys in LDS; a wavefront
@@ -87,13 +89,14 @@ ScoreArgs make_score_args(const moei_eamc* c, const int32_t* d_best, int B, int 
                           float eps, const int32_t* d_cur_idx, int n_cur, float* d_prefetch, float* d_evict,
                           int32_t* d_n_pf, int32_t* d_n_ev) {
     return ScoreArgs{c->d_traces, c->cell_bytes, c->n_cap, c->N, c->d.L, c->d.E, d_best, B, cur_layer, d_slot_of,
-                     (double)eps, d_cur_idx, d_cur_idx ? n_cur : 0, d_prefetch, d_evict, c->d_keys, d_n_pf, d_n_ev};
+                     (double)eps, d_cur_idx, d_cur_idx ? n_cur : 0, d_prefetch, d_evict, c->d_keys, d_n_pf, d_n_ev,
+                     nullptr, nullptr, 0, 0, nullptr, nullptr, nullptr, nullptr, nullptr};
 }
 
 // The two orders from the keys that score_cells left in c->d_keys.
-int launch_priority_rank(const moei_eamc* c, const int32_t* d_n_pf, const int32_t* d_n_ev, int32_t* d_pf_order,
-                         int32_t* d_ev_order, hipStream_t s) {
-    const size_t LE = (size_t)c->d.L * c->d.E;
+int launch_priority_rank(const moei_model_desc& d, const unsigned long long* d_keys, const int32_t* d_n_pf,
+                         const int32_t* d_n_ev, int32_t* d_pf_order, int32_t* d_ev_order, hipStream_t s) {
+    const size_t LE = (size_t)d.L * d.E;
     const size_t smem = LE * 8;
     if (smem > 64 * 1024) {
         static size_t allowed = 0;
@@ -106,7 +109,7 @@ int launch_priority_rank(const moei_eamc* c, const int32_t* d_n_pf, const int32_
     // enough wavefronts that each ranks only a few cells
     int blocks = (int)((LE + 4 * (kRankThreads / kWave) - 1) / (4 * (kRankThreads / kWave)));
     blocks = blocks < 1 ? 1 : (blocks > 256 ? 256 : blocks);
-    launch(K_PRIO_RANK, priority_rank_kernel, dim3(blocks, 2), dim3(kRankThreads), smem, s, (const u64*)c->d_keys,
+    launch(K_PRIO_RANK, priority_rank_kernel, dim3(blocks, 2), dim3(kRankThreads), smem, s, (const u64*)d_keys,
            (int)LE, d_n_pf, d_n_ev, d_pf_order, d_ev_order);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
@@ -133,5 +136,5 @@ extern "C" int expert_priority(const moei_eamc* c, const int32_t* d_best, int32_
                                   d_n_ev);
     launch(K_PRIO_SCORE, priority_score_kernel, dim3(1), dim3(kScoreThreads), 0, s, a);
     MOEI_LAUNCH_CHECK();
-    return launch_priority_rank(c, d_n_pf, d_n_ev, d_pf_order, d_ev_order, s);
+    return launch_priority_rank(c->d, c->d_keys, d_n_pf, d_n_ev, d_pf_order, d_ev_order, s);
 }

@@ -209,6 +209,9 @@ __global__ void __launch_bounds__(kRouteWaves * kWave) route_fused_kernel(RouteF
     } else {
         wave_topk(z, a.E, a.k, a.renorm, lane, my_idx, my_w);
     }
+    // the synchronous step reads the picks on the host: they go straight into pinned host memory (what a
+    // kernel has written there is visible to the host once the kernel has completed), no copy behind the kernel
+    if (lane < a.k && a.host_idx) a.host_idx[lane] = bad ? -1 : my_idx;
     if (lane < a.k && bad) {
         a.idx[lane] = -1;
         a.w[lane] = 0.f;

@@ -112,10 +112,12 @@ def _replay(m, cfg, S, n_tokens, n_unique, cell_bytes, rid=0, match_m=1, f64_cac
     for t in tokens:
         for l in range(L):
             idx, best, n_miss = m.moe_decode_layer(cache, eamc, d_eam, l, d_routers[l], d_bias[l], d_x[t, l], y)
+            pf_head, ev_head = cache.last_heads()      # what the step itself selected, before the full ranking
             last = cache.last_step()
             ref = O.decode_layer(T, ref_eam, ref_cache, l, routers[l], req.bias[l], req.x[t, l], expert_of, shared_of,
                                  k, bool(cfg.renorm), EPS, m=match_m)
             where = f"token {t} layer {l}"
+            assert ev_head.tolist() == ref["ev_order"][:k] and pf_head.tolist() == [], where
             assert idx.tolist() == ref["idx"].tolist(), where
             np.testing.assert_allclose(last["w"], ref["w"], rtol=1e-4, err_msg=where)
             assert (d_eam.cpu().numpy() == ref_eam).all(), where
@@ -283,10 +285,12 @@ def _async_against_oracle(m, cfg, n_unique, n_tokens, rid):
     for t in tokens:
         for l in range(L):
             m.moe_decode_layer(cache, eamc, d_eam, l, d_routers[l], d_bias[l], d_x[t, l], y, sync=False)
+            _, ev_head = cache.last_heads()
             last = cache.last_step()
             ref = O.decode_layer(T, ref_eam, ref_cache, l, routers[l], req.bias[l], req.x[t, l], expert_of, shared_of,
                                  k, bool(cfg.renorm), EPS)
             assert all(e[1] for e in ref["events"])
+            assert ev_head.tolist() == ref["ev_order"][:k], (t, l)
             _check_step(cfg, f"async token {t} layer {l}", last, cache.last_matches()[0].tolist(), ref,
                         y.cpu().numpy(), d_eam.cpu().numpy(), ref_eam)
     assert cache.error_flags() == 0

@@ -158,6 +158,9 @@ def _replay_prefetch(m, cfg, S, n_tokens, depth, match_m=1, rid=0):
             where = f"token {t} layer {l}"
             assert idx.tolist() == ref["idx"].tolist(), where
             assert best == ref["best"], where
+            pf_head, ev_head = cache.last_heads()     # the heads the step selected: k + depth victims, depth candidates
+            assert ev_head.tolist() == ref["ev_order"][:k + depth], where
+            assert pf_head.tolist() == ref["pf_order"][:depth], where
             assert n_miss == sum(1 for e in ref["events"] if not e[1]), where
             assert cache.last_prefetch() == [(f, v) for f, v, _ in ref["prefetched"]], where
             assert (cache.get_slots() == ref_cache.slot_of).all(), where
@@ -186,3 +189,80 @@ def test_prefetching_lowers_misses_on_the_same_request(m):
     _, base = _replay_prefetch(m, cfg, S, 10, depth=0, rid=3)
     _, with_pf = _replay_prefetch(m, cfg, S, 10, depth=8, rid=3)
     assert with_pf < base
+
+
+def test_prefetches_planned_by_asynchronous_steps(m):
+    # Device-driven (asynchronous) layer steps with prefetching: the step plans on the device, the host
+    # carries the plan out at the next call on the cache.  All layers but the last are resident and are
+    # stepped asynchronously (they cannot miss); the last layer's experts start out on the host, are
+    # prefetched into the free slots as the prediction names them, and that layer is stepped synchronously
+    # (it may still miss).  Every step's prefetches, the slot table and the outputs against the oracle,
+    # whose decode_layer prefetches right after the step: nothing touches the cache in between, so the
+    # one-call lag changes no state.
+    cfg = mi.get_config("C2").scaled(L=5, H=256, I=192, N=120, prompt=64, E=32)
+    L, E, k, depth = cfg.L, cfg.E, cfg.k, 4
+    S = L * E - E // 2                                      # half of the last layer never fits: real evictions too
+    T, _, _ = mi.eamc_traces(cfg, threads=4)
+    req = mi.make_request(cfg, 9, decode=14)
+    tokens = pick_clear_tokens(cfg, req, 6)
+    bank = mi.expert_bank(cfg, L * E, threads=4)
+    shared = mi.expert_bank(cfg.scaled(cid=cfg.cid + 50), L * cfg.n_shared, threads=2)
+    routers = [mi.router_weights(cfg, l) for l in range(L)]
+    desc = m.ModelDesc.from_config(cfg)
+    eamc = m.Eamc(desc, cfg.N, 4)
+    eamc.load(T)
+    cache = m.Cache(desc, S, pinned(pack_bank(m, cfg, bank)), pinned(pack_bank(m, cfg, shared)))
+    n_res = (L - 1) * E
+    cache.reset(n_res)
+    cache.set_prefetch(depth)
+    ref_cache = O.ExpertCache(L, E, S, warm=False)
+    for l in range(L - 1):
+        ref_cache.retrieve(l, list(range(E)))               # flat ids 0 .. n_res-1 in slots of the same number
+    assert (cache.get_slots() == ref_cache.slot_of).all()
+    d_eam = dev(req.prefill_eam.astype(np.int32))
+    ref_eam = req.prefill_eam.astype(np.int64).copy()
+    d_routers, d_bias, d_x = [dev(w) for w in routers], dev(req.bias), dev(req.x)
+    y = torch.empty(cfg.H, dtype=torch.float32, device="cuda")
+    n_pf = n_miss_total = 0
+    for t in tokens:
+        for l in range(L):
+            last_layer = l == L - 1
+            ref = O.decode_layer(T, ref_eam, ref_cache, l, routers[l], req.bias[l], req.x[t, l],
+                                 lambda f: split_expert(cfg, bank[f]),
+                                 lambda layer: [split_expert(cfg, shared[layer * cfg.n_shared + s]) for s in range(cfg.n_shared)],
+                                 k, bool(cfg.renorm), EPS, prefetch_depth=depth)
+            where = f"token {t} layer {l}"
+            if last_layer:
+                idx, best, n_miss = m.moe_decode_layer(cache, eamc, d_eam, l, d_routers[l], d_bias[l], d_x[t, l], y)
+                assert idx.tolist() == ref["idx"].tolist() and best == ref["best"], where
+                assert n_miss == sum(1 for e in ref["events"] if not e[1]), where
+                n_miss_total += n_miss
+            else:
+                assert all(e[1] for e in ref["events"]), where       # resident layers never miss
+                m.moe_decode_layer(cache, eamc, d_eam, l, d_routers[l], d_bias[l], d_x[t, l], y, sync=False)
+                cache.join()                                         # the host carries the step's plan out
+            assert cache.last_prefetch() == [(f, v) for f, v, _ in ref["prefetched"]], where
+            assert (cache.get_slots() == ref_cache.slot_of).all(), where
+            torch.cuda.synchronize()
+            assert (d_eam.cpu().numpy() == ref_eam).all(), where
+            assert rel_max_err(y.cpu().numpy(), ref["y"]) <= FFN_TOL, where
+            n_pf += len(ref["prefetched"])
+    assert n_pf > 0
+    assert cache.error_flags() == 0
+    # the plan of an asynchronous step is also carried out by the next layer step itself (no join between)
+    cache.reset(n_res)
+    ref_cache = O.ExpertCache(L, E, S, warm=False)
+    for l in range(L - 1):
+        ref_cache.retrieve(l, list(range(E)))
+    d_eam.copy_(dev(req.prefill_eam.astype(np.int32)))
+    ref_eam = req.prefill_eam.astype(np.int64).copy()
+    t = tokens[0]
+    for l in range(L - 1):
+        O.decode_layer(T, ref_eam, ref_cache, l, routers[l], req.bias[l], req.x[t, l], lambda f: split_expert(cfg, bank[f]),
+                       lambda layer: [split_expert(cfg, shared[layer * cfg.n_shared + s]) for s in range(cfg.n_shared)],
+                       k, bool(cfg.renorm), EPS, prefetch_depth=depth)
+        m.moe_decode_layer(cache, eamc, d_eam, l, d_routers[l], d_bias[l], d_x[t, l], y, sync=False)
+    cache.join()
+    assert (cache.get_slots() == ref_cache.slot_of).all()
+    eamc.close()
+    cache.close()
