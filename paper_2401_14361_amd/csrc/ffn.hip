@@ -555,7 +555,10 @@ __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(Gr
     extern __shared__ __align__(16) float smem[];
     __shared__ int s_cnt[256];
     __shared__ int s_base;
-    float* xs = smem;              // [TB][H] inputs of the item's tokens, fp32
+    // [TB][H] inputs of the item's tokens: fp32 for fp32 weights; for bf16 weights the stored bf16 values
+    // themselves, in the first half of each row, for the two-element dot products
+    constexpr bool kPacked = std::is_same<WT, uint16_t>::value;
+    float* xs = smem;
     float* yp = smem + TB * a.H;   // [kGroupedWaves][H] y rows of one token, one per wavefront
     GroupItem* s_items = reinterpret_cast<GroupItem*>(yp + (size_t)kGroupedWaves * a.H);  // [max_items]
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
@@ -596,8 +599,15 @@ __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(Gr
         }
         __syncthreads();  // the previous segment is done with xs and yp
         for (int j = 0; j < TB; ++j)
-            if (j < it.ntok)
-                stage_as_f32(reinterpret_cast<const WT*>(a.x) + (size_t)it.tok[j] * H, xs + (size_t)j * H, H);
+            if (j < it.ntok) {
+                const WT* xsrc = reinterpret_cast<const WT*>(a.x) + (size_t)it.tok[j] * H;
+                if constexpr (kPacked) {
+                    uint4* dst = reinterpret_cast<uint4*>(xs + (size_t)j * H);
+                    for (int c = tid; c < H / 8; c += kGroupedWaves * kWave) dst[c] = *reinterpret_cast<const uint4*>(xsrc + c * 8);
+                } else {
+                    stage_as_f32(xsrc, xs + (size_t)j * H, H);
+                }
+            }
         __syncthreads();
         float acc[TB][NCH * N];
 #pragma unroll
@@ -617,15 +627,23 @@ __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(Gr
 #pragma unroll
                     for (int j = 0; j < TB; ++j) {
                         if (j < it.ntok) {  // uniform
-                            float xf[N];
+                            if constexpr (kPacked) {
+                                const uint4 xp = reinterpret_cast<const uint4*>(xs + (size_t)j * H)[(s >> 1) * kWave + lane];
+                                if ((s & 1) == 0)
+                                    gs[j] = V::dot_packed(cur, xp, gs[j]);
+                                else
+                                    us[j] = V::dot_packed(cur, xp, us[j]);
+                            } else {
+                                float xf[N];
 #pragma unroll
-                            for (int t = 0; t < N; t += 4)
-                                *reinterpret_cast<float4*>(xf + t) = *reinterpret_cast<const float4*>(
-                                    xs + (size_t)j * H + (s >> 1) * CW + lane * N + t);
-                            if ((s & 1) == 0)
-                                gs[j] = V::dot(cur, xf, gs[j]);
-                            else
-                                us[j] = V::dot(cur, xf, us[j]);
+                                for (int t = 0; t < N; t += 4)
+                                    *reinterpret_cast<float4*>(xf + t) = *reinterpret_cast<const float4*>(
+                                        xs + (size_t)j * H + (s >> 1) * CW + lane * N + t);
+                                if ((s & 1) == 0)
+                                    gs[j] = V::dot(cur, xf, gs[j]);
+                                else
+                                    us[j] = V::dot(cur, xf, us[j]);
+                            }
                         }
                     }
                 } else {

@@ -39,6 +39,7 @@ struct DotArgs {
     int TN;               // traces per tile
     int rowV;             // vectors per trace row
     int once;             // the scan exceeds the last-level cache: load with the non-temporal hint
+    int lane_rows;        // a trace row's vectors sit in rowV consecutive lanes (see the kernel)
 };
 
 template <typename CT, int VEC>
@@ -102,6 +103,49 @@ struct CellVec<uint16_t, 1> {
     }
 };
 
+// The query rows of a workgroup's layers, for its NB queries, into LDS: sixteen independent loads in
+// flight per thread instead of one trip to memory per element.
+template <int NB>
+__device__ __forceinline__ void stage_queries(const int32_t* __restrict__ q, int B, int L, int E, int b0, int l0, int nl,
+                                              int q_stride, int32_t* qs) {
+    const int per = nl * E;  // cells per query
+    const int total = NB * per;
+    for (int i0 = 0; i0 < total; i0 += 16 * kDotThreads) {
+        int32_t v[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int i = i0 + r * kDotThreads + (int)threadIdx.x;
+            const int b = i / per, c = i - b * per;
+            v[r] = (i < total && b0 + b < B) ? q[((size_t)(b0 + b) * L + l0) * E + c] : 0;
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int i = i0 + r * kDotThreads + (int)threadIdx.x;
+            const int b = i / per, c = i - b * per;
+            if (i < total) qs[b * q_stride + c] = v[r];
+        }
+    }
+}
+
+// Sum of a 64-bit value over each group of `group` consecutive lanes (a power of two up to 64; all 64
+// lanes take part; every lane of a group ends with the group's sum): two-word adds with carry over
+// DPP exchanges inside a row of 16 lanes, shuffles beyond.
+__device__ __forceinline__ u64 add_step_dpp(u64 v, unsigned lo_o, unsigned hi_o) {
+    const unsigned lo = (unsigned)v + lo_o;
+    const unsigned hi = (unsigned)(v >> 32) + hi_o + (lo < lo_o ? 1u : 0u);
+    return ((u64)hi << 32) | lo;
+}
+#define MOEI_GROUP_STEP(v, ctrl) (v) = add_step_dpp((v), MOEI_DPP_U32((unsigned)(v), ctrl), MOEI_DPP_U32((unsigned)((v) >> 32), ctrl))
+__device__ __forceinline__ u64 group_sum_u64(u64 v, int group) {
+    if (group >= 2) MOEI_GROUP_STEP(v, 0xB1);    // quad_perm [1,0,3,2]
+    if (group >= 4) MOEI_GROUP_STEP(v, 0x4E);    // quad_perm [2,3,0,1]
+    if (group >= 8) MOEI_GROUP_STEP(v, 0x141);   // row_half_mirror
+    if (group >= 16) MOEI_GROUP_STEP(v, 0x140);  // row_mirror
+    if (group >= 32) v += ((u64)__shfl_xor((unsigned)(v >> 32), 16, 64) << 32 | __shfl_xor((unsigned)v, 16, 64));
+    if (group >= 64) v += ((u64)__shfl_xor((unsigned)(v >> 32), 32, 64) << 32 | __shfl_xor((unsigned)v, 32, 64));
+    return v;
+}
+
 // grid (tiles, layer splits, query groups).  Thread t owns vectors p = j*256 + t (j < J) of its
 // tile; vector p belongs to trace p / rowV of the tile in EVERY layer, so the accumulators
 // live in registers across the whole layer walk.  A workgroup serves NB queries at once:
@@ -125,13 +169,12 @@ __global__ void __launch_bounds__(kDotThreads) eamc_dot_kernel(DotArgs a) {
     const int n0 = blockIdx.x * a.TN;
     const int tn = min(a.TN, a.N - n0);
 
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        const bool on = b0 + b < a.B;
-        const int32_t* qsrc = a.q + ((size_t)(on ? b0 + b : 0) * a.L + l0) * a.E;
-        for (int i = tid; i < nl * a.E; i += kDotThreads) qs[b * q_stride + i] = on ? qsrc[i] : 0;
-    }
-    for (int i = tid; i < NB * a.TN; i += kDotThreads) rowsum[i] = 0;
+    stage_queries<NB>(a.q, a.B, a.L, a.E, b0, l0, nl, q_stride, qs);
+    // a.lane_rows: the vectors of a trace row lie in a.rowV consecutive lanes (a power of two that divides
+    // the wavefront): their sums are added across those lanes and stored by the first of them; otherwise
+    // the row sums are gathered with LDS atomics, which many lanes on one address make slow
+    if (!a.lane_rows)
+        for (int i = tid; i < NB * a.TN; i += kDotThreads) rowsum[i] = 0;
     __syncthreads();
 
     bool valid[J];
@@ -149,29 +192,59 @@ __global__ void __launch_bounds__(kDotThreads) eamc_dot_kernel(DotArgs a) {
     }
     const size_t lstride = (size_t)a.n_cap * a.E;
     const CT* base = reinterpret_cast<const CT*>(a.traces) + ((size_t)l0 * a.n_cap + n0) * a.E + (size_t)tid * VEC;
-    const int32_t* ql = qs;
-#pragma unroll 2
-    for (int l = 0; l < nl; ++l) {
-        typename CV::raw v[J];
+    // The loads of the next layers are kept in flight by hand: a ring of kAhead layers of this thread's
+    // vectors, a slot refilled as soon as its layer has been taken out.  A vector past the tile's end
+    // reads the thread's first vector instead (in bounds; its sums are dropped at the end), so the loop
+    // has no divergent branch.
+    constexpr int kAhead = J <= 2 ? 4 : 2;
+    size_t voff[J];
 #pragma unroll
-        for (int j = 0; j < J; ++j)
-            if (valid[j])
-                v[j] = a.once ? CV::load_once(base + (size_t)j * kDotThreads * VEC)
-                              : CV::load(base + (size_t)j * kDotThreads * VEC);
+    for (int j = 0; j < J; ++j) voff[j] = valid[j] ? (size_t)j * kDotThreads * VEC : 0;
+    const bool any = valid[0];  // the thread has a vector in this tile at all
+    typename CV::raw ring[kAhead][J];
+    auto fetch = [&](typename CV::raw* dst, int l) {
+        const CT* src = base + (size_t)l * lstride;
 #pragma unroll
-        for (int j = 0; j < J; ++j)
-            if (valid[j]) {
+        for (int j = 0; j < J; ++j) dst[j] = a.once ? CV::load_once(src + voff[j]) : CV::load(src + voff[j]);
+    };
+    if (any) {
 #pragma unroll
-                for (int b = 0; b < NB; ++b) acc[j][b] = CV::dot(v[j], ql + b * q_stride + col[j], acc[j][b]);
+        for (int d = 0; d < kAhead; ++d)
+            if (d < nl) fetch(ring[d], d);
+        for (int l0r = 0; l0r < nl; l0r += kAhead) {
+#pragma unroll
+            for (int d = 0; d < kAhead; ++d) {
+                const int l = l0r + d;
+                if (l < nl) {  // uniform over the workgroup
+                    typename CV::raw v[J];
+#pragma unroll
+                    for (int j = 0; j < J; ++j) v[j] = ring[d][j];
+                    if (l + kAhead < nl) fetch(ring[d], l + kAhead);
+                    const int32_t* ql = qs + (size_t)l * a.E;
+#pragma unroll
+                    for (int j = 0; j < J; ++j)
+#pragma unroll
+                        for (int b = 0; b < NB; ++b) acc[j][b] = CV::dot(v[j], ql + b * q_stride + col[j], acc[j][b]);
+                }
             }
-        base += lstride;
-        ql += a.E;
+        }
     }
+    if (a.lane_rows) {
+        const bool first = (tid & (a.rowV - 1)) == 0;
 #pragma unroll
-    for (int j = 0; j < J; ++j)
+        for (int j = 0; j < J; ++j)
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
-            if (valid[j] && acc[j][b] != 0) atomicAdd(&rowsum[b * a.TN + row[j]], acc[j][b]);
+            for (int b = 0; b < NB; ++b) {
+                const u64 t = group_sum_u64(valid[j] ? acc[j][b] : 0, a.rowV);  // rows are valid or not as a whole
+                if (first && valid[j]) rowsum[b * a.TN + row[j]] = t;
+            }
+    } else {
+#pragma unroll
+        for (int j = 0; j < J; ++j)
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+                if (valid[j] && acc[j][b] != 0) atomicAdd(&rowsum[b * a.TN + row[j]], acc[j][b]);
+    }
     __syncthreads();
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
@@ -646,16 +719,18 @@ struct Plan {
 Plan make_plan(const moei_eamc* c, int L_scan, int B) {
     static const int kTargetBlocks = getenv("MOEI_MATCH_BLOCKS") ? atoi(getenv("MOEI_MATCH_BLOCKS")) : 0;
     Plan p{};
-    p.NB = B >= 3 ? 4 : (B == 2 ? 2 : 1);  // queries served by one pass over the traces
+    p.NB = B > 8 ? 16 : (B > 4 ? 8 : (B >= 3 ? 4 : (B == 2 ? 2 : 1)));  // queries served by one pass over the traces
     const int E = c->d.E;
     const int full = 16 / c->cell_bytes;
     p.VEC = (E % full == 0) ? full : 1;
     p.rowV = E / p.VEC;
     const long total_vec = (long)c->N * L_scan * p.rowV;
-    const int jt = total_vec >= (1L << 20) ? 4 : 1;  // fewer vectors per thread when the whole scan is small
+    // vectors per thread: fewer when the whole scan is small, and when many queries' accumulators need the registers
+    const int jt = total_vec >= (1L << 20) ? (p.NB >= 8 ? 2 : 4) : 1;
     p.TN = (kDotThreads * jt) / p.rowV;
     if (p.TN < 1) p.TN = 1;
     p.J = (p.TN * p.rowV + kDotThreads - 1) / kDotThreads;
+    if (p.J > 2 && p.NB > 4) p.NB = 4;  // very wide rows: the accumulators of 8 or 16 queries would not fit the registers
     p.n_tiles = (c->N + p.TN - 1) / p.TN;
     // aim at two rounds of workgroups over the chip (short scans too: 4.2 instead of 4.5 us for
     // 1,000 traces beside the streaming FFN); the query groups multiply the grid as well
@@ -679,17 +754,26 @@ int launch_dot_nb(const Plan& p, const DotArgs& a, dim3 grid, hipStream_t s) {
     case JJ:                                                                                           \
         launch(K_MATCH_DOT, eamc_dot_kernel<CT, VEC, JJ, NB>, grid, dim3(kDotThreads), p.smem, s, a);  \
         break;
-    switch (p.J) {
-        MOEI_DOT_CASE(1)
-        MOEI_DOT_CASE(2)
-        MOEI_DOT_CASE(3)
-        MOEI_DOT_CASE(4)
-        MOEI_DOT_CASE(5)
-        MOEI_DOT_CASE(6)
-        MOEI_DOT_CASE(7)
-        MOEI_DOT_CASE(8)
-        default:
-            MOEI_FAIL(MOEI_EINVAL, "eamc_match: no kernel for %d vectors per thread", p.J);
+    if constexpr (NB >= 8) {  // the plan gives batches of 8 and 16 queries at most two vectors per thread
+        switch (p.J) {
+            MOEI_DOT_CASE(1)
+            MOEI_DOT_CASE(2)
+            default:
+                MOEI_FAIL(MOEI_EINVAL, "eamc_match: no kernel for %d vectors per thread and %d queries per pass", p.J, NB);
+        }
+    } else {
+        switch (p.J) {
+            MOEI_DOT_CASE(1)
+            MOEI_DOT_CASE(2)
+            MOEI_DOT_CASE(3)
+            MOEI_DOT_CASE(4)
+            MOEI_DOT_CASE(5)
+            MOEI_DOT_CASE(6)
+            MOEI_DOT_CASE(7)
+            MOEI_DOT_CASE(8)
+            default:
+                MOEI_FAIL(MOEI_EINVAL, "eamc_match: no kernel for %d vectors per thread", p.J);
+        }
     }
 #undef MOEI_DOT_CASE
     MOEI_LAUNCH_CHECK();
@@ -698,6 +782,8 @@ int launch_dot_nb(const Plan& p, const DotArgs& a, dim3 grid, hipStream_t s) {
 
 template <typename CT, int VEC>
 int launch_dot_j(const Plan& p, const DotArgs& a, dim3 grid, hipStream_t s) {
+    if (p.NB == 16) return launch_dot_nb<CT, VEC, 16>(p, a, grid, s);
+    if (p.NB == 8) return launch_dot_nb<CT, VEC, 8>(p, a, grid, s);
     if (p.NB == 4) return launch_dot_nb<CT, VEC, 4>(p, a, grid, s);
     if (p.NB == 2) return launch_dot_nb<CT, VEC, 2>(p, a, grid, s);
     return launch_dot_nb<CT, VEC, 1>(p, a, grid, s);
@@ -952,7 +1038,8 @@ int launch_dots(const moei_eamc* c, const int32_t* d_eam, int B, int layer_hi, i
     // scan is read once per match and should not displace other data
     const size_t scan_bytes = (size_t)c->N * (layer_hi + 1) * E * c->cell_bytes;
     DotArgs a{c->d_traces, d_eam, c->d_part, c->n_cap, c->N, L, E, B, layer_hi + 1, p.lper, p.n_lsplit, p.TN, p.rowV,
-              scan_bytes > ((size_t)192 << 20)};
+              scan_bytes > ((size_t)192 << 20),
+              p.rowV <= kWave && (p.rowV & (p.rowV - 1)) == 0 && kDotThreads % p.rowV == 0};
     dim3 grid(p.n_tiles, p.n_lsplit, (B + p.NB - 1) / p.NB);
     if (c->cell_bytes == 4)
         return p.VEC == 4 ? launch_dot_j<int32_t, 4>(p, a, grid, s) : launch_dot_j<int32_t, 1>(p, a, grid, s);

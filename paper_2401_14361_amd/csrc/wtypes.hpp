@@ -61,6 +61,16 @@ struct WVec<uint16_t> {
         acc = __builtin_fmaf(bf16_hi(w.w), xf[7], acc);
         return acc;
     }
+    // acc += sum_i w[i] * x[i] with x given as eight bf16 values too: four two-element dot products
+    // with fp32 accumulation (v_dot2c_f32_bf16), a quarter of the instructions of the form above
+    static __device__ __forceinline__ float dot_packed(raw w, uint4 x, float acc) {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.x), __builtin_bit_cast(bf16x2, x.x), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.y), __builtin_bit_cast(bf16x2, x.y), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.z), __builtin_bit_cast(bf16x2, x.z), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.w), __builtin_bit_cast(bf16x2, x.w), acc, false);
+        return acc;
+    }
     static __device__ __forceinline__ void unpack(raw w, float* f) {
         f[0] = bf16_lo(w.x); f[1] = bf16_hi(w.x);
         f[2] = bf16_lo(w.y); f[3] = bf16_hi(w.y);
