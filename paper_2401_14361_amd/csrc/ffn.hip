@@ -89,6 +89,7 @@ __global__ void __launch_bounds__((StreamShape<NCH>::kMaxWaves * kWave)) ffn_fus
     extern __shared__ __align__(16) float smem[];
     float* xs = smem;
     float* yp = smem + a.H;
+    constexpr bool kPacked = std::is_same<WT, uint16_t>::value;  // bf16: x stays bf16 in LDS, products by v_dot2c_f32_bf16
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     // the wavefront index in a scalar register: unit ids, slot ids and base addresses are
     // then scalar too
@@ -137,7 +138,12 @@ __global__ void __launch_bounds__((StreamShape<NCH>::kMaxWaves * kWave)) ffn_fus
 #pragma unroll
         for (int s = 0; s < PF; ++s) win[s] = ld(p, step_off(s));
     }
-    stage_as_f32(reinterpret_cast<const WT*>(a.x), xs, H);
+    if constexpr (kPacked) {
+        uint4* dst = reinterpret_cast<uint4*>(xs);
+        for (int c = tid; c < H / 8; c += blockDim.x) dst[c] = reinterpret_cast<const uint4*>(a.x)[c];
+    } else {
+        stage_as_f32(reinterpret_cast<const WT*>(a.x), xs, H);
+    }
     if (tid < a.n_act) {
         s_slot[tid] = a.slot_ids[tid];
         s_gate[tid] = a.gate_w[tid];
@@ -155,18 +161,27 @@ __global__ void __launch_bounds__((StreamShape<NCH>::kMaxWaves * kWave)) ffn_fus
         }
         float g = 0.f, u = 0.f, ai = 0.f;
         float xf[N];
+        uint4 xp = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
             const Raw cur = win[s % PF];
             if (s < 2 * NCH) {
-                if ((s & 1) == 0) {
-#pragma unroll
-                    for (int k = 0; k < N; k += 4)
-                        *reinterpret_cast<float4*>(xf + k) =
-                            *reinterpret_cast<const float4*>(xs + (s >> 1) * CW + lane * N + k);
-                    g = V::dot(cur, xf, g);
+                if constexpr (kPacked) {
+                    if ((s & 1) == 0) xp = reinterpret_cast<const uint4*>(xs)[(s >> 1) * kWave + lane];
+                    if ((s & 1) == 0)
+                        g = V::dot_packed(cur, xp, g);
+                    else
+                        u = V::dot_packed(cur, xp, u);
                 } else {
-                    u = V::dot(cur, xf, u);
+                    if ((s & 1) == 0) {
+#pragma unroll
+                        for (int k = 0; k < N; k += 4)
+                            *reinterpret_cast<float4*>(xf + k) =
+                                *reinterpret_cast<const float4*>(xs + (s >> 1) * CW + lane * N + k);
+                        g = V::dot(cur, xf, g);
+                    } else {
+                        u = V::dot(cur, xf, u);
+                    }
                 }
             } else {
                 if (s == 2 * NCH) {

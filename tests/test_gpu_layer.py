@@ -411,10 +411,10 @@ def test_layer_steps_in_a_hip_graph_against_the_oracle(m):
 # ------------------------------------------------------------------ full benchmark shapes
 def test_full_size_deepseek_v2_lite_tokens_with_capped_cache(m):
     # configuration 2 at full size (26 x 64 experts of 2048 x 1408 bf16, 1,000 traces, 416 slots):
-    # 8 decode tokens = 208 layer steps, every one compared in full while the cache keeps evicting
+    # 12 decode tokens = 312 layer steps, every one compared in full while the cache keeps evicting
     cfg = mi.get_config("C2")
-    misses = _replay(m, cfg, cfg.S, 8, 24, 4)
-    assert misses > 8 * cfg.k
+    misses = _replay(m, cfg, cfg.S, 12, 24, 4)
+    assert misses > 12 * cfg.k
 
 
 def test_full_size_deepseek_v2_lite_async_and_graph_steps(m):
@@ -427,9 +427,9 @@ def test_full_size_deepseek_v2_lite_async_and_graph_steps(m):
 
 def test_full_size_mixtral_request_all_layers(m):
     # configuration 3 at full size: all 32 layers x 8 experts of 4096 x 14336 bf16 (352 MB each),
-    # 96 of 256 slots, 1,000 traces; two decode tokens = 64 layer steps with misses from host memory
+    # 96 of 256 slots, 1,000 traces; three decode tokens = 96 layer steps with misses from host memory
     cfg = mi.get_config("C3")
-    misses = _replay(m, cfg, cfg.S, 2, 6, 4, f64_cache=True)
+    misses = _replay(m, cfg, cfg.S, 3, 6, 4, f64_cache=True)
     assert misses > 0
 
 
