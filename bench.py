@@ -56,7 +56,8 @@ def parse():
     ap.add_argument("--policy-requests", type=int, default=6)
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-shapes", action="store_true",
-                    help="skip the FFN kernel at the C3/C4 widths and the full C4 match (extra.other_shapes)")
+                    help="skip the FFN kernel at the C3/C4 widths, the full C4 match (extra.other_shapes) and the short "
+                         "decode-batch and prefill legs of the default run")
     ap.add_argument("--batch-sweep", action="store_true",
                     help="also time the batched match and grouped FFN for B = 1..16 (EAMC of 10,000 traces)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -407,13 +408,15 @@ def main():
         extra["other_shapes"] = shapes
 
     # ------------------------------------------------ optional: decode batches on this shape
-    if args.batch_sweep:
+    # (the default run on C2 carries a short form of it: B = 1, 4, 16)
+    short_legs = args.config == "C2" and not args.no_shapes
+    if args.batch_sweep or short_legs:
         big_cfg = cfg.scaled(cid=5, N=10000)
         tr10k, _, _ = mi.eamc_traces(big_cfg, threads=16)
         e10k = m.Eamc(desc, big_cfg.N, 4)
         e10k.load(tr10k)
         sweep = []
-        for Bq in (1, 2, 4, 8, 16):
+        for Bq in ((1, 2, 4, 8, 16) if args.batch_sweep else (1, 4, 16)):
             rq = [mi.make_request(cfg, 200 + b, decode=1) for b in range(Bq)]
             q = dev(np.stack([r.prefill_eam for r in rq]).astype(np.int32))
             xb = dev(np.stack([r.x[0, 0] for r in rq]))
@@ -444,9 +447,10 @@ def main():
         e10k.close()
 
     # ------------------------------------------------ optional: the prefill iteration on this shape
-    if args.prefill and cfg.wdtype == "bf16" and H <= 4096:
+    # (the default run on C2 carries a short form of it: 512 and 2,048 tokens)
+    if (args.prefill or short_legs) and cfg.wdtype == "bf16" and H <= 4096:
         rows = []
-        for n_tok in (64, 128, 256, 512, 1024, 2048):
+        for n_tok in ((64, 128, 256, 512, 1024, 2048) if args.prefill else (512, 2048)):
             if n_tok > args.prefill_max:
                 break
             rng = np.random.default_rng(n_tok)

@@ -19,6 +19,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <type_traits>
+
 #include "kernels.hpp"
 #include "topk.hpp"
 #include "wtypes.hpp"
@@ -266,8 +268,9 @@ struct MmArgs {
     float* yc;      // [rows][H]
     int H, I;
     int32_t* flags;
-    int n_ub;  // gate/up: blocks of 64 units;  down: blocks of 512 columns
+    int n_ub;  // gate/up: blocks of 64 (wide kernel: 128) units;  down: blocks of 512 columns
     int n_cb;
+    int dn_split;  // the down kernel takes an item in this many parts of TM tokens (items of the wide tile: 2)
 };
 
 // Workgroups are handed to the chip's 8 XCDs in turn, and every XCD has an L2 of its own.  The
@@ -282,6 +285,15 @@ __device__ __forceinline__ bool xcd_work(int n_blocks, int* item, int* block) {
     *item = w / per;
     *block = xcd + kXcds * (w % per);
     return *block < n_blocks;
+}
+
+// The other way round, for the kernel whose workgroups each stream weights of their own: all output
+// blocks of an item on one XCD, so that the item's input rows come through that L2 once.
+__device__ __forceinline__ bool xcd_item_work(int n_blocks, int* item, int* block) {
+    const int v = blockIdx.x, xcd = v % kXcds, w = v / kXcds;
+    *block = w % n_blocks;
+    *item = xcd + kXcds * (w / n_blocks);
+    return true;
 }
 
 __device__ __forceinline__ bf16x8 ld_bf16x8(const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
@@ -415,6 +427,209 @@ __global__ void __launch_bounds__(TM * 4) prefill_gateup_kernel(MmArgs a) {
     }
 }
 
+// 3a, long prompts.  Above ~128 tokens per expert the layer is bound by how fast a compute unit can
+// pull its operands in.  Measured on this part: 16-byte loads into registers deliver ~16 bytes per
+// clock and CU even from L2 (9.5 TB/s over the chip, whatever the depth); loads that go from global
+// memory straight into LDS ~3.5 times that, but by the cache line - a 64-byte piece of a line costs
+// as much as the whole 128 bytes; a stream that misses L2 ~20 GB/s per CU with 64 KiB in flight.
+// So this kernel gives every workgroup a weight stream of its own - 128 units (gate and up: 256
+// rows) of one expert - and as many of the expert's tokens as the accumulators hold (256), and
+// brings both operands in with loads straight into LDS, one cache line (64 k-values) of every row
+// per stage.  The weights come from HBM and the inputs mostly from L2, and a wavefront's loads
+// complete in order, so the two are loaded by different wavefronts into rings of their own:
+// wavefronts 0..3 keep two stages of weight rows in flight (a ring of three), wavefronts 4..7 one
+// stage of input rows (a ring of two); all unit blocks of an item run on one XCD, so the item's
+// input rows pass through that L2 once.  Chunk c of ring row r sits at chunk position
+// c ^ ((r >> 1) % 8): the sixteen lanes that read one operand (sixteen consecutive rows, the same
+// chunk) then touch all 64 banks once.  A wavefront owns 32 units (two 16-row blocks of gate, two of
+// up) x 128 tokens (the even or the odd 16-token blocks of the item, so that a partly filled item
+// leaves both halves of the workgroup the same work; blocks without tokens are neither read nor
+// multiplied), 32 accumulator tiles, and multiplies a stage in two halves of 32 k-values.
+constexpr int kTileTokWide = 256;
+constexpr int kWdUnits = 128;   // intermediate units per workgroup
+constexpr int kWdKS = 64;       // k-values per stage: 128 bytes of a row
+constexpr int kWdStagesW = 3;   // ring of weight stages
+constexpr int kWdStagesX = 2;   // ring of input stages
+constexpr int kWdThreads = 512;
+constexpr int kWdStageElems = 256 * kWdKS;  // a stage of either ring: 256 rows
+__device__ __forceinline__ int wd_pos(int row, int chunk) { return row * kWdKS + ((chunk ^ ((row >> 1) & 7)) << 3); }
+
+// A 16-byte load per lane that goes from global memory straight into LDS: the wavefront's 64 pieces
+// land side by side, 1 KiB from `lds_addr` on (an LDS byte address, the same in every lane).  The
+// load counts as a vector memory operation of the wavefront (vmcnt); nothing says when the data is
+// in LDS but a later wait on that counter.  m0 (the LDS base of such loads) is a register the
+// compiler reserves and sets itself right before each of its own uses, so writing it here is safe.
+__device__ __forceinline__ void load16_to_lds(const void* gsrc, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gsrc) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+// waits until at most `stages` * 8 of this wavefront's vector memory operations are outstanding
+__device__ __forceinline__ void wait_but_stages(int stages) {
+    // s_waitcnt: vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima
+    if (stages >= 2)
+        __builtin_amdgcn_s_waitcnt(0x4f70);  // 16
+    else if (stages == 1)
+        __builtin_amdgcn_s_waitcnt(0x0f78);  // 8
+    else
+        __builtin_amdgcn_s_waitcnt(0x0f70);
+}
+
+__global__ void __launch_bounds__(kWdThreads, 2) prefill_gateup_wide_kernel(MmArgs a) {
+    constexpr int TM = kTileTokWide;
+    constexpr int NLD = 8;        // loads per wavefront and stage, 8 rows each: four wavefronts fill 256 rows
+    constexpr int NTB = TM / 32;  // 16-token blocks per wavefront: 8
+    static_assert(2 * kWdUnits == 256 && TM == 256 && kWdThreads == 8 * kWave && kWdKS == 64, "four wavefronts load 256 rows of 128 bytes");
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    uint16_t* ring_w = reinterpret_cast<uint16_t*>(smem_raw);        // [kWdStagesW][256][64]
+    uint16_t* ring_x = ring_w + (size_t)kWdStagesW * kWdStageElems;  // [kWdStagesX][256][64]
+    int item, ub;
+    if (!xcd_item_work(a.n_ub, &item, &ub)) return;
+    if (item >= a.meta[0]) return;
+    const PItem it = a.items[item];
+    if (it.slot < 0 || it.slot >= a.n_slots_total) return;  // the down kernel writes the zeros and raises the flag
+    const int H = a.H, I = a.I;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int lrow = lane & 15, lgrp = lane >> 4;
+    const int rg = wv & 3, th = wv >> 2;  // unit group (32 units); the even or the odd 16-token blocks
+    // 16-token blocks of this wavefront that hold tokens of the item (blocks th, th + 2, ...)
+    const int n_live = max(0, ((it.ntok + 15) / 16 - th + 1) / 2);
+    const bool loads_w = wv < 4;  // else the inputs
+    const uint16_t* wslot = a.pool + (size_t)it.slot * a.slot_elems;
+    const int u_wg = ub * kWdUnits;
+
+    // load j of this wavefront fills rows 8 * (4 * j + wv % 4) .. + 8 of a stage of its ring; this
+    // lane brings chunk position lane % 8 of row .. + lane / 8.  Weight rows 0..127 are gate rows,
+    // 128..255 up rows.  Units past I repeat unit I - 1 and tokens past the item repeat its first
+    // token: what they yield is never stored.
+    const uint16_t* src[NLD];
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+        const int r = 8 * (4 * j + (wv & 3)) + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        if (loads_w) {
+            const int u = min(u_wg + (r & (kWdUnits - 1)), I - 1);
+            src[j] = wslot + (size_t)u * 3 * H + (r >= kWdUnits ? H : 0) + c * 8;
+        } else {
+            const int t = r < it.ntok ? r : 0;
+            const int tok = it.first_tok >= 0 ? it.first_tok + t : a.perm[it.list_off + t];
+            src[j] = a.X + (size_t)tok * H + c * 8;
+        }
+    }
+    const int depth = loads_w ? kWdStagesW : kWdStagesX;  // uniform over the wavefront
+    const uint32_t my_ring = lds_address(loads_w ? ring_w : ring_x) + (uint32_t)(8 * (wv & 3)) * (kWdKS * 2);
+    auto issue = [&](int s) {
+        const uint32_t st = my_ring + (uint32_t)(s % depth) * (kWdStageElems * 2);
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) load16_to_lds(src[j] + (size_t)s * kWdKS, st + (uint32_t)(32 * j) * (kWdKS * 2));
+    };
+
+    f32x4 G[2][NTB], U[2][NTB];
+#pragma unroll
+    for (int bl = 0; bl < 2; ++bl)
+#pragma unroll
+        for (int tb = 0; tb < NTB; ++tb) G[bl][tb] = U[bl][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // The operands of a half stage are read into registers one half step before they are multiplied,
+    // so the LDS reads of half step t + 1 run beside the matrix instructions of half step t, and a
+    // ring slot is free again as soon as every wavefront has read both its halves.
+    struct Ops {
+        bf16x8 ag[2], au[2], b[NTB];
+    };
+    // NT: token blocks of this wavefront that are read and multiplied (the live ones, rounded up to even)
+    auto read_ops = [&](int t, Ops& o, auto nt_tag) {  // half step t: stage t / 2, chunks 4 * (t % 2) .. + 4
+        constexpr int NT = decltype(nt_tag)::value;
+        const int s = t >> 1, c = 4 * (t & 1) + lgrp;
+        const uint16_t* sw = ring_w + (size_t)(s % kWdStagesW) * kWdStageElems;
+        const uint16_t* sx = ring_x + (size_t)(s % kWdStagesX) * kWdStageElems;
+#pragma unroll
+        for (int bl = 0; bl < 2; ++bl) {
+            const int r = 32 * rg + 16 * bl + lrow;
+            o.ag[bl] = ld_bf16x8(sw + wd_pos(r, c));
+            o.au[bl] = ld_bf16x8(sw + wd_pos(kWdUnits + r, c));
+        }
+#pragma unroll
+        for (int tb = 0; tb < NT; ++tb) o.b[tb] = ld_bf16x8(sx + wd_pos((2 * tb + th) * 16 + lrow, c));
+    };
+    auto multiply = [&](const Ops& o, auto nt_tag) {
+        constexpr int NT = decltype(nt_tag)::value;
+#pragma unroll
+        for (int tb = 0; tb < NT; ++tb)
+#pragma unroll
+            for (int bl = 0; bl < 2; ++bl) {
+                G[bl][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o.ag[bl], o.b[tb], G[bl][tb], 0, 0, 0);
+                U[bl][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o.au[bl], o.b[tb], U[bl][tb], 0, 0, 0);
+            }
+    };
+    const int n_slices = H / kWdKS;   // H is a multiple of 128: at least two stages
+    const int n_half = 2 * n_slices;  // at least four half steps, an even number
+    for (int s = 0; s < depth; ++s)
+        if (s < n_slices) issue(s);
+    wait_but_stages(min(n_slices, depth) - 1);  // stage 0 has landed
+    __syncthreads();
+    // Half step t multiplies half t and reads half t + 1.  When that is the first half of stage s + 1
+    // (t odd), the stage has landed for all once the wavefronts that load have seen their loads of it
+    // complete and the barrier is passed; by then every wavefront has read both halves of stage s,
+    // whose ring slots take stages s + 3 (weights) and s + 2 (inputs).  The loop is written once for
+    // each count of token blocks a wavefront may have, and its last half step is peeled, so that no
+    // path through a half step skips its reads.
+    auto run = [&](auto nt_tag) {
+        constexpr int NT = decltype(nt_tag)::value;
+        Ops opA, opB;
+        if constexpr (NT > 0) read_ops(0, opA, nt_tag);
+        auto half = [&](int t, const Ops& cur, Ops& nxt, bool enters_stage) {
+            if (enters_stage) {
+                const int s = t >> 1;
+                wait_but_stages(min(n_slices - 2 - s, depth - 2));  // stages younger than s + 1 that have been issued
+                __syncthreads();
+                if (s + depth < n_slices) issue(s + depth);
+            }
+            if constexpr (NT > 0) {
+                read_ops(t + 1, nxt, nt_tag);
+                multiply(cur, nt_tag);
+            }
+        };
+        for (int t = 0; t + 2 < n_half; t += 2) {
+            half(t, opA, opB, false);
+            half(t + 1, opB, opA, true);
+        }
+        half(n_half - 2, opA, opB, false);
+        if constexpr (NT > 0) multiply(opB, nt_tag);
+    };
+    switch ((n_live + 1) / 2) {  // uniform over the wavefront
+        case 0: run(std::integral_constant<int, 0>{}); break;
+        case 1: run(std::integral_constant<int, 2>{}); break;
+        case 2: run(std::integral_constant<int, 4>{}); break;
+        case 3: run(std::integral_constant<int, 6>{}); break;
+        default: run(std::integral_constant<int, 8>{}); break;
+    }
+    // D[unit 4*lgrp + v][token lrow] -> activation, bf16, act[row][unit]
+    const bool packed = (I & 3) == 0;
+#pragma unroll
+    for (int tb = 0; tb < NTB; ++tb) {
+        const int tok = (2 * tb + th) * 16 + lrow;
+        if (tok >= it.ntok) continue;
+        const float gw = it.first_tok >= 0 ? 1.0f : a.pgate[it.list_off + tok];
+        uint16_t* dst_row = a.act + (size_t)(it.row0 + tok) * I;
+#pragma unroll
+        for (int bl = 0; bl < 2; ++bl) {
+            const int u0 = u_wg + 32 * rg + 16 * bl + lgrp * 4;
+            uint32_t h[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) h[v] = bf16_bits(silu_f(G[bl][tb][v]) * U[bl][tb][v] * gw);
+            if (packed && u0 + 3 < I) {
+                *reinterpret_cast<uint2*>(dst_row + u0) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (u0 + v < I) dst_row[u0 + v] = (uint16_t)h[v];
+            }
+        }
+    }
+}
+
 // 3b.  grid (ceil(H / 512), items).  D = A B with A = 16 tokens x 32 units from LDS, B = 32 units x
 // 16 columns of W_down.  The slot stores W_down unit-major, so a lane loads eight units x eight
 // columns and transposes them in registers into eight operands of eight units each; the column
@@ -425,9 +640,12 @@ __global__ void __launch_bounds__(TM * 4, 2) prefill_down_kernel(MmArgs a) {  //
     constexpr int kMmThreads = TM * 4;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     uint16_t* As = reinterpret_cast<uint16_t*>(smem_raw);  // [2][TM][128], chunks swizzled
-    const int item = blockIdx.y;
+    const int item = blockIdx.y / a.dn_split, part = blockIdx.y % a.dn_split;
     if (item >= a.meta[0]) return;
-    const PItem it = a.items[item];
+    PItem it = a.items[item];
+    it.row0 += part * TM;  // this workgroup's TM tokens of the item
+    it.ntok = min(TM, it.ntok - part * TM);
+    if (it.ntok <= 0) return;
     const int H = a.H, I = a.I;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -600,21 +818,33 @@ int tile_tokens(const moei_model_desc& d, int n) {
     const char* v = getenv("MOEI_PREFILL_TILE");
     if (v && atoi(v) == kTileTok) return kTileTok;
     if (v && atoi(v) == kTileTokBig) return kTileTokBig;
+    if (v && atoi(v) == kTileTokWide) return kTileTokWide;
+    if ((long)n * d.k > (long)kTileTokBig * d.E) return kTileTokWide;
     return (long)n * d.k > (long)kTileTok * d.E ? kTileTokBig : kTileTok;
 }
 
 template <int TM>
-int launch_mm(const moei_model_desc& d, const MmArgs& a, int max_items, hipStream_t s) {
-    const size_t gu_smem = (size_t)(TM + 2 * kGuUnits) * kTileK * 2;
+int launch_mm(const moei_model_desc& d, MmArgs a, int max_items, hipStream_t s) {
     const size_t dn_smem = (size_t)2 * TM * kTileK * 2;
-    int rc = pf_allow_lds(prefill_gateup_kernel<TM>, gu_smem);
+    int rc = pf_allow_lds(prefill_down_kernel<TM>, dn_smem);
     if (rc) return rc;
-    rc = pf_allow_lds(prefill_down_kernel<TM>, dn_smem);
-    if (rc) return rc;
-    const int gu_per = (a.n_ub + kXcds - 1) / kXcds;
-    launch(K_PF_GATEUP, prefill_gateup_kernel<TM>, dim3(kXcds * gu_per * max_items), dim3(TM * 4), gu_smem, s, a);
+    if (a.dn_split == 1) {
+        const size_t gu_smem = (size_t)(TM + 2 * kGuUnits) * kTileK * 2;
+        rc = pf_allow_lds(prefill_gateup_kernel<TM>, gu_smem);
+        if (rc) return rc;
+        a.n_ub = (d.I + kGuUnits - 1) / kGuUnits;
+        const int gu_per = (a.n_ub + kXcds - 1) / kXcds;
+        launch(K_PF_GATEUP, prefill_gateup_kernel<TM>, dim3(kXcds * gu_per * max_items), dim3(TM * 4), gu_smem, s, a);
+    } else {  // items of the wide tile: TM is the down kernel's share of one
+        const size_t gu_smem = (size_t)(kWdStagesW + kWdStagesX) * kWdStageElems * 2;
+        rc = pf_allow_lds(prefill_gateup_wide_kernel, gu_smem);
+        if (rc) return rc;
+        a.n_ub = (d.I + kWdUnits - 1) / kWdUnits;
+        const int item_rounds = (max_items + kXcds - 1) / kXcds;
+        launch(K_PF_GATEUP, prefill_gateup_wide_kernel, dim3(kXcds * a.n_ub * item_rounds), dim3(kWdThreads), gu_smem, s, a);
+    }
     MOEI_LAUNCH_CHECK();
-    launch(K_PF_DOWN, prefill_down_kernel<TM>, dim3((d.H + kDnCols - 1) / kDnCols, max_items), dim3(TM * 4), dn_smem, s, a);
+    launch(K_PF_DOWN, prefill_down_kernel<TM>, dim3((d.H + kDnCols - 1) / kDnCols, max_items * a.dn_split), dim3(TM * 4), dn_smem, s, a);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
 }
@@ -651,9 +881,9 @@ int launch_prefill(const moei_model_desc& d, const PrefillScratch& ps, const voi
     const int max_items = max_items_for(d, n, tm);
     MmArgs a{reinterpret_cast<const uint16_t*>(d_pool), slot_elems, n_slots_total,
              reinterpret_cast<const PItem*>(ps.d_items), ps.d_meta, reinterpret_cast<const uint16_t*>(d_X), ps.d_perm,
-             ps.d_pgate, ps.d_act, ps.d_yc, d.H, d.I, d_flags, (d.I + kGuUnits - 1) / kGuUnits,
-             (d.H + kDnCols - 1) / kDnCols};
-    rc = tm == kTileTokBig ? launch_mm<kTileTokBig>(d, a, max_items, s) : launch_mm<kTileTok>(d, a, max_items, s);
+             ps.d_pgate, ps.d_act, ps.d_yc, d.H, d.I, d_flags, 0, (d.H + kDnCols - 1) / kDnCols,
+             tm == kTileTokWide ? 2 : 1};
+    rc = tm == kTileTok ? launch_mm<kTileTok>(d, a, max_items, s) : launch_mm<kTileTokBig>(d, a, max_items, s);
     if (rc) return rc;
     launch(K_PF_REDUCE, prefill_reduce_kernel, dim3(n), dim3(256), 0, s, (const float*)ps.d_yc,
            (const int32_t*)ps.d_where, n, d.k, d.n_shared, d.H, d_Y);

@@ -131,6 +131,21 @@ def test_prefill_ragged_rows_and_small_expert_counts(m):
     _check(_prefill_case(m, cfg, 300, layer=0))
 
 
+def test_prefill_long_prompts_with_256_token_items(m):
+    # n k > 128 E: the items hold up to 256 tokens and the gate/up products run in the kernel that
+    # fills its LDS ring straight from global memory.  Mixtral structure, I = 72 (less than one
+    # 128-unit block); then top-2 of 8 with two shared experts, I = 200 (a ragged second block),
+    # H = 384 (twelve 32-wide stages), most experts with a full item and a ragged one
+    cfg = mi.get_config("C3").scaled(L=2, H=512, I=72, N=8, prompt=16)
+    _check(_prefill_case(m, cfg, 700, layer=1))
+    cfg = mi.get_config("C2").scaled(L=2, E=8, k=2, H=384, I=200, N=8, prompt=16)
+    _check(_prefill_case(m, cfg, 1100, layer=0))
+    # an item of exactly 256 tokens and its neighbours (one expert, every token picks it)
+    cfg = mi.get_config("C3").scaled(L=1, E=2, k=2, H=256, I=128, N=8, prompt=16)
+    for n in (255, 256, 257):
+        _check(_prefill_case(m, cfg, n, layer=0))
+
+
 def test_prefill_wide_rows(m):
     cfg = mi.get_config("C3").scaled(L=1, H=4096, I=160, N=8, prompt=16)
     _check(_prefill_case(m, cfg, 40, layer=0, n_unique=4))
@@ -148,6 +163,15 @@ def test_prefill_full_width_long_prompt_with_128_token_items(m):
     # tokens; every token's picks, gate weights and the EAM in full, the outputs of 40 sampled tokens
     cfg = mi.get_config("C2").scaled(L=1, N=8, prompt=16)
     o = _prefill_case(m, cfg, 1024, layer=0, n_unique=16, sample=40)
+    assert o["finite"]
+    _check(o)
+
+
+def test_prefill_full_width_2048_token_prompt_with_256_token_items(m):
+    # configuration 2 at full width with a 2,048-token prompt: n k > 128 E, items of up to 256 tokens;
+    # every token's picks, gate weights and the EAM in full, the outputs of 40 sampled tokens
+    cfg = mi.get_config("C2").scaled(L=1, N=8, prompt=16)
+    o = _prefill_case(m, cfg, 2048, layer=0, n_unique=16, sample=40)
     assert o["finite"]
     _check(o)
 
