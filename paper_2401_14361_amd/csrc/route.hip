@@ -3,6 +3,8 @@
 // Every token goes to k of a layer's E experts (Sec. 2 of the paper); each such pick
 // adds one to the request's Expert Activation Matrix (Sec. 4.3).  One wavefront serves
 // one token: the E logits sit in LDS and every expert's rank is counted against them.
+#include <type_traits>
+
 #include "kernels.hpp"
 #include "topk.hpp"
 #include "wtypes.hpp"
@@ -149,26 +151,34 @@ __global__ void __launch_bounds__(kRouteWaves * kWave) route_fused_kernel(RouteF
         const WT* x = reinterpret_cast<const WT*>(a.x);
         float acc = 0.f;
         if (a.vec_ok) {
-            // four chunks' loads go out together (one round trip for rows up to 4 x 64 vectors); the
-            // sum still runs over the chunks in ascending order
+            // the chunks' loads go out together, four at a time for rows of up to 4 x 64 vectors, else
+            // ten (one round trip for 5,120 bf16 values); the sum still runs over the chunks in
+            // ascending order
             constexpr int CW = kWave * V::N;
-            for (int c0 = lane * V::N; c0 < a.H; c0 += 4 * CW) {
-                typename V::raw wr[4], xv[4];
+            auto row_dot = [&](auto nq_tag) {
+                constexpr int NQ = decltype(nq_tag)::value;
+                for (int c0 = lane * V::N; c0 < a.H; c0 += NQ * CW) {
+                    typename V::raw wr[NQ], xv[NQ];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int c = c0 + q * CW < a.H ? c0 + q * CW : c0;
-                    wr[q] = V::load(row + c);
-                    xv[q] = V::load(x + c);
-                }
+                    for (int q = 0; q < NQ; ++q) {
+                        const int c = c0 + q * CW < a.H ? c0 + q * CW : c0;
+                        wr[q] = V::load(row + c);
+                        xv[q] = V::load(x + c);
+                    }
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (c0 + q * CW < a.H) {
-                        float xf[V::N];
-                        V::unpack(xv[q], xf);
-                        acc = V::dot(wr[q], xf, acc);
+                    for (int q = 0; q < NQ; ++q) {
+                        if (c0 + q * CW < a.H) {
+                            float xf[V::N];
+                            V::unpack(xv[q], xf);
+                            acc = V::dot(wr[q], xf, acc);
+                        }
                     }
                 }
-            }
+            };
+            if (a.H <= 4 * CW)
+                row_dot(std::integral_constant<int, 4>{});
+            else
+                row_dot(std::integral_constant<int, 10>{});
         } else {
             for (int c = lane; c < a.H; c += kWave) acc = __builtin_fmaf(V::one(row + c), V::one(x + c), acc);
         }
