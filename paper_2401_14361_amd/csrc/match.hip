@@ -146,6 +146,38 @@ __device__ __forceinline__ u64 group_sum_u64(u64 v, int group) {
     return v;
 }
 
+// The same for NB = 8 or 16 values per lane and groups of 16 lanes, at a quarter of the additions: at
+// each level of the exchange a lane keeps one half of its values and hands the other half to its
+// partner, which keeps that half (the partner at a level differs in that level's bit of the lane
+// number; the partners are those of the patterns above).  Lane i of a group ends with the group's sum
+// of value number i % NB.
+template <int NB>
+__device__ __forceinline__ u64 row16_sum_scatter(u64 (&v)[NB], int lane) {
+    static_assert(NB == 8 || NB == 16, "eight or sixteen values");
+#define MOEI_DPP_U64(x, ctrl) (((u64)MOEI_DPP_U32((unsigned)((x) >> 32), ctrl) << 32) | MOEI_DPP_U32((unsigned)(x), ctrl))
+#define MOEI_SCATTER_LEVEL(n, bit, ctrl)                              \
+    {                                                                 \
+        const bool up = (lane & (bit)) != 0;                          \
+        _Pragma("unroll") for (int k = 0; k < (n); ++k) {             \
+            const u64 keep = up ? v[k + (n)] : v[k];                  \
+            const u64 send = up ? v[k] : v[k + (n)];                  \
+            v[k] = keep + MOEI_DPP_U64(send, ctrl);                   \
+        }                                                             \
+    }
+    if constexpr (NB == 16) {
+        MOEI_SCATTER_LEVEL(8, 8, 0x140)  // row_mirror
+    } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) MOEI_GROUP_STEP(v[k], 0x140);
+    }
+    MOEI_SCATTER_LEVEL(4, 4, 0x141)  // row_half_mirror
+    MOEI_SCATTER_LEVEL(2, 2, 0x4E)   // quad_perm [2,3,0,1]
+    MOEI_SCATTER_LEVEL(1, 1, 0xB1)   // quad_perm [1,0,3,2]
+#undef MOEI_SCATTER_LEVEL
+#undef MOEI_DPP_U64
+    return v[0];
+}
+
 // grid (tiles, layer splits, query groups).  Thread t owns vectors p = j*256 + t (j < J) of its
 // tile; vector p belongs to trace p / rowV of the tile in EVERY layer, so the accumulators
 // live in registers across the whole layer walk.  A workgroup serves NB queries at once:
@@ -229,7 +261,19 @@ __global__ void __launch_bounds__(kDotThreads) eamc_dot_kernel(DotArgs a) {
             }
         }
     }
-    if (a.lane_rows) {
+    if (a.lane_rows && a.rowV == 16 && NB >= 8) {
+        // 16 lanes per trace row and 8 or 16 queries: every lane ends with one query's row sum and stores it
+        constexpr int NBS = NB >= 8 ? NB : 8;
+        const int lane = tid & (kWave - 1);
+#pragma unroll
+        for (int j = 0; j < J; ++j) {
+            u64 v[NBS];
+#pragma unroll
+            for (int b = 0; b < NBS; ++b) v[b] = (b < NB && valid[j]) ? acc[j][b < NB ? b : 0] : 0;
+            const u64 t = row16_sum_scatter<NBS>(v, lane);
+            if (valid[j] && (NB == 16 || (lane & 8) == 0)) rowsum[(lane & (NB - 1)) * a.TN + row[j]] = t;
+        }
+    } else if (a.lane_rows) {
         const bool first = (tid & (a.rowV - 1)) == 0;
 #pragma unroll
         for (int j = 0; j < J; ++j)
