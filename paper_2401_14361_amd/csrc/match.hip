@@ -103,27 +103,28 @@ struct CellVec<uint16_t, 1> {
     }
 };
 
-// The query rows of a workgroup's layers, for its NB queries, into LDS: sixteen independent loads in
-// flight per thread instead of one trip to memory per element.
+// The query rows of a workgroup's layers, for its NB queries, into LDS.  A query's cells of these
+// layers are contiguous: each thread copies every 256th of them, query after query, with no index
+// arithmetic beyond an addition (an index split by division costs more instructions here than the
+// scan's own multiply-adds), the loads of all queries for several rounds in flight together.
 template <int NB>
 __device__ __forceinline__ void stage_queries(const int32_t* __restrict__ q, int B, int L, int E, int b0, int l0, int nl,
                                               int q_stride, int32_t* qs) {
     const int per = nl * E;  // cells per query
-    const int total = NB * per;
-    for (int i0 = 0; i0 < total; i0 += 16 * kDotThreads) {
-        int32_t v[16];
+    constexpr int R = NB >= 16 ? 3 : (NB >= 8 ? 6 : (NB >= 4 ? 12 : 16));  // rounds whose loads go out together
+    for (int c0 = (int)threadIdx.x; c0 < per; c0 += R * kDotThreads) {
+        int32_t v[NB][R];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int i = i0 + r * kDotThreads + (int)threadIdx.x;
-            const int b = i / per, c = i - b * per;
-            v[r] = (i < total && b0 + b < B) ? q[((size_t)(b0 + b) * L + l0) * E + c] : 0;
+        for (int b = 0; b < NB; ++b) {
+            const int32_t* src = q + ((size_t)min(b0 + b, B - 1) * L + l0) * E;  // past B: a copy, stored as zeros
+#pragma unroll
+            for (int r = 0; r < R; ++r) v[b][r] = c0 + r * kDotThreads < per ? src[c0 + r * kDotThreads] : 0;
         }
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int i = i0 + r * kDotThreads + (int)threadIdx.x;
-            const int b = i / per, c = i - b * per;
-            if (i < total) qs[b * q_stride + c] = v[r];
-        }
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (c0 + r * kDotThreads < per) qs[b * q_stride + c0 + r * kDotThreads] = b0 + b < B ? v[b][r] : 0;
     }
 }
 
