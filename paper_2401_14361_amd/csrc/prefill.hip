@@ -520,10 +520,14 @@ __global__ void __launch_bounds__(kWdThreads, 2) prefill_gateup_wide_kernel(MmAr
     }
     const int depth = loads_w ? kWdStagesW : kWdStagesX;  // uniform over the wavefront
     const uint32_t my_ring = lds_address(loads_w ? ring_w : ring_x) + (uint32_t)(8 * (wv & 3)) * (kWdKS * 2);
+    // input rows past the item's tokens are not loaded (what the ring holds there is multiplied at most
+    // within a token block that also holds tokens, and never stored): this wavefront's loads j < n_ld
+    const int n_ld = loads_w ? NLD : min(NLD, max(0, (it.ntok - 8 * (wv & 3) + 31) / 32));
     auto issue = [&](int s) {
         const uint32_t st = my_ring + (uint32_t)(s % depth) * (kWdStageElems * 2);
 #pragma unroll
-        for (int j = 0; j < NLD; ++j) load16_to_lds(src[j] + (size_t)s * kWdKS, st + (uint32_t)(32 * j) * (kWdKS * 2));
+        for (int j = 0; j < NLD; ++j)
+            if (j < n_ld) load16_to_lds(src[j] + (size_t)s * kWdKS, st + (uint32_t)(32 * j) * (kWdKS * 2));
     };
 
     f32x4 G[2][NTB], U[2][NTB];
@@ -567,7 +571,11 @@ __global__ void __launch_bounds__(kWdThreads, 2) prefill_gateup_wide_kernel(MmAr
     const int n_half = 2 * n_slices;  // at least four half steps, an even number
     for (int s = 0; s < depth; ++s)
         if (s < n_slices) issue(s);
-    wait_but_stages(min(n_slices, depth) - 1);  // stage 0 has landed
+    static_assert(kWdStagesX == 2, "the wavefronts that load inputs wait for all their loads: their count per stage varies");
+    if (loads_w)
+        wait_but_stages(min(n_slices, depth) - 1);  // stage 0 has landed
+    else if (n_ld > 0)
+        wait_but_stages(0);  // (stage 1's loads with it)
     __syncthreads();
     // Half step t multiplies half t and reads half t + 1.  When that is the first half of stage s + 1
     // (t odd), the stage has landed for all once the wavefronts that load have seen their loads of it
@@ -582,7 +590,7 @@ __global__ void __launch_bounds__(kWdThreads, 2) prefill_gateup_wide_kernel(MmAr
         auto half = [&](int t, const Ops& cur, Ops& nxt, bool enters_stage) {
             if (enters_stage) {
                 const int s = t >> 1;
-                wait_but_stages(min(n_slices - 2 - s, depth - 2));  // stages younger than s + 1 that have been issued
+                wait_but_stages(loads_w ? min(n_slices - 2 - s, depth - 2) : 0);  // stages younger than s + 1 that have been issued
                 __syncthreads();
                 if (s + depth < n_slices) issue(s + depth);
             }
@@ -774,16 +782,18 @@ constexpr int kDwStagesW = 4;
 constexpr int kDwStagesA = 3;
 constexpr int kDwStageElemsW = kDwKS * kDwCols;       // 64 rows of 128 columns: 16 KiB
 constexpr int kDwStageElemsA = kTileTokWide * kDwKS;  // 256 rows of 64 units: 32 KiB
-// waits until at most `n` of this wavefront's vector memory operations are outstanding (n a multiple of 4, <= 20)
+// waits until at most `n` of this wavefront's vector memory operations are outstanding (n <= 20)
 __device__ __forceinline__ void wait_vm(int n) {
+    // s_waitcnt: vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima
+#define MOEI_WAIT_CASE(v) case v: __builtin_amdgcn_s_waitcnt(0x0f70 | ((v) & 15) | (((v) >> 4) << 14)); break;
     switch (n) {
-        case 0: __builtin_amdgcn_s_waitcnt(0x0f70); break;
-        case 4: __builtin_amdgcn_s_waitcnt(0x0f74); break;
-        case 8: __builtin_amdgcn_s_waitcnt(0x0f78); break;
-        case 12: __builtin_amdgcn_s_waitcnt(0x0f7c); break;
-        case 16: __builtin_amdgcn_s_waitcnt(0x4f70); break;
+        MOEI_WAIT_CASE(0) MOEI_WAIT_CASE(1) MOEI_WAIT_CASE(2) MOEI_WAIT_CASE(3) MOEI_WAIT_CASE(4) MOEI_WAIT_CASE(5)
+        MOEI_WAIT_CASE(6) MOEI_WAIT_CASE(7) MOEI_WAIT_CASE(8) MOEI_WAIT_CASE(9) MOEI_WAIT_CASE(10) MOEI_WAIT_CASE(11)
+        MOEI_WAIT_CASE(12) MOEI_WAIT_CASE(13) MOEI_WAIT_CASE(14) MOEI_WAIT_CASE(15) MOEI_WAIT_CASE(16) MOEI_WAIT_CASE(17)
+        MOEI_WAIT_CASE(18) MOEI_WAIT_CASE(19)
         default: __builtin_amdgcn_s_waitcnt(0x4f74); break;  // 20
     }
+#undef MOEI_WAIT_CASE
 }
 
 __global__ void __launch_bounds__(kWdThreads, 2) prefill_down_wide_kernel(MmArgs a) {
@@ -827,7 +837,9 @@ __global__ void __launch_bounds__(kWdThreads, 2) prefill_down_wide_kernel(MmArgs
         src0 = a.act + (size_t)it.row0 * I + c * 8;
     }
     const int depth = loads_w ? kDwStagesW : kDwStagesA;  // uniform over the wavefront
-    const int nld = loads_w ? 4 : 8;                      // loads per stage of this wavefront
+    // loads per stage of this wavefront; activation rows past the item's tokens are not loaded (what the
+    // ring holds there is multiplied at most within a token block that also holds tokens, never stored)
+    const int nld = loads_w ? 4 : min(8, max(0, (it.ntok - 8 * (wv & 3) + 31) / 32));
     const uint32_t my_ring = lds_address(loads_w ? ring_w : ring_a) + (uint32_t)(wv & 3) * 1024;
     auto issue = [&](int s) {
         if (loads_w) {
@@ -840,7 +852,7 @@ __global__ void __launch_bounds__(kWdThreads, 2) prefill_down_wide_kernel(MmArgs
             const uint16_t* p = src0 + s * kDwKS;
 #pragma unroll
             for (int j = 0; j < 8; ++j)
-                load16_to_lds(p + (uint32_t)min(arow + 32 * j, it.ntok - 1) * (uint32_t)I, st + (uint32_t)j * 4096);
+                if (j < nld) load16_to_lds(p + (uint32_t)min(arow + 32 * j, it.ntok - 1) * (uint32_t)I, st + (uint32_t)j * 4096);
         }
     };
 
@@ -996,8 +1008,7 @@ int tile_tokens(const moei_model_desc& d, int n) {
     if (v && atoi(v) == kTileTok) return kTileTok;
     if (v && atoi(v) == kTileTokBig) return kTileTokBig;
     if (v && atoi(v) == kTileTokWide) return kTileTokWide;
-    if ((long)n * d.k > (long)kTileTokBig * d.E) return kTileTokWide;
-    return (long)n * d.k > (long)kTileTok * d.E ? kTileTokBig : kTileTok;
+    return (long)n * d.k > (long)kTileTok * d.E ? kTileTokWide : kTileTok;
 }
 
 template <int TM>

@@ -146,6 +146,18 @@ def test_prefill_long_prompts_with_256_token_items(m):
         _check(_prefill_case(m, cfg, n, layer=0))
 
 
+@pytest.mark.parametrize("tile", [64, 128, 256])
+def test_prefill_every_item_size_on_one_prompt(m, tile, monkeypatch):
+    # the item size is chosen from the prompt length; MOEI_PREFILL_TILE (read at every call) forces one, so
+    # that each pair of matrix kernels serves the same prompt: 64- and 128-token items through the
+    # kernels that stage through registers, 256-token items through the LDS-ring kernels (a prompt
+    # shorter than their tile: most of the input rows of an item are absent and are not loaded)
+    monkeypatch.setenv("MOEI_PREFILL_TILE", str(tile))
+    cfg = mi.get_config("C2").scaled(L=2, E=8, k=2, H=256, I=128, N=8, prompt=16)
+    _check(_prefill_case(m, cfg, 150, layer=1))
+    _check(_prefill_case(m, cfg, 9, layer=0))
+
+
 def test_prefill_wide_rows(m):
     cfg = mi.get_config("C3").scaled(L=1, H=4096, I=160, N=8, prompt=16)
     _check(_prefill_case(m, cfg, 40, layer=0, n_unique=4))
@@ -158,9 +170,10 @@ def test_prefill_full_width_deepseek_v2_lite_layer(m):
     _check(o)
 
 
-def test_prefill_full_width_long_prompt_with_128_token_items(m):
-    # configuration 2 at full width with a 1,024-token prompt: n k > 64 E, so the items hold up to 128
-    # tokens; every token's picks, gate weights and the EAM in full, the outputs of 40 sampled tokens
+def test_prefill_full_width_1024_token_prompt(m):
+    # configuration 2 at full width with a 1,024-token prompt: n k > 64 E, so the items hold up to 256
+    # tokens (96 on average: partly filled items); every token's picks, gate weights and the EAM in
+    # full, the outputs of 40 sampled tokens
     cfg = mi.get_config("C2").scaled(L=1, N=8, prompt=16)
     o = _prefill_case(m, cfg, 1024, layer=0, n_unique=16, sample=40)
     assert o["finite"]
