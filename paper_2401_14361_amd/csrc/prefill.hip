@@ -175,16 +175,19 @@ __global__ void __launch_bounds__(kGrpThreads) prefill_count_kernel(GroupArgsP g
 __global__ void __launch_bounds__(kGrpThreads) prefill_place_kernel(GroupArgsP g) {
     __shared__ int s_red[3][kGrpWaves];
     const int e = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    // tokens and items of the experts before this one, items of all experts
+    // tokens of the experts before this one (the grouped rows stay in expert order); items of the
+    // experts that come before it in the item list, which runs from the expert with the most tokens to the
+    // one with the fewest (equal counts: by index), so that the matrix kernels' longest workgroups start
+    // first; items of all experts
+    int my_c = 0;
+    for (int w = 0; w < kGrpWaves; ++w) my_c += g.cntw[e * kGrpWaves + w];
     int toks = 0, its = 0, its_all = 0;
     for (int f = tid; f < g.E; f += kGrpThreads) {
         int c = 0;
         for (int w = 0; w < kGrpWaves; ++w) c += g.cntw[f * kGrpWaves + w];
         const int ni = (c + g.TM - 1) / g.TM;
-        if (f < e) {
-            toks += c;
-            its += ni;
-        }
+        if (f < e) toks += c;
+        if (c > my_c || (c == my_c && f < e)) its += ni;
         its_all += ni;
     }
     toks = (int)wave_sum_u32_dpp((unsigned)toks);
@@ -222,13 +225,17 @@ __global__ void __launch_bounds__(kGrpThreads) prefill_place_kernel(GroupArgsP g
     }
     const int slot = g.slot_of_row[e];
     if (cnt > 0 && slot < 0 && tid == 0) atomicOr(g.flags, 2);
+    // the shared experts' items come first in the list: they are full, and the matrix kernels' grids
+    // start with the list's head, so the longest workgroups are not the last to start
+    const int tiles = (g.n + g.TM - 1) / g.TM;
+    const int n_sh_items = g.n_shared * tiles;
     for (int it = tid; it * g.TM < cnt; it += kGrpThreads)
-        g.items[ioff + it] = PItem{slot, min(g.TM, cnt - it * g.TM), off + it * g.TM, -1, off + it * g.TM, cnt <= g.TM};
+        g.items[n_sh_items + ioff + it] =
+            PItem{slot, min(g.TM, cnt - it * g.TM), off + it * g.TM, -1, off + it * g.TM, cnt <= g.TM};
     if (e == 0) {
-        const int tiles = (g.n + g.TM - 1) / g.TM;
-        for (int q = tid; q < g.n_shared * tiles; q += kGrpThreads) {
+        for (int q = tid; q < n_sh_items; q += kGrpThreads) {
             const int s = q / tiles, tile = q - s * tiles;
-            g.items[n_routed + q] =
+            g.items[q] =
                 PItem{g.shared_base + s, min(g.TM, g.n - tile * g.TM), 0, tile * g.TM, g.n * g.k + s * g.n + tile * g.TM,
                       tiles == 1};
         }
