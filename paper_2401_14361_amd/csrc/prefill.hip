@@ -143,8 +143,10 @@ struct GroupArgsP {
     int32_t* meta;  // [0] = items in all, [1] = routed items
     int32_t* cntw;  // [E][4] tokens that pick the expert, per wavefront range of the grouping kernels
     int32_t* flags;
+    int spread_shared;  // list the items so that all items of a shared expert fall on one XCD of the wide kernels
 };
 
+constexpr int kXcds = 8;  // workgroups are handed to the chip's 8 XCDs in turn
 constexpr int kGrpThreads = 256;
 constexpr int kGrpWaves = kGrpThreads / kWave;
 
@@ -226,16 +228,25 @@ __global__ void __launch_bounds__(kGrpThreads) prefill_place_kernel(GroupArgsP g
     const int slot = g.slot_of_row[e];
     if (cnt > 0 && slot < 0 && tid == 0) atomicOr(g.flags, 2);
     // the shared experts' items come first in the list: they are full, and the matrix kernels' grids
-    // start with the list's head, so the longest workgroups are not the last to start
+    // start with the list's head, so the longest workgroups are not the last to start.  For the wide
+    // kernels, which run item p on XCD p % 8, item `tile` of shared expert s sits at position
+    // s + 8 * tile instead (and the routed items fill the other positions in their order): all items of
+    // a shared expert then run on one XCD, several of them at a time, and its weights pass through
+    // that L2 once for them.  (Needs at most 8 shared experts and enough routed items to leave no gap.)
     const int tiles = (g.n + g.TM - 1) / g.TM;
     const int n_sh_items = g.n_shared * tiles;
-    for (int it = tid; it * g.TM < cnt; it += kGrpThreads)
-        g.items[n_sh_items + ioff + it] =
-            PItem{slot, min(g.TM, cnt - it * g.TM), off + it * g.TM, -1, off + it * g.TM, cnt <= g.TM};
+    const int free8 = kXcds - g.n_shared;  // routed positions per block of 8 among the first 8 * tiles
+    const bool spread = g.spread_shared && g.n_shared > 0 && g.n_shared <= kXcds && n_routed >= tiles * free8;
+    for (int it = tid; it * g.TM < cnt; it += kGrpThreads) {
+        const int r = ioff + it;  // number of this item among the routed ones
+        int p = n_sh_items + r;
+        if (spread && r < tiles * free8) p = kXcds * (r / free8) + g.n_shared + r % free8;
+        g.items[p] = PItem{slot, min(g.TM, cnt - it * g.TM), off + it * g.TM, -1, off + it * g.TM, cnt <= g.TM};
+    }
     if (e == 0) {
         for (int q = tid; q < n_sh_items; q += kGrpThreads) {
             const int s = q / tiles, tile = q - s * tiles;
-            g.items[q] =
+            g.items[spread ? s + kXcds * tile : q] =
                 PItem{g.shared_base + s, min(g.TM, g.n - tile * g.TM), 0, tile * g.TM, g.n * g.k + s * g.n + tile * g.TM,
                       tiles == 1};
         }
@@ -285,7 +296,6 @@ struct MmArgs {
 // (unit blocks / column blocks, i.e. the same weight rows) for item after item: the items of
 // one expert follow each other in the list, so the second and later ones find the expert's
 // weights in that XCD's L2 instead of fetching them again.
-constexpr int kXcds = 8;
 __device__ __forceinline__ bool xcd_work(int n_blocks, int* item, int* block) {
     const int per = (n_blocks + kXcds - 1) / kXcds;  // output blocks per XCD
     const int v = blockIdx.x, xcd = v % kXcds, w = v / kXcds;
@@ -1077,7 +1087,8 @@ int launch_prefill(const moei_model_desc& d, const PrefillScratch& ps, const voi
     MOEI_LAUNCH_CHECK();
     const int tm = tile_tokens(d, n);
     GroupArgsP g{ps.d_idx, ps.d_w, n, d.k, d.E, d.n_shared, tm, d_slot_of_row, shared_base, d_eam_row, ps.d_perm,
-                 ps.d_pgate, ps.d_where, reinterpret_cast<PItem*>(ps.d_items), ps.d_meta, ps.d_cntw, d_flags};
+                 ps.d_pgate, ps.d_where, reinterpret_cast<PItem*>(ps.d_items), ps.d_meta, ps.d_cntw, d_flags,
+                 tm == kTileTokWide};
     launch(K_FFN_GROUP, prefill_count_kernel, dim3(d.E), dim3(kGrpThreads), 0, s, g);
     MOEI_LAUNCH_CHECK();
     launch(K_FFN_GROUP, prefill_place_kernel, dim3(d.E), dim3(kGrpThreads), 0, s, g);
