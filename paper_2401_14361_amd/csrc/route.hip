@@ -123,12 +123,13 @@ constexpr int kRouteWaves = 4;  // expert rows per workgroup: fewer workgroups, 
 template <typename WT>
 __global__ void __launch_bounds__(kRouteWaves * kWave) route_fused_kernel(RouteFusedArgs a) {
     using V = WVec<WT>;
-    extern __shared__ float z[];  // E logits, then E slot ids, then the E counts of this layer's EAM row
+    extern __shared__ float z[];  // E logits, then E slot ids, the E counts of this layer's EAM row, 4 x E partial ranks
     __shared__ unsigned s_ticket;
     __shared__ int s_pick[kWave];
     __shared__ float s_pw[kWave];
     int* s_slot = reinterpret_cast<int*>(z + a.E);
     int* s_eam = s_slot + a.E;
+    int* s_prank = s_eam + a.E;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     constexpr int NT = kRouteWaves * kWave;
     const int e = blockIdx.x * kRouteWaves + wv;
@@ -200,6 +201,14 @@ __global__ void __launch_bounds__(kRouteWaves * kWave) route_fused_kernel(RouteF
     for (int j = tid; j < a.E; j += NT)
         z[j] = __hip_atomic_load(&a.logits[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
+    // every expert's rank is a count over all experts: each of the four wavefronts counts over a quarter
+    // of them (at 160 experts the loop of one wavefront alone took as long as the rest of the kernel)
+    const bool by_rank = a.E <= kRankMaxE;
+    if (by_rank) {
+        const int q = (a.E + kRouteWaves - 1) / kRouteWaves;
+        rank_part(z, a.E, lane, min(a.E, wv * q), min(a.E, (wv + 1) * q), s_prank + wv * a.E);
+        __syncthreads();
+    }
     if (wv != 0) return;
     int my_idx;
     float my_w;
@@ -210,8 +219,8 @@ __global__ void __launch_bounds__(kRouteWaves * kWave) route_fused_kernel(RouteF
         my_idx = -1;
         my_w = 0.f;
         if (lane == 0 && a.flags) atomicOr(a.flags, 4);
-    } else if (a.E <= kRankMaxE) {
-        const float sel = wave_topk_rank(z, a.E, a.k, a.renorm, lane, s_pick, s_pw, false);
+    } else if (by_rank) {
+        const float sel = wave_topk_rank(z, a.E, a.k, a.renorm, lane, s_pick, s_pw, false, s_prank, kRouteWaves);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
         my_idx = lane < a.k ? s_pick[lane] : -1;
@@ -265,10 +274,10 @@ int launch_route_fused(RouteFusedArgs a, int wdtype, hipStream_t s) {
     a.vec_ok = (a.H % n == 0) && ((uintptr_t)a.W % 16 == 0) && ((uintptr_t)a.x % 16 == 0);
     if (wdtype == MOEI_WDTYPE_BF16)
         launch(K_ROUTE_TOPK, route_fused_kernel<uint16_t>, dim3((a.E + kRouteWaves - 1) / kRouteWaves), dim3(kRouteWaves * kWave),
-               3 * a.E * sizeof(float), s, a);
+               (3 + (a.E <= kRankMaxE ? kRouteWaves : 0)) * a.E * sizeof(float), s, a);
     else
         launch(K_ROUTE_TOPK, route_fused_kernel<float>, dim3((a.E + kRouteWaves - 1) / kRouteWaves), dim3(kRouteWaves * kWave),
-               3 * a.E * sizeof(float), s, a);
+               (3 + (a.E <= kRankMaxE ? kRouteWaves : 0)) * a.E * sizeof(float), s, a);
     MOEI_LAUNCH_CHECK();
     return MOEI_OK;
 }

@@ -46,8 +46,23 @@ __device__ __forceinline__ bool wave_logits_bad(const float* z, int E, int lane)
 // whole workgroup (divide_here), else by the caller, after its own barrier, with the
 // returned sum (valid in every lane).
 constexpr int kRankMaxE = 1024;
+// part_rank (or null): [n_part][E] counts in LDS, formed beforehand by n_part wavefronts, each over its
+// own range of the experts (rank_part below): the rank is then their sum and the quadratic loop is
+// shared by the workgroup.
+__device__ __forceinline__ void rank_part(const float* z, int E, int lane, int j0, int j1, int* out) {
+    for (int e = lane; e < E; e += kWave) {
+        const float v = z[e];
+        int c = 0;
+        for (int j = j0; j < j1; ++j) {
+            const float u = z[j];
+            c += (u > v || (u == v && j < e)) ? 1 : 0;
+        }
+        out[e] = c;
+    }
+}
 __device__ __forceinline__ float wave_topk_rank(const float* z, int E, int k, int renorm, int lane, int* s_idx,
-                                                float* s_w, bool divide_here = true) {
+                                                float* s_w, bool divide_here = true, const int* part_rank = nullptr,
+                                                int n_part = 0) {
     const int per = (E + kWave - 1) / kWave;
     float m = -INFINITY;
     for (int r = 0; r < per; ++r) {
@@ -67,9 +82,13 @@ __device__ __forceinline__ float wave_topk_rank(const float* z, int E, int k, in
         if (e < E) {
             const float v = z[e];
             int rank = 0;
-            for (int j = 0; j < E; ++j) {
-                const float u = z[j];
-                rank += (u > v || (u == v && j < e)) ? 1 : 0;
+            if (part_rank) {
+                for (int w = 0; w < n_part; ++w) rank += part_rank[w * E + e];
+            } else {
+                for (int j = 0; j < E; ++j) {
+                    const float u = z[j];
+                    rank += (u > v || (u == v && j < e)) ? 1 : 0;
+                }
             }
             if (rank < k) {
                 const float p = expf(v - m) / s;
