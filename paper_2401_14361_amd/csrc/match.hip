@@ -554,7 +554,8 @@ __global__ void __launch_bounds__(kPickThreads) eamc_pick_kernel(PickArgs a) {
     if (gridDim.x == 1) {
         if (tid == 0) {
             a.best[b] = r.idx;
-            if (a.best_sim) a.best_sim[b] = r.idx >= 0 ? (float)cosine(r.dot, nq, a.norm2[r.idx]) : 0.f;
+            // (the winner carries its norm: no second trip to memory for it; an all-zero trace has dot 0)
+            if (a.best_sim) a.best_sim[b] = r.idx >= 0 ? (float)cosine(r.dot, nq, r.nt) : 0.f;
             s_best[0] = r.idx;
         }
         if (a.do_score) score_and_heads(a.sc, s_heads, s_keys, s_sn, s_best, true);
@@ -585,7 +586,7 @@ __global__ void __launch_bounds__(kPickThreads) eamc_pick_kernel(PickArgs a) {
     fin = block_pick(fin, s_dot, s_nt, s_idx);
     if (tid == 0) {
         a.best[b] = fin.idx;
-        if (a.best_sim) a.best_sim[b] = fin.idx >= 0 ? (float)cosine(fin.dot, nq, a.norm2[fin.idx]) : 0.f;
+        if (a.best_sim) a.best_sim[b] = fin.idx >= 0 ? (float)cosine(fin.dot, nq, fin.nt) : 0.f;
         a.ticket[b] = 0;  // ready for the next launch on this stream
         s_best[0] = fin.idx;
     }
