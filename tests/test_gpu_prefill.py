@@ -161,6 +161,9 @@ def test_prefill_every_item_size_on_one_prompt(m, tile, monkeypatch):
 def test_prefill_wide_rows(m):
     cfg = mi.get_config("C3").scaled(L=1, H=4096, I=160, N=8, prompt=16)
     _check(_prefill_case(m, cfg, 40, layer=0, n_unique=4))
+    # the widest rows with 256-token items: 64 ring stages in the gate/up product, three in the down product
+    cfg = mi.get_config("C3").scaled(L=1, H=4096, I=192, N=8, prompt=16)
+    _check(_prefill_case(m, cfg, 600, layer=0, n_unique=4))
 
 
 def test_prefill_full_width_deepseek_v2_lite_layer(m):
