@@ -781,23 +781,24 @@ __global__ void __launch_bounds__(TM * 4, 2) prefill_down_kernel(MmArgs a) {  //
 }
 
 // 3b, long prompts: the down product for items of up to 256 tokens, built like the wide gate/up
-// kernel.  A workgroup forms 256 tokens x 128 columns; its stream of W_down (64 units x 128 columns
-// = 64 rows of 256 bytes per stage, ring of six) and the item's activations (256 rows of 128 bytes
+// kernel.  A workgroup forms 256 tokens x 256 columns; its stream of W_down (64 units x 256 columns
+// = 64 rows of 512 bytes per stage, ring of three) and the item's activations (256 rows of 128 bytes
 // per stage, ring of two) go from global memory straight into LDS, loaded by wavefronts 0..3 and
 // 4..7; all column blocks of an item run on one XCD.  (The kernel above loads W_down into registers,
 // every token quarter again: at 256 tokens that path, ~16 bytes per clock and CU, is what bounds
-// it.)  A wavefront owns four 16-token blocks (blocks q, q + 4, ... of the item for quarter q) x 64
-// columns; operands are read from LDS one half stage ahead, eight units x four columns per lane
-// from the W_down rows, transposed in registers into four operands of eight units each: the column
-// a lane serves in matrix i is col0 + 4*lrow + i.  In the W_down ring the 16-byte piece p of row r
-// sits at piece position p ^ 8 * ((r >> 3) % 2), so that the two rows that lanes 0..31 read
-// together fall on different halves of the banks.  Needs I % 64 == 0; other shapes take the kernel
-// above, an item in two parts.
-constexpr int kDwCols = 128;
+// it.)  A wavefront owns four 16-token blocks (blocks q, q + 4, ... of the item for quarter q) x 128
+// columns: 32 accumulator tiles, which leave registers for one set of W_down pieces (eight units x
+// eight columns per lane, transposed in registers as above) and two of activations.  So the
+// activations of a half stage are read one half step ahead and the W_down pieces at its start, and
+// each ring has a barrier of its own: before the first half of a stage the wavefronts that load
+// W_down have seen that stage land (after the barrier the stage before it has been read by all and
+// its slot is loaded again), before the second half the same for the activations of the next stage.
+// Needs I % 64 == 0 and H % 256 == 0; other shapes take the kernel above, an item in two parts.
+constexpr int kDwCols = 256;
 constexpr int kDwKS = 64;
-constexpr int kDwStagesW = 4;
-constexpr int kDwStagesA = 3;
-constexpr int kDwStageElemsW = kDwKS * kDwCols;       // 64 rows of 128 columns: 16 KiB
+constexpr int kDwStagesW = 3;
+constexpr int kDwStagesA = 2;
+constexpr int kDwStageElemsW = kDwKS * kDwCols;       // 64 rows of 256 columns: 32 KiB
 constexpr int kDwStageElemsA = kTileTokWide * kDwKS;  // 256 rows of 64 units: 32 KiB
 // waits until at most `n` of this wavefront's vector memory operations are outstanding (n <= 20)
 __device__ __forceinline__ void wait_vm(int n) {
@@ -815,7 +816,7 @@ __device__ __forceinline__ void wait_vm(int n) {
 
 __global__ void __launch_bounds__(kWdThreads, 2) prefill_down_wide_kernel(MmArgs a) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    uint16_t* ring_w = reinterpret_cast<uint16_t*>(smem_raw);         // [kDwStagesW][64][128], pieces swizzled
+    uint16_t* ring_w = reinterpret_cast<uint16_t*>(smem_raw);         // [kDwStagesW][64][256]
     uint16_t* ring_a = ring_w + (size_t)kDwStagesW * kDwStageElemsW;  // [kDwStagesA][256][64], chunks swizzled
     int item, cb;
     xcd_item_work(a.n_cb, &item, &cb);
@@ -825,7 +826,7 @@ __global__ void __launch_bounds__(kWdThreads, 2) prefill_down_wide_kernel(MmArgs
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int lrow = lane & 15, lgrp = lane >> 4;
-    const int cg = wv & 1, tq = wv >> 1;  // column group (64 columns), token quarter
+    const int cg = wv & 1, tq = wv >> 1;  // column group (128 columns), token quarter
     const int col_wg = cb * kDwCols;
     if (it.slot < 0 || it.slot >= a.n_slots_total) {  // not resident: the rows are zero, the flag says so
         if (tid == 0) atomicOr(a.flags, 1);
@@ -838,32 +839,29 @@ __global__ void __launch_bounds__(kWdThreads, 2) prefill_down_wide_kernel(MmArgs
     const bool loads_w = wv < 4;  // else the activations
     const uint16_t* wd = a.pool + (size_t)it.slot * a.slot_elems + 2 * H + col_wg;
 
-    // Weights: load j (of 4) of wavefront w fills rows 4 * (4 * j + w) .. + 4 of a stage (a row = 128
-    // columns = 16 pieces); this lane brings piece position lane % 16 of row .. + lane / 16.
-    // Activations: load j (of 8) fills rows 8 * (4 * j + w) .. + 8 (a row = 64 units = 8 pieces),
-    // chunk position lane % 8 of row .. + lane / 8; rows past the item repeat its last token: what
-    // they yield is never stored.  One source address per lane; the loads of a stage lie a fixed
-    // number of rows apart.
+    // Weights: load j (of 8) of wavefront w fills rows 2 * (4 * j + w) .. + 2 of a stage (a row = 256
+    // columns = 32 pieces); this lane brings piece lane % 32 of row .. + lane / 32.  Activations: load
+    // j (of at most 8) fills rows 8 * (4 * j + w) .. + 8 (a row = 64 units = 8 pieces), chunk position
+    // lane % 8 of row .. + lane / 8; rows past the item's tokens are not loaded (what the ring holds
+    // there is multiplied at most within a token block that also holds tokens, never stored).  One
+    // source address per lane; the loads of a stage lie a fixed number of rows apart.
     const uint16_t* src0;
     const int arow = 8 * (wv & 3) + (lane >> 3);  // this lane's row of an activation load, before 32 * j
     if (loads_w) {
-        const int r = 4 * (wv & 3) + (lane >> 4);  // rows 16 apart share the swizzle key
-        src0 = wd + (size_t)r * 3 * H + ((lane & 15) ^ (8 * ((r >> 3) & 1))) * 8;
+        const int r = 2 * (wv & 3) + (lane >> 5);
+        src0 = wd + (size_t)r * 3 * H + (lane & 31) * 8;
     } else {
         const int c = (lane & 7) ^ ((arow >> 1) & 7);  // rows 32 apart share the swizzle key
         src0 = a.act + (size_t)it.row0 * I + c * 8;
     }
-    const int depth = loads_w ? kDwStagesW : kDwStagesA;  // uniform over the wavefront
-    // loads per stage of this wavefront; activation rows past the item's tokens are not loaded (what the
-    // ring holds there is multiplied at most within a token block that also holds tokens, never stored)
-    const int nld = loads_w ? 4 : min(8, max(0, (it.ntok - 8 * (wv & 3) + 31) / 32));
+    const int nld = loads_w ? 8 : min(8, max(0, (it.ntok - 8 * (wv & 3) + 31) / 32));  // loads per stage of this wavefront
     const uint32_t my_ring = lds_address(loads_w ? ring_w : ring_a) + (uint32_t)(wv & 3) * 1024;
-    auto issue = [&](int s) {
+    auto issue = [&](int s) {  // the calling wavefront's share of stage s of its ring
         if (loads_w) {
             const uint32_t st = my_ring + (uint32_t)(s % kDwStagesW) * (kDwStageElemsW * 2);
             const uint16_t* p = src0 + (size_t)s * kDwKS * 3 * H;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) load16_to_lds(p + (size_t)j * 16 * 3 * H, st + (uint32_t)j * 4096);
+            for (int j = 0; j < 8; ++j) load16_to_lds(p + (size_t)j * 8 * 3 * H, st + (uint32_t)j * 4096);
         } else {
             const uint32_t st = my_ring + (uint32_t)(s % kDwStagesA) * (kDwStageElemsA * 2);
             const uint16_t* p = src0 + s * kDwKS;
@@ -873,38 +871,35 @@ __global__ void __launch_bounds__(kWdThreads, 2) prefill_down_wide_kernel(MmArgs
         }
     };
 
-    f32x4 Y[4][4];
+    f32x4 Y[4][8];
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) Y[tb][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < 8; ++i) Y[tb][i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    struct Ops {
-        uint2 w[8];    // units 8 * lgrp + j of the half stage, columns 4 * lrow .. + 4 of the wavefront's 64
-        bf16x8 av[4];  // the token blocks' activations
+    struct Acts {
+        bf16x8 av[4];  // the token blocks' activations of a half stage
     };
-    auto read_ops = [&](int t, Ops& o, auto nt_tag) {  // half step t: stage t / 2, units 32 * (t % 2) .. + 32
+    auto read_acts = [&](int t, Acts& o, auto nt_tag) {  // half step t: stage t / 2, units 32 * (t % 2) .. + 32
         constexpr int NT = decltype(nt_tag)::value;
-        const int s = t >> 1, hh = t & 1;
-        const uint16_t* sw = ring_w + (size_t)(s % kDwStagesW) * kDwStageElemsW;
-        const uint16_t* sa = ring_a + (size_t)(s % kDwStagesA) * kDwStageElemsA;
-        // row 32 * hh + 8 * lgrp + j: swizzle key lgrp % 2; 8-byte unit cg * 16 + lrow of the row
-        const int piece = ((cg * 16 + lrow) >> 1) ^ (8 * (lgrp & 1));
+        const uint16_t* sa = ring_a + (size_t)((t >> 1) % kDwStagesA) * kDwStageElemsA;
+#pragma unroll
+        for (int tb = 0; tb < NT; ++tb) o.av[tb] = ld_bf16x8(sa + wd_pos((4 * tb + tq) * 16 + lrow, 4 * (t & 1) + lgrp));
+    };
+    auto multiply = [&](int t, const Acts& o, auto nt_tag) {
+        constexpr int NT = decltype(nt_tag)::value;
+        const uint16_t* sw = ring_w + (size_t)((t >> 1) % kDwStagesW) * kDwStageElemsW;
+        uint4 w[8];  // units 8 * lgrp + j of the half stage, columns 8 * lrow .. + 8 of the wavefront's 128
 #pragma unroll
         for (int j = 0; j < 8; ++j)
-            o.w[j] = *reinterpret_cast<const uint2*>(sw + (size_t)(32 * hh + 8 * lgrp + j) * kDwCols + piece * 8 + (lrow & 1) * 4);
+            w[j] = *reinterpret_cast<const uint4*>(sw + (size_t)(32 * (t & 1) + 8 * lgrp + j) * kDwCols + cg * 128 + lrow * 8);
 #pragma unroll
-        for (int tb = 0; tb < NT; ++tb) o.av[tb] = ld_bf16x8(sa + wd_pos((4 * tb + tq) * 16 + lrow, 4 * hh + lgrp));
-    };
-    auto multiply = [&](const Ops& o, auto nt_tag) {
-        constexpr int NT = decltype(nt_tag)::value;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 8; ++i) {
             uint32_t dw[4];
 #pragma unroll
             for (int p2 = 0; p2 < 4; ++p2) {
-                const uint32_t lo = (i >> 1) ? o.w[2 * p2].y : o.w[2 * p2].x;
-                const uint32_t hi = (i >> 1) ? o.w[2 * p2 + 1].y : o.w[2 * p2 + 1].x;
+                const uint32_t lo = reinterpret_cast<const uint32_t*>(&w[2 * p2])[i >> 1];
+                const uint32_t hi = reinterpret_cast<const uint32_t*>(&w[2 * p2 + 1])[i >> 1];
                 dw[p2] = (i & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
             }
             bf16x8 wt;
@@ -913,51 +908,62 @@ __global__ void __launch_bounds__(kWdThreads, 2) prefill_down_wide_kernel(MmArgs
             for (int tb = 0; tb < NT; ++tb) Y[tb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(o.av[tb], wt, Y[tb][i], 0, 0, 0);
         }
     };
-    const int n_slices = I / kDwKS;   // I is a multiple of 64 here
-    const int n_half = 2 * n_slices;
-    for (int s = 0; s < depth; ++s)
-        if (s < n_slices) issue(s);
-    wait_vm((min(n_slices, depth) - 1) * nld);  // stage 0 has landed
+    const int n_slices = I / kDwKS;  // I is a multiple of 64 here
+    // both rings start full; stage 0 of both has landed for all after the first barrier
+    if (loads_w) {
+        for (int s = 0; s < kDwStagesW; ++s)
+            if (s < n_slices) issue(s);
+        wait_vm((min(n_slices, kDwStagesW) - 1) * 8);
+    } else {
+        for (int s = 0; s < kDwStagesA; ++s)
+            if (s < n_slices) issue(s);
+        wait_vm((min(n_slices, kDwStagesA) - 1) * nld);
+    }
     __syncthreads();
-    // half steps as in the wide gate/up kernel
     auto run = [&](auto nt_tag) {
         constexpr int NT = decltype(nt_tag)::value;
-        Ops opA, opB;
-        if constexpr (NT > 0) read_ops(0, opA, nt_tag);
-        auto half = [&](int t, const Ops& cur, Ops& nxt, bool enters_stage) {
-            if (enters_stage) {
-                const int s = t >> 1;
-                wait_vm(min(n_slices - 2 - s, depth - 2) * nld);  // stages younger than s + 1 that have been issued
+        Acts actA, actB;
+        if constexpr (NT > 0) read_acts(0, actA, nt_tag);
+        for (int s = 0; s < n_slices; ++s) {
+            // first half of stage s: its W_down rows have landed (stages 0 .. s + 1 have been issued);
+            // stage s - 1 has been read by all, its slot takes stage s + 2
+            if (s >= 1) {
+                if (loads_w) wait_vm(min(n_slices - 1 - s, 1) * 8);
                 __syncthreads();
-                if (s + depth < n_slices) issue(s + depth);
+                if (loads_w && s + 2 < n_slices) issue(s + 2);
             }
             if constexpr (NT > 0) {
-                read_ops(t + 1, nxt, nt_tag);
-                multiply(cur, nt_tag);
+                read_acts(2 * s + 1, actB, nt_tag);
+                multiply(2 * s, actA, nt_tag);
             }
-        };
-        for (int t = 0; t + 2 < n_half; t += 2) {
-            half(t, opA, opB, false);
-            half(t + 1, opB, opA, true);
+            // second half: the activations of stage s + 1 (read during this half step) have landed; those of
+            // stage s have been read by all, their slot takes stage s + 2
+            if (s + 1 < n_slices) {
+                if (!loads_w) wait_vm(0);
+                __syncthreads();
+                if (!loads_w && s + 2 < n_slices) issue(s + 2);
+                if constexpr (NT > 0) read_acts(2 * s + 2, actA, nt_tag);
+            }
+            if constexpr (NT > 0) multiply(2 * s + 1, actB, nt_tag);
         }
-        half(n_half - 2, opA, opB, false);
-        if constexpr (NT > 0) multiply(opB, nt_tag);
     };
     switch ((n_live + 1) / 2) {  // uniform over the wavefront
         case 0: run(std::integral_constant<int, 0>{}); break;
         case 1: run(std::integral_constant<int, 2>{}); break;
         default: run(std::integral_constant<int, 4>{}); break;
     }
-    // D[token 4*lgrp + v][column lrow] of matrix i is column col0 + 4*lrow + i
-    const int col0 = col_wg + cg * 64;
+    // D[token 4*lgrp + v][column lrow] of matrix i is column col0 + 8*lrow + i
+    const int col0 = col_wg + cg * 128;
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int tok = (4 * tb + tq) * 16 + lgrp * 4 + v;
-            if (tok < it.ntok)
-                *reinterpret_cast<float4*>(a.yc + (size_t)(it.row0 + tok) * H + col0 + lrow * 4) =
-                    make_float4(Y[tb][0][v], Y[tb][1][v], Y[tb][2][v], Y[tb][3][v]);
+            if (tok < it.ntok) {
+                float* dst = a.yc + (size_t)(it.row0 + tok) * H + col0 + lrow * 8;
+                *reinterpret_cast<float4*>(dst) = make_float4(Y[tb][0][v], Y[tb][1][v], Y[tb][2][v], Y[tb][3][v]);
+                *reinterpret_cast<float4*>(dst + 4) = make_float4(Y[tb][4][v], Y[tb][5][v], Y[tb][6][v], Y[tb][7][v]);
+            }
         }
 }
 
@@ -1049,7 +1055,7 @@ int launch_mm(const moei_model_desc& d, MmArgs a, int max_items, hipStream_t s) 
         launch(K_PF_GATEUP, prefill_gateup_wide_kernel, dim3(kXcds * a.n_ub * item_rounds), dim3(kWdThreads), gu_smem, s, a);
     }
     MOEI_LAUNCH_CHECK();
-    if (a.dn_split == 2 && d.I % kDwKS == 0) {  // H is a multiple of 128
+    if (a.dn_split == 2 && d.I % kDwKS == 0 && d.H % kDwCols == 0) {
         const size_t dw_smem = (size_t)(kDwStagesW * kDwStageElemsW + kDwStagesA * kDwStageElemsA) * 2;
         rc = pf_allow_lds(prefill_down_wide_kernel, dw_smem);
         if (rc) return rc;
