@@ -31,6 +31,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8 ld_bf16x8(const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
 
 // LDS tiles of the matrix kernels hold rows of 128 bf16 (sixteen 16-byte chunks) with no padding;
 // chunk c of row r sits at chunk position c ^ (r % 16).  Staging writes (sixteen lanes along one
@@ -313,7 +314,6 @@ __device__ __forceinline__ bool xcd_item_work(int n_blocks, int* item, int* bloc
     return true;
 }
 
-__device__ __forceinline__ bf16x8 ld_bf16x8(const uint16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
 
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + expf(-g)); }
 
@@ -800,7 +800,7 @@ constexpr int kDwStagesW = 3;
 constexpr int kDwStagesA = 2;
 constexpr int kDwStageElemsW = kDwKS * kDwCols;       // 64 rows of 256 columns: 32 KiB
 constexpr int kDwStageElemsA = kTileTokWide * kDwKS;  // 256 rows of 64 units: 32 KiB
-// waits until at most `n` of this wavefront's vector memory operations are outstanding (n <= 20)
+// waits until at most `n` of this wavefront's vector memory operations are outstanding (n <= 32)
 __device__ __forceinline__ void wait_vm(int n) {
     // s_waitcnt: vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima
 #define MOEI_WAIT_CASE(v) case v: __builtin_amdgcn_s_waitcnt(0x0f70 | ((v) & 15) | (((v) >> 4) << 14)); break;
@@ -808,8 +808,10 @@ __device__ __forceinline__ void wait_vm(int n) {
         MOEI_WAIT_CASE(0) MOEI_WAIT_CASE(1) MOEI_WAIT_CASE(2) MOEI_WAIT_CASE(3) MOEI_WAIT_CASE(4) MOEI_WAIT_CASE(5)
         MOEI_WAIT_CASE(6) MOEI_WAIT_CASE(7) MOEI_WAIT_CASE(8) MOEI_WAIT_CASE(9) MOEI_WAIT_CASE(10) MOEI_WAIT_CASE(11)
         MOEI_WAIT_CASE(12) MOEI_WAIT_CASE(13) MOEI_WAIT_CASE(14) MOEI_WAIT_CASE(15) MOEI_WAIT_CASE(16) MOEI_WAIT_CASE(17)
-        MOEI_WAIT_CASE(18) MOEI_WAIT_CASE(19)
-        default: __builtin_amdgcn_s_waitcnt(0x4f74); break;  // 20
+        MOEI_WAIT_CASE(18) MOEI_WAIT_CASE(19) MOEI_WAIT_CASE(20) MOEI_WAIT_CASE(21) MOEI_WAIT_CASE(22) MOEI_WAIT_CASE(23)
+        MOEI_WAIT_CASE(24) MOEI_WAIT_CASE(25) MOEI_WAIT_CASE(26) MOEI_WAIT_CASE(27) MOEI_WAIT_CASE(28) MOEI_WAIT_CASE(29)
+        MOEI_WAIT_CASE(30) MOEI_WAIT_CASE(31)
+        default: __builtin_amdgcn_s_waitcnt(0x8f70); break;  // 32
     }
 #undef MOEI_WAIT_CASE
 }
@@ -992,6 +994,195 @@ __global__ void __launch_bounds__(256) prefill_reduce_kernel(const float* __rest
     }
 }
 
+// 1, long prompts.  The routing kernel of short prompts spends its time on the multiply-adds of the
+// logits (n x E x H of them on the vector ALUs: 46 us at 2,048 tokens).  Here they run on the matrix
+// cores.  grid ceil(n / 16), eight wavefronts: a workgroup forms the logits of 16 tokens,
+// D = A B with A = 16 router rows x 32 k and B = 32 k x 16 tokens.  Both operands pass through LDS
+// with loads that go straight there (a compute unit takes in 16-byte register loads at a quarter of
+// that rate, and the workgroup reads the whole router matrix): a stage holds 64 k-values (one cache
+// line) of the 16 token rows and of every router row, laid out like a stage of the wide matrix
+// kernels above, in a ring as deep as LDS allows; every wavefront loads its share of a stage's rows.
+// Wavefront w multiplies the k-values 32 * (w / 4) .. + 32 of each stage for the 16-expert blocks
+// w % 4, w % 4 + 4, ... (E <= 256: at most four), so each logit is formed as two partial sums, which
+// are added in a fixed order with the bias once the ring is done and its LDS is free.  Then
+// wavefront w takes the top-k of tokens w and w + 8 with the code of the kernel for short prompts.
+// A logit's sum runs over k in the matrix instruction's order, not the decode routing's: the two
+// agree to rounding, not bit for bit.
+// A step of the loop is two LDS reads and one matrix instruction per block, so what the loop costs
+// is its control: the count a wavefront waits for is a compile-time constant (the loop is written
+// once per number of loads a wavefront has per stage, its last steps unrolled), and ring slots are
+// counted, not divided.
+constexpr int kRtTok = 16;
+constexpr int kRtMaxE = 256;
+constexpr int kRtKS = 64;  // k-values per stage: 128 bytes of a row
+constexpr int kRtThreads = 512;
+constexpr int kRtWaves = kRtThreads / kWave;
+// rows of a stage: the 16 tokens, then the experts, in groups of 8 rows (what one load instruction of a wavefront fills)
+__host__ __device__ inline int rt_row_groups(int E) { return kRtTok / 8 + (E + 7) / 8; }
+__host__ __device__ inline int rt_stage_elems(int E) { return rt_row_groups(E) * 8 * kRtKS; }
+// Ring depth for NB blocks per wavefront (E <= 64 NB): what a workgroup has in flight bounds its
+// rate, so the ring takes the LDS a workgroup may have (160 KiB less the 4 KiB of the picks).
+__host__ __device__ constexpr int rt_depth(int nb) { return nb == 1 ? 15 : (nb == 2 ? 8 : (nb == 3 ? 6 : 4)); }
+static_assert(rt_depth(1) * (2 + 8) * 8 * kRtKS * 2 <= 156 * 1024 && rt_depth(2) * (2 + 16) * 8 * kRtKS * 2 <= 156 * 1024 &&
+                  rt_depth(3) * (2 + 24) * 8 * kRtKS * 2 <= 156 * 1024 && rt_depth(4) * (2 + 32) * 8 * kRtKS * 2 <= 156 * 1024,
+              "the ring fits");
+inline int rt_blocks_per_wave(int E) { return ((E + 15) / 16 + 3) / 4; }
+inline size_t rt_lds_bytes(int E) { return (size_t)rt_depth(rt_blocks_per_wave(E)) * rt_stage_elems(E) * 2; }
+
+// waits until at most N of this wavefront's vector memory operations are outstanding
+template <int N>
+__device__ __forceinline__ void wait_vm_c() {
+    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
+}
+// f(R), f(R - 1), ..., f(0), each with its argument as a compile-time constant
+template <int R, typename F>
+__device__ __forceinline__ void count_down(F&& f) {
+    if constexpr (R >= 0) {
+        f(std::integral_constant<int, R>{});
+        count_down<R - 1>(f);
+    }
+}
+
+template <int NB>  // blocks of 16 experts per wavefront: ceil(ceil(E / 16) / 4)
+__global__ void __launch_bounds__(kRtThreads) prefill_route_wide_kernel(const uint16_t* __restrict__ W,
+                                                                        const float* __restrict__ bias,
+                                                                        const uint16_t* __restrict__ X, int n, int H, int E,
+                                                                        int k, int renorm, int32_t* __restrict__ idx,
+                                                                        float* __restrict__ w, int32_t* __restrict__ where,
+                                                                        int32_t* __restrict__ flags) {
+    constexpr int NLD = NB + 1;  // loads per wavefront and stage: ceil((2 + 8 * NB) / 8) row groups at most
+    constexpr int DEPTH = rt_depth(NB);
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    uint16_t* ring = reinterpret_cast<uint16_t*>(smem_raw);  // [DEPTH][8 * row groups][64], chunks swizzled
+    float* zs = reinterpret_cast<float*>(smem_raw);          // afterwards: [2][16][E] partial logits
+    __shared__ int s_idx[kRtWaves][kWave];
+    __shared__ float s_w[kRtWaves][kWave];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int lrow = lane & 15, lgrp = lane >> 4;
+    const int eb = wv & 3, kh = wv >> 2;
+    const int t0 = blockIdx.x * kRtTok;
+    const int n_groups = rt_row_groups(E);
+    const int stage_elems = rt_stage_elems(E);
+    // load j of this wavefront fills row group wv + 8 * j of a stage; this lane brings chunk position
+    // lane % 8 of the group's row lane / 8.  Tokens past n repeat the last token and experts past E
+    // the last expert: what they yield is never stored.
+    const uint16_t* src[NLD];
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+        const int r = 8 * (wv + kRtWaves * j) + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> 1) & 7);
+        src[j] = (r < kRtTok ? X + (size_t)min(t0 + r, n - 1) * H : W + (size_t)min(r - kRtTok, E - 1) * H) + c * 8;
+    }
+    const int n_ld = max(0, (n_groups - wv + kRtWaves - 1) / kRtWaves);  // row groups of this wavefront: <= NLD
+    const int n_slices = H / kRtKS;
+    // Every workgroup reads the same router rows, and the pieces of one stage lie a whole row apart.
+    // Workgroups that share an L2 (every eighth one) therefore start at different slices of k and
+    // wrap around, so that at any moment they ask different parts of the cache for their lines.
+    const int first_slice = (int)((blockIdx.x / kXcds) * 2u % (unsigned)n_slices);
+    const uint32_t my_ring = lds_address(ring) + (uint32_t)(8 * wv) * (kRtKS * 2);
+    // the operand rows this lane reads in every stage (a block past the router's last row group reads
+    // the last group instead: never stored)
+    const int c_op = 4 * kh + lgrp;
+    const int x_pos = wd_pos(lrow, c_op);
+    int w_pos[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) w_pos[j] = wd_pos(min(kRtTok + 16 * (eb + 4 * j) + lrow, 8 * n_groups - 1), c_op);
+    f32x4 acc[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto run = [&](auto nld_tag) {
+        constexpr int N = decltype(nld_tag)::value;  // this wavefront's loads per stage
+        // stage s holds slice (first_slice + s) % n_slices and sits in ring slot s % DEPTH
+        int issue_slice = first_slice, issue_slot = 0;
+        auto issue = [&]() {
+            const uint32_t st = my_ring + (uint32_t)issue_slot * (uint32_t)(stage_elems * 2);
+#pragma unroll
+            for (int j = 0; j < N; ++j)
+                load16_to_lds(src[j] + (size_t)issue_slice * kRtKS, st + (uint32_t)(8 * kRtWaves * j) * (kRtKS * 2));
+            if (++issue_slice == n_slices) issue_slice = 0;
+            if (++issue_slot == DEPTH) issue_slot = 0;
+        };
+        int slot = 0;
+        auto multiply = [&]() {
+            const uint16_t* st = ring + (size_t)slot * stage_elems;
+            const bf16x8 xb = ld_bf16x8(st + x_pos);
+            bf16x8 wb[NB];
+#pragma unroll
+            for (int j = 0; j < NB; ++j) wb[j] = ld_bf16x8(st + w_pos[j]);
+#pragma unroll
+            for (int j = 0; j < NB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb[j], xb, acc[j], 0, 0, 0);
+            if (++slot == DEPTH) slot = 0;
+        };
+        for (int s = 0; s < DEPTH - 1; ++s)
+            if (s < n_slices) issue();
+        // Stage s has landed for all once every wavefront has seen its own loads of it complete and
+        // the barrier is passed; by then every wavefront has multiplied stage s - 1, whose slot takes
+        // stage s + DEPTH - 1.  While DEPTH - 2 younger stages are in flight the count to wait for is
+        // (DEPTH - 2) N; the last steps, with R = DEPTH - 3 .. 0 younger stages, are unrolled.
+        int s = 0;
+        for (; s + DEPTH - 2 < n_slices; ++s) {
+            wait_vm_c<(DEPTH - 2) * N>();
+            __syncthreads();
+            if (s + DEPTH - 1 < n_slices) issue();
+            multiply();
+        }
+        count_down<DEPTH - 3>([&](auto r_tag) {
+            constexpr int R = decltype(r_tag)::value;
+            if (R < n_slices) {  // stage n_slices - 1 - R
+                wait_vm_c<R * N>();
+                __syncthreads();
+                multiply();
+            }
+        });
+    };
+    switch (n_ld) {  // uniform over the wavefront
+        case 0: run(std::integral_constant<int, 0>{}); break;
+        case 1: run(std::integral_constant<int, 1>{}); break;
+        case 2: run(std::integral_constant<int, NLD < 2 ? NLD : 2>{}); break;
+        case 3: run(std::integral_constant<int, NLD < 3 ? NLD : 3>{}); break;
+        case 4: run(std::integral_constant<int, NLD < 4 ? NLD : 4>{}); break;
+        default: run(std::integral_constant<int, NLD>{}); break;
+    }
+    __syncthreads();  // the ring has been read: its LDS takes the partial logits
+    // D[expert 4 * lgrp + v][token lrow]
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int e = 16 * (eb + 4 * j) + 4 * lgrp + v;
+            if (e < E) zs[((size_t)kh * kRtTok + lrow) * E + e] = acc[j][v];
+        }
+    __syncthreads();
+    for (int tt = wv; tt < kRtTok && t0 + tt < n; tt += kRtWaves) {  // uniform over the wavefront
+        const int t = t0 + tt;
+        float* z = zs + (size_t)tt * E;
+        for (int e = lane; e < E; e += kWave) z[e] = (z[e] + z[(size_t)kRtTok * E + e]) + (bias ? bias[e] : 0.f);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();  // the logits are whole; the previous token's picks have been read
+        int my_idx;
+        float my_w;
+        if (wave_logits_bad(z, E, lane)) {  // the token gets no picks and only its shared experts' output
+            my_idx = -1;
+            my_w = 0.f;
+            if (lane == 0) atomicOr(flags, 4);
+        } else {
+            const float sel = wave_topk_rank(z, E, k, renorm, lane, s_idx[wv], s_w[wv], false);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            my_idx = lane < k ? s_idx[wv][lane] : -1;
+            my_w = lane < k ? (renorm ? s_w[wv][lane] / sel : s_w[wv][lane]) : 0.f;
+        }
+        if (lane < k) {
+            idx[(size_t)t * k + lane] = my_idx;
+            w[(size_t)t * k + lane] = my_w;
+            where[(size_t)t * k + lane] = -1;  // no contribution row yet: the grouping names one per placed pick
+        }
+    }
+}
+
 template <typename K>
 int pf_allow_lds(K kernel, size_t bytes) {
     static const void* seen_fn[8];
@@ -1085,11 +1276,37 @@ int launch_prefill(const moei_model_desc& d, const PrefillScratch& ps, const voi
     if ((uintptr_t)d_X % 16 != 0 || (uintptr_t)d_pool % 16 != 0 || (slot_elems * 2) % 16 != 0 || (uintptr_t)d_Y % 16 != 0)
         MOEI_FAIL(MOEI_EINVAL, "moe_prefill_layer: buffers must be 16-byte aligned");
     const int vec_ok = (d.H % 8 == 0) && ((uintptr_t)d_router_w % 16 == 0);
-    const size_t route_smem = ((size_t)d.H + (size_t)d.E) * sizeof(float);
-    rc = pf_allow_lds(prefill_route_kernel<uint16_t>, route_smem);
-    if (rc) return rc;
-    launch(K_PF_ROUTE, prefill_route_kernel<uint16_t>, dim3(n), dim3(4 * kWave), route_smem, s, d_router_w,
-           d_router_bias, d_X, n, d.H, d.E, d.k, (int)(d.renorm_topk != 0), vec_ok, ps.d_idx, ps.d_w, ps.d_where, d_flags);
+    // long prompts: the logits on the matrix cores (a workgroup of that kernel takes ~15 us whatever n; the
+    // kernel with a workgroup per token takes 11 us at 512 tokens, 22 us at 1,024 and 46 us at 2,048)
+    if (n >= 1024 && d.E <= kRtMaxE && d.H % 128 == 0 && (uintptr_t)d_router_w % 16 == 0) {
+        const int nbw = rt_blocks_per_wave(d.E);
+        const dim3 rgrid((n + kRtTok - 1) / kRtTok), rblock(kRtThreads);
+        const size_t rsmem = rt_lds_bytes(d.E);
+        const uint16_t* rw = reinterpret_cast<const uint16_t*>(d_router_w);
+        const uint16_t* rx = reinterpret_cast<const uint16_t*>(d_X);
+        const int rn = (int)(d.renorm_topk != 0);
+#define MOEI_ROUTE_CASE(NB_)                                                                                       \
+    case NB_:                                                                                                      \
+        rc = pf_allow_lds(prefill_route_wide_kernel<NB_>, rsmem);                                                  \
+        if (rc) return rc;                                                                                         \
+        launch(K_PF_ROUTE, prefill_route_wide_kernel<NB_>, rgrid, rblock, rsmem, s, rw, d_router_bias, rx, n, d.H, d.E, \
+               d.k, rn, ps.d_idx, ps.d_w, ps.d_where, d_flags);                                                    \
+        break;
+        switch (nbw) {
+            MOEI_ROUTE_CASE(1)
+            MOEI_ROUTE_CASE(2)
+            MOEI_ROUTE_CASE(3)
+            default:
+                MOEI_ROUTE_CASE(4)
+        }
+#undef MOEI_ROUTE_CASE
+    } else {
+        const size_t route_smem = ((size_t)d.H + (size_t)d.E) * sizeof(float);
+        rc = pf_allow_lds(prefill_route_kernel<uint16_t>, route_smem);
+        if (rc) return rc;
+        launch(K_PF_ROUTE, prefill_route_kernel<uint16_t>, dim3(n), dim3(4 * kWave), route_smem, s, d_router_w,
+               d_router_bias, d_X, n, d.H, d.E, d.k, (int)(d.renorm_topk != 0), vec_ok, ps.d_idx, ps.d_w, ps.d_where, d_flags);
+    }
     MOEI_LAUNCH_CHECK();
     const int tm = tile_tokens(d, n);
     GroupArgsP g{ps.d_idx, ps.d_w, n, d.k, d.E, d.n_shared, tm, d_slot_of_row, shared_base, d_eam_row, ps.d_perm,

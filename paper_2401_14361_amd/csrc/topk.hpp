@@ -49,16 +49,26 @@ constexpr int kRankMaxE = 1024;
 // part_rank (or null): [n_part][E] counts in LDS, formed beforehand by n_part wavefronts, each over its
 // own range of the experts (rank_part below): the rank is then their sum and the quadratic loop is
 // shared by the workgroup.
-__device__ __forceinline__ void rank_part(const float* z, int E, int lane, int j0, int j1, int* out) {
-    for (int e = lane; e < E; e += kWave) {
-        const float v = z[e];
-        int c = 0;
-        for (int j = j0; j < j1; ++j) {
-            const float u = z[j];
-            c += (u > v || (u == v && j < e)) ? 1 : 0;
-        }
-        out[e] = c;
+// how many of z[j0..j1) come before (v, e): larger, or equal with a lower index.  The broadcast
+// reads go out eight at a time, so that their latencies overlap, and the three comparisons are
+// combined as bits: written with && and || they become a branch per element.
+__device__ __forceinline__ int comes_before(float u, int j, float v, int e) {
+    return (int)(u > v) | ((int)(u == v) & (int)(j < e));
+}
+__device__ __forceinline__ int count_before(const float* z, int j0, int j1, float v, int e) {
+    int c = 0, j = j0;
+    for (; j + 8 <= j1; j += 8) {
+        float u[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) u[q] = z[j + q];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) c += comes_before(u[q], j + q, v, e);
     }
+    for (; j < j1; ++j) c += comes_before(z[j], j, v, e);
+    return c;
+}
+__device__ __forceinline__ void rank_part(const float* z, int E, int lane, int j0, int j1, int* out) {
+    for (int e = lane; e < E; e += kWave) out[e] = count_before(z, j0, j1, z[e], e);
 }
 __device__ __forceinline__ float wave_topk_rank(const float* z, int E, int k, int renorm, int lane, int* s_idx,
                                                 float* s_w, bool divide_here = true, const int* part_rank = nullptr,
@@ -85,10 +95,7 @@ __device__ __forceinline__ float wave_topk_rank(const float* z, int E, int k, in
             if (part_rank) {
                 for (int w = 0; w < n_part; ++w) rank += part_rank[w * E + e];
             } else {
-                for (int j = 0; j < E; ++j) {
-                    const float u = z[j];
-                    rank += (u > v || (u == v && j < e)) ? 1 : 0;
-                }
+                rank = count_before(z, 0, E, v, e);
             }
             if (rank < k) {
                 const float p = expf(v - m) / s;

@@ -158,6 +158,28 @@ def test_prefill_every_item_size_on_one_prompt(m, tile, monkeypatch):
     _check(_prefill_case(m, cfg, 9, layer=0))
 
 
+@pytest.mark.parametrize("E,k,n", [(40, 4, 1030), (100, 6, 1027), (160, 6, 1100), (256, 8, 1277)])
+def test_prefill_long_prompt_routing_over_expert_counts(m, E, k, n):
+    # prompts of 1,024 tokens and more form their logits in the routing kernel that runs on the matrix
+    # cores, sixteen tokens per workgroup: fewer row groups than wavefronts (E = 40), a ragged last
+    # 16-expert block (100), three and four blocks per wavefront (160, 256); n is no multiple of 16.
+    # Every token's picks, gate weights and the EAM in full, the outputs of 12 sampled tokens.
+    cfg = mi.get_config("C2").scaled(L=1, E=E, k=k, H=256, I=64, N=8, prompt=16)
+    _check(_prefill_case(m, cfg, n, layer=0, sample=12))
+
+
+def test_prefill_long_prompt_with_a_token_without_softmax(m):
+    # the same kernel meets a NaN logit: that token alone gets no picks
+    cfg = mi.get_config("C2").scaled(L=1, H=256, I=64, N=8, prompt=16)
+    n, bad = 1040, 1033
+    o = _prefill_case(m, cfg, n, layer=0, nan_token=bad, sample=12)
+    assert o["flags"] & 4 and (o["idx"][bad] == -1).all() and (o["w"][bad] == 0).all()
+    keep = [t for t in range(n) if t != bad]
+    assert (o["idx"][keep] == o["ridx"][keep]).all()
+    np.testing.assert_allclose(o["w"][keep], o["rw"][keep], rtol=1e-4)
+    assert int(o["eam"][0].sum() - o["eam0"][0].sum()) == (n - 1) * cfg.k
+
+
 def test_prefill_wide_rows(m):
     cfg = mi.get_config("C3").scaled(L=1, H=4096, I=160, N=8, prompt=16)
     _check(_prefill_case(m, cfg, 40, layer=0, n_unique=4))
