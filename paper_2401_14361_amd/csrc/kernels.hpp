@@ -91,6 +91,7 @@ struct moei_eamc {
     int32_t n_cap = 0;
     int32_t N = 0;
     int32_t cell_bytes = 4;
+    int32_t max_cell = 0;                // no stored cell has ever been larger (kept by load and insert)
     void* d_traces = nullptr;            // [L][n_cap][E] cells
     unsigned long long* d_norm2 = nullptr;  // [n_cap] squared norms of the flattened traces
     unsigned long long* d_part = nullptr;   // [B_max][lsplit_max][n_cap] partial dot products

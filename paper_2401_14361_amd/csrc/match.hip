@@ -12,6 +12,7 @@
 #include <string.h>
 
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include <stdio.h>
@@ -296,6 +297,252 @@ __global__ void __launch_bounds__(kDotThreads) eamc_dot_kernel(DotArgs a) {
         if (b0 + b >= a.B) break;
         u64* out = a.part + ((size_t)(b0 + b) * a.n_lsplit + split) * a.n_cap + n0;
         for (int i = tid; i < tn; i += kDotThreads) out[i] = rowsum[b * a.TN + i];
+    }
+}
+
+// ---- the batched scan on the matrix cores.  For several queries the scan is a matrix product,
+// [traces x cells] . [cells x queries], with integer entries and an exact integer result.  Cells
+// are split into 7-bit digits (c = sum_i d_i 128^i, 0 <= d_i < 128) and the digit planes are
+// multiplied pairwise by the 8-bit integer matrix instruction (16 traces x 64 cells times 64 cells
+// x 16 queries, 32-bit sums): products of equal weight 128^(i + j) share an accumulator, and the
+// accumulators are combined in 64-bit arithmetic before any of them can overflow, so the dot
+// products are the same integers the kernel above forms.  The instruction does the sum over the
+// cells: no sums across lanes are left, and the vector ALUs only cut digits (about a tenth of the
+// instructions of sixteen 64-bit multiply-adds per cell), so the kernel runs at the speed of the
+// scan itself.  How many digit planes are needed is known on the host for the traces (the largest
+// cell ever stored: DA) and found while staging for the queries (DB, per workgroup).
+//
+// grid (workgroups along the tiles of 64 J traces, layer splits, groups of 16 queries), 4 wavefronts;
+// a workgroup stages the queries of its split once and then walks every gridDim.x-th tile in one
+// stream of loads.  A unit is 64
+// cells of one layer of 16 traces: lane (r = lane % 16, g = lane / 16) loads four 16-byte pieces,
+// piece p = cells 16 p + 4 g .. + 3 of trace r (so one load instruction covers 64 contiguous bytes
+// of each trace), and byte j of digit word p is the digit of cell 16 p + 4 g + j.  The query planes
+// lie in LDS in the same order: [digit][query][unit][g][p][j], a lane reads its 16 bytes at once;
+// the stride between queries is an odd number of 16-byte steps, so the sixteen lanes that read
+// one g together touch every bank once.  Cells past E in a row's last unit are zero in the query
+// planes; the traces' pieces there are read from the row's start instead and multiply those zeros.
+constexpr int kMmQueries = 16;
+constexpr int kDigitBits = 7;
+constexpr int kMaxDigits = 4;  // 28 bits: cells up to MOEI_MAX_COUNT (24 bits)
+static_assert(MOEI_MAX_COUNT < (1 << (kDigitBits * kMaxDigits)), "four digits hold every cell");
+// cells an accumulator may take before it is emptied: at most kMaxDigits digit pairs of 127 x 127 each per cell
+constexpr int kMmFlushCells = (int)(0x7fffffffu / (kMaxDigits * 127u * 127u)) / 64 * 64;
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+struct DotMmArgs {
+    const int32_t* traces;  // [L][n_cap][E]
+    const int32_t* q;       // [B][L][E]
+    u64* part;              // [B][n_lsplit][n_cap]
+    int n_cap, N, L, E, B;
+    int L_scan, lper, n_lsplit;
+    int nblk;      // units per trace row: ceil(E / 64)
+    int n_tiles;   // tiles of 64 J traces
+    int q_stride;  // bytes per query in a digit plane: lper * nblk * 64, rounded up to an odd number of 16-byte steps
+    int once;      // the scan exceeds the last-level cache: load with the non-temporal hint
+};
+
+// digit d of four cells, one per byte
+__device__ __forceinline__ int digit4(int4 x, int d) {
+    const unsigned sh = kDigitBits * d;
+    return (int)((((unsigned)x.x >> sh) & 0x7fu) | ((((unsigned)x.y >> sh) & 0x7fu) << 8) |
+                 ((((unsigned)x.z >> sh) & 0x7fu) << 16) | ((((unsigned)x.w >> sh) & 0x7fu) << 24));
+}
+__device__ __forceinline__ int digits_of(unsigned v) { return v >> 21 ? 4 : (v >> 14 ? 3 : (v >> 7 ? 2 : 1)); }
+inline int digits_of_host(unsigned v) { return v >> 21 ? 4 : (v >> 14 ? 3 : (v >> 7 ? 2 : 1)); }
+
+template <int J, int DA>
+__global__ void __launch_bounds__(kDotThreads) eamc_dot_mm_kernel(DotMmArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];  // [kMaxDigits][16][q_stride]
+    __shared__ unsigned s_or[kDotThreads / kWave];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int lrow = lane & 15, lgrp = lane >> 4;
+    const int split = blockIdx.y, b0 = blockIdx.z * kMmQueries;
+    const int l0 = split * a.lper;
+    const int nl = max(0, min(l0 + a.lper, a.L_scan) - l0);
+    const int E = a.E, nblk = a.nblk, S = a.q_stride;
+    const size_t plane = (size_t)kMmQueries * S;
+    const int n_units = nl * nblk;
+    // this workgroup's tiles: blockIdx.x, blockIdx.x + gridDim.x, ...  (gridDim.x <= n_tiles)
+    const int n_mine = (a.n_tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int total = n_mine * n_units;  // units of the whole stream
+
+    // 1. the first loads of the query rows go out (sixteen threads per query; thread i of them takes
+    // the 16-byte pieces i, i + 16, ... of every layer's row - piece c4 = cells 4 c4 .. + 3: unit
+    // c4 / 16, g = c4 % 4, p = c4 % 16 / 4 - eight layers' loads in flight together; a query past B
+    // repeats the last one: its column is never stored)
+    constexpr int R = 8;
+    const int qb = tid >> 4, qi = tid & 15;
+    const int32_t* qsrc = a.q + ((size_t)min(b0 + qb, a.B - 1) * a.L + l0) * E;
+    auto load_q = [&](int4 (&x)[R], int c4, int lr) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            x[r] = (4 * c4 < E && lr + r < nl) ? *reinterpret_cast<const int4*>(qsrc + (size_t)(lr + r) * E + 4 * c4)
+                                               : make_int4(0, 0, 0, 0);
+    };
+    int4 q_first[R];
+    load_q(q_first, qi, 0);
+
+    // 2. then the first loads of the trace stream (they return after the query rows, which are
+    // cached, and are not waited for until the matrix products start).  The stream runs over the
+    // units of all tiles of the workgroup; this lane's row in layer l0 of a tile is trace
+    // 64 J tile + 16 (wv + 4 jg) + lrow (past N: the last trace, never stored), cell 4 lgrp.
+    constexpr int kAhead = J == 1 ? 4 : 2;  // units in flight per 16-trace group: 16 loads per lane
+    const size_t lstride = (size_t)a.n_cap * E;
+    const int32_t* fbase[J];
+    auto set_base = [&](int tile) {
+#pragma unroll
+        for (int jg = 0; jg < J; ++jg)
+            fbase[jg] = a.traces + ((size_t)l0 * a.n_cap + min(64 * J * tile + 16 * (wv + 4 * jg) + lrow, a.N - 1)) * E + 4 * lgrp;
+    };
+    int f_tile = blockIdx.x, f_l = 0, f_blk = 0;  // the next unit to request
+    set_base(f_tile);
+    int4 ring[kAhead][J][4];
+    auto fetch = [&](int4 (&dst)[J][4]) {
+        const size_t row = (size_t)f_l * lstride;
+#pragma unroll
+        for (int jg = 0; jg < J; ++jg)
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int c = f_blk * 64 + 16 * p;  // the piece's first cell is c + 4 lgrp
+                const int32_t* src = fbase[jg] + row + (c + 4 * lgrp < E ? c : 0);
+                if (a.once) {
+                    const uint4 v = load_once_16(src);
+                    dst[jg][p] = make_int4((int)v.x, (int)v.y, (int)v.z, (int)v.w);
+                } else {
+                    dst[jg][p] = *reinterpret_cast<const int4*>(src);
+                }
+            }
+        if (++f_blk == nblk) {
+            f_blk = 0;
+            if (++f_l == nl) {
+                f_l = 0;
+                f_tile += gridDim.x;
+                set_base(f_tile);
+            }
+        }
+    };
+#pragma unroll
+    for (int d = 0; d < kAhead; ++d)
+        if (d < total) fetch(ring[d]);
+
+    // 3. the query rows become digit planes in LDS
+    {
+        unsigned char* dst = smem + (size_t)qb * S;
+        unsigned seen = 0;
+        auto store_q = [&](const int4 (&x)[R], int c4, int lr) {
+            const int word = ((c4 >> 4) << 6) + ((((c4 & 3) << 2) + ((c4 & 15) >> 2)) << 2);  // byte offset in the row's units
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (lr + r < nl) {
+                    seen |= (unsigned)(x[r].x | x[r].y | x[r].z | x[r].w);
+#pragma unroll
+                    for (int d = 0; d < kMaxDigits; ++d)
+                        *reinterpret_cast<int*>(dst + d * plane + (size_t)(lr + r) * nblk * 64 + word) = digit4(x[r], d);
+                }
+        };
+        store_q(q_first, qi, 0);
+        for (int c4 = qi; c4 < nblk * 16; c4 += 16)
+            for (int lr = (c4 == qi ? R : 0); lr < nl; lr += R) {
+                int4 x[R];
+                load_q(x, c4, lr);
+                store_q(x, c4, lr);
+            }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) seen |= (unsigned)__shfl_xor((int)seen, off, 64);
+        if (lane == 0) s_or[wv] = seen;
+    }
+    __syncthreads();
+    static_assert(kDotThreads / kWave == 4, "four wavefronts");
+    const int DB = digits_of(s_or[0] | s_or[1] | s_or[2] | s_or[3]);  // uniform over the workgroup
+
+    auto run = [&](auto db_tag) {
+        constexpr int DBC = decltype(db_tag)::value;
+        constexpr int NW = DA + DBC - 1;  // weights 128^0 .. 128^(NW - 1)
+        i32x4 acc[J][NW];
+        u64 tot[J][4];
+#pragma unroll
+        for (int jg = 0; jg < J; ++jg) {
+#pragma unroll
+            for (int w = 0; w < NW; ++w) acc[jg][w] = i32x4{0, 0, 0, 0};
+#pragma unroll
+            for (int v = 0; v < 4; ++v) tot[jg][v] = 0;
+        }
+        auto flush = [&]() {
+#pragma unroll
+            for (int jg = 0; jg < J; ++jg)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    u64 t = 0;
+#pragma unroll
+                    for (int w = 0; w < NW; ++w) t += (u64)(unsigned)acc[jg][w][v] << (kDigitBits * w);
+                    tot[jg][v] += t;
+                }
+#pragma unroll
+            for (int jg = 0; jg < J; ++jg)
+#pragma unroll
+                for (int w = 0; w < NW; ++w) acc[jg][w] = i32x4{0, 0, 0, 0};
+        };
+        int cells = 0, cu = 0, c_tile = blockIdx.x;  // the unit being multiplied: unit cu of tile c_tile
+        const unsigned char* qrow = smem + (size_t)lrow * S + lgrp * 16;
+        for (int g0 = 0; g0 < total; g0 += kAhead) {
+#pragma unroll
+            for (int d = 0; d < kAhead; ++d) {
+                const int g = g0 + d;
+                if (g < total) {  // uniform over the workgroup
+                    int4 x[J][4];
+#pragma unroll
+                    for (int jg = 0; jg < J; ++jg)
+#pragma unroll
+                        for (int p = 0; p < 4; ++p) x[jg][p] = ring[d][jg][p];
+                    if (g + kAhead < total) fetch(ring[d]);
+                    i32x4 bq[DBC];
+#pragma unroll
+                    for (int db = 0; db < DBC; ++db) bq[db] = *reinterpret_cast<const i32x4*>(qrow + db * plane + (size_t)cu * 64);
+#pragma unroll
+                    for (int jg = 0; jg < J; ++jg)
+#pragma unroll
+                        for (int da = 0; da < DA; ++da) {
+                            const i32x4 ad = {digit4(x[jg][0], da), digit4(x[jg][1], da), digit4(x[jg][2], da), digit4(x[jg][3], da)};
+#pragma unroll
+                            for (int db = 0; db < DBC; ++db)
+                                acc[jg][da + db] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ad, bq[db], acc[jg][da + db], 0, 0, 0);
+                        }
+                    cells += 64;
+                    if (++cu == n_units) {
+                        // the tile is done: D[trace 4 lgrp + v][query lrow]
+                        flush();
+                        if (b0 + lrow < a.B) {
+                            u64* out = a.part + ((size_t)(b0 + lrow) * a.n_lsplit + split) * a.n_cap;
+#pragma unroll
+                            for (int jg = 0; jg < J; ++jg)
+#pragma unroll
+                                for (int v = 0; v < 4; ++v) {
+                                    const int n = 64 * J * c_tile + 16 * (wv + 4 * jg) + 4 * lgrp + v;
+                                    if (n < a.N) out[n] = tot[jg][v];
+                                }
+                        }
+#pragma unroll
+                        for (int jg = 0; jg < J; ++jg)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) tot[jg][v] = 0;
+                        cu = 0;
+                        cells = 0;
+                        c_tile += gridDim.x;
+                    } else if (cells >= kMmFlushCells) {
+                        flush();
+                        cells = 0;
+                    }
+                }
+            }
+        }
+    };
+    switch (DB) {
+        case 1: run(std::integral_constant<int, 1>{}); break;
+        case 2: run(std::integral_constant<int, 2>{}); break;
+        case 3: run(std::integral_constant<int, 3>{}); break;
+        default: run(std::integral_constant<int, 4>{}); break;
     }
 }
 
@@ -835,6 +1082,74 @@ int launch_dot_j(const Plan& p, const DotArgs& a, dim3 grid, hipStream_t s) {
     return launch_dot_nb<CT, VEC, 1>(p, a, grid, s);
 }
 
+// The plan of the matrix-core scan: tiles of 64 J traces, layer splits that keep the query planes of
+// a split within 64 KiB of LDS, and about two workgroups per compute unit, each walking several tiles.
+struct MmPlan {
+    bool ok;
+    int J, n_tiles, grid_x, n_lsplit, lper, nblk, q_stride, DA;
+    size_t smem;
+};
+
+MmPlan make_mm_plan(const moei_eamc* c, int L_scan, int B) {
+    static const int kForceJ = getenv("MOEI_MATCH_MM_J") ? atoi(getenv("MOEI_MATCH_MM_J")) : 0;
+    static const int kTarget = getenv("MOEI_MATCH_MM_BLOCKS") ? atoi(getenv("MOEI_MATCH_MM_BLOCKS")) : 0;
+    static const int kSplits = getenv("MOEI_MATCH_MM_SPLITS") ? atoi(getenv("MOEI_MATCH_MM_SPLITS")) : 0;
+    MmPlan p{};
+    const int E = c->d.E;
+    p.nblk = (E + 63) / 64;
+    const int lper_max = 15 / p.nblk;  // 4 planes x 16 queries x (lper nblk 64 + 16) bytes <= 64 KiB
+    if (lper_max < 1) return p;
+    const size_t scan_bytes = (size_t)c->N * L_scan * E * 4;
+    // 64 traces per tile; 128 only for scans so long that the tiles alone give every compute unit several workgroups
+    p.J = kForceJ == 1 || kForceJ == 2 ? kForceJ : (scan_bytes >= ((size_t)512 << 20) ? 2 : 1);
+    p.n_tiles = (c->N + 64 * p.J - 1) / (64 * p.J);
+    const int groups = (B + kMmQueries - 1) / kMmQueries;
+    const int target = kTarget > 0 ? kTarget : 450;  // measured at 10,000 traces of 26 x 64 cells: 3 splits 16.2 us, 2 splits 20.4, 4 splits 17.4
+    // layer splits: as few as the LDS allows (every split writes a partial sum per trace and query that
+    // the pick reads again), more only where the tiles alone do not fill the chip
+    const int lmax = L_scan < c->lsplit_max ? L_scan : c->lsplit_max;
+    const int min_split = (L_scan + lper_max - 1) / lper_max;
+    int want = kSplits > 0 ? kSplits : (target + p.n_tiles * groups - 1) / (p.n_tiles * groups);
+    if (want < min_split) want = min_split;
+    p.n_lsplit = want > lmax ? lmax : want;
+    if (p.n_lsplit < min_split) return p;
+    p.lper = (L_scan + p.n_lsplit - 1) / p.n_lsplit;
+    p.n_lsplit = (L_scan + p.lper - 1) / p.lper;
+    // workgroups along the tiles: each takes every grid_x-th tile and stages its queries once
+    p.grid_x = target / (p.n_lsplit * groups);
+    if (p.grid_x < 1) p.grid_x = 1;
+    if (p.grid_x > p.n_tiles) p.grid_x = p.n_tiles;
+    p.grid_x = (p.n_tiles + (p.n_tiles + p.grid_x - 1) / p.grid_x - 1) / ((p.n_tiles + p.grid_x - 1) / p.grid_x);  // the same count of tiles each, but for the last
+    p.q_stride = p.lper * p.nblk * 64;
+    if ((p.q_stride / 16) % 2 == 0) p.q_stride += 16;
+    p.smem = (size_t)kMaxDigits * kMmQueries * p.q_stride;
+    p.DA = digits_of_host((unsigned)c->max_cell);
+    p.ok = p.smem <= 64 * 1024 - 64;
+    return p;
+}
+
+int launch_dot_mm(const MmPlan& p, const DotMmArgs& a, dim3 grid, hipStream_t s) {
+#define MOEI_MM_CASE(JJ, DD)                                                                         \
+    case (JJ) * 8 + (DD):                                                                            \
+        launch(K_MATCH_DOT, eamc_dot_mm_kernel<JJ, DD>, grid, dim3(kDotThreads), p.smem, s, a);     \
+        break;
+    switch (p.J * 8 + p.DA) {
+        MOEI_MM_CASE(1, 1)
+        MOEI_MM_CASE(1, 2)
+        MOEI_MM_CASE(1, 3)
+        MOEI_MM_CASE(1, 4)
+        MOEI_MM_CASE(2, 1)
+        MOEI_MM_CASE(2, 2)
+        MOEI_MM_CASE(2, 3)
+        MOEI_MM_CASE(2, 4)
+        default:
+            MOEI_FAIL(MOEI_EINVAL, "eamc_match: no matrix-core scan for %d groups per wavefront and %d digits", p.J, p.DA);
+    }
+#undef MOEI_MM_CASE
+    MOEI_LAUNCH_CHECK();
+    return MOEI_OK;
+}
+
 size_t cells(const moei_eamc* c) { return (size_t)c->d.L * c->n_cap * c->d.E; }
 
 }  // namespace
@@ -895,11 +1210,15 @@ extern "C" int moei_eamc_size(const moei_eamc* c) {
 
 namespace {
 
-int check_cells(const int32_t* p, size_t n, int cell_bytes) {
+int check_cells(const int32_t* p, size_t n, int cell_bytes, int32_t* largest) {
     const int32_t hi = cell_bytes == 2 ? 65535 : MOEI_MAX_COUNT;
-    for (size_t i = 0; i < n; ++i)
+    int32_t m = 0;
+    for (size_t i = 0; i < n; ++i) {
         if (p[i] < 0 || p[i] > hi)
             MOEI_FAIL(MOEI_EINVAL, "EAM cell %zu holds %d, outside [0, %d]", i, p[i], hi);
+        m = p[i] > m ? p[i] : m;
+    }
+    *largest = m;
     return MOEI_OK;
 }
 
@@ -918,11 +1237,13 @@ extern "C" int moei_eamc_load(moei_eamc* c, const int32_t* h_traces, int32_t N) 
     MOEI_REQUIRE(N == 0 || h_traces, "moei_eamc_load: null traces");
     const int L = c->d.L, E = c->d.E;
     const size_t LE = (size_t)L * E;
+    int32_t largest = 0;
     if (N > 0) {  // refused input leaves the collection as it was
-        int rc = check_cells(h_traces, (size_t)N * LE, c->cell_bytes);
+        int rc = check_cells(h_traces, (size_t)N * LE, c->cell_bytes, &largest);
         if (rc) return rc;
     }
     c->N = 0;
+    c->max_cell = largest;
     if (N == 0) return MOEI_OK;
     // trace-major -> layer-major staging, one layer at a time
     std::vector<unsigned long long> norm((size_t)N);
@@ -956,7 +1277,8 @@ extern "C" int moei_eamc_insert(moei_eamc* c, const int32_t* h_eam, int32_t vict
     MOEI_REQUIRE(c && h_eam, "moei_eamc_insert: null pointer");
     const int L = c->d.L, E = c->d.E;
     const size_t LE = (size_t)L * E;
-    int rc = check_cells(h_eam, LE, c->cell_bytes);
+    int32_t largest = 0;
+    int rc = check_cells(h_eam, LE, c->cell_bytes, &largest);
     if (rc) return rc;
     int pos;
     if (c->N < c->n_cap) {
@@ -978,6 +1300,7 @@ extern "C" int moei_eamc_insert(moei_eamc* c, const int32_t* h_eam, int32_t vict
     unsigned long long n2 = norm2_of(h_eam, LE);
     MOEI_HIP(hipMemcpy(c->d_norm2 + pos, &n2, 8, hipMemcpyHostToDevice));
     if (pos == c->N) c->N += 1;
+    if (largest > c->max_cell) c->max_cell = largest;  // (a replaced trace may have held the old maximum: the bound stays)
     return MOEI_OK;
 }
 
@@ -1076,6 +1399,20 @@ int launch_dots(const moei_eamc* c, const int32_t* d_eam, int B, int layer_hi, i
     const int L = c->d.L, E = c->d.E;
     *n_lsplit = 0;
     if (c->N == 0) return MOEI_OK;
+    // a.  Three queries and more: the scan as a matrix product (4-byte cells, rows of whole 16-byte
+    // pieces); it takes the same time for 3 as for 16 queries, and for two the kernel below is faster
+    static const bool kNoMm = getenv("MOEI_MATCH_NO_MM") && atoi(getenv("MOEI_MATCH_NO_MM")) != 0;
+    if (B >= 3 && !kNoMm && c->cell_bytes == 4 && E % 4 == 0 && (uintptr_t)d_eam % 16 == 0) {
+        const MmPlan mp = make_mm_plan(c, layer_hi + 1, B);
+        if (mp.ok) {
+            *n_lsplit = mp.n_lsplit;
+            const size_t bytes = (size_t)c->N * (layer_hi + 1) * E * 4;
+            DotMmArgs ma{reinterpret_cast<const int32_t*>(c->d_traces), d_eam, c->d_part, c->n_cap, c->N, L, E, B,
+                         layer_hi + 1, mp.lper, mp.n_lsplit, mp.nblk, mp.n_tiles, mp.q_stride, bytes > ((size_t)192 << 20)};
+            return launch_dot_mm(mp, ma, dim3(mp.grid_x, mp.n_lsplit, (B + kMmQueries - 1) / kMmQueries), s);
+        }
+    }
+    // b.  One or two queries, 2-byte cells, other shapes: the scan on the vector ALUs
     Plan p = make_plan(c, layer_hi + 1, B);
     *n_lsplit = p.n_lsplit;
     if (p.n_lsplit > c->lsplit_max || p.smem > 64 * 1024)

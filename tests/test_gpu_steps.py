@@ -145,6 +145,52 @@ def test_eamc_match_workload_traces_and_partial_rows(m):
     _check_match(m, T, Qp, 2, layer_hi=8)
 
 
+@pytest.mark.parametrize("t_hi,q_hi", [(100, 90), (100, 3_000_000), (16_000, 16_000), (2_000_000, 120),
+                                       (16_777_215, 16_777_215), (130, 16_383)])
+def test_eamc_match_batches_over_cell_sizes(m, t_hi, q_hi):
+    # two and more queries are matched by a matrix product over 7-bit digits of the cells: one to
+    # four digits on either side, sixteen queries and five (a partly filled group), rows of 96 cells
+    # (a full 64-cell unit and half of one), a layer range that splits unevenly, an exact tie
+    rng = np.random.default_rng(t_hi % 1000 + q_hi % 77)
+    N, L, E = 333, 7, 96
+    T = (rng.integers(0, t_hi + 1, size=(N, L, E), dtype=np.int64) * (rng.random((N, L, E)) < 0.4)).astype(np.int32)
+    T[7, 3, 95] = t_hi                                    # the largest value is present, in a row's last cell
+    T[9] = 0
+    for B in (16, 5, 3):
+        Q = (rng.integers(0, q_hi + 1, size=(B, L, E), dtype=np.int64) * (rng.random((B, L, E)) < 0.5)).astype(np.int32)
+        Q[B - 1, 6, 95] = q_hi
+        Q[1] = T[20]
+        Q[2] = 0
+        if t_hi <= 5_000_000:
+            T[21] = 3 * T[20]                             # ties with trace 20 for every query
+        _check_match(m, T, Q, 4)
+    Q[:, 5:] = 0                                          # rows above the current layer are zero and are not scanned
+    _check_match(m, T, Q, 4, layer_hi=4)
+
+
+def test_eamc_match_batch_after_an_insert_with_larger_cells(m):
+    # the number of digit planes of the traces follows the largest cell ever stored: a trace inserted
+    # later may raise it
+    rng = np.random.default_rng(11)
+    N, L, E = 80, 4, 64
+    T = rng.integers(0, 100, size=(N, L, E)).astype(np.int32)
+    Q = rng.integers(0, 50, size=(4, L, E)).astype(np.int32)
+    desc = m.ModelDesc(L, E, 1, 0, 8, 8, m.WDTYPE_BF16, 0, EPS)
+    eamc = m.Eamc(desc, N + 2, 4)
+    eamc.load(T)
+    big = (Q[3].astype(np.int64) * 40_000).astype(np.int32)   # parallel to query 3, cells up to 2 million
+    eamc.insert(big)
+    best, sim, sims = m.eamc_match(eamc, dev(Q), want_sims=True)
+    torch.cuda.synchronize()
+    T2 = np.concatenate([T, big[None]])
+    for b in range(4):
+        rb, rs, rsims = O.eamc_match(T2, Q[b])
+        assert int(best.cpu()[b]) == rb
+        np.testing.assert_allclose(sims.cpu().numpy()[b], rsims, rtol=SIM_RTOL, atol=1e-30)
+    assert int(best.cpu()[3]) == N
+    eamc.close()
+
+
 def test_eamc_match_large_counts_and_empty_collection(m):
     rng = np.random.default_rng(3)
     T = rng.integers(0, 16777215, size=(40, 3, 16), dtype=np.int64).astype(np.int32)
