@@ -118,7 +118,9 @@ int eam_update(int32_t* d_eam, int32_t B, int32_t L, int32_t E, int32_t layer,
  * A zero vector has similarity 0 to everything.  Empty collection: best = -1, sim = 0.
  * layer_hi: the caller promises rows > layer_hi of every query are zero, so only
  * layers 0..layer_hi are scanned (L-1 scans everything); norms are always those of
- * the full matrices.  B <= 16. */
+ * the full matrices.  B <= 16.  The device does not check the queries' cells: a cell
+ * outside [0, MOEI_MAX_COUNT] gives an unspecified (but in-bounds, finite) result for
+ * that query. */
 int eamc_match(const moei_eamc* c, const int32_t* d_eam, int32_t B, int32_t layer_hi,
                int32_t* d_best, float* d_best_sim, float* d_sims, void* stream);
 
