@@ -116,7 +116,7 @@ def _check(o):
 @pytest.mark.parametrize("n", [1, 7, 64, 65, 130, 200, 700])
 def test_prefill_reduced_deepseek_shape(m, n):
     # DeepSeek-V2-Lite structure (top-6 of 64 + 2 shared, bf16), narrow matrices; token counts around the 64-token
-    # tile, and one prompt long enough (n k > 64 E) that the items hold up to 128 tokens
+    # tile, and prompts long enough (n k >= 48 E) that the items hold up to 256 tokens
     cfg = mi.get_config("C2").scaled(L=3, H=256, I=192, N=8, prompt=16)
     _check(_prefill_case(m, cfg, n, layer=1))
 
@@ -189,14 +189,24 @@ def test_prefill_wide_rows(m):
 
 
 def test_prefill_full_width_deepseek_v2_lite_layer(m):
-    # configuration 2 at full width (2048 x 1408 bf16 experts), one layer, a 512-token prompt
+    # configuration 2 at full width (2048 x 1408 bf16 experts), one layer, a 512-token prompt (48 tokens per
+    # expert on average: 256-token items, most of them a fifth full)
     cfg = mi.get_config("C2").scaled(L=1, N=8, prompt=16)
     o = _prefill_case(m, cfg, 512, layer=0, n_unique=16)
     _check(o)
 
 
+def test_prefill_full_width_short_prompt_with_64_token_items(m):
+    # the same layer with a 200-token prompt, which takes the 64-token items and the kernels that stage
+    # through registers; every token's picks, gate weights and the EAM in full, the outputs of 24 sampled tokens
+    cfg = mi.get_config("C2").scaled(L=1, N=8, prompt=16)
+    o = _prefill_case(m, cfg, 200, layer=0, n_unique=16, sample=24)
+    assert o["finite"]
+    _check(o)
+
+
 def test_prefill_full_width_1024_token_prompt(m):
-    # configuration 2 at full width with a 1,024-token prompt: n k > 64 E, so the items hold up to 256
+    # configuration 2 at full width with a 1,024-token prompt: n k >= 48 E, so the items hold up to 256
     # tokens (96 on average: partly filled items); every token's picks, gate weights and the EAM in
     # full, the outputs of 40 sampled tokens
     cfg = mi.get_config("C2").scaled(L=1, N=8, prompt=16)
