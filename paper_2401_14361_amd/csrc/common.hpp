@@ -157,6 +157,27 @@ __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u 
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 __device__ __forceinline__ float bf16_one(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
 
+// A 16-byte load per lane that goes from global memory straight into LDS: the wavefront's 64 pieces
+// land side by side, 1 KiB from `lds_addr` on (an LDS byte address, the same in every lane).  The
+// load counts as a vector memory operation of the wavefront (vmcnt); nothing says when the data is
+// in LDS but a later wait on that counter.  m0 (the LDS base of such loads) is a register the
+// compiler reserves and sets itself right before each of its own uses, so writing it here is safe.
+__device__ __forceinline__ void load16_to_lds(const void* gsrc, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gsrc) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+// waits until at most N of the wavefront's vector memory operations are outstanding; no memory access of
+// the program moves across it
+template <int N>
+__device__ __forceinline__ void wait_vm_fence() {
+    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// waits until the wavefront's LDS reads have returned (before their LDS is written again by such a load)
+__device__ __forceinline__ void wait_lds_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
 #endif  // __HIPCC__
 
 }  // namespace moei

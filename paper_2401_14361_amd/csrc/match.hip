@@ -305,30 +305,47 @@ __global__ void __launch_bounds__(kDotThreads) eamc_dot_kernel(DotArgs a) {
 // are split into 7-bit digits (c = sum_i d_i 128^i, 0 <= d_i < 128) and the digit planes are
 // multiplied pairwise by the 8-bit integer matrix instruction (16 traces x 64 cells times 64 cells
 // x 16 queries, 32-bit sums): products of equal weight 128^(i + j) share an accumulator, and the
-// accumulators are combined in 64-bit arithmetic before any of them can overflow, so the dot
-// products are the same integers the kernel above forms.  The instruction does the sum over the
-// cells: no sums across lanes are left, and the vector ALUs only cut digits (about a tenth of the
-// instructions of sixteen 64-bit multiply-adds per cell), so the kernel runs at the speed of the
-// scan itself.  How many digit planes are needed is known on the host for the traces (the largest
-// cell ever stored: DA) and found while staging for the queries (DB, per workgroup).
+// accumulators are combined in 64-bit arithmetic at the end of a tile, long before any of them can
+// overflow, so the dot products are the same integers the kernel above forms.  The instruction
+// does the sum over the cells: no sums across lanes are left, and the vector ALUs only cut digits,
+// so the kernel runs close to the speed of the scan itself.  How many digit planes are needed is
+// known on the host for the traces (the largest cell ever stored: DA) and found while staging for
+// the queries (DB, per workgroup).
 //
-// grid (workgroups along the tiles of 64 J traces, layer splits, groups of 16 queries), 4 wavefronts;
-// a workgroup stages the queries of its split once and then walks every gridDim.x-th tile in one
-// stream of loads.  A unit is 64
-// cells of one layer of 16 traces: lane (r = lane % 16, g = lane / 16) loads four 16-byte pieces,
-// piece p = cells 16 p + 4 g .. + 3 of trace r (so one load instruction covers 64 contiguous bytes
-// of each trace), and byte j of digit word p is the digit of cell 16 p + 4 g + j.  The query planes
-// lie in LDS in the same order: [digit][query][unit][g][p][j], a lane reads its 16 bytes at once;
-// the stride between queries is an odd number of 16-byte steps, so the sixteen lanes that read
-// one g together touch every bank once.  Cells past E in a row's last unit are zero in the query
-// planes; the traces' pieces there are read from the row's start instead and multiply those zeros.
+// grid (tiles of 64 traces, layer splits, groups of 16 queries), 4 wavefronts of 16 traces each.  A
+// unit is 64 cells of one layer of 16 traces (4 KiB; rows of 256 bytes).  The matrix instruction
+// wants lane (r = lane % 16, g = lane / 16) to hold 16 cells of trace r, so a load into registers
+// would bring 64 bytes of each of 16 rows per instruction, and the compiler moves such loads down
+// to their use (a wavefront then has one unit in flight whatever ring the source spells out).  So
+// the units go from global memory straight into a ring in LDS, whole rows at a time, as
+// instructions the compiler leaves where they are, with wait counts written by hand; lane (r, g)
+// then reads piece p = cells 16 p + 4 g .. + 3 of row r from LDS, and byte j of digit word p is the
+// digit of cell 16 p + 4 g + j.  The query planes lie in LDS in the same order,
+// [digit][query][unit][g][p][j], a lane reads its 16 bytes at once; the stride between queries is
+// an odd number of 16-byte steps, so the sixteen lanes that read one g together touch every bank
+// once.  Cells past E in a row's last unit are zero in the query planes.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr int kMmQueries = 16;
 constexpr int kDigitBits = 7;
 constexpr int kMaxDigits = 4;  // 28 bits: cells up to MOEI_MAX_COUNT (24 bits)
 static_assert(MOEI_MAX_COUNT < (1 << (kDigitBits * kMaxDigits)), "four digits hold every cell");
-// cells an accumulator may take before it is emptied: at most kMaxDigits digit pairs of 127 x 127 each per cell
-constexpr int kMmFlushCells = (int)(0x7fffffffu / (kMaxDigits * 127u * 127u)) / 64 * 64;
-typedef int i32x4 __attribute__((ext_vector_type(4)));
+// Units (of 64 cells) per tile and layer split: what 30 KiB of LDS hold of query planes (two
+// workgroups of 48 KiB of rings each then share a compute unit).  An
+// accumulator takes at most kMaxDigits digit pairs of 127 x 127 per cell, so it cannot overflow.
+constexpr int kMmMaxUnits = 7;
+constexpr int kMmRing = 3;           // units of a wavefront's ring: two in flight while one is multiplied
+constexpr int kMmUnitBytes = 4096;   // 16 traces x 64 cells
+// f(0), f(1), ... while the index is below n (and below MAX), each call nested in the check before it
+template <int U, int MAX, typename F>
+__device__ __forceinline__ void nest_up(int n, F&& f) {
+    if constexpr (U < MAX) {
+        if (U < n) {
+            f(std::integral_constant<int, U>{});
+            nest_up<U + 1, MAX>(n, f);
+        }
+    }
+}
+static_assert((long)kMmMaxUnits * 64 * kMaxDigits * 127 * 127 < 0x7fffffffL, "32-bit sums hold a tile");
 
 struct DotMmArgs {
     const int32_t* traces;  // [L][n_cap][E]
@@ -339,21 +356,48 @@ struct DotMmArgs {
     int nblk;      // units per trace row: ceil(E / 64)
     int n_tiles;   // tiles of 64 J traces
     int q_stride;  // bytes per query in a digit plane: lper * nblk * 64, rounded up to an odd number of 16-byte steps
-    int once;      // the scan exceeds the last-level cache: load with the non-temporal hint
 };
 
-// digit d of four cells, one per byte
-__device__ __forceinline__ int digit4(int4 x, int d) {
-    const unsigned sh = kDigitBits * d;
-    return (int)((((unsigned)x.x >> sh) & 0x7fu) | ((((unsigned)x.y >> sh) & 0x7fu) << 8) |
-                 ((((unsigned)x.z >> sh) & 0x7fu) << 16) | ((((unsigned)x.w >> sh) & 0x7fu) << 24));
+// The first ND 7-bit digits of four cells, digit i of the four cells in the four bytes of d[i].  Byte
+// permutes first gather byte j of the four cells into one word (two words for the two low bytes of
+// each pair, two more to interleave the pairs), then each digit is cut from at most two byte planes
+// with masks that keep every byte to itself: about half the instructions of shifting and masking
+// the cells one by one.
+template <int ND>
+__device__ __forceinline__ void cut_digits(int4 x, int (&d)[ND]);
+template <int ND>
+__device__ __forceinline__ void cut_digits(i32x4 v, int (&d)[ND]) {
+    cut_digits<ND>(make_int4(v[0], v[1], v[2], v[3]), d);
+}
+template <int ND>
+__device__ __forceinline__ void cut_digits(int4 x, int (&d)[ND]) {
+    static_assert(ND >= 1 && ND <= kMaxDigits, "one to four digits");
+    // v_perm_b32: selector bytes 0..3 take bytes of the second operand, 4..7 of the first
+    const unsigned p01 = __builtin_amdgcn_perm((unsigned)x.y, (unsigned)x.x, 0x05010400u);  // x.b0 y.b0 x.b1 y.b1
+    const unsigned p23 = __builtin_amdgcn_perm((unsigned)x.w, (unsigned)x.z, 0x05010400u);  // z.b0 w.b0 z.b1 w.b1
+    const unsigned b0 = __builtin_amdgcn_perm(p23, p01, 0x05040100u);                        // byte 0 of x y z w
+    d[0] = (int)(b0 & 0x7f7f7f7fu);
+    if constexpr (ND >= 2) {
+        const unsigned b1 = __builtin_amdgcn_perm(p23, p01, 0x07060302u);  // byte 1 of x y z w
+        d[1] = (int)(((b1 & 0x3f3f3f3fu) << 1) | ((b0 >> 7) & 0x01010101u));
+        if constexpr (ND >= 3) {
+            const unsigned q01 = __builtin_amdgcn_perm((unsigned)x.y, (unsigned)x.x, 0x07030602u);  // x.b2 y.b2 x.b3 y.b3
+            const unsigned q23 = __builtin_amdgcn_perm((unsigned)x.w, (unsigned)x.z, 0x07030602u);
+            const unsigned b2 = __builtin_amdgcn_perm(q23, q01, 0x05040100u);                        // byte 2 of x y z w
+            d[2] = (int)(((b2 & 0x1f1f1f1fu) << 2) | ((b1 >> 6) & 0x03030303u));
+            if constexpr (ND >= 4) {
+                const unsigned b3 = __builtin_amdgcn_perm(q23, q01, 0x07060302u);  // byte 3 of x y z w
+                d[3] = (int)(((b3 & 0x0f0f0f0fu) << 3) | ((b2 >> 5) & 0x07070707u));
+            }
+        }
+    }
 }
 __device__ __forceinline__ int digits_of(unsigned v) { return v >> 21 ? 4 : (v >> 14 ? 3 : (v >> 7 ? 2 : 1)); }
 inline int digits_of_host(unsigned v) { return v >> 21 ? 4 : (v >> 14 ? 3 : (v >> 7 ? 2 : 1)); }
 
-template <int J, int DA>
+template <int DA>
 __global__ void __launch_bounds__(kDotThreads) eamc_dot_mm_kernel(DotMmArgs a) {
-    extern __shared__ __align__(16) unsigned char smem[];  // [kMaxDigits][16][q_stride]
+    extern __shared__ __align__(16) unsigned char smem[];  // the wavefronts' rings, then [kMaxDigits][16][q_stride] query planes
     __shared__ unsigned s_or[kDotThreads / kWave];
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wv = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -363,178 +407,141 @@ __global__ void __launch_bounds__(kDotThreads) eamc_dot_mm_kernel(DotMmArgs a) {
     const int nl = max(0, min(l0 + a.lper, a.L_scan) - l0);
     const int E = a.E, nblk = a.nblk, S = a.q_stride;
     const size_t plane = (size_t)kMmQueries * S;
-    const int n_units = nl * nblk;
-    // this workgroup's tiles: blockIdx.x, blockIdx.x + gridDim.x, ...  (gridDim.x <= n_tiles)
-    const int n_mine = (a.n_tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
-    const int total = n_mine * n_units;  // units of the whole stream
+    const int n_units = nl * nblk;  // units of the tile: at most kMmMaxUnits
+    const int tile = blockIdx.x;
+    unsigned char* planes = smem + (size_t)(kDotThreads / kWave) * kMmRing * kMmUnitBytes;
 
-    // 1. the first loads of the query rows go out (sixteen threads per query; thread i of them takes
+    // 1. the query rows become digit planes in LDS (sixteen threads per query; thread i of them takes
     // the 16-byte pieces i, i + 16, ... of every layer's row - piece c4 = cells 4 c4 .. + 3: unit
     // c4 / 16, g = c4 % 4, p = c4 % 16 / 4 - eight layers' loads in flight together; a query past B
     // repeats the last one: its column is never stored)
-    constexpr int R = 8;
-    const int qb = tid >> 4, qi = tid & 15;
-    const int32_t* qsrc = a.q + ((size_t)min(b0 + qb, a.B - 1) * a.L + l0) * E;
-    auto load_q = [&](int4 (&x)[R], int c4, int lr) {
+    {
+        constexpr int R = 8;
+        const int qb = tid >> 4, qi = tid & 15;
+        const int32_t* qsrc = a.q + ((size_t)min(b0 + qb, a.B - 1) * a.L + l0) * E;
+        unsigned char* dst = planes + (size_t)qb * S;
+        unsigned seen = 0;
+        for (int c4 = qi; c4 < nblk * 16; c4 += 16) {
+            const int word = ((c4 >> 4) << 6) + ((((c4 & 3) << 2) + ((c4 & 15) >> 2)) << 2);  // byte offset in the row's units
+            for (int lr = 0; lr < nl; lr += R) {
+                int4 x[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r)
-            x[r] = (4 * c4 < E && lr + r < nl) ? *reinterpret_cast<const int4*>(qsrc + (size_t)(lr + r) * E + 4 * c4)
-                                               : make_int4(0, 0, 0, 0);
-    };
-    int4 q_first[R];
-    load_q(q_first, qi, 0);
-
-    // 2. then the first loads of the trace stream (they return after the query rows, which are
-    // cached, and are not waited for until the matrix products start).  The stream runs over the
-    // units of all tiles of the workgroup; this lane's row in layer l0 of a tile is trace
-    // 64 J tile + 16 (wv + 4 jg) + lrow (past N: the last trace, never stored), cell 4 lgrp.
-    constexpr int kAhead = J == 1 ? 4 : 2;  // units in flight per 16-trace group: 16 loads per lane
-    const size_t lstride = (size_t)a.n_cap * E;
-    const int32_t* fbase[J];
-    auto set_base = [&](int tile) {
+                for (int r = 0; r < R; ++r)
+                    x[r] = (4 * c4 < E && lr + r < nl) ? *reinterpret_cast<const int4*>(qsrc + (size_t)(lr + r) * E + 4 * c4)
+                                                       : make_int4(0, 0, 0, 0);
 #pragma unroll
-        for (int jg = 0; jg < J; ++jg)
-            fbase[jg] = a.traces + ((size_t)l0 * a.n_cap + min(64 * J * tile + 16 * (wv + 4 * jg) + lrow, a.N - 1)) * E + 4 * lgrp;
-    };
-    int f_tile = blockIdx.x, f_l = 0, f_blk = 0;  // the next unit to request
-    set_base(f_tile);
-    int4 ring[kAhead][J][4];
-    auto fetch = [&](int4 (&dst)[J][4]) {
-        const size_t row = (size_t)f_l * lstride;
+                for (int r = 0; r < R; ++r)
+                    if (lr + r < nl) {
+                        seen |= (unsigned)(x[r].x | x[r].y | x[r].z | x[r].w);
+                        int dg[kMaxDigits];
+                        cut_digits<kMaxDigits>(x[r], dg);
 #pragma unroll
-        for (int jg = 0; jg < J; ++jg)
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const int c = f_blk * 64 + 16 * p;  // the piece's first cell is c + 4 lgrp
-                const int32_t* src = fbase[jg] + row + (c + 4 * lgrp < E ? c : 0);
-                if (a.once) {
-                    const uint4 v = load_once_16(src);
-                    dst[jg][p] = make_int4((int)v.x, (int)v.y, (int)v.z, (int)v.w);
-                } else {
-                    dst[jg][p] = *reinterpret_cast<const int4*>(src);
-                }
-            }
-        if (++f_blk == nblk) {
-            f_blk = 0;
-            if (++f_l == nl) {
-                f_l = 0;
-                f_tile += gridDim.x;
-                set_base(f_tile);
+                        for (int d = 0; d < kMaxDigits; ++d)
+                            *reinterpret_cast<int*>(dst + d * plane + (size_t)(lr + r) * nblk * 64 + word) = dg[d];
+                    }
             }
         }
-    };
-#pragma unroll
-    for (int d = 0; d < kAhead; ++d)
-        if (d < total) fetch(ring[d]);
-
-    // 3. the query rows become digit planes in LDS
-    {
-        unsigned char* dst = smem + (size_t)qb * S;
-        unsigned seen = 0;
-        auto store_q = [&](const int4 (&x)[R], int c4, int lr) {
-            const int word = ((c4 >> 4) << 6) + ((((c4 & 3) << 2) + ((c4 & 15) >> 2)) << 2);  // byte offset in the row's units
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (lr + r < nl) {
-                    seen |= (unsigned)(x[r].x | x[r].y | x[r].z | x[r].w);
-#pragma unroll
-                    for (int d = 0; d < kMaxDigits; ++d)
-                        *reinterpret_cast<int*>(dst + d * plane + (size_t)(lr + r) * nblk * 64 + word) = digit4(x[r], d);
-                }
-        };
-        store_q(q_first, qi, 0);
-        for (int c4 = qi; c4 < nblk * 16; c4 += 16)
-            for (int lr = (c4 == qi ? R : 0); lr < nl; lr += R) {
-                int4 x[R];
-                load_q(x, c4, lr);
-                store_q(x, c4, lr);
-            }
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) seen |= (unsigned)__shfl_xor((int)seen, off, 64);
         if (lane == 0) s_or[wv] = seen;
     }
-    __syncthreads();
+
+    // 2. the trace stream of this wavefront: 16 traces, unit after unit, through a ring of kMmRing
+    // units in its own part of LDS.  Load instruction p of a unit brings rows 4 p .. 4 p + 3: lane
+    // i the 16-byte chunk of row 4 p + i / 16 that belongs at chunk position i % 16 of the row's
+    // 256 bytes in LDS, which is chunk (i % 16) ^ (row % 16) of the unit's piece of the row (the
+    // reads below then touch every bank once).  An address is a uniform part (layer, tile, unit)
+    // plus this lane's row and chunk as a 32-bit byte offset.  Rows past N repeat the last trace
+    // (never stored); in a row's ragged last unit a chunk past the row's end is read from the row's
+    // last chunk instead (it multiplies zeros).
+    const char* tbytes = reinterpret_cast<const char*>(a.traces);
+    const bool ragged = (E & 63) != 0;
+    unsigned piece_full[4], piece_last[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int row = 4 * p + (lane >> 4);
+        const unsigned r = (unsigned)(min(64 * tile + 16 * wv + row, a.N - 1) - 64 * tile);
+        const int c = (lane & 15) ^ row;  // the chunk: cells 4 c .. + 3 of the unit
+        piece_full[p] = (r * (unsigned)E + 4u * c) * 4u;
+        piece_last[p] = (r * (unsigned)E + (unsigned)min(64 * (nblk - 1) + 4 * c, E - 4)) * 4u;
+    }
+    const uint32_t my_ring = lds_address(smem) + (uint32_t)wv * (kMmRing * kMmUnitBytes);
+    int f_l = 0, f_blk = 0;  // the next unit to request
+    auto fetch = [&](int slot) {
+        const bool last = ragged && f_blk == nblk - 1;  // uniform
+        const char* ubase = tbytes + (((size_t)(l0 + f_l) * a.n_cap + (size_t)64 * tile) * E) * 4 +
+                            (last ? (size_t)0 : (size_t)f_blk * 256);
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+            load16_to_lds(ubase + (last ? piece_last[p] : piece_full[p]), my_ring + (uint32_t)slot * kMmUnitBytes + 1024u * p);
+        if (++f_blk == nblk) {
+            f_blk = 0;
+            ++f_l;
+        }
+    };
+#pragma unroll
+    for (int d = 0; d < kMmRing; ++d)
+        if (d < n_units) fetch(d);
+    __syncthreads();  // the query planes are whole
     static_assert(kDotThreads / kWave == 4, "four wavefronts");
     const int DB = digits_of(s_or[0] | s_or[1] | s_or[2] | s_or[3]);  // uniform over the workgroup
 
+    // 3. the products.  The walk over the tile's units is written out unit by unit, each nested in
+    // the check that it exists, so ring slots and wait counts are compile-time constants.  A unit's
+    // loads have landed once at most those of the units requested after it are outstanding; its
+    // slot is requested again once its pieces have been read out of LDS.  The accumulators cannot
+    // overflow inside a tile and are touched by the matrix instructions alone until its end.
     auto run = [&](auto db_tag) {
         constexpr int DBC = decltype(db_tag)::value;
         constexpr int NW = DA + DBC - 1;  // weights 128^0 .. 128^(NW - 1)
-        i32x4 acc[J][NW];
-        u64 tot[J][4];
+        const unsigned char* qrow = planes + (size_t)lrow * S + lgrp * 16;
+        const unsigned char* ring = smem + (size_t)wv * (kMmRing * kMmUnitBytes);
+        i32x4 acc[NW];
 #pragma unroll
-        for (int jg = 0; jg < J; ++jg) {
+        for (int w = 0; w < NW; ++w) acc[w] = i32x4{0, 0, 0, 0};
+        nest_up<0, kMmMaxUnits>(n_units, [&](auto u_tag) {
+            constexpr int U = decltype(u_tag)::value;
+            constexpr int D = U % kMmRing;
+            // units requested after this one: min(kMmRing - 1, n_units - 1 - U)
+            if (U + 2 < n_units)
+                wait_vm_fence<8>();
+            else if (U + 1 < n_units)
+                wait_vm_fence<4>();
+            else
+                wait_vm_fence<0>();
+            static_assert(kMmRing == 3, "the wait counts above are those of a ring of three");
+            i32x4 x[4];
 #pragma unroll
-            for (int w = 0; w < NW; ++w) acc[jg][w] = i32x4{0, 0, 0, 0};
+            for (int p = 0; p < 4; ++p)
+                x[p] = *reinterpret_cast<const i32x4*>(ring + D * kMmUnitBytes + lrow * 256 + (((4 * p + lgrp) ^ lrow) << 4));
+            i32x4 bq[DBC];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) tot[jg][v] = 0;
-        }
-        auto flush = [&]() {
+            for (int db = 0; db < DBC; ++db) bq[db] = *reinterpret_cast<const i32x4*>(qrow + db * plane + (size_t)U * 64);
+            int dg[4][DA];
 #pragma unroll
-            for (int jg = 0; jg < J; ++jg)
+            for (int p = 0; p < 4; ++p) cut_digits<DA>(x[p], dg[p]);
+            if (U + kMmRing < n_units) {
+                wait_lds_fence();  // the slot has been read
+                fetch(D);
+            }
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    u64 t = 0;
+            for (int da = 0; da < DA; ++da) {
+                const i32x4 ad = {dg[0][da], dg[1][da], dg[2][da], dg[3][da]};
 #pragma unroll
-                    for (int w = 0; w < NW; ++w) t += (u64)(unsigned)acc[jg][w][v] << (kDigitBits * w);
-                    tot[jg][v] += t;
-                }
+                for (int db = 0; db < DBC; ++db)
+                    acc[da + db] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ad, bq[db], acc[da + db], 0, 0, 0);
+            }
+        });
+        // D[trace 4 lgrp + v][query lrow]
+        if (b0 + lrow < a.B) {
+            u64* out = a.part + ((size_t)(b0 + lrow) * a.n_lsplit + split) * a.n_cap;
 #pragma unroll
-            for (int jg = 0; jg < J; ++jg)
+            for (int v = 0; v < 4; ++v) {
+                u64 t = 0;
 #pragma unroll
-                for (int w = 0; w < NW; ++w) acc[jg][w] = i32x4{0, 0, 0, 0};
-        };
-        int cells = 0, cu = 0, c_tile = blockIdx.x;  // the unit being multiplied: unit cu of tile c_tile
-        const unsigned char* qrow = smem + (size_t)lrow * S + lgrp * 16;
-        for (int g0 = 0; g0 < total; g0 += kAhead) {
-#pragma unroll
-            for (int d = 0; d < kAhead; ++d) {
-                const int g = g0 + d;
-                if (g < total) {  // uniform over the workgroup
-                    int4 x[J][4];
-#pragma unroll
-                    for (int jg = 0; jg < J; ++jg)
-#pragma unroll
-                        for (int p = 0; p < 4; ++p) x[jg][p] = ring[d][jg][p];
-                    if (g + kAhead < total) fetch(ring[d]);
-                    i32x4 bq[DBC];
-#pragma unroll
-                    for (int db = 0; db < DBC; ++db) bq[db] = *reinterpret_cast<const i32x4*>(qrow + db * plane + (size_t)cu * 64);
-#pragma unroll
-                    for (int jg = 0; jg < J; ++jg)
-#pragma unroll
-                        for (int da = 0; da < DA; ++da) {
-                            const i32x4 ad = {digit4(x[jg][0], da), digit4(x[jg][1], da), digit4(x[jg][2], da), digit4(x[jg][3], da)};
-#pragma unroll
-                            for (int db = 0; db < DBC; ++db)
-                                acc[jg][da + db] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ad, bq[db], acc[jg][da + db], 0, 0, 0);
-                        }
-                    cells += 64;
-                    if (++cu == n_units) {
-                        // the tile is done: D[trace 4 lgrp + v][query lrow]
-                        flush();
-                        if (b0 + lrow < a.B) {
-                            u64* out = a.part + ((size_t)(b0 + lrow) * a.n_lsplit + split) * a.n_cap;
-#pragma unroll
-                            for (int jg = 0; jg < J; ++jg)
-#pragma unroll
-                                for (int v = 0; v < 4; ++v) {
-                                    const int n = 64 * J * c_tile + 16 * (wv + 4 * jg) + 4 * lgrp + v;
-                                    if (n < a.N) out[n] = tot[jg][v];
-                                }
-                        }
-#pragma unroll
-                        for (int jg = 0; jg < J; ++jg)
-#pragma unroll
-                            for (int v = 0; v < 4; ++v) tot[jg][v] = 0;
-                        cu = 0;
-                        cells = 0;
-                        c_tile += gridDim.x;
-                    } else if (cells >= kMmFlushCells) {
-                        flush();
-                        cells = 0;
-                    }
-                }
+                for (int w = 0; w < NW; ++w) t += (u64)(unsigned)acc[w][v] << (kDigitBits * w);
+                const int n = 64 * tile + 16 * wv + 4 * lgrp + v;
+                if (n < a.N) out[n] = t;
             }
         }
     };
@@ -1083,30 +1090,26 @@ int launch_dot_j(const Plan& p, const DotArgs& a, dim3 grid, hipStream_t s) {
 }
 
 // The plan of the matrix-core scan: tiles of 64 J traces, layer splits that keep the query planes of
-// a split within 64 KiB of LDS, and about two workgroups per compute unit, each walking several tiles.
+// a split within 64 KiB of LDS (more splits where the tiles alone do not fill the chip).
 struct MmPlan {
     bool ok;
-    int J, n_tiles, grid_x, n_lsplit, lper, nblk, q_stride, DA;
+    int n_tiles, n_lsplit, lper, nblk, q_stride, DA;
     size_t smem;
 };
 
+// The plan of the matrix-core scan: tiles of 64 traces and the layer splits that keep a split's units
+// within kMmMaxUnits (more splits where the tiles alone do not fill the chip).
 MmPlan make_mm_plan(const moei_eamc* c, int L_scan, int B) {
-    static const int kForceJ = getenv("MOEI_MATCH_MM_J") ? atoi(getenv("MOEI_MATCH_MM_J")) : 0;
     static const int kTarget = getenv("MOEI_MATCH_MM_BLOCKS") ? atoi(getenv("MOEI_MATCH_MM_BLOCKS")) : 0;
     static const int kSplits = getenv("MOEI_MATCH_MM_SPLITS") ? atoi(getenv("MOEI_MATCH_MM_SPLITS")) : 0;
     MmPlan p{};
     const int E = c->d.E;
     p.nblk = (E + 63) / 64;
-    const int lper_max = 15 / p.nblk;  // 4 planes x 16 queries x (lper nblk 64 + 16) bytes <= 64 KiB
+    const int lper_max = kMmMaxUnits / p.nblk;
     if (lper_max < 1) return p;
-    const size_t scan_bytes = (size_t)c->N * L_scan * E * 4;
-    // 64 traces per tile; 128 only for scans so long that the tiles alone give every compute unit several workgroups
-    p.J = kForceJ == 1 || kForceJ == 2 ? kForceJ : (scan_bytes >= ((size_t)512 << 20) ? 2 : 1);
-    p.n_tiles = (c->N + 64 * p.J - 1) / (64 * p.J);
+    p.n_tiles = (c->N + 63) / 64;
     const int groups = (B + kMmQueries - 1) / kMmQueries;
-    const int target = kTarget > 0 ? kTarget : 450;  // measured at 10,000 traces of 26 x 64 cells: 3 splits 16.2 us, 2 splits 20.4, 4 splits 17.4
-    // layer splits: as few as the LDS allows (every split writes a partial sum per trace and query that
-    // the pick reads again), more only where the tiles alone do not fill the chip
+    const int target = kTarget > 0 ? kTarget : 512;
     const int lmax = L_scan < c->lsplit_max ? L_scan : c->lsplit_max;
     const int min_split = (L_scan + lper_max - 1) / lper_max;
     int want = kSplits > 0 ? kSplits : (target + p.n_tiles * groups - 1) / (p.n_tiles * groups);
@@ -1115,35 +1118,33 @@ MmPlan make_mm_plan(const moei_eamc* c, int L_scan, int B) {
     if (p.n_lsplit < min_split) return p;
     p.lper = (L_scan + p.n_lsplit - 1) / p.n_lsplit;
     p.n_lsplit = (L_scan + p.lper - 1) / p.lper;
-    // workgroups along the tiles: each takes every grid_x-th tile and stages its queries once
-    p.grid_x = target / (p.n_lsplit * groups);
-    if (p.grid_x < 1) p.grid_x = 1;
-    if (p.grid_x > p.n_tiles) p.grid_x = p.n_tiles;
-    p.grid_x = (p.n_tiles + (p.n_tiles + p.grid_x - 1) / p.grid_x - 1) / ((p.n_tiles + p.grid_x - 1) / p.grid_x);  // the same count of tiles each, but for the last
     p.q_stride = p.lper * p.nblk * 64;
     if ((p.q_stride / 16) % 2 == 0) p.q_stride += 16;
-    p.smem = (size_t)kMaxDigits * kMmQueries * p.q_stride;
+    p.smem = (size_t)(kDotThreads / kWave) * kMmRing * kMmUnitBytes + (size_t)kMaxDigits * kMmQueries * p.q_stride;
     p.DA = digits_of_host((unsigned)c->max_cell);
-    p.ok = p.smem <= 64 * 1024 - 64;
+    p.ok = true;
     return p;
 }
 
 int launch_dot_mm(const MmPlan& p, const DotMmArgs& a, dim3 grid, hipStream_t s) {
-#define MOEI_MM_CASE(JJ, DD)                                                                         \
-    case (JJ) * 8 + (DD):                                                                            \
-        launch(K_MATCH_DOT, eamc_dot_mm_kernel<JJ, DD>, grid, dim3(kDotThreads), p.smem, s, a);     \
-        break;
-    switch (p.J * 8 + p.DA) {
-        MOEI_MM_CASE(1, 1)
-        MOEI_MM_CASE(1, 2)
-        MOEI_MM_CASE(1, 3)
-        MOEI_MM_CASE(1, 4)
-        MOEI_MM_CASE(2, 1)
-        MOEI_MM_CASE(2, 2)
-        MOEI_MM_CASE(2, 3)
-        MOEI_MM_CASE(2, 4)
+#define MOEI_MM_CASE(DD)                                                                          \
+    case DD: {                                                                                    \
+        static bool allowed = false; /* more than 64 KiB of dynamic LDS must be asked for once */ \
+        if (!allowed) {                                                                           \
+            MOEI_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(eamc_dot_mm_kernel<DD>),   \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024)); \
+            allowed = true;                                                                       \
+        }                                                                                         \
+        launch(K_MATCH_DOT, eamc_dot_mm_kernel<DD>, grid, dim3(kDotThreads), p.smem, s, a);      \
+        break;                                                                                    \
+    }
+    switch (p.DA) {
+        MOEI_MM_CASE(1)
+        MOEI_MM_CASE(2)
+        MOEI_MM_CASE(3)
+        MOEI_MM_CASE(4)
         default:
-            MOEI_FAIL(MOEI_EINVAL, "eamc_match: no matrix-core scan for %d groups per wavefront and %d digits", p.J, p.DA);
+            MOEI_FAIL(MOEI_EINVAL, "eamc_match: no matrix-core scan for %d digits", p.DA);
     }
 #undef MOEI_MM_CASE
     MOEI_LAUNCH_CHECK();
@@ -1406,10 +1407,9 @@ int launch_dots(const moei_eamc* c, const int32_t* d_eam, int B, int layer_hi, i
         const MmPlan mp = make_mm_plan(c, layer_hi + 1, B);
         if (mp.ok) {
             *n_lsplit = mp.n_lsplit;
-            const size_t bytes = (size_t)c->N * (layer_hi + 1) * E * 4;
             DotMmArgs ma{reinterpret_cast<const int32_t*>(c->d_traces), d_eam, c->d_part, c->n_cap, c->N, L, E, B,
-                         layer_hi + 1, mp.lper, mp.n_lsplit, mp.nblk, mp.n_tiles, mp.q_stride, bytes > ((size_t)192 << 20)};
-            return launch_dot_mm(mp, ma, dim3(mp.grid_x, mp.n_lsplit, (B + kMmQueries - 1) / kMmQueries), s);
+                         layer_hi + 1, mp.lper, mp.n_lsplit, mp.nblk, mp.n_tiles, mp.q_stride};
+            return launch_dot_mm(mp, ma, dim3(mp.n_tiles, mp.n_lsplit, (B + kMmQueries - 1) / kMmQueries), s);
         }
     }
     // b.  One or two queries, 2-byte cells, other shapes: the scan on the vector ALUs

@@ -471,17 +471,6 @@ constexpr int kWdThreads = 512;
 constexpr int kWdStageElems = 256 * kWdKS;  // a stage of either ring: 256 rows
 __device__ __forceinline__ int wd_pos(int row, int chunk) { return row * kWdKS + ((chunk ^ ((row >> 1) & 7)) << 3); }
 
-// A 16-byte load per lane that goes from global memory straight into LDS: the wavefront's 64 pieces
-// land side by side, 1 KiB from `lds_addr` on (an LDS byte address, the same in every lane).  The
-// load counts as a vector memory operation of the wavefront (vmcnt); nothing says when the data is
-// in LDS but a later wait on that counter.  m0 (the LDS base of such loads) is a register the
-// compiler reserves and sets itself right before each of its own uses, so writing it here is safe.
-__device__ __forceinline__ void load16_to_lds(const void* gsrc, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gsrc) : "memory");
-}
-__device__ __forceinline__ uint32_t lds_address(const void* p) {
-    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
-}
 // waits until at most `stages` * 8 of this wavefront's vector memory operations are outstanding
 __device__ __forceinline__ void wait_but_stages(int stages) {
     // s_waitcnt: vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima
