@@ -1267,9 +1267,9 @@ int launch_prefill(const moei_model_desc& d, const PrefillScratch& ps, const voi
     if ((uintptr_t)d_X % 16 != 0 || (uintptr_t)d_pool % 16 != 0 || (slot_elems * 2) % 16 != 0 || (uintptr_t)d_Y % 16 != 0)
         MOEI_FAIL(MOEI_EINVAL, "moe_prefill_layer: buffers must be 16-byte aligned");
     const int vec_ok = (d.H % 8 == 0) && ((uintptr_t)d_router_w % 16 == 0);
-    // long prompts: the logits on the matrix cores (a workgroup of that kernel takes ~15 us whatever n; the
-    // kernel with a workgroup per token takes 11 us at 512 tokens, 22 us at 1,024 and 46 us at 2,048)
-    if (n >= 1024 && d.E <= kRtMaxE && d.H % 128 == 0 && (uintptr_t)d_router_w % 16 == 0) {
+    // long prompts: the logits on the matrix cores (that kernel takes 15 - 18 us whatever n; the kernel
+    // with a workgroup per token takes 11 us at 256 tokens, 19 us at 512, 22 us at 1,024 and 46 us at 2,048)
+    if (n >= 512 && d.E <= kRtMaxE && d.H % 128 == 0 && (uintptr_t)d_router_w % 16 == 0) {
         const int nbw = rt_blocks_per_wave(d.E);
         const dim3 rgrid((n + kRtTok - 1) / kRtTok), rblock(kRtThreads);
         const size_t rsmem = rt_lds_bytes(d.E);

@@ -160,7 +160,7 @@ def test_prefill_every_item_size_on_one_prompt(m, tile, monkeypatch):
 
 @pytest.mark.parametrize("E,k,n", [(40, 4, 1030), (100, 6, 1027), (160, 6, 1100), (256, 8, 1277)])
 def test_prefill_long_prompt_routing_over_expert_counts(m, E, k, n):
-    # prompts of 1,024 tokens and more form their logits in the routing kernel that runs on the matrix
+    # prompts of 512 tokens and more form their logits in the routing kernel that runs on the matrix
     # cores, sixteen tokens per workgroup: fewer row groups than wavefronts (E = 40), a ragged last
     # 16-expert block (100), three and four blocks per wavefront (160, 256); n is no multiple of 16.
     # Every token's picks, gate weights and the EAM in full, the outputs of 12 sampled tokens.
