@@ -146,7 +146,6 @@ void prefill_scratch_free(PrefillScratch* p) {
     (void)hipFree(p->d_where);
     (void)hipFree(p->d_items);
     (void)hipFree(p->d_meta);
-    (void)hipFree(p->d_cntw);
     (void)hipFree(p->d_act);
     (void)hipFree(p->d_yc);
     *p = PrefillScratch{};
@@ -667,7 +666,6 @@ extern "C" int moe_prefill_layer(moei_cache* c, int32_t* d_eam, int32_t layer, c
         if (e == hipSuccess) e = hipMalloc((void**)&p.d_where, nk * 4);
         if (e == hipSuccess) e = hipMalloc(&p.d_items, (size_t)prefill_max_items(d, n_max) * prefill_item_bytes());
         if (e == hipSuccess) e = hipMalloc((void**)&p.d_meta, 8);
-        if (e == hipSuccess) e = hipMalloc((void**)&p.d_cntw, (size_t)d.E * 4 * 4);
         if (e == hipSuccess) e = hipMalloc((void**)&p.d_act, prefill_rows(d, n_max) * d.I * 2);
         if (e == hipSuccess) e = hipMalloc((void**)&p.d_yc, prefill_rows(d, n_max) * d.H * sizeof(float));
         if (e != hipSuccess) {

@@ -70,7 +70,6 @@ struct PrefillScratch {
     int32_t* d_where = nullptr;  // [n_max*k] row of every (token, pick)
     void* d_items = nullptr;
     int32_t* d_meta = nullptr;  // [2]
-    int32_t* d_cntw = nullptr;  // [E][4]
     uint16_t* d_act = nullptr;  // [n_max*(k+n_shared)][I] activations, bf16
     float* d_yc = nullptr;      // [n_max*(k+n_shared)][H] contributions
 };

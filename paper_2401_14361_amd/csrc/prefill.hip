@@ -1,12 +1,11 @@
 // The prefill iteration of one MoE layer: all n prompt tokens pass the layer together.
 //
 // Sec. 4.3 of the paper: an iteration routes n tokens and every token adds its k picks to
-// row l of the request's EAM.  Four launches:
+// row l of the request's EAM.  Five launches:
 //   1. prefill_route_kernel   router logits + softmax/top-k, one wavefront per token (the
 //                             same summation order as the decode routing, so the same bits)
-//   2. prefill_count_kernel / prefill_place_kernel
-//                             histogram of the picks -> EAM row; tokens grouped per expert in
-//                             ascending token order, cut into items of <= 64 tokens
+//   2. prefill_group_kernel   histogram of the picks -> EAM row; tokens grouped per expert in
+//                             ascending token order, cut into items of <= 64 (long prompts: 256) tokens
 //   3. prefill_gateup_kernel, prefill_down_kernel
 //                             grouped SwiGLU expert FFN on the matrix cores as two tiled products
 //                             per item; an expert's weights pass once per item
@@ -142,7 +141,6 @@ struct GroupArgsP {
     int32_t* where;    // [n*k] row (= position in perm) of every routed (token, pick)
     PItem* items;
     int32_t* meta;  // [0] = items in all, [1] = routed items
-    int32_t* cntw;  // [E][4] tokens that pick the expert, per wavefront range of the grouping kernels
     int32_t* flags;
     int spread_shared;  // list the items so that all items of a shared expert fall on one XCD of the wide kernels
 };
@@ -163,31 +161,49 @@ __device__ __forceinline__ int pick_of(const GroupArgsP& g, int t, int e) {
 // tokens [w*span, (w+1)*span) belong to wavefront w of an expert's workgroup
 __device__ __forceinline__ int group_span(int n) { return ((n + kGrpWaves - 1) / kGrpWaves + kWave - 1) / kWave * kWave; }
 
-// 2a. grid E: how many tokens pick expert e, per wavefront range -> cntw[e][kGrpWaves]
-__global__ void __launch_bounds__(kGrpThreads) prefill_count_kernel(GroupArgsP g) {
-    const int e = blockIdx.x, lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
-    const int span = group_span(g.n);
-    int c = 0;
-    for (int t0 = wv * span; t0 < min(g.n, (wv + 1) * span); t0 += kWave)
-        c += __popcll(__ballot(pick_of(g, t0 + lane, e) >= 0));
-    if (lane == 0) g.cntw[e * kGrpWaves + wv] = c;
-}
-
-// 2b. grid E: offsets by a prefix over the counts, EAM row update, placement in ascending
-// token order, the expert's items; workgroup 0 also lists the shared experts' items.
-__global__ void __launch_bounds__(kGrpThreads) prefill_place_kernel(GroupArgsP g) {
+// 2. grid E, dynamic LDS E ints.  Every workgroup first forms the histogram of all picks for itself (a
+// few thousand LDS additions: less than the launch a kernel of its own for it would cost) and, in
+// the same pass, the count of its own expert per wavefront range; then offsets by a prefix over the
+// counts, EAM row update, placement in ascending token order, the expert's items; workgroup 0 also
+// lists the shared experts' items.
+__global__ void __launch_bounds__(kGrpThreads) prefill_group_kernel(GroupArgsP g) {
+    extern __shared__ int s_hist[];  // [E] tokens that pick each expert
     __shared__ int s_red[3][kGrpWaves];
+    __shared__ int s_cw[kGrpWaves];  // tokens that pick this expert, per wavefront range
     const int e = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    for (int f = tid; f < g.E; f += kGrpThreads) s_hist[f] = 0;
+    __syncthreads();
+    const int span = group_span(g.n);
+    {
+        // the picks of this wavefront's token range are one run of integers: read flat (a token's picks are
+        // distinct, so the picks equal to e count the tokens that pick it), eight loads in flight per lane
+        const int p0 = wv * span * g.k, p1 = min(g.n, (wv + 1) * span) * g.k;
+        int c = 0;
+        for (int i0 = p0; i0 < p1; i0 += 8 * kWave) {
+            int f[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kWave + lane;
+                f[u] = i < p1 ? g.idx[i] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if ((unsigned)f[u] < (unsigned)g.E) atomicAdd(&s_hist[f[u]], 1);  // (a token without a softmax has picks -1)
+                c += f[u] == e ? 1 : 0;
+            }
+        }
+        c = (int)wave_sum_u32_dpp((unsigned)c);
+        if (lane == 0) s_cw[wv] = c;
+    }
+    __syncthreads();
     // tokens of the experts before this one (the grouped rows stay in expert order); items of the
     // experts that come before it in the item list, which runs from the expert with the most tokens to the
     // one with the fewest (equal counts: by index), so that the matrix kernels' longest workgroups start
     // first; items of all experts
-    int my_c = 0;
-    for (int w = 0; w < kGrpWaves; ++w) my_c += g.cntw[e * kGrpWaves + w];
+    const int my_c = s_hist[e];
     int toks = 0, its = 0, its_all = 0;
     for (int f = tid; f < g.E; f += kGrpThreads) {
-        int c = 0;
-        for (int w = 0; w < kGrpWaves; ++w) c += g.cntw[f * kGrpWaves + w];
+        const int c = s_hist[f];
         const int ni = (c + g.TM - 1) / g.TM;
         if (f < e) toks += c;
         if (c > my_c || (c == my_c && f < e)) its += ni;
@@ -207,24 +223,28 @@ __global__ void __launch_bounds__(kGrpThreads) prefill_place_kernel(GroupArgsP g
         off += s_red[0][w];
         ioff += s_red[1][w];
         n_routed += s_red[2][w];
-        const int cw = g.cntw[e * kGrpWaves + w];
+        const int cw = s_cw[w];
         if (w < wv) before += cw;
         cnt += cw;
     }
     if (tid == 0) g.eam_row[e] += cnt;  // Sec. 4.3: the n tokens add n*k to row l
-    const int span = group_span(g.n);
     int pos = before;
-    for (int t0 = wv * span; t0 < min(g.n, (wv + 1) * span); t0 += kWave) {
-        const int t = t0 + lane;
-        const int j = pick_of(g, t, e);
-        const unsigned long long mask = __ballot(j >= 0);
-        if (j >= 0) {
-            const int r = pos + __popcll(mask & ((1ull << lane) - 1ull));
-            g.perm[off + r] = t;
-            g.pgate[off + r] = g.w[(size_t)t * g.k + j];
-            g.where[(size_t)t * g.k + j] = off + r;
+    for (int t0 = wv * span; t0 < min(g.n, (wv + 1) * span); t0 += 4 * kWave) {
+        int jj[4];  // four 64-token groups' lookups go out together
+#pragma unroll
+        for (int u = 0; u < 4; ++u) jj[u] = pick_of(g, t0 + u * kWave + lane < min(g.n, (wv + 1) * span) ? t0 + u * kWave + lane : g.n, e);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int t = t0 + u * kWave + lane, j = jj[u];
+            const unsigned long long mask = __ballot(j >= 0);
+            if (j >= 0) {
+                const int r = pos + __popcll(mask & ((1ull << lane) - 1ull));
+                g.perm[off + r] = t;
+                g.pgate[off + r] = g.w[(size_t)t * g.k + j];
+                g.where[(size_t)t * g.k + j] = off + r;
+            }
+            pos += __popcll(mask);
         }
-        pos += __popcll(mask);
     }
     const int slot = g.slot_of_row[e];
     if (cnt > 0 && slot < 0 && tid == 0) atomicOr(g.flags, 2);
@@ -1301,11 +1321,9 @@ int launch_prefill(const moei_model_desc& d, const PrefillScratch& ps, const voi
     MOEI_LAUNCH_CHECK();
     const int tm = tile_tokens(d, n);
     GroupArgsP g{ps.d_idx, ps.d_w, n, d.k, d.E, d.n_shared, tm, d_slot_of_row, shared_base, d_eam_row, ps.d_perm,
-                 ps.d_pgate, ps.d_where, reinterpret_cast<PItem*>(ps.d_items), ps.d_meta, ps.d_cntw, d_flags,
+                 ps.d_pgate, ps.d_where, reinterpret_cast<PItem*>(ps.d_items), ps.d_meta, d_flags,
                  tm == kTileTokWide};
-    launch(K_FFN_GROUP, prefill_count_kernel, dim3(d.E), dim3(kGrpThreads), 0, s, g);
-    MOEI_LAUNCH_CHECK();
-    launch(K_FFN_GROUP, prefill_place_kernel, dim3(d.E), dim3(kGrpThreads), 0, s, g);
+    launch(K_FFN_GROUP, prefill_group_kernel, dim3(d.E), dim3(kGrpThreads), (size_t)d.E * sizeof(int), s, g);
     MOEI_LAUNCH_CHECK();
     // the number of items is known on the device only: the grids cover the largest possible count
     const int max_items = max_items_for(d, n, tm);
