@@ -1400,10 +1400,13 @@ int launch_dots(const moei_eamc* c, const int32_t* d_eam, int B, int layer_hi, i
     const int L = c->d.L, E = c->d.E;
     *n_lsplit = 0;
     if (c->N == 0) return MOEI_OK;
-    // a.  Three queries and more: the scan as a matrix product (4-byte cells, rows of whole 16-byte
-    // pieces); it takes the same time for 3 as for 16 queries, and for two the kernel below is faster
+    // a.  Three queries and more (five and more for rows of several units, where a split holds few layers):
+    // the scan as a matrix product (4-byte cells, rows of whole 16-byte pieces); it takes the same time
+    // for 3 as for 16 queries.  Measured at 10,000 traces: 26 x 64 cells, 4 queries 27.8 against 28.2 us
+    // and 16 queries 29.3 against 44.7 us; 59 x 160 cells, 4 queries 100 against 84 us and 16 queries 111
+    // against 207 us.
     static const bool kNoMm = getenv("MOEI_MATCH_NO_MM") && atoi(getenv("MOEI_MATCH_NO_MM")) != 0;
-    if (B >= 3 && !kNoMm && c->cell_bytes == 4 && E % 4 == 0 && (uintptr_t)d_eam % 16 == 0) {
+    if (B >= (E <= 64 ? 3 : 5) && !kNoMm && c->cell_bytes == 4 && E % 4 == 0 && (uintptr_t)d_eam % 16 == 0) {
         const MmPlan mp = make_mm_plan(c, layer_hi + 1, B);
         if (mp.ok) {
             *n_lsplit = mp.n_lsplit;

@@ -168,6 +168,19 @@ def test_eamc_match_batches_over_cell_sizes(m, t_hi, q_hi):
     _check_match(m, T, Q, 4, layer_hi=4)
 
 
+@pytest.mark.parametrize("N,L,E,B", [(300, 5, 160, 6), (130, 3, 448, 16), (65, 4, 452, 7), (100, 2, 512, 8)])
+def test_eamc_match_batches_over_row_widths(m, N, L, E, B):
+    # rows of several 64-cell units: 2.5 units (the DeepSeek-V2 width), 7 (the most a layer split holds), 7 with
+    # a ragged last one, and 8 (too wide for the matrix-core scan: served by the other kernel)
+    rng = np.random.default_rng(N + E)
+    T = (rng.integers(0, 900, size=(N, L, E)) * (rng.random((N, L, E)) < 0.3)).astype(np.int32)
+    Q = (rng.integers(0, 200, size=(B, L, E)) * (rng.random((B, L, E)) < 0.5)).astype(np.int32)
+    T[3, L - 1, E - 1] = 899
+    Q[0, L - 1, E - 1] = 199
+    Q[B - 1] = T[N - 1]
+    _check_match(m, T, Q, 4)
+
+
 def test_eamc_match_batch_after_an_insert_with_larger_cells(m):
     # the number of digit planes of the traces follows the largest cell ever stored: a trace inserted
     # later may raise it
