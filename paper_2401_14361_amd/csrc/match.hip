@@ -334,7 +334,6 @@ static_assert(MOEI_MAX_COUNT < (1 << (kDigitBits * kMaxDigits)), "four digits ho
 // accumulator takes at most kMaxDigits digit pairs of 127 x 127 per cell, so it cannot overflow.
 constexpr int kMmMaxUnits = 7;
 constexpr int kMmRing = 3;           // units of a wavefront's ring: two in flight while one is multiplied
-constexpr int kMmUnitBytes = 4096;   // 16 traces x 64 cells
 // f(0), f(1), ... while the index is below n (and below MAX), each call nested in the check before it
 template <int U, int MAX, typename F>
 __device__ __forceinline__ void nest_up(int n, F&& f) {
@@ -348,9 +347,9 @@ __device__ __forceinline__ void nest_up(int n, F&& f) {
 static_assert((long)kMmMaxUnits * 64 * kMaxDigits * 127 * 127 < 0x7fffffffL, "32-bit sums hold a tile");
 
 struct DotMmArgs {
-    const int32_t* traces;  // [L][n_cap][E]
-    const int32_t* q;       // [B][L][E]
-    u64* part;              // [B][n_lsplit][n_cap]
+    const void* traces;  // [L][n_cap][E] cells of 4 or 2 bytes
+    const int32_t* q;    // [B][L][E]
+    u64* part;           // [B][n_lsplit][n_cap]
     int n_cap, N, L, E, B;
     int L_scan, lper, n_lsplit;
     int nblk;      // units per trace row: ceil(E / 64)
@@ -392,11 +391,27 @@ __device__ __forceinline__ void cut_digits(int4 x, int (&d)[ND]) {
         }
     }
 }
+// The same for four 2-byte cells in two words (cells 0, 1 in w0, cells 2, 3 in w1): up to three digits.
+template <int ND>
+__device__ __forceinline__ void cut_digits16(unsigned w0, unsigned w1, int (&d)[ND]) {
+    static_assert(ND >= 1 && ND <= 3, "16 bits are three digits at most");
+    const unsigned b0 = __builtin_amdgcn_perm(w1, w0, 0x06040200u);  // the low bytes of the four cells
+    d[0] = (int)(b0 & 0x7f7f7f7fu);
+    if constexpr (ND >= 2) {
+        const unsigned b1 = __builtin_amdgcn_perm(w1, w0, 0x07050301u);  // their high bytes
+        d[1] = (int)(((b1 & 0x3f3f3f3fu) << 1) | ((b0 >> 7) & 0x01010101u));
+        if constexpr (ND >= 3) d[2] = (int)((b1 >> 6) & 0x03030303u);
+    }
+}
 __device__ __forceinline__ int digits_of(unsigned v) { return v >> 21 ? 4 : (v >> 14 ? 3 : (v >> 7 ? 2 : 1)); }
 inline int digits_of_host(unsigned v) { return v >> 21 ? 4 : (v >> 14 ? 3 : (v >> 7 ? 2 : 1)); }
 
-template <int DA>
+template <int DA, int CB>  // digit planes of the traces; bytes per stored cell (4 or 2)
 __global__ void __launch_bounds__(kDotThreads) eamc_dot_mm_kernel(DotMmArgs a) {
+    constexpr int UB = 64 * 16 * CB;      // bytes of a unit: 16 rows of 64 cells
+    constexpr int RB = 64 * CB;           // bytes of a unit's row in LDS
+    constexpr int NLD = UB / 1024;        // load instructions per unit
+    constexpr int CPC = 16 / CB;          // cells per 16-byte chunk
     extern __shared__ __align__(16) unsigned char smem[];  // the wavefronts' rings, then [kMaxDigits][16][q_stride] query planes
     __shared__ unsigned s_or[kDotThreads / kWave];
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
@@ -409,7 +424,7 @@ __global__ void __launch_bounds__(kDotThreads) eamc_dot_mm_kernel(DotMmArgs a) {
     const size_t plane = (size_t)kMmQueries * S;
     const int n_units = nl * nblk;  // units of the tile: at most kMmMaxUnits
     const int tile = blockIdx.x;
-    unsigned char* planes = smem + (size_t)(kDotThreads / kWave) * kMmRing * kMmUnitBytes;
+    unsigned char* planes = smem + (size_t)(kDotThreads / kWave) * kMmRing * UB;
 
     // 1. the query rows become digit planes in LDS (sixteen threads per query; thread i of them takes
     // the 16-byte pieces i, i + 16, ... of every layer's row - piece c4 = cells 4 c4 .. + 3: unit
@@ -447,33 +462,33 @@ __global__ void __launch_bounds__(kDotThreads) eamc_dot_mm_kernel(DotMmArgs a) {
     }
 
     // 2. the trace stream of this wavefront: 16 traces, unit after unit, through a ring of kMmRing
-    // units in its own part of LDS.  Load instruction p of a unit brings rows 4 p .. 4 p + 3: lane
-    // i the 16-byte chunk of row 4 p + i / 16 that belongs at chunk position i % 16 of the row's
-    // 256 bytes in LDS, which is chunk (i % 16) ^ (row % 16) of the unit's piece of the row (the
-    // reads below then touch every bank once).  An address is a uniform part (layer, tile, unit)
-    // plus this lane's row and chunk as a 32-bit byte offset.  Rows past N repeat the last trace
-    // (never stored); in a row's ragged last unit a chunk past the row's end is read from the row's
-    // last chunk instead (it multiplies zeros).
+    // units in its own part of LDS.  A load instruction fills 1 KiB: rows 4 p .. 4 p + 3 of the unit
+    // (4-byte cells: rows of 256 bytes, 16 chunks of 16 bytes) or rows 8 p .. 8 p + 7 (2-byte cells:
+    // rows of 128 bytes, 8 chunks); the lane that fills chunk position q of row r brings the row's
+    // chunk q ^ (r % 16) resp. q ^ (r / 2 % 8), so that the reads below touch every bank once.  An
+    // address is a uniform part (layer, tile, unit) plus this lane's row and chunk as a 32-bit byte
+    // offset.  Rows past N repeat the last trace (never stored); in a row's ragged last unit a
+    // chunk past the row's end is read from the row's last chunk instead (it multiplies zeros).
     const char* tbytes = reinterpret_cast<const char*>(a.traces);
     const bool ragged = (E & 63) != 0;
-    unsigned piece_full[4], piece_last[4];
+    unsigned piece_full[NLD], piece_last[NLD];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const int row = 4 * p + (lane >> 4);
+    for (int p = 0; p < NLD; ++p) {
+        const int row = CB == 4 ? 4 * p + (lane >> 4) : 8 * p + (lane >> 3);
         const unsigned r = (unsigned)(min(64 * tile + 16 * wv + row, a.N - 1) - 64 * tile);
-        const int c = (lane & 15) ^ row;  // the chunk: cells 4 c .. + 3 of the unit
-        piece_full[p] = (r * (unsigned)E + 4u * c) * 4u;
-        piece_last[p] = (r * (unsigned)E + (unsigned)min(64 * (nblk - 1) + 4 * c, E - 4)) * 4u;
+        const int c = CB == 4 ? (lane & 15) ^ row : (lane & 7) ^ ((row >> 1) & 7);  // the chunk: cells CPC c .. of the unit
+        piece_full[p] = (r * (unsigned)E + (unsigned)(CPC * c)) * CB;
+        piece_last[p] = (r * (unsigned)E + (unsigned)min(64 * (nblk - 1) + CPC * c, E - CPC)) * CB;
     }
-    const uint32_t my_ring = lds_address(smem) + (uint32_t)wv * (kMmRing * kMmUnitBytes);
+    const uint32_t my_ring = lds_address(smem) + (uint32_t)wv * (kMmRing * UB);
     int f_l = 0, f_blk = 0;  // the next unit to request
     auto fetch = [&](int slot) {
         const bool last = ragged && f_blk == nblk - 1;  // uniform
-        const char* ubase = tbytes + (((size_t)(l0 + f_l) * a.n_cap + (size_t)64 * tile) * E) * 4 +
-                            (last ? (size_t)0 : (size_t)f_blk * 256);
+        const char* ubase = tbytes + (((size_t)(l0 + f_l) * a.n_cap + (size_t)64 * tile) * E) * CB +
+                            (last ? (size_t)0 : (size_t)f_blk * RB);
 #pragma unroll
-        for (int p = 0; p < 4; ++p)
-            load16_to_lds(ubase + (last ? piece_last[p] : piece_full[p]), my_ring + (uint32_t)slot * kMmUnitBytes + 1024u * p);
+        for (int p = 0; p < NLD; ++p)
+            load16_to_lds(ubase + (last ? piece_last[p] : piece_full[p]), my_ring + (uint32_t)slot * UB + 1024u * p);
         if (++f_blk == nblk) {
             f_blk = 0;
             ++f_l;
@@ -495,7 +510,7 @@ __global__ void __launch_bounds__(kDotThreads) eamc_dot_mm_kernel(DotMmArgs a) {
         constexpr int DBC = decltype(db_tag)::value;
         constexpr int NW = DA + DBC - 1;  // weights 128^0 .. 128^(NW - 1)
         const unsigned char* qrow = planes + (size_t)lrow * S + lgrp * 16;
-        const unsigned char* ring = smem + (size_t)wv * (kMmRing * kMmUnitBytes);
+        const unsigned char* ring = smem + (size_t)wv * (kMmRing * UB);
         i32x4 acc[NW];
 #pragma unroll
         for (int w = 0; w < NW; ++w) acc[w] = i32x4{0, 0, 0, 0};
@@ -504,22 +519,32 @@ __global__ void __launch_bounds__(kDotThreads) eamc_dot_mm_kernel(DotMmArgs a) {
             constexpr int D = U % kMmRing;
             // units requested after this one: min(kMmRing - 1, n_units - 1 - U)
             if (U + 2 < n_units)
-                wait_vm_fence<8>();
+                wait_vm_fence<2 * NLD>();
             else if (U + 1 < n_units)
-                wait_vm_fence<4>();
+                wait_vm_fence<NLD>();
             else
                 wait_vm_fence<0>();
             static_assert(kMmRing == 3, "the wait counts above are those of a ring of three");
-            i32x4 x[4];
+            // lane (lrow, lgrp) takes piece p = cells 16 p + 4 lgrp .. + 3 of row lrow
+            int dg[4][DA];
+            const unsigned char* urow = ring + D * UB + lrow * RB;
+            if constexpr (CB == 4) {
+                i32x4 x[4];
 #pragma unroll
-            for (int p = 0; p < 4; ++p)
-                x[p] = *reinterpret_cast<const i32x4*>(ring + D * kMmUnitBytes + lrow * 256 + (((4 * p + lgrp) ^ lrow) << 4));
+                for (int p = 0; p < 4; ++p) x[p] = *reinterpret_cast<const i32x4*>(urow + (((4 * p + lgrp) ^ lrow) << 4));
+#pragma unroll
+                for (int p = 0; p < 4; ++p) cut_digits<DA>(x[p], dg[p]);
+            } else {
+                uint2 x[4];  // chunk 2 p + lgrp / 2, its half lgrp % 2
+#pragma unroll
+                for (int p = 0; p < 4; ++p)
+                    x[p] = *reinterpret_cast<const uint2*>(urow + (((2 * p + (lgrp >> 1)) ^ ((lrow >> 1) & 7)) << 4) + 8 * (lgrp & 1));
+#pragma unroll
+                for (int p = 0; p < 4; ++p) cut_digits16<DA>(x[p].x, x[p].y, dg[p]);
+            }
             i32x4 bq[DBC];
 #pragma unroll
             for (int db = 0; db < DBC; ++db) bq[db] = *reinterpret_cast<const i32x4*>(qrow + db * plane + (size_t)U * 64);
-            int dg[4][DA];
-#pragma unroll
-            for (int p = 0; p < 4; ++p) cut_digits<DA>(x[p], dg[p]);
             if (U + kMmRing < n_units) {
                 wait_lds_fence();  // the slot has been read
                 fetch(D);
@@ -1120,31 +1145,34 @@ MmPlan make_mm_plan(const moei_eamc* c, int L_scan, int B) {
     p.n_lsplit = (L_scan + p.lper - 1) / p.lper;
     p.q_stride = p.lper * p.nblk * 64;
     if ((p.q_stride / 16) % 2 == 0) p.q_stride += 16;
-    p.smem = (size_t)(kDotThreads / kWave) * kMmRing * kMmUnitBytes + (size_t)kMaxDigits * kMmQueries * p.q_stride;
+    p.smem = (size_t)(kDotThreads / kWave) * kMmRing * (64 * 16 * c->cell_bytes) + (size_t)kMaxDigits * kMmQueries * p.q_stride;
     p.DA = digits_of_host((unsigned)c->max_cell);
     p.ok = true;
     return p;
 }
 
-int launch_dot_mm(const MmPlan& p, const DotMmArgs& a, dim3 grid, hipStream_t s) {
-#define MOEI_MM_CASE(DD)                                                                          \
-    case DD: {                                                                                    \
-        static bool allowed = false; /* more than 64 KiB of dynamic LDS must be asked for once */ \
-        if (!allowed) {                                                                           \
-            MOEI_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(eamc_dot_mm_kernel<DD>),   \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024)); \
-            allowed = true;                                                                       \
-        }                                                                                         \
-        launch(K_MATCH_DOT, eamc_dot_mm_kernel<DD>, grid, dim3(kDotThreads), p.smem, s, a);      \
-        break;                                                                                    \
+int launch_dot_mm(const MmPlan& p, const DotMmArgs& a, int cell_bytes, dim3 grid, hipStream_t s) {
+#define MOEI_MM_CASE(DD, CB_)                                                                         \
+    case (DD) * 8 + (CB_): {                                                                          \
+        static bool allowed = false; /* more than 64 KiB of dynamic LDS must be asked for once */     \
+        if (!allowed) {                                                                               \
+            MOEI_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(eamc_dot_mm_kernel<DD, CB_>),  \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));     \
+            allowed = true;                                                                           \
+        }                                                                                             \
+        launch(K_MATCH_DOT, eamc_dot_mm_kernel<DD, CB_>, grid, dim3(kDotThreads), p.smem, s, a);     \
+        break;                                                                                        \
     }
-    switch (p.DA) {
-        MOEI_MM_CASE(1)
-        MOEI_MM_CASE(2)
-        MOEI_MM_CASE(3)
-        MOEI_MM_CASE(4)
+    switch (p.DA * 8 + cell_bytes) {
+        MOEI_MM_CASE(1, 4)
+        MOEI_MM_CASE(2, 4)
+        MOEI_MM_CASE(3, 4)
+        MOEI_MM_CASE(4, 4)
+        MOEI_MM_CASE(1, 2)
+        MOEI_MM_CASE(2, 2)
+        MOEI_MM_CASE(3, 2)
         default:
-            MOEI_FAIL(MOEI_EINVAL, "eamc_match: no matrix-core scan for %d digits", p.DA);
+            MOEI_FAIL(MOEI_EINVAL, "eamc_match: no matrix-core scan for %d digits of %d-byte cells", p.DA, cell_bytes);
     }
 #undef MOEI_MM_CASE
     MOEI_LAUNCH_CHECK();
@@ -1401,21 +1429,21 @@ int launch_dots(const moei_eamc* c, const int32_t* d_eam, int B, int layer_hi, i
     *n_lsplit = 0;
     if (c->N == 0) return MOEI_OK;
     // a.  Three queries and more (five and more for rows of several units, where a split holds few layers):
-    // the scan as a matrix product (4-byte cells, rows of whole 16-byte pieces); it takes the same time
+    // the scan as a matrix product (rows of whole 16-byte pieces); it takes the same time
     // for 3 as for 16 queries.  Measured at 10,000 traces: 26 x 64 cells, 4 queries 27.8 against 28.2 us
     // and 16 queries 29.3 against 44.7 us; 59 x 160 cells, 4 queries 100 against 84 us and 16 queries 111
     // against 207 us.
     static const bool kNoMm = getenv("MOEI_MATCH_NO_MM") && atoi(getenv("MOEI_MATCH_NO_MM")) != 0;
-    if (B >= (E <= 64 ? 3 : 5) && !kNoMm && c->cell_bytes == 4 && E % 4 == 0 && (uintptr_t)d_eam % 16 == 0) {
+    if (B >= (E <= 64 ? 3 : 5) && !kNoMm && E % (16 / c->cell_bytes) == 0 && (uintptr_t)d_eam % 16 == 0) {
         const MmPlan mp = make_mm_plan(c, layer_hi + 1, B);
         if (mp.ok) {
             *n_lsplit = mp.n_lsplit;
-            DotMmArgs ma{reinterpret_cast<const int32_t*>(c->d_traces), d_eam, c->d_part, c->n_cap, c->N, L, E, B,
+            DotMmArgs ma{c->d_traces, d_eam, c->d_part, c->n_cap, c->N, L, E, B,
                          layer_hi + 1, mp.lper, mp.n_lsplit, mp.nblk, mp.n_tiles, mp.q_stride};
-            return launch_dot_mm(mp, ma, dim3(mp.n_tiles, mp.n_lsplit, (B + kMmQueries - 1) / kMmQueries), s);
+            return launch_dot_mm(mp, ma, c->cell_bytes, dim3(mp.n_tiles, mp.n_lsplit, (B + kMmQueries - 1) / kMmQueries), s);
         }
     }
-    // b.  One or two queries, 2-byte cells, other shapes: the scan on the vector ALUs
+    // b.  One or two queries, other shapes: the scan on the vector ALUs
     Plan p = make_plan(c, layer_hi + 1, B);
     *n_lsplit = p.n_lsplit;
     if (p.n_lsplit > c->lsplit_max || p.smem > 64 * 1024)

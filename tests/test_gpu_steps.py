@@ -146,7 +146,7 @@ def test_eamc_match_workload_traces_and_partial_rows(m):
 
 
 @pytest.mark.parametrize("t_hi,q_hi", [(100, 90), (100, 3_000_000), (16_000, 16_000), (2_000_000, 120),
-                                       (16_777_215, 16_777_215), (130, 16_383)])
+                                       (16_777_215, 16_777_215), (130, 16_383), (65_535, 70_000)])
 def test_eamc_match_batches_over_cell_sizes(m, t_hi, q_hi):
     # two and more queries are matched by a matrix product over 7-bit digits of the cells: one to
     # four digits on either side, sixteen queries and five (a partly filled group), rows of 96 cells
@@ -164,8 +164,12 @@ def test_eamc_match_batches_over_cell_sizes(m, t_hi, q_hi):
         if t_hi <= 5_000_000:
             T[21] = 3 * T[20]                             # ties with trace 20 for every query
         _check_match(m, T, Q, 4)
+        if int(T.max()) <= 65535:
+            _check_match(m, T, Q, 2)                      # the same traces stored in 2-byte cells
     Q[:, 5:] = 0                                          # rows above the current layer are zero and are not scanned
     _check_match(m, T, Q, 4, layer_hi=4)
+    if int(T.max()) <= 65535:
+        _check_match(m, T, Q, 2, layer_hi=4)
 
 
 @pytest.mark.parametrize("N,L,E,B", [(300, 5, 160, 6), (130, 3, 448, 16), (65, 4, 452, 7), (100, 2, 512, 8)])
@@ -179,6 +183,20 @@ def test_eamc_match_batches_over_row_widths(m, N, L, E, B):
     Q[0, L - 1, E - 1] = 199
     Q[B - 1] = T[N - 1]
     _check_match(m, T, Q, 4)
+    if E % 8 == 0:
+        _check_match(m, T, Q, 2)
+
+
+def test_eamc_match_batch_of_two_byte_cells_up_to_their_limit(m):
+    # 2-byte cells hold counts up to 65,535: three 7-bit digits; queries of one to four digits
+    rng = np.random.default_rng(77)
+    N, L, E = 150, 6, 64
+    T = (rng.integers(0, 65536, size=(N, L, E)) * (rng.random((N, L, E)) < 0.4)).astype(np.int32)
+    T[11, 5, 63] = 65535
+    for q_hi in (100, 20_000, 16_777_215):
+        Q = (rng.integers(0, q_hi + 1, size=(9, L, E), dtype=np.int64) * (rng.random((9, L, E)) < 0.5)).astype(np.int32)
+        Q[8] = T[140]
+        _check_match(m, T, Q, 2)
 
 
 def test_eamc_match_batch_after_an_insert_with_larger_cells(m):
