@@ -313,7 +313,7 @@ __global__ void __launch_bounds__(kDotThreads) eamc_dot_kernel(DotArgs a) {
 // the queries (DB, per workgroup).
 //
 // grid (tiles of 64 traces, layer splits, groups of 16 queries), 4 wavefronts of 16 traces each.  A
-// unit is 64 cells of one layer of 16 traces (4 KiB; rows of 256 bytes).  The matrix instruction
+// unit is 64 cells of one layer of 16 traces (4 KiB, rows of 256 bytes; half that with 2-byte cells).  The matrix instruction
 // wants lane (r = lane % 16, g = lane / 16) to hold 16 cells of trace r, so a load into registers
 // would bring 64 bytes of each of 16 rows per instruction, and the compiler moves such loads down
 // to their use (a wavefront then has one unit in flight whatever ring the source spells out).  So
