@@ -218,8 +218,9 @@ int expert_ffn_gemv_static(moei_cache* c, const int32_t* d_slot_ids, const float
  * expert on the device and an expert's weights are streamed once per group of up to 4 of its
  * tokens, so bytes read grow with the number of distinct experts, not with B.
  * d_idx[B][k] int32, d_w[B][k] fp32, d_x[B][H] in desc->wdtype, d_y[B][H] fp32.  A pick that is
- * not resident contributes nothing and raises error flag bit 1.  Needs H to be a multiple of
- * 64 lanes x 16 bytes.  Results are bit-reproducible run to run. */
+ * not resident contributes nothing and raises error flag bit 1; a pick outside [0, E) (a token
+ * that got no picks) is passed over.  Needs H to be a multiple of 64 lanes x 16 bytes, E <= 256
+ * and B * k <= 512 (MOEI_EINVAL otherwise).  Results are bit-reproducible run to run. */
 int expert_ffn_grouped(moei_cache* c, int32_t layer, const int32_t* d_idx, const float* d_w, int32_t B,
                        const void* d_x, float* d_y, void* stream);
 /* Device-side error flags raised by kernels since the last call (bit 0: bad slot id,

@@ -451,68 +451,97 @@ struct GroupArgs {
 
 // The item list of a call, built by every workgroup for itself (the picks of a batch are a few
 // hundred bytes, the list a few kilobytes of LDS; a launch of its own would cost more than all
-// workgroups repeating it).  Thread e < 256 collects the tokens routed to expert e (in token
-// order) and cuts them into items of at most tb tokens; item positions follow expert order, the
-// shared experts last.  All threads of the workgroup call; with `publish` the list also goes to
-// global memory for the reduction kernel and a pick that is not resident raises its flag.
-// Returns the item count (in every thread).
-__device__ __forceinline__ int build_items(const GroupArgs& a, GroupItem* s_items, int* s_pick, int* s_cnt, int* s_base,
+// workgroups repeating it).  The tokens routed to an expert, in token order, are cut into items of
+// at most tb tokens; item positions follow expert order, the shared experts last.  The work is
+// spread over the picks: the thread of pick p counts the earlier picks of the same expert (its
+// rank there), LDS counters give every expert its number of tokens, a scan over the experts gives
+// each its first item, and the thread then writes its token into place.  All threads of the
+// workgroup call (at least 256 of them); with `publish` the list also goes to global memory for
+// the reduction kernel and a pick that is not resident raises its flag.  Returns the item count
+// (in every thread).  E <= 256 (checked by the host).
+struct ItemScratch {
+    int cnt[256];    // tokens routed to the expert
+    int start[256];  // its first item
+    int slot[256];   // its slot, -1: not resident
+    int wsum[4];
+};
+
+__device__ __forceinline__ int build_items(const GroupArgs& a, GroupItem* s_items, int* s_pick, ItemScratch* sc,
                                            bool publish) {
-    // s_pick[B*k] and, behind it, the gate weights: the call's picks are loaded once, then every
-    // expert's scan runs over LDS
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const int n_pick = a.B * a.k;
     float* s_pickw = reinterpret_cast<float*>(s_pick + n_pick);
     for (int p = tid; p < n_pick; p += blockDim.x) {
-        s_pick[p] = a.idx[p];
+        int e = a.idx[p];
+        if (e < 0 || e >= a.E) e = -1;  // a token without picks (no softmax exists for its logits)
+        s_pick[p] = e;
         s_pickw[p] = a.w[p];
     }
+    if (tid < 256) sc->cnt[tid] = 0;
     __syncthreads();
-    int base = 0;
-    for (int e0 = 0; e0 < a.E; e0 += 256) {
-        const int e = e0 + tid;
-        int ntok = 0;
-        int toks[kMaxBatch];
-        float ws[kMaxBatch];
-        if (tid < 256 && e < a.E)
-            for (int p = 0; p < n_pick; ++p)
-                if (s_pick[p] == e && ntok < kMaxBatch) {
-                    toks[ntok] = p / a.k;
-                    ws[ntok] = s_pickw[p];
-                    ++ntok;
-                }
-        int slot = -1;
+    // rank of every pick among the picks of its expert; tokens per expert
+    int my_rank[2] = {0, 0};  // a thread takes at most two picks (16 tokens x k picks over >= 256 threads)
+    int my_n = 0;
+    for (int p = tid; p < n_pick && my_n < 2; p += blockDim.x, ++my_n) {
+        const int e = s_pick[p];
+        int r = 0;  // four picks per LDS read (the weights behind the picks make the last read safe)
+        for (int q = 0; q < p; q += 4) {
+            const int4 v = *reinterpret_cast<const int4*>(s_pick + q);
+            r += (v.x == e) + ((q + 1 < p) & (v.y == e)) + ((q + 2 < p) & (v.z == e)) + ((q + 3 < p) & (v.w == e));
+        }
+        my_rank[my_n] = r;
+        if (e >= 0) atomicAdd(&sc->cnt[e], 1);
+    }
+    __syncthreads();
+    // items per expert, scanned over the experts
+    int mine = 0;
+    if (tid < 256) {
+        int slot = -1, ntok = tid < a.E ? sc->cnt[tid] : 0;
         if (ntok > 0) {
-            slot = a.slot_of_row[e];
+            slot = a.slot_of_row[tid];
             if (slot < 0) {  // not resident: contributes nothing, flagged
                 if (publish) atomicOr(a.flags, 2);
                 ntok = 0;
             }
         }
-        const int my_items = (ntok + a.tb - 1) / a.tb;
-        if (tid < 256) s_cnt[tid] = my_items;
-        __syncthreads();
-        if (tid < 256) {
-            int before = 0;
-            for (int i = 0; i < tid; ++i) before += s_cnt[i];
-            if (tid == 255) *s_base = before + my_items;
-            for (int g = 0; g < my_items; ++g) {
-                GroupItem it;
-                it.slot = slot;
-                it.ntok = min(a.tb, ntok - g * a.tb);
-                for (int j = 0; j < kMaxGroup; ++j) {
-                    const bool on = j < it.ntok;
-                    it.tok[j] = on ? toks[g * a.tb + j] : 0;
-                    it.w[j] = on ? ws[g * a.tb + j] : 0.f;
-                }
-                s_items[base + before + g] = it;
+        sc->slot[tid] = slot;
+        mine = (ntok + a.tb - 1) / a.tb;
+    }
+    int incl = mine;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int up = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += up;
+    }
+    if (lane == kWave - 1 && wv < 4) sc->wsum[wv] = incl;
+    __syncthreads();
+    if (tid < 256) {
+        int before = 0;
+        for (int w = 0; w < wv; ++w) before += sc->wsum[w];
+        sc->start[tid] = before + incl - mine;
+    }
+    int n = sc->wsum[0] + sc->wsum[1] + sc->wsum[2] + sc->wsum[3];
+    __syncthreads();
+    // every pick writes its token into its item; the first of an item also writes the item's head
+    my_n = 0;
+    for (int p = tid; p < n_pick && my_n < 2; p += blockDim.x, ++my_n) {
+        const int e = s_pick[p];
+        if (e < 0 || sc->slot[e] < 0) continue;
+        const int r = my_rank[my_n];
+        GroupItem* it = s_items + sc->start[e] + r / a.tb;
+        const int pos = r % a.tb;
+        it->tok[pos] = p / a.k;
+        it->w[pos] = s_pickw[p];
+        if (pos == 0) {
+            const int ntok = min(a.tb, sc->cnt[e] - r);
+            it->slot = sc->slot[e];
+            it->ntok = ntok;
+            for (int j = ntok; j < kMaxGroup; ++j) {
+                it->tok[j] = 0;
+                it->w[j] = 0.f;
             }
         }
-        __syncthreads();
-        base += *s_base;
-        __syncthreads();
     }
-    int n = base;
     const int tiles = (a.B + a.tb - 1) / a.tb;
     for (int q = tid; q < a.n_shared * tiles; q += blockDim.x) {
         const int sh = q / tiles, t0 = (q - sh * tiles) * a.tb;
@@ -568,8 +597,7 @@ __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(Gr
     constexpr int STEPS = StreamShape<NCH>::kSteps;
     constexpr int PF = StreamShape<NCH>::kWindow;
     extern __shared__ __align__(16) float smem[];
-    __shared__ int s_cnt[256];
-    __shared__ int s_base;
+    __shared__ ItemScratch s_is;
     // [TB][H] inputs of the item's tokens: fp32 for fp32 weights; for bf16 weights the stored bf16 values
     // themselves, in the first half of each row, for the two-element dot products
     constexpr bool kPacked = std::is_same<WT, uint16_t>::value;
@@ -582,7 +610,7 @@ __global__ void __launch_bounds__((kGroupedWaves * kWave)) ffn_grouped_kernel(Gr
     const WT* pool = reinterpret_cast<const WT*>(a.pool);
     const unsigned lane_off = (unsigned)lane * N;
     int* s_pick = reinterpret_cast<int*>(s_items + a.max_items);  // [2][B*k]
-    const int n_items = build_items(a.grp, s_items, s_pick, s_cnt, &s_base, blockIdx.x == 0);
+    const int n_items = build_items(a.grp, s_items, s_pick, &s_is, blockIdx.x == 0);
     const long total = (long)n_items * I;
     const long R0 = grouped_range_begin(total, blockIdx.x, gridDim.x);
     const long R1 = grouped_range_begin(total, blockIdx.x + 1, gridDim.x);
@@ -948,6 +976,9 @@ int launch_expert_ffn_grouped(const moei_model_desc& d, const void* d_pool, size
                               const int32_t* d_idx, const float* d_w, int B, const void* d_x, float* d_y,
                               int32_t* d_flags, hipStream_t s) {
     if (B > kMaxBatch) MOEI_FAIL(MOEI_EINVAL, "expert_ffn_grouped: B = %d exceeds %d", B, kMaxBatch);
+    // the item list is built by a thread per pick and per expert of a 256-thread group
+    if (d.E > 256 || B * d.k > 512)
+        MOEI_FAIL(MOEI_EINVAL, "expert_ffn_grouped: E = %d, B * k = %d exceed 256 experts or 512 picks", d.E, B * d.k);
     const int wb = d.wdtype == MOEI_WDTYPE_BF16 ? 2 : 4;
     const int n = 16 / wb;
     if (d.H % (kWave * n) != 0 || (uintptr_t)d_pool % 16 != 0 || (slot_elems * wb) % 16 != 0)

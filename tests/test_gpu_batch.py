@@ -89,7 +89,8 @@ def test_batch_sweep_on_the_deepseek_v2_lite_shape(m):
     _batch_case(m, cfg, 24, [1, 2, 4, 8, 16])
 
 
-@pytest.mark.parametrize("wdtype,H,I", [("fp32", 256, 96), ("bf16", 1024, 72), ("bf16", 4096, 40), ("fp32", 1024, 130)])
+@pytest.mark.parametrize("wdtype,H,I", [("fp32", 256, 96), ("bf16", 1024, 72), ("bf16", 4096, 40), ("fp32", 1024, 130),
+                                          ("fp32", 2048, 37), ("bf16", 2048, 3)])
 def test_batched_ffn_other_shapes(m, wdtype, H, I):
     cfg = mi.get_config("C5").scaled(L=2, E=16, k=3, n_shared=1, N=60, prompt=16, H=H, I=I, wdtype=wdtype)
     _batch_case(m, cfg, 32, [3, 16])
