@@ -131,22 +131,43 @@ __global__ void __launch_bounds__((StreamShape<NCH>::kMaxWaves * kWave)) ffn_fus
     float gate = 0.f, gate_n = 0.f;
     bool ok = false, ok_n = false;
     size_t p = 0;
-    if (t < NT) {  // the first loads are on their way while x is staged
-        const int e = t / I;
-        p = unit_off(a.slot_ids[e], t - e * I, ok);
+    // A wavefront's loads complete in issue order, so what is staged into LDS is requested BEFORE the
+    // first window: its data is then there after one trip to the cache, the wavefront starts on the
+    // window's first load as soon as that one arrives and refills from then on.  Requested behind the
+    // window it would arrive after the window's last load, and until then no refill would be issued.
+    constexpr int kXRounds = (NCH + 3) / 4;  // x is NCH x 64 pieces of 16 bytes, a workgroup has at least 256 threads
+    uint4 xv[kXRounds];
+    if constexpr (kPacked) {
+#pragma unroll
+        for (int u = 0; u < kXRounds; ++u)  // a piece past the row is read as the row's last one (and not stored)
+            xv[u] = reinterpret_cast<const uint4*>(a.x)[min(tid + u * (int)blockDim.x, NCH * kWave - 1)];
+    }
+    const int act = min(tid, a.n_act - 1);
+    const int my_slot = a.slot_ids[act];
+    const float my_gate = a.gate_w[act];
+    {  // the first window is on its way while x is staged; a wavefront without units reads the pool's
+       // first unit instead, so that there is one path and the wait counts stay exact
+        const bool any = t < NT;
+        const int e = any ? t / I : 0;
+        const int slot0 = a.slot_ids[e];
         gate = a.gate_w[e];
+        if (any) p = unit_off(slot0, t - e * I, ok);
 #pragma unroll
         for (int s = 0; s < PF; ++s) win[s] = ld(p, step_off(s));
     }
     if constexpr (kPacked) {
         uint4* dst = reinterpret_cast<uint4*>(xs);
-        for (int c = tid; c < H / 8; c += blockDim.x) dst[c] = reinterpret_cast<const uint4*>(a.x)[c];
+#pragma unroll
+        for (int u = 0; u < kXRounds; ++u) {
+            const int c = tid + u * (int)blockDim.x;
+            if (c < NCH * kWave) dst[c] = xv[u];
+        }
     } else {
         stage_as_f32(reinterpret_cast<const WT*>(a.x), xs, H);
     }
     if (tid < a.n_act) {
-        s_slot[tid] = a.slot_ids[tid];
-        s_gate[tid] = a.gate_w[tid];
+        s_slot[tid] = my_slot;
+        s_gate[tid] = my_gate;
     }
     __syncthreads();
 
