@@ -134,58 +134,81 @@ __global__ void __launch_bounds__(kRouteWaves * kWave) route_fused_kernel(RouteF
     constexpr int NT = kRouteWaves * kWave;
     const int e = blockIdx.x * kRouteWaves + wv;
     int32_t* eam_row = a.eam + (size_t)a.layer * a.E;
+    // Everything this workgroup reads before the arrival counter is requested at once, the router row
+    // and the token first (a wavefront's loads complete in issue order, and the logit is what the
+    // other workgroups wait for); one trip to the cache instead of three.
+    constexpr int CW = kWave * V::N;
+    const WT* row = reinterpret_cast<const WT*>(a.W) + (size_t)(e < a.E ? e : 0) * a.H;
+    const WT* x = reinterpret_cast<const WT*>(a.x);
+    const bool one_round = a.vec_ok && a.H <= 4 * CW;  // the whole row in four chunk loads per lane
+    typename V::raw wr[4], xv[4];
+    if (one_round) {
+        const int c0 = lane * V::N;
+        const int cin = c0 < a.H ? c0 : 0;  // rows shorter than 64 vectors: the lanes past the end read the start
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int c = c0 + q * CW < a.H ? c0 + q * CW : cin;
+            wr[q] = V::load(row + c);
+            xv[q] = V::load(x + c);
+        }
+    }
     // any workgroup may turn out to be the last: each fetches the layer's slot row and EAM row
     // now, so that nothing but the logits is left to load after the arrival counter
-    for (int j = tid; j < a.E; j += NT) {
-        s_slot[j] = a.slot_of_row[j];
-        s_eam[j] = eam_row[j];
-    }
+    const int j0 = tid < a.E ? tid : 0;
+    const int slot0 = a.slot_of_row[j0], eam0 = eam_row[j0];
     // every workgroup copies its share of the EAM into the snapshot the match will read
     // (this step's k increments are added to the snapshot by the last workgroup)
-    {
-        const int seg = (a.LE + (int)gridDim.x - 1) / (int)gridDim.x;
-        const int i1 = min(a.LE, ((int)blockIdx.x + 1) * seg);
-        for (int i = blockIdx.x * seg + tid; i < i1; i += NT) a.snap[i] = a.eam[i];
-    }
+    const int seg = (a.LE + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int i0 = blockIdx.x * seg + tid, i1 = min(a.LE, ((int)blockIdx.x + 1) * seg);
+    const int snap0 = a.eam[i0 < a.LE ? i0 : 0];
+    float acc = 0.f;
     if (e < a.E) {  // uniform over the wavefront
-        const WT* row = reinterpret_cast<const WT*>(a.W) + (size_t)e * a.H;
-        const WT* x = reinterpret_cast<const WT*>(a.x);
-        float acc = 0.f;
-        if (a.vec_ok) {
-            // the chunks' loads go out together, four at a time for rows of up to 4 x 64 vectors, else
-            // ten (one round trip for 5,120 bf16 values); the sum still runs over the chunks in
-            // ascending order
-            constexpr int CW = kWave * V::N;
-            auto row_dot = [&](auto nq_tag) {
-                constexpr int NQ = decltype(nq_tag)::value;
-                for (int c0 = lane * V::N; c0 < a.H; c0 += NQ * CW) {
-                    typename V::raw wr[NQ], xv[NQ];
+        if (one_round) {
+            const int c0 = lane * V::N;
 #pragma unroll
-                    for (int q = 0; q < NQ; ++q) {
-                        const int c = c0 + q * CW < a.H ? c0 + q * CW : c0;
-                        wr[q] = V::load(row + c);
-                        xv[q] = V::load(x + c);
-                    }
+            for (int q = 0; q < 4; ++q) {  // the sum runs over the chunks in ascending order
+                if (c0 + q * CW < a.H) {
+                    float xf[V::N];
+                    V::unpack(xv[q], xf);
+                    acc = V::dot(wr[q], xf, acc);
+                }
+            }
+        } else if (a.vec_ok) {
+            // longer rows: ten chunk loads go out together (one round trip for 5,120 bf16 values)
+            constexpr int NQ = 10;
+            for (int c0 = lane * V::N; c0 < a.H; c0 += NQ * CW) {
+                typename V::raw wr10[NQ], xv10[NQ];
 #pragma unroll
-                    for (int q = 0; q < NQ; ++q) {
-                        if (c0 + q * CW < a.H) {
-                            float xf[V::N];
-                            V::unpack(xv[q], xf);
-                            acc = V::dot(wr[q], xf, acc);
-                        }
+                for (int q = 0; q < NQ; ++q) {
+                    const int c = c0 + q * CW < a.H ? c0 + q * CW : c0;
+                    wr10[q] = V::load(row + c);
+                    xv10[q] = V::load(x + c);
+                }
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    if (c0 + q * CW < a.H) {
+                        float xf[V::N];
+                        V::unpack(xv10[q], xf);
+                        acc = V::dot(wr10[q], xf, acc);
                     }
                 }
-            };
-            if (a.H <= 4 * CW)
-                row_dot(std::integral_constant<int, 4>{});
-            else
-                row_dot(std::integral_constant<int, 10>{});
+            }
         } else {
             for (int c = lane; c < a.H; c += kWave) acc = __builtin_fmaf(V::one(row + c), V::one(x + c), acc);
         }
         acc = wave_sum_dpp(acc);
         if (lane == 0) a.logits[e] = acc + (a.bias ? a.bias[e] : 0.f);
     }
+    if (tid < a.E) {
+        s_slot[tid] = slot0;
+        s_eam[tid] = eam0;
+    }
+    for (int j = tid + NT; j < a.E; j += NT) {
+        s_slot[j] = a.slot_of_row[j];
+        s_eam[j] = eam_row[j];
+    }
+    if (i0 < i1) a.snap[i0] = snap0;
+    for (int i = i0 + NT; i < i1; i += NT) a.snap[i] = a.eam[i];
     __syncthreads();
     if (tid == 0) {
         // release by the fence, then a relaxed arrival count (an acquire-release read-modify-write
