@@ -136,11 +136,16 @@ __global__ void __launch_bounds__((StreamShape<NCH>::kMaxWaves * kWave)) ffn_fus
     // window's first load as soon as that one arrives and refills from then on.  Requested behind the
     // window it would arrive after the window's last load, and until then no refill would be issued.
     constexpr int kXRounds = (NCH + 3) / 4;  // x is NCH x 64 pieces of 16 bytes, a workgroup has at least 256 threads
-    uint4 xv[kXRounds];
+    static_assert(kXRounds <= 4, "four named registers sets hold the token");
+    // (named variables, not an array: an array indexed in two loops is kept in scratch memory here)
+    uint4 xv0 = make_uint4(0u, 0u, 0u, 0u), xv1 = xv0, xv2 = xv0, xv3 = xv0;
     if constexpr (kPacked) {
-#pragma unroll
-        for (int u = 0; u < kXRounds; ++u)  // a piece past the row is read as the row's last one (and not stored)
-            xv[u] = reinterpret_cast<const uint4*>(a.x)[min(tid + u * (int)blockDim.x, NCH * kWave - 1)];
+        // a piece past the row is read as the row's last one (and not stored)
+        auto piece = [&](int u) { return reinterpret_cast<const uint4*>(a.x)[min(tid + u * (int)blockDim.x, NCH * kWave - 1)]; };
+        xv0 = piece(0);
+        if constexpr (kXRounds > 1) xv1 = piece(1);
+        if constexpr (kXRounds > 2) xv2 = piece(2);
+        if constexpr (kXRounds > 3) xv3 = piece(3);
     }
     const int act = min(tid, a.n_act - 1);
     const int my_slot = a.slot_ids[act];
@@ -157,11 +162,14 @@ __global__ void __launch_bounds__((StreamShape<NCH>::kMaxWaves * kWave)) ffn_fus
     }
     if constexpr (kPacked) {
         uint4* dst = reinterpret_cast<uint4*>(xs);
-#pragma unroll
-        for (int u = 0; u < kXRounds; ++u) {
+        auto put = [&](int u, uint4 v) {
             const int c = tid + u * (int)blockDim.x;
-            if (c < NCH * kWave) dst[c] = xv[u];
-        }
+            if (c < NCH * kWave) dst[c] = v;
+        };
+        put(0, xv0);
+        if constexpr (kXRounds > 1) put(1, xv1);
+        if constexpr (kXRounds > 2) put(2, xv2);
+        if constexpr (kXRounds > 3) put(3, xv3);
     } else {
         stage_as_f32(reinterpret_cast<const WT*>(a.x), xs, H);
     }
