@@ -1,8 +1,11 @@
 // The expert cache (Sec. 4.7, Alg. 1 of the paper) as a pool of HBM slots with a
 // host-side slot table, miss fills from pinned host memory on a copy stream, and the
 // fused per-layer decode step that strings the five steps together.
+#include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
+#include <chrono>
 #include <new>
 #include <vector>
 
@@ -44,9 +47,31 @@ struct Pinned {
     float best_sim;
     int32_t n_list[2];  // n_pf, n_ev
     int32_t flags;
+    int32_t best_seq;  // number of the step whose `best` is in place (written by the scoring workgroup after it)
 };
 
 }  // namespace
+
+// The synchronous step reads a few words that a kernel writes straight into pinned host memory.
+// Waiting for an event costs 10-15 us each time; polling the words themselves costs the time the
+// stores take to arrive.  `ready` is polled for at most `limit_us`; false = not seen in time (the
+// caller then waits for the event, which also surfaces a failed launch).
+template <typename Ready>
+static bool poll_pinned(Ready ready, double limit_us) {
+    const auto t0 = std::chrono::steady_clock::now();
+    for (int spin = 0;; ++spin) {
+        if (ready()) {
+            std::atomic_thread_fence(std::memory_order_acquire);
+            return true;
+        }
+        if ((spin & 63) == 63 &&
+            std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count() > limit_us)
+            return false;
+        __builtin_ia32_pause();
+    }
+}
+constexpr int32_t kNotWritten = -2;  // a pick the routing kernel has not stored yet (picks are >= -1)
+constexpr double kPollLimitUs = 500.0;
 
 void set_error(const char* fmt, ...) {
     va_list ap;
@@ -88,6 +113,8 @@ struct moei_cache {
                                                   // ev_side aliases the most recent of the two
     bool match_pending[kRing] = {};
     bool side_pending = false;
+    bool poll = true;      // the synchronous step polls pinned memory before it falls back to events (MOEI_SYNC_POLL=0: events only)
+    int32_t step_seq = 0;  // number of the last step whose scoring writes into pinned memory
     int parity = 0;  // which buffer set the current step writes
     FfnScratch ffn;
     void* d_items = nullptr;        // batched FFN: token groups, allocated at the first batched call
@@ -255,6 +282,10 @@ int cache_alloc(moei_cache* c) {
     MOEI_HIP(hipMemset(c->d_best, 0xff, kMaxMatchBatch * 4));
     int rc = ffn_scratch_alloc(d, na, &c->ffn);
     if (rc) return rc;
+    {
+        const char* v = getenv("MOEI_SYNC_POLL");  // read when a cache is created
+        c->poll = !(v && *v == '0');
+    }
     // mapped, coherent host memory: the routing and scoring kernels of a synchronous step store what the
     // host reads next (picks, matched trace, heads, scores) straight into it
     MOEI_HIP(hipHostMalloc((void**)&c->pin, sizeof(Pinned), hipHostMallocMapped | hipHostMallocCoherent));
@@ -780,6 +811,10 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
     ra.gate = c->d_gate;
     ra.flags = sync_mode ? nullptr : c->d_flags;
     ra.host_idx = sync_mode ? c->pin_dev->idx : nullptr;
+    if (sync_mode && c->poll) {  // only synchronous steps write these words, and each waits for its own
+        volatile int32_t* pi = c->pin->idx;
+        for (int j = 0; j < k; ++j) pi[j] = kNotWritten;
+    }
     rc = launch_route_fused(ra, d.wdtype, s);
     if (rc) return rc;
     MOEI_HIP(hipEventRecord(c->ev_routed, s));
@@ -815,6 +850,8 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
         sc.host_pf_head = c->pin_dev->pf_head;
         sc.host_ev_head = c->pin_dev->ev_head;
         sc.host_V = (c->pf_depth > 0 && c->policy == kPolicyEam) ? c->pin_V_dev : nullptr;
+        sc.host_seq = &c->pin_dev->best_seq;
+        sc.seq = ++c->step_seq;
     }
     if (c->match_m == 1)
         rc = launch_match(eamc, d_snap, 1, d.L - 1, c->d_best, c->d_best_sim, nullptr, &sc, side);
@@ -841,7 +878,15 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
     }
     if (!sync_mode) return MOEI_OK;
     {
-        MOEI_HIP(hipEventSynchronize(c->ev_routed));
+        {
+            volatile int32_t* pi = c->pin->idx;
+            const bool seen = c->poll && poll_pinned([&] {
+                for (int j = 0; j < k; ++j)
+                    if (pi[j] == kNotWritten) return false;
+                return true;
+            }, kPollLimitUs);
+            if (!seen) MOEI_HIP(hipEventSynchronize(c->ev_routed));
+        }
         int n_miss = 0;
         int32_t protect[kMaxAct];
         for (int j = 0; j < k; ++j) {
@@ -895,7 +940,12 @@ extern "C" int moe_decode_layer(moei_cache* c, const moei_eamc* eamc, int32_t* d
         if (h_topk_idx) memcpy(h_topk_idx, c->pin->idx, (size_t)k * 4);
         if (h_n_miss) *h_n_miss = n_miss;
         if (h_best) {
-            if (!side_done) MOEI_HIP(hipEventSynchronize(c->ev_side));
+            if (!side_done) {  // only the matched trace is needed: it is announced by the step's number
+                volatile int32_t* ps = &c->pin->best_seq;
+                const int32_t want = c->step_seq;
+                const bool seen = c->poll && poll_pinned([&] { return *ps == want; }, kPollLimitUs);
+                if (!seen) MOEI_HIP(hipEventSynchronize(c->ev_side));
+            }
             *h_best = c->pin->best;
         }
     }

@@ -38,6 +38,10 @@ struct ScoreArgs {
     int32_t* host_pf_head;
     int32_t* host_ev_head;
     float* host_V;          // [L*E] or null
+    // a host that polls instead of waiting for an event: after host_best has been written (and made
+    // visible to the host) the step's number goes to *host_seq (pinned, or null)
+    int32_t* host_seq;
+    int32_t seq;
 };
 
 __device__ __forceinline__ uint32_t cell_at(const void* traces, int cell_bytes, size_t i) {
@@ -154,6 +158,10 @@ __device__ __forceinline__ void score_cells(const ScoreArgs& a, int* s_n, int* s
             a.host_n[1] = s_n[1];
         }
         if (a.host_best) *a.host_best = s_best[0];
+        if (a.host_seq) {
+            __threadfence_system();  // the matched trace is in host memory before the number that announces it
+            __hip_atomic_store(a.host_seq, a.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
     }
 }
 
