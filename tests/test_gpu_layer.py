@@ -196,6 +196,15 @@ def test_decode_request_tiny_config(m):
     assert misses > 0                                   # the capped cache really evicts
 
 
+def test_decode_request_tiny_config_waiting_for_events_only(m, monkeypatch):
+    # the synchronous step normally polls the pinned words its kernels write and falls back to the
+    # events; the same replay with the polling switched off (read when the cache is created)
+    monkeypatch.setenv("MOEI_SYNC_POLL", "0")
+    cfg = mi.get_config("C1")
+    misses = _replay(m, cfg, cfg.S, cfg.decode, cfg.L * cfg.E, 4)
+    assert misses > 0
+
+
 @pytest.mark.parametrize("cell_bytes", [4, 2])
 def test_decode_request_reduced_deepseek_shape(m, cell_bytes):
     # DeepSeek-V2-Lite structure (top-6 of 64 + 2 shared, bf16, 25 % of experts cached), narrow matrices
